@@ -1,0 +1,221 @@
+/*
+ * parse.h -- C ABI of the MI355X (gfx950) routed low-rank linear layer.
+ *
+ * The layer computes, per prompt p with rank subset S_p (Sec. 4.1, Eq. 4),
+ *
+ *        y = sum_{i in S_p} sigma_i u_i (v_i^T x) = A_S (B_S^T x)        (Sec. 4.4, Eq. 10)
+ *
+ * where A = U Sigma and B^T = V are stored offline with Sigma (and any whitening) absorbed,
+ * the rank experts are grouped into G groups of gs = R/G consecutive ranks, a linear router
+ * scores the groups for each prompt and keeps the top k (Sec. 4.1, Eq. 5), a pattern cache
+ * answers for similar prompts without running the router (Sec. 4.3), the selected groups are
+ * aggregated into contiguous memory (Sec. 4.4, "Expert Memory Aggregation") and the subset
+ * chosen at prefill is reused for every decode step (Sec. 4.3, "Rank Reuse for Decoding").
+ *
+ * Conventions that hold for every entry point unless stated otherwise
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library never frees or keeps a caller's pointer beyond
+ *     the call (the kernels it enqueued still read/write them until the stream drains).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and return; they do not synchronise unless the comment says so.
+ *   - return value: PARSE_OK (0) or a negative parse_status.  Arguments are checked on the
+ *     host before anything is enqueued; on an error nothing was launched and no output
+ *     was written.  Contents of device-resident index arrays cannot be checked on the
+ *     host: every kernel bounds-checks what it reads from them and skips an invalid
+ *     entry (documented per call); parse_check_offsets / parse_check_subset validate
+ *     host copies.
+ *   - device pointers must be 16-byte aligned; bf16 buffers hold raw bfloat16 bit patterns.
+ *   - same inputs give the same bits on every run (no floating-point atomics anywhere).
+ */
+#ifndef PARSE_H_
+#define PARSE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *parse_stream; /* a hipStream_t */
+
+typedef enum { PARSE_F32 = 0, PARSE_BF16 = 1 } parse_dtype;
+
+typedef enum {
+  PARSE_OK = 0,
+  PARSE_EINVAL = -1,     /* NULL pointer, bad enum, non-positive size */
+  PARSE_ESHAPE = -2,     /* sizes inconsistent with each other or with a kernel's limits */
+  PARSE_EALIGN = -3,     /* pointer or leading dimension not aligned as required */
+  PARSE_ECAPACITY = -4,  /* pattern cache is full */
+  PARSE_EWORKSPACE = -5, /* workspace missing or smaller than the *_workspace_bytes query */
+  PARSE_EHIP = -6,       /* a HIP runtime call failed; text via parse_last_hip_error() */
+  PARSE_ELAYOUT = -7     /* factor layout not supported by this call */
+} parse_status;
+
+/* How a factor matrix is laid out in device memory.
+ *
+ * PARSE_ROWMAJOR   Vt[R][n] and Ut[R][m], rank-major: row r of Vt is v_r^T (row r of B^T),
+ *                  row r of Ut is sigma_r u_r^T (column r of A).  A rank group is gs
+ *                  consecutive rows = one contiguous slab.
+ * PARSE_MFMA16     bf16 only; the same numbers reordered into the operand order of the
+ *                  32x32x16 bf16 matrix instruction, so that a wavefront fetches one 1 KiB
+ *                  operand (32 rows x 16 reduction indices) with a single fully coalesced
+ *                  16-byte-per-lane load.  With e = 8 bf16 held by one lane:
+ *                    Vt element (r, i):  rb=r/32 j=r%32 kb=i/16 q=(i%16)/8 e=i%8
+ *                        offset = (((rb*(n/16) + kb)*2 + q)*32 + j)*8 + e
+ *                    Ut element (r, c):  kb=r/16 q=(r%16)/8 e=r%8 cb=c/32 j=c%32
+ *                        offset = (((kb*(m/32) + cb)*2 + q)*32 + j)*8 + e
+ *                  Needs n % 16 == 0, m % 32 == 0, gs % 32 == 0.  A rank group is still one
+ *                  contiguous slab of gs*n (resp. gs*m) elements in both matrices, so
+ *                  aggregation stays a plain slab copy.
+ */
+typedef enum { PARSE_ROWMAJOR = 0, PARSE_MFMA16 = 1 } parse_layout;
+
+/* One routed low-rank linear (Sec. 4.4, Eq. 10).  Host struct; Vt/Ut are device pointers. */
+typedef struct {
+  int32_t n;      /* d_in  */
+  int32_t m;      /* d_out */
+  int32_t R;      /* stored rank */
+  int32_t G;      /* rank groups; gs = R / G, R % G == 0 */
+  int32_t dtype;  /* parse_dtype of Vt, Ut and of the activations */
+  int32_t layout; /* parse_layout of Vt and Ut */
+  const void *Vt; /* B^T           : R x n */
+  const void *Ut; /* A^T = (U Sigma)^T : R x m */
+} parse_layer;
+
+/* Text for a status code (static storage). */
+const char *parse_status_string(int status);
+/* Text of the HIP error behind the last PARSE_EHIP on this thread (static storage). */
+const char *parse_last_hip_error(void);
+/* Library version: major*10000 + minor*100 + patch. */
+int parse_version(void);
+
+/* Host-side validators for arrays that the other calls take as device pointers.
+ * parse_check_offsets: tok_offsets_host[P+1] must start at 0, be strictly increasing (no empty
+ *   prompt) and end at `rows`.  parse_check_subset: k group ids, strictly ascending, each in [0, G).
+ * Return PARSE_OK, PARSE_EINVAL (NULL / non-positive sizes) or PARSE_ESHAPE. */
+int parse_check_offsets(const int32_t *tok_offsets_host, int32_t P, int32_t rows);
+int parse_check_subset(const int32_t *subset_host, int32_t k, int32_t G);
+
+/* ---- offline preparation (Sec. 4.4: factors are reorganised once, offline) -------------
+ * Reorders a PARSE_ROWMAJOR bf16 layer into PARSE_MFMA16.  Vt_out / Ut_out: device buffers of
+ * R*n and R*m bf16.  PARSE_ELAYOUT if src is not row-major bf16, PARSE_ESHAPE if the divisibility
+ * rules above fail. */
+int parse_layer_to_mfma16(const parse_layer *src, void *Vt_out, void *Ut_out, parse_stream stream);
+
+/* ---- a1 + a2: pool and route (Sec. 4.1, Eq. 5; prompt-level embedding, end of Sec. 4.1) ----
+ * e_p = mean of prompt p's token rows of X (fp32 accumulation); s_p = Wr e_p; subset_out[p] = the
+ * k groups with the largest scores, ties to the lower id, written in ascending id order.
+ *   X            device [rows][d], dtype xdtype, row-major.  A ready-made embedding is a prompt of length 1.
+ *   tok_offsets  device int32 [P+1], prompt p owns rows [tok_offsets[p], tok_offsets[p+1]).  Rows are
+ *                clamped to [0, rows]; a prompt that ends up empty gets e_p = 0.
+ *   Wr           device float [G][d], bias-free router.      1 <= k <= G <= 64, d % 8 == 0, d <= 16384.
+ *   subset_out   device int32 [P][subset_stride] (k ids per row; subset_stride >= k lets a caller
+ *                interleave several layers' subsets), scores_out device float [P][G] or NULL,
+ *                emb_out device float [P][d] or NULL.
+ *   workspace    device, at least parse_route_workspace_bytes(rows, P, d) bytes. */
+size_t parse_route_workspace_bytes(int32_t rows, int32_t P, int32_t d);
+int parse_route(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_offsets, int32_t P,
+                int32_t d, const float *Wr, int32_t G, int32_t k, int32_t *subset_out,
+                int32_t subset_stride, float *scores_out, float *emb_out, void *workspace,
+                size_t workspace_bytes, parse_stream stream);
+
+/* ---- a3: pattern cache (Sec. 4.3, "Rank Retrieval for Prefilling") -------------------------
+ * Maps prompt embeddings to the rank subsets of all L routed matrices of a model.  The only
+ * library-owned state: keys float [capacity][d], values int32 [capacity][L][k], a device-side
+ * entry count, and scratch for one batch of at most max_batch prompts.  A lookup answers with
+ * the nearest key by cosine similarity (smallest entry index on equal similarity); it is a hit
+ * when the similarity is >= tau.  Calls on one cache must be issued on one stream (or be ordered
+ * by the caller); calls that overlap on one cache race.
+ * create/destroy/count/insert/clear synchronise; lookup and lookup_or_route only enqueue. */
+typedef struct parse_cache parse_cache;
+int parse_cache_create(parse_cache **cache, int32_t capacity, int32_t d, int32_t L, int32_t k,
+                       int32_t max_batch);
+int parse_cache_destroy(parse_cache *cache);
+int parse_cache_clear(parse_cache *cache, parse_stream stream);
+/* count_out: host int32. */
+int parse_cache_count(parse_cache *cache, int32_t *count_out, parse_stream stream);
+/* Appends one entry.  emb device float [d]; subsets device int32 [L][k].  PARSE_ECAPACITY when full. */
+int parse_cache_insert(parse_cache *cache, const float *emb, const int32_t *subsets,
+                       parse_stream stream);
+/* Pure lookup for P <= max_batch embeddings (device float [P][d]).
+ *   entry_out  device int32 [P]: the entry that answered, -1 on a miss (also when the cache is empty)
+ *   sim_out    device float [P] or NULL: best cosine similarity (-inf if the cache is empty)
+ *   subset_out device int32 [P][L][k] or NULL: stored subsets on a hit, untouched on a miss */
+int parse_cache_lookup(parse_cache *cache, const float *emb, int32_t P, float tau,
+                       int32_t *entry_out, float *sim_out, int32_t *subset_out,
+                       parse_stream stream);
+/* Lookup with sequential semantics in arrival order: prompt i that misses is routed with
+ * Wr (device float [L][G][d], G <= 64) for every layer and, while there is room, appended at once,
+ * so that prompt i+1 of the same batch can hit it.
+ *   entry_out  device int32 [P]: hit entry, or the new entry's index, or -1 (miss, cache full)
+ *   hit_out    device uint8 [P]: 1 = hit, 0 = miss
+ *   sim_out    device float [P] or NULL;   subset_out device int32 [P][L][k] (always written) */
+int parse_cache_lookup_or_route(parse_cache *cache, const float *emb, int32_t P, float tau,
+                                const float *Wr, int32_t G, int32_t *entry_out, uint8_t *hit_out,
+                                float *sim_out, int32_t *subset_out, parse_stream stream);
+
+/* ---- a5: bucket prompts by identical subset ---------------------------------------------
+ * Patterns are numbered by first appearance in arrival order.
+ *   subset      device int32, prompt p's k ids at subset[p*subset_stride .. +k)
+ *   pattern_id  device int32 [P];  perm device int32 [P]: prompts ordered by (pattern id, arrival);
+ *   bucket_off  device int32 [P+1]: bucket j is perm[bucket_off[j] .. bucket_off[j+1]), entries past
+ *               n_patterns repeat P;  n_patterns device int32 [1];  rep device int32 [P]: first prompt
+ *               of pattern j for j < n_patterns, -1 after.            1 <= P <= 1024, 1 <= k <= 64. */
+int parse_bucket_patterns(const int32_t *subset, int32_t P, int32_t k, int32_t subset_stride,
+                          int32_t *pattern_id, int32_t *perm, int32_t *bucket_off,
+                          int32_t *n_patterns, int32_t *rep, parse_stream stream);
+
+/* ---- a4: expert memory aggregation (Sec. 4.4) ---------------------------------------------
+ * Copies the k selected group slabs of Vt and Ut, in the order the ids are stored (ascending by
+ * contract), into Vt_S [k*gs][n] and Ut_S [k*gs][m]; the result has the source's dtype and layout
+ * (in both layouts a rank group is one contiguous slab, so this is 2k coalesced slab copies).
+ * An id outside [0, G) leaves its slab of the destination untouched.
+ *   subset  device int32 [k] */
+int parse_pack_experts(const parse_layer *layer, const int32_t *subset, int32_t k, void *Vt_S,
+                       void *Ut_S, parse_stream stream);
+/* The same for every pattern of a batch without a host round trip: pattern j < *n_patterns is taken
+ * from prompt rep[j]'s subset (subset[rep[j]*subset_stride .. +k)) and written to
+ * Vt_S + j*k*gs*n and Ut_S + j*k*gs*m elements; j >= *n_patterns (device value) is skipped.
+ * Destinations must hold max_patterns patterns.  rep == NULL means pattern j = row j. */
+int parse_pack_patterns(const parse_layer *layer, const int32_t *subset, int32_t subset_stride,
+                        int32_t k, const int32_t *rep, const int32_t *n_patterns,
+                        int32_t max_patterns, void *Vt_S, void *Ut_S, parse_stream stream);
+
+/* ---- a6 / a7: the routed product ------------------------------------------------------------
+ * Patterns of one call.  All patterns of a layer have the same active rank r_S = k*gs. */
+typedef struct {
+  const void *Vt_S;       /* device, packed [n_patterns][k*gs][n] in the layer's layout; prefill only */
+  const void *Ut_S;       /* device, packed [n_patterns][k*gs][m];                       prefill only */
+  const int32_t *subsets; /* device int32, pattern j's ids at subsets[j*subset_stride .. +k); decode only */
+  int32_t subset_stride;
+  int32_t n_patterns;     /* capacity of the arrays above; pattern ids outside [0, n_patterns) give zero rows */
+  int32_t k;
+} parse_patterns;
+
+typedef enum { PARSE_PREFILL = 0, PARSE_DECODE = 1 } parse_mode;
+
+size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *layer, int32_t rows,
+                                     int32_t k);
+/* PARSE_PREFILL  Y[t] = A_S (B_S^T x_t) for every token t of prompt p, S = pattern pattern_id[p]
+ *                (Eq. 4 / Eq. 10), read from the packed factors.  bf16 layers must be PARSE_MFMA16:
+ *                one fused kernel, both products on the bf16 matrix cores with fp32 accumulation, the
+ *                r_S-wide intermediate rounded to bf16 and kept in LDS.  f32 layers must be
+ *                PARSE_ROWMAJOR (plain fp32 kernels, intermediate in the workspace).
+ *                  X device [rows][n], Y device [rows][m] (layer dtype), tok_offsets device int32 [P+1],
+ *                  pattern_id device int32 [P].
+ * PARSE_DECODE   one token per sequence (rows == P, tok_offsets ignored, may be NULL), bf16 PARSE_MFMA16
+ *                layers only, rows <= 32 per call.  Streams every group that some sequence selected exactly
+ *                once from the layer's own store (layer->Vt / layer->Ut, not the packed copies) and applies
+ *                it to the sequences whose pattern holds it (Sec. 4.3, rank reuse: pattern_id is fixed
+ *                at prefill).  Bandwidth-bound.
+ * workspace: device, >= parse_lowrank_workspace_bytes(mode, layer, rows, k) bytes. */
+int parse_lowrank_forward(int32_t mode, const parse_layer *layer, const parse_patterns *patterns,
+                          const void *X, int32_t rows, const int32_t *tok_offsets,
+                          const int32_t *pattern_id, int32_t P, void *Y, void *workspace,
+                          size_t workspace_bytes, parse_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARSE_H_ */

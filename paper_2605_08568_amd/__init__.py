@@ -1,0 +1,10 @@
+"""MI355X (gfx950) routed low-rank linear layer: thin Python binding over the C-ABI library libparse.so.
+
+Every step of the path runs in the library's HIP kernels; this package only marshals arguments
+(PyTorch supplies device memory and streams).  Importing it without a built library raises."""
+from .binding import (  # noqa: F401
+    PARSE_BF16, PARSE_DECODE, PARSE_F32, PARSE_MFMA16, PARSE_PREFILL, PARSE_ROWMAJOR,
+    Cache, Layer, ParseError, Patterns, bf16_from_bits, bf16_to_bits, bucket_patterns,
+    check_offsets, check_subset, layer_to_mfma16, lib, lowrank_forward, lowrank_workspace_bytes,
+    pack_experts, pack_patterns, route, route_workspace_bytes, status_string, version,
+)

@@ -1,0 +1,61 @@
+// parse_lowrank_forward: argument checks and dispatch to the fp32 / bf16 prefill kernels and the decode kernels.
+#include "common.hpp"
+
+namespace parse {
+int forward_f32(const parse_layer *L, const parse_patterns *pt, const float *X, int rows, const int32_t *tok_offsets,
+                const int32_t *pattern_id, int P, float *Y, void *workspace, hipStream_t s);
+int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *X, int rows,
+                         const int32_t *tok_offsets, const int32_t *pattern_id, int P, uint16_t *Y, hipStream_t s);
+size_t prefill_lds_bytes(int BM, int rS);
+size_t decode_workspace_bytes(const parse_layer *L);
+int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *x, int B,
+                        const int32_t *pattern_id, uint16_t *y, void *workspace, hipStream_t s);
+}  // namespace parse
+
+using namespace parse;
+
+extern "C" {
+
+size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *L, int32_t rows, int32_t k) {
+  if (!L || rows <= 0 || k <= 0 || L->G <= 0 || L->R <= 0) return 0;
+  if (mode == PARSE_DECODE) return decode_workspace_bytes(L);
+  if (L->dtype == PARSE_F32) return round_up((size_t)rows * k * (L->R / L->G) * sizeof(float), 256);
+  return 0;
+}
+
+int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patterns *pt, const void *X, int32_t rows,
+                          const int32_t *tok_offsets, const int32_t *pattern_id, int32_t P, void *Y, void *workspace,
+                          size_t workspace_bytes, parse_stream stream) {
+  if (mode != PARSE_PREFILL && mode != PARSE_DECODE) return PARSE_EINVAL;
+  int st = check_layer(L);
+  if (st != PARSE_OK) return st;
+  if (!pt || !X || !Y || !pattern_id) return PARSE_EINVAL;
+  if (rows <= 0 || P <= 0 || pt->n_patterns <= 0 || pt->k <= 0) return PARSE_EINVAL;
+  if (pt->k > L->G || P > rows) return PARSE_ESHAPE;
+  if (!aligned16(X) || !aligned16(Y)) return PARSE_EALIGN;
+  const size_t need = parse_lowrank_workspace_bytes(mode, L, rows, pt->k);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return PARSE_EWORKSPACE;
+  if (need > 0 && !aligned16(workspace)) return PARSE_EALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  const int gs = L->R / L->G, rS = pt->k * gs;
+
+  if (mode == PARSE_DECODE) {
+    if (L->dtype != PARSE_BF16 || L->layout != PARSE_MFMA16) return PARSE_ELAYOUT;
+    if (!pt->subsets) return PARSE_EINVAL;
+    if (rows != P || rows > 32 || L->G > 64 || pt->subset_stride < pt->k) return PARSE_ESHAPE;
+    return forward_decode_bf16(L, pt, (const uint16_t *)X, rows, pattern_id, (uint16_t *)Y, workspace, s);
+  }
+
+  if (!tok_offsets || !pt->Vt_S || !pt->Ut_S) return PARSE_EINVAL;
+  if (!aligned16(pt->Vt_S) || !aligned16(pt->Ut_S)) return PARSE_EALIGN;
+  if (L->dtype == PARSE_F32) {
+    if (L->layout != PARSE_ROWMAJOR) return PARSE_ELAYOUT;
+    return forward_f32(L, pt, (const float *)X, rows, tok_offsets, pattern_id, P, (float *)Y, workspace, s);
+  }
+  if (L->layout != PARSE_MFMA16) return PARSE_ELAYOUT;
+  if (rS % 32 != 0) return PARSE_ESHAPE;
+  if (prefill_lds_bytes(32, rS) > 160 * 1024) return PARSE_ESHAPE;
+  return forward_prefill_bf16(L, pt, (const uint16_t *)X, rows, tok_offsets, pattern_id, P, (uint16_t *)Y, s);
+}
+
+}  // extern "C"

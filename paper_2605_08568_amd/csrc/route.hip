@@ -1,0 +1,140 @@
+// a1 + a2: prompt pooling and the linear router with top-k (Sec. 4.1, Eq. 5).
+//
+// Two launches, both deterministic:
+//   pool_partial  grid (column blocks, Q token slices, P prompts): fp32 partial sums of a slice of the
+//                 prompt's token rows, 16 bytes per lane per row, rows streamed once.
+//   route_finish  one block per prompt: adds the Q partials in slice order, divides by the length,
+//                 scores the G groups (one wavefront per group, butterfly reduction) and selects the
+//                 top k with a rank count inside one wavefront.
+#include "common.hpp"
+#include "topk.hpp"
+
+namespace parse {
+
+constexpr int kPoolThreads = 256;
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+template <bool BF16>
+__global__ __launch_bounds__(kPoolThreads) void pool_partial(const void *__restrict__ X, int rows, int d,
+                                                             const int32_t *__restrict__ tok_offsets,
+                                                             int Q, float *__restrict__ partial) {
+  constexpr int PER = BF16 ? 8 : 4;  // columns per lane = 16 bytes
+  const int p = blockIdx.z, q = blockIdx.y;
+  const int c0 = (blockIdx.x * kPoolThreads + threadIdx.x) * PER;
+  if (c0 >= d) return;
+  const int a = clampi(tok_offsets[p], 0, rows);
+  const int b = clampi(tok_offsets[p + 1], a, rows);
+  const long long len = b - a;
+  const int r0 = a + (int)((len * q) / Q), r1 = a + (int)((len * (q + 1)) / Q);
+  float acc[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) acc[i] = 0.f;
+  if constexpr (BF16) {
+    const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
+#pragma unroll 4
+    for (int r = r0; r < r1; ++r) {
+      const u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)r * d + c0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += __uint_as_float(v[i] << 16);
+        acc[2 * i + 1] += __uint_as_float(v[i] & 0xFFFF0000u);
+      }
+    }
+  } else {
+    const float *x = reinterpret_cast<const float *>(X);
+#pragma unroll 4
+    for (int r = r0; r < r1; ++r) {
+      const float4 v = *reinterpret_cast<const float4 *>(x + (size_t)r * d + c0);
+      acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+    }
+  }
+  float *dst = partial + ((size_t)p * Q + q) * d + c0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) dst[i] = acc[i];
+}
+
+__global__ __launch_bounds__(256) void route_finish(const float *__restrict__ partial, int Q, int rows, int d,
+                                                    const int32_t *__restrict__ tok_offsets,
+                                                    const float *__restrict__ Wr, int G, int k,
+                                                    int32_t *__restrict__ subset_out, int subset_stride,
+                                                    float *__restrict__ scores_out,
+                                                    float *__restrict__ emb_out) {
+  extern __shared__ float lds[];
+  float *e = lds;          // [d]
+  float *s = lds + d;      // [64]
+  const int p = blockIdx.x;
+  const int a = clampi(tok_offsets[p], 0, rows);
+  const int b = clampi(tok_offsets[p + 1], a, rows);
+  const float inv = (b > a) ? 1.0f / (float)(b - a) : 0.f;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float acc = 0.f;
+    for (int q = 0; q < Q; ++q) acc += partial[((size_t)p * Q + q) * d + c];
+    const float v = acc * inv;
+    e[c] = v;
+    if (emb_out) emb_out[(size_t)p * d + c] = v;
+  }
+  __syncthreads();
+  block_router_scores(Wr, e, d, G, s);
+  if (scores_out)
+    for (int g = threadIdx.x; g < G; g += blockDim.x) scores_out[(size_t)p * G + g] = s[g];
+  if (threadIdx.x < 64) wave_topk_ascending(s, G, k, subset_out + (size_t)p * subset_stride);
+}
+
+static int pool_slices(int rows, int P, int d, bool bf16) {
+  const int per_block = kPoolThreads * (bf16 ? 8 : 4);
+  const int colblocks = (d + per_block - 1) / per_block;
+  long long want = (2048 + (long long)P * colblocks - 1) / ((long long)P * colblocks);
+  long long avg = rows / (P > 0 ? P : 1);
+  long long by_len = avg / 8 > 0 ? avg / 8 : 1;
+  long long q = want < by_len ? want : by_len;
+  if (q > 32) q = 32;
+  if (q < 1) q = 1;
+  return (int)q;
+}
+
+}  // namespace parse
+
+using namespace parse;
+
+extern "C" {
+
+size_t parse_route_workspace_bytes(int32_t rows, int32_t P, int32_t d) {
+  if (rows <= 0 || P <= 0 || d <= 0) return 0;
+  // the slice count does not depend on the dtype beyond the column-block count; size for the larger one
+  const int q = pool_slices(rows, P, d, false) > pool_slices(rows, P, d, true) ? pool_slices(rows, P, d, false)
+                                                                                  : pool_slices(rows, P, d, true);
+  return round_up((size_t)P * q * d * sizeof(float), 256);
+}
+
+int parse_route(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_offsets, int32_t P, int32_t d,
+                const float *Wr, int32_t G, int32_t k, int32_t *subset_out, int32_t subset_stride,
+                float *scores_out, float *emb_out, void *workspace, size_t workspace_bytes,
+                parse_stream stream) {
+  if (!X || !tok_offsets || !Wr || !subset_out) return PARSE_EINVAL;
+  if (xdtype != PARSE_F32 && xdtype != PARSE_BF16) return PARSE_EINVAL;
+  if (rows <= 0 || P <= 0 || d <= 0 || G <= 0 || k <= 0) return PARSE_EINVAL;
+  if (k > G || G > 64 || d > 16384 || P > rows || subset_stride < k) return PARSE_ESHAPE;
+  if (d % 8 != 0) return PARSE_EALIGN;
+  if (!aligned16(X) || !aligned16(Wr) || !aligned16(workspace)) return PARSE_EALIGN;
+  if (emb_out && !aligned16(emb_out)) return PARSE_EALIGN;
+  if (!workspace || workspace_bytes < parse_route_workspace_bytes(rows, P, d)) return PARSE_EWORKSPACE;
+  const bool bf16 = xdtype == PARSE_BF16;
+  const int Q = pool_slices(rows, P, d, bf16);
+  const int per_block = kPoolThreads * (bf16 ? 8 : 4);
+  dim3 grid((d + per_block - 1) / per_block, Q, P);
+  hipStream_t s = (hipStream_t)stream;
+  float *partial = reinterpret_cast<float *>(workspace);
+  if (bf16)
+    hipLaunchKernelGGL(pool_partial<true>, grid, dim3(kPoolThreads), 0, s, X, rows, d, tok_offsets, Q, partial);
+  else
+    hipLaunchKernelGGL(pool_partial<false>, grid, dim3(kPoolThreads), 0, s, X, rows, d, tok_offsets, Q, partial);
+  PARSE_LAUNCH_CHECK();
+  const size_t lds = (size_t)(d + 64) * sizeof(float);
+  hipLaunchKernelGGL(route_finish, dim3(P), dim3(256), lds, s, partial, Q, rows, d, tok_offsets, Wr, G, k,
+                     subset_out, subset_stride, scores_out, emb_out);
+  PARSE_LAUNCH_CHECK();
+  return PARSE_OK;
+}
+
+}  // extern "C"

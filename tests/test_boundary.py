@@ -1,0 +1,128 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
+declares, and rejects bad arguments with the documented status before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "parse.h")
+
+pa = pytest.importorskip("paper_2605_08568_amd")
+from paper_2605_08568_amd import binding as B  # noqa: E402
+
+FAKE = C.c_void_p(0x1000)      # non-NULL, 16-byte aligned, never dereferenced: every check below fails first
+FAKE2 = C.c_void_p(0x2000)
+ODD = C.c_void_p(0x1004)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(parse_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pa.lib()
+    names = declared_functions()
+    assert {"parse_route", "parse_cache_lookup", "parse_pack_experts", "parse_lowrank_forward"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings_and_version():
+    assert pa.version() >= 100
+    for code in range(0, -8, -1):
+        assert pa.status_string(code) != "unknown status"
+    assert pa.status_string(-99) == "unknown status"
+
+
+def test_check_offsets():
+    assert pa.check_offsets(np.array([0, 3, 5]), 5) == 0
+    assert pa.check_offsets(np.array([0, 3, 3, 5]), 5) == -2      # empty prompt
+    assert pa.check_offsets(np.array([0, 4, 3, 5]), 5) == -2      # not ascending
+    assert pa.check_offsets(np.array([1, 3, 5]), 5) == -2         # does not start at 0
+    assert pa.check_offsets(np.array([0, 3, 5]), 6) == -2         # does not end at rows
+    assert pa.lib().parse_check_offsets(None, 2, 5) == -1
+
+
+def test_check_subset():
+    assert pa.check_subset(np.array([0, 2, 5]), 6) == 0
+    assert pa.check_subset(np.array([0, 2, 6]), 6) == -2          # out of range
+    assert pa.check_subset(np.array([2, 2]), 6) == -2             # duplicate
+    assert pa.check_subset(np.array([3, 1]), 6) == -2             # not ascending
+    assert pa.check_subset(np.arange(7), 6) == -2                 # k > G
+
+
+def _layer(n=64, m=64, R=32, G=2, dtype=0, layout=0, Vt=FAKE, Ut=FAKE2):
+    return B._Layer(n, m, R, G, dtype, layout, Vt.value, Ut.value)
+
+
+def test_route_rejects_bad_arguments():
+    lib = pa.lib()
+    ok = dict(X=FAKE, xdt=0, rows=8, off=FAKE, P=2, d=64, Wr=FAKE, G=4, k=2, out=FAKE, stride=2, ws=FAKE, wsb=1 << 20)
+
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return lib.parse_route(a["X"], a["xdt"], a["rows"], a["off"], a["P"], a["d"], a["Wr"], a["G"], a["k"],
+                               a["out"], a["stride"], None, None, a["ws"], a["wsb"], None)
+
+    assert call(X=None) == -1 and call(off=None) == -1 and call(Wr=None) == -1 and call(out=None) == -1
+    assert call(xdt=7) == -1 and call(rows=0) == -1
+    assert call(k=5) == -2 and call(G=65, k=2) == -2 and call(P=9) == -2 and call(stride=1) == -2
+    assert call(d=60) == -3 and call(X=ODD) == -3
+    assert call(ws=None) == -5 and call(wsb=16) == -5
+
+
+def test_cache_create_rejects_bad_arguments():
+    lib = pa.lib()
+    h = C.c_void_p()
+    assert lib.parse_cache_create(None, 4, 64, 1, 2, 4) == -1
+    assert lib.parse_cache_create(C.byref(h), 0, 64, 1, 2, 4) == -1
+    assert lib.parse_cache_create(C.byref(h), 4, 62, 1, 2, 4) == -3
+    assert lib.parse_cache_create(C.byref(h), 4, 64, 1, 65, 4) == -2
+    assert lib.parse_cache_lookup(None, FAKE, 1, 0.9, FAKE, None, None, None) == -1
+    assert lib.parse_cache_destroy(None) == -1
+
+
+def test_pack_and_bucket_reject_bad_arguments():
+    lib = pa.lib()
+    L = _layer()
+    assert lib.parse_pack_experts(C.byref(L), None, 1, FAKE, FAKE, None) == -1
+    assert lib.parse_pack_experts(C.byref(L), FAKE, 3, FAKE, FAKE, None) == -2       # k > G
+    assert lib.parse_pack_experts(C.byref(L), FAKE, 1, ODD, FAKE, None) == -3
+    bad = _layer(R=33)                                                                 # R % G != 0
+    assert lib.parse_pack_experts(C.byref(bad), FAKE, 1, FAKE, FAKE, None) == -2
+    bad = _layer(n=62)                                                                 # rows not 16-byte multiples
+    assert lib.parse_pack_experts(C.byref(bad), FAKE, 1, FAKE, FAKE, None) == -3
+    bad = _layer(dtype=0, layout=1)                                                    # operand order is bf16 only
+    assert lib.parse_pack_experts(C.byref(bad), FAKE, 1, FAKE, FAKE, None) == -7
+    bad = _layer(dtype=1, layout=1, R=32, G=2)                                         # gs = 16 not a multiple of 32
+    assert lib.parse_pack_experts(C.byref(bad), FAKE, 1, FAKE, FAKE, None) == -2
+    assert lib.parse_layer_to_mfma16(C.byref(_layer(dtype=0)), FAKE, FAKE, None) == -7
+    assert lib.parse_bucket_patterns(FAKE, 2000, 2, 2, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -2
+    assert lib.parse_bucket_patterns(FAKE, 4, 2, 1, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -2
+    assert lib.parse_bucket_patterns(None, 4, 2, 2, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -1
+
+
+def test_forward_rejects_bad_arguments():
+    lib = pa.lib()
+    L = _layer()
+    pt = B._Patterns(FAKE.value, FAKE.value, FAKE.value, 1, 2, 1)
+
+    def call(mode=0, layer=L, pat=pt, X=FAKE, rows=8, off=FAKE, pid=FAKE, P=2, Y=FAKE, ws=FAKE, wsb=1 << 20):
+        return lib.parse_lowrank_forward(mode, C.byref(layer), C.byref(pat), X, rows, off, pid, P, Y, ws, wsb, None)
+
+    assert call(mode=3) == -1 and call(X=None) == -1 and call(Y=None) == -1 and call(pid=None) == -1
+    assert call(off=None) == -1 and call(rows=0) == -1
+    assert call(P=9) == -2 and call(X=ODD) == -3
+    assert call(ws=None) == -5 and call(wsb=8) == -5                     # fp32 prefill needs the Z workspace
+    assert call(pat=B._Patterns(FAKE.value, FAKE.value, FAKE.value, 3, 2, 3)) == -2   # k > G
+    assert call(layer=_layer(dtype=1, layout=0)) == -7                  # bf16 prefill needs operand order
+    assert call(mode=1) == -7                                           # decode is bf16 operand-order only
+    Lb = _layer(n=64, m=64, R=64, G=2, dtype=1, layout=1)
+    assert call(mode=1, layer=Lb, rows=40, P=40) == -2                  # more than 32 sequences
+    assert call(mode=1, layer=Lb, rows=8, P=4) == -2                    # decode: one row per sequence
+    assert lib.parse_lowrank_workspace_bytes(0, C.byref(L), 8, 1) >= 8 * 16 * 4

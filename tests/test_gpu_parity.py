@@ -1,0 +1,373 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle on the same seeded inputs.
+Indexing results must match bit for bit; products within the stated relative error
+(1e-4 fp32, 1e-2 bf16 inputs with fp32 accumulation), Frobenius-norm and max-norm."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import parse_oracle as po
+
+pytestmark = pytest.mark.gpu
+
+pa = pytest.importorskip("paper_2605_08568_amd")
+from helpers import i32, mfma16_u, mfma16_v, oracle_factors, upload_layer, upload_tokens  # noqa: E402
+
+TOL_F32, TOL_BF16 = 1e-4, 1e-2
+DEV = "cuda"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def assert_close(Y, Yref, tol, what):
+    fro, mx = po.rel_errors(Y, Yref)
+    say(f"    {what}: fro {fro:.2e} max {mx:.2e} (tol {tol:g})")
+    assert fro <= tol and mx <= tol, (what, fro, mx)
+
+
+# ------------------------------------------------------------------ a1 + a2 route
+@pytest.mark.parametrize("dtype,lengths,d,G,k", [
+    ("f32", [64, 64, 64, 64], 1024, 8, 4),
+    ("bf16", [1, 7, 300, 33, 2], 512, 16, 8),
+    ("f32", [1] * 9, 264, 20, 10),
+    ("bf16", [513, 40], 4096, 64, 1),
+])
+def test_route_matches_oracle(dtype, lengths, d, G, k):
+    say(f"route dtype={dtype} lengths={lengths} d={d} G={G} k={k}")
+    rng = np.random.default_rng(101)
+    off = si.offsets_from_lengths(lengths)
+    X = si.make_tokens(rng, int(off[-1]), d, dtype)
+    Wr = si.make_router(rng, 1, G, d)[0]
+    Xv = si.bf16_bits_to_f32(X).astype(np.float64) if dtype == "bf16" else X.astype(np.float64)
+    E = po.pool(Xv, off)
+    ref, margin = po.route(E, Wr, k)
+    S = po.route_scores(E, Wr)
+    assert np.all(margin > 1e-4 * np.abs(S).max()), "re-seed: a top-k decision is within rounding"
+    P = len(lengths)
+    scores = torch.empty((P, G), dtype=torch.float32, device=DEV)
+    emb = torch.empty((P, d), dtype=torch.float32, device=DEV)
+    sub = pa.route(upload_tokens(X, dtype), i32(off), torch.from_numpy(Wr).to(DEV), k, scores_out=scores, emb_out=emb)
+    torch.cuda.synchronize()
+    assert np.array_equal(sub.cpu().numpy(), ref)
+    assert np.allclose(emb.cpu().numpy(), E, rtol=1e-5, atol=1e-6)
+    assert np.allclose(scores.cpu().numpy(), S, rtol=1e-4, atol=1e-5)
+
+
+def test_route_strided_output_and_determinism():
+    say("route strided output / repeatability")
+    rng = np.random.default_rng(102)
+    off = si.offsets_from_lengths([50, 3, 120])
+    X = si.make_tokens(rng, int(off[-1]), 256, "bf16")
+    Wr = si.make_router(rng, 1, 12, 256)[0]
+    ref, _ = po.route(po.pool(si.bf16_bits_to_f32(X).astype(np.float64), off), Wr, 5)
+    out = torch.full((3, 3, 5), -7, dtype=torch.int32, device=DEV)
+    Xd, offd, Wd = upload_tokens(X, "bf16"), i32(off), torch.from_numpy(Wr).to(DEV)
+    pa.route(Xd, offd, Wd, 5, subset_out=out[:, 1, :], subset_stride=15)
+    e1 = torch.empty((3, 256), dtype=torch.float32, device=DEV); e2 = torch.empty_like(e1)
+    pa.route(Xd, offd, Wd, 5, emb_out=e1); pa.route(Xd, offd, Wd, 5, emb_out=e2)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert np.array_equal(o[:, 1, :], ref) and np.all(o[:, 0, :] == -7) and np.all(o[:, 2, :] == -7)
+    assert torch.equal(e1, e2)
+
+
+# ------------------------------------------------------------------ a3 cache
+def _cache_inputs(P, d, L, G, nclus, seed):
+    rng = np.random.default_rng(seed)
+    E, cid = si.clustered_embeddings(rng, P, d, nclus, 0.1)
+    Wr = si.make_router(rng, L, G, d)
+    return E, cid, Wr
+
+
+def _check_cache_batch(cache, oc, E, tau, Wr):
+    e_ref, h_ref, s_ref, sims_ref, rmargin = oc.lookup_or_route(E, tau, Wr, return_detail=True)
+    # decisions must not sit within rounding of the threshold or of a router tie
+    finite = np.isfinite(sims_ref)
+    assert np.all(np.abs(sims_ref[finite] - tau) > 1e-3), "re-seed: similarity within rounding of tau"
+    assert np.all(rmargin > 1e-5), "re-seed: router near-tie"
+    entry, hit, sim, subs = cache.lookup_or_route(torch.from_numpy(E).to(DEV), tau, torch.from_numpy(Wr).to(DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(entry.cpu().numpy(), e_ref)
+    assert np.array_equal(hit.cpu().numpy(), h_ref)
+    assert np.array_equal(subs.cpu().numpy(), s_ref)
+    assert np.allclose(sim.cpu().numpy()[finite], sims_ref[finite], atol=2e-5)
+    assert cache.count() == oc.count
+
+
+def test_cache_sequential_batches_match_oracle():
+    say("cache lookup_or_route, three batches, clustered embeddings")
+    P, d, L, G, k = 48, 512, 3, 20, 10
+    E, cid, Wr = _cache_inputs(3 * P, d, L, G, 7, 201)
+    cache = pa.Cache(64, d, L, k, P)
+    oc = po.PatternCache(64, d, L, k)
+    for b in range(3):
+        _check_cache_batch(cache, oc, E[b * P:(b + 1) * P], 0.9, Wr)
+    assert cache.count() == len(set(cid.tolist()))
+    # pure lookup afterwards: same answers as the oracle's, nothing inserted
+    q = np.concatenate([E[:5], -E[5:7]]).astype(np.float32)
+    ent_ref, sim_ref = oc.lookup(q, 0.9)
+    ent, sim, subs = cache.lookup(torch.from_numpy(q).to(DEV), 0.9)
+    torch.cuda.synchronize()
+    assert np.array_equal(ent.cpu().numpy(), ent_ref) and np.allclose(sim.cpu().numpy(), sim_ref, atol=2e-5)
+    for p in range(len(q)):
+        if ent_ref[p] >= 0:
+            assert np.array_equal(subs[p].cpu().numpy(), oc.values[ent_ref[p]])
+        else:
+            assert np.all(subs[p].cpu().numpy() == -1)          # untouched on a miss
+    assert cache.count() == oc.count
+    cache.close()
+
+
+def test_cache_empty_full_and_insert():
+    say("cache: empty lookup, explicit insert, capacity overflow")
+    d, L, G, k = 256, 2, 8, 3
+    E, cid, Wr = _cache_inputs(12, d, L, G, 12, 202)     # 12 distinct clusters -> all miss
+    cache = pa.Cache(4, d, L, k, 16)
+    oc = po.PatternCache(4, d, L, k)
+    ent, sim, _ = cache.lookup(torch.from_numpy(E[:3]).to(DEV), 0.9)
+    torch.cuda.synchronize()
+    assert ent.cpu().tolist() == [-1, -1, -1] and np.all(np.isneginf(sim.cpu().numpy()))
+    # explicit insert of entry 0, then a batch that overflows the capacity of 4
+    s0 = np.stack([po.route(E[0:1].astype(np.float64), Wr[l], k)[0][0] for l in range(L)])
+    cache.insert(torch.from_numpy(E[0]).to(DEV), i32(s0)); oc.insert(E[0], s0)
+    assert cache.count() == 1
+    _check_cache_batch(cache, oc, E, 0.9, Wr)
+    assert cache.count() == 4
+    with pytest.raises(pa.ParseError) as ei:
+        cache.insert(torch.from_numpy(E[5]).to(DEV), i32(s0))
+    assert ei.value.status == -4
+    cache.clear()
+    assert cache.count() == 0
+    cache.close()
+
+
+def test_cache_clustered_workload_hit_rate():
+    say("cache: 256 prompts, 16 clusters, d=4096, tau=0.9 -> 93.75 % hits")
+    E, cid, off, Wr = si.config4_embeddings()
+    cache = pa.Cache(1024, 4096, 3, 10, 256)
+    oc = po.PatternCache(1024, 4096, 3, 10)
+    _check_cache_batch(cache, oc, E, 0.9, Wr)
+    entry, hit, sim, subs = cache.lookup_or_route(torch.from_numpy(E).to(DEV), 0.9, torch.from_numpy(Wr).to(DEV))
+    torch.cuda.synchronize()
+    assert cache.count() == 16 and int(hit.sum().item()) == 256          # second pass: everything hits
+    cache.close()
+
+
+# ------------------------------------------------------------------ a5 bucket
+@pytest.mark.parametrize("P,k,npat,stride", [(32, 10, 4, 10), (256, 10, 16, 30), (1, 3, 1, 3), (1024, 2, 700, 2)])
+def test_bucket_matches_oracle(P, k, npat, stride):
+    say(f"bucket P={P} k={k} patterns<={npat} stride={stride}")
+    rng = np.random.default_rng(301)
+    pats = np.stack([np.sort(rng.choice(24, size=k, replace=False)) for _ in range(npat)]).astype(np.int32)
+    which = rng.integers(0, npat, size=P)
+    full = rng.integers(0, 24, size=(P, stride)).astype(np.int32)
+    full[:, :k] = pats[which]
+    pid_r, perm_r, off_r, n_r, rep_r = po.bucket(full[:, :k])
+    pid, perm, off, n, rep = pa.bucket_patterns(i32(full), k, stride)
+    torch.cuda.synchronize()
+    assert int(n.item()) == n_r
+    assert np.array_equal(pid.cpu().numpy(), pid_r) and np.array_equal(perm.cpu().numpy(), perm_r)
+    assert np.array_equal(off.cpu().numpy()[:n_r + 1], off_r) and np.all(off.cpu().numpy()[n_r + 1:] == P)
+    assert np.array_equal(rep.cpu().numpy()[:n_r], rep_r) and np.all(rep.cpu().numpy()[n_r:] == -1)
+
+
+# ------------------------------------------------------------------ a4 pack (+ offline reorder)
+@pytest.mark.parametrize("dtype,n,m,R,G,subset", [
+    ("f32", 1024, 1024, 256, 8, [1, 2, 5, 7]),
+    ("bf16", 512, 768, 256, 8, [0, 3, 4]),
+    ("bf16", 1032, 520, 96, 3, [2]),
+])
+def test_pack_rowmajor_bytes(dtype, n, m, R, G, subset):
+    say(f"pack row-major dtype={dtype} n={n} m={m} R={R} G={G} S={subset}")
+    lay = si.small_layer(401, n, m, R, G, dtype)
+    Vr, Ur = po.pack(lay.Vt_store, lay.Ut_store, subset, lay.gs)
+    Vs, Us = pa.pack_experts(upload_layer(lay), i32(subset))
+    torch.cuda.synchronize()
+    get = pa.bf16_to_bits if dtype == "bf16" else (lambda t: t.cpu().numpy())
+    assert get(Vs).tobytes() == Vr.tobytes() and get(Us).tobytes() == Ur.tobytes()
+
+
+def test_reorder_and_pack_in_operand_order():
+    say("offline reorder to operand order + pack of patterns, byte-exact through the documented index map")
+    lay = si.small_layer(402, 512, 768, 256, 8, "bf16")
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    torch.cuda.synchronize()
+    assert pa.bf16_to_bits(dl.Vt).tobytes() == mfma16_v(lay.Vt_store).tobytes()
+    assert pa.bf16_to_bits(dl.Ut).tobytes() == mfma16_u(lay.Ut_store).tobytes()
+    # patterns of a batch, packed without a host round trip: rows 0,1,3 are the representatives
+    subs = np.array([[0, 2, 7], [1, 2, 3], [0, 2, 7], [4, 5, 6]], np.int32)
+    pid, perm, off, npat, rep = pa.bucket_patterns(i32(subs), 3)
+    Vs, Us = pa.pack_patterns(dl, i32(subs), 3, 3, rep, npat, 4)
+    torch.cuda.synchronize()
+    for j, row in enumerate([0, 1, 3]):
+        Vr, Ur = po.pack(lay.Vt_store, lay.Ut_store, subs[row], lay.gs)
+        assert pa.bf16_to_bits(Vs[j]).tobytes() == mfma16_v(Vr).tobytes()
+        assert pa.bf16_to_bits(Us[j]).tobytes() == mfma16_u(Ur).tobytes()
+
+
+def test_pack_skips_invalid_group_ids():
+    say("pack: an id outside [0, G) leaves its slab untouched")
+    lay = si.small_layer(403, 256, 256, 64, 4, "f32")
+    dl = upload_layer(lay)
+    Vs = torch.full((32, 256), 9.0, device=DEV); Us = torch.full((32, 256), 9.0, device=DEV)
+    pa.pack_experts(dl, i32([1, 77]), Vs, Us)
+    torch.cuda.synchronize()
+    assert np.array_equal(Vs[:16].cpu().numpy(), lay.Vt_store[16:32]) and torch.all(Vs[16:] == 9.0)
+
+
+# ------------------------------------------------------------------ a6 prefill forward
+def _run_prefill(lay, lengths, subsets_per_prompt, seed, dtype):
+    rng = np.random.default_rng(seed)
+    off = si.offsets_from_lengths(lengths)
+    X = si.make_tokens(rng, int(off[-1]), lay.n, dtype)
+    Xv = si.bf16_bits_to_f32(X).astype(np.float64) if dtype == "bf16" else X.astype(np.float64)
+    U0, sg, V = oracle_factors(lay)
+    Yref = po.forward(U0, sg, V, lay.gs, Xv, off, subsets_per_prompt)
+    subs = np.asarray(subsets_per_prompt, np.int32)
+    k = subs.shape[1]
+    dl = upload_layer(lay)
+    if dtype == "bf16":
+        dl = pa.layer_to_mfma16(dl)
+    sd = i32(subs)
+    pid, perm, boff, npat, rep = pa.bucket_patterns(sd, k)
+    Vs, Us = pa.pack_patterns(dl, sd, k, k, rep, npat, len(lengths))
+    Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, len(lengths), Vs, Us), upload_tokens(X, dtype),
+                           i32(off), pid)
+    torch.cuda.synchronize()
+    Yg = Y.float().cpu().numpy().astype(np.float64)
+    return Yg, Yref, off
+
+
+def test_prefill_config0_fp32():
+    say("prefill config 0 (fp32, n=m=1024, R=256, 8 groups, top-4, 4 x 64 tokens), routed subsets")
+    w = si.config0()
+    lay = w.layers[0]
+    subs, margin = po.route(po.pool(w.X_values(), w.tok_offsets), w.Wr[0], w.k)
+    dl = upload_layer(lay)
+    sd = i32(subs)
+    pid, perm, boff, npat, rep = pa.bucket_patterns(sd, w.k)
+    Vs, Us = pa.pack_patterns(dl, sd, w.k, w.k, rep, npat, w.P)
+    Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us), upload_tokens(w.X, "f32"),
+                           i32(w.tok_offsets), pid)
+    torch.cuda.synchronize()
+    Yref = po.forward(lay.U0, lay.sigma, lay.V, lay.gs, w.X_values(), w.tok_offsets, subs)
+    for p in range(w.P):
+        a, b = w.tok_offsets[p], w.tok_offsets[p + 1]
+        assert_close(Y[a:b].cpu().numpy(), Yref[a:b], TOL_F32, f"prompt {p}")
+
+
+@pytest.mark.parametrize("n,m,R,G,k,lengths", [
+    (512, 768, 256, 8, 4, [70, 1, 33, 129, 64]),          # r_S = 128: one rank block per wave, ragged tiles
+    (1024, 1024, 512, 4, 3, [64, 200]),                   # r_S = 384: uneven rank blocks per wave
+    (528, 544, 160, 5, 2, [5, 90]),                       # n not a multiple of the staged tile, r_S = 64
+    (512, 512, 2560, 20, 10, [40, 100]),                  # r_S = 1280: 32-token workgroups
+])
+def test_prefill_bf16_small(n, m, R, G, k, lengths):
+    say(f"prefill bf16 n={n} m={m} R={R} G={G} k={k} lengths={lengths}")
+    if R > min(n, m):
+        lay = si.make_layer(np.random.default_rng(501), n, m, min(n, m), 1, "bf16")
+        # stored rank above min(n, m) cannot be orthonormal: tile independent blocks instead (values only matter
+        # through the stored arrays, which the oracle reads back)
+        reps = R // min(n, m)
+        lays = [si.make_layer(np.random.default_rng(510 + i), n, m, min(n, m), 1, "bf16") for i in range(reps)]
+        lay = si.Layer(n, m, R, G, "bf16", None, None, None,
+                       np.concatenate([l.Vt_store for l in lays]), np.concatenate([l.Ut_store for l in lays]))
+    else:
+        lay = si.small_layer(502, n, m, R, G, "bf16")
+    rng = np.random.default_rng(503)
+    subs = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in lengths]).astype(np.int32)
+    Yg, Yref, off = _run_prefill(lay, lengths, subs, 504, "bf16")
+    for p in range(len(lengths)):
+        assert_close(Yg[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"prompt {p}")
+
+
+def test_prefill_invalid_pattern_gives_zero_rows_and_is_repeatable():
+    say("prefill bf16: out-of-range pattern id -> zero rows; two runs give the same bits")
+    lay = si.small_layer(505, 256, 256, 128, 4, "bf16")
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    subs = i32([[0, 1], [2, 3]])
+    Vs, Us = pa.pack_patterns(dl, subs, 2, 2, None, None, 2)
+    X = upload_tokens(si.make_tokens(np.random.default_rng(1), 100, 256, "bf16"), "bf16")
+    off = i32([0, 30, 70, 100]); pid = i32([1, 5, 0])
+    pt = pa.Patterns(2, 2, Vs, Us)
+    Y1 = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid)
+    Y2 = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1.view(torch.int16), Y2.view(torch.int16))
+    assert torch.all(Y1[30:70] == 0) and torch.any(Y1[:30] != 0) and torch.any(Y1[70:] != 0)
+
+
+def test_prefill_config1_full_size_sampled():
+    say("prefill config 1 (bf16 4096x4096, R=2048, 16 groups, top-8, 8 x 512 tokens): sampled rows vs oracle")
+    w = si.config1()
+    lay = w.layers[0]
+    Xv = w.X_values()
+    subs, margin = po.route(po.pool(Xv, w.tok_offsets), w.Wr[0], w.k)
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    Xd, offd = upload_tokens(w.X, "bf16"), i32(w.tok_offsets)
+    sub_d = pa.route(Xd, offd, torch.from_numpy(w.Wr[0]).to(DEV), w.k)
+    pid, perm, boff, npat, rep = pa.bucket_patterns(sub_d, w.k)
+    Vs, Us = pa.pack_patterns(dl, sub_d, w.k, w.k, rep, npat, w.P)
+    Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us), Xd, offd, pid)
+    torch.cuda.synchronize()
+    assert np.all(margin > 1e-4) and np.array_equal(sub_d.cpu().numpy(), subs)
+    Vt, Ut = lay.stored_values()
+    rng = np.random.default_rng(7)
+    for p in range(w.P):
+        rows = po.group_rows(subs[p], lay.gs)
+        ts = w.tok_offsets[p] + np.concatenate([[0, 63, 64, 511], rng.integers(0, 512, size=4)])
+        Yref = (Xv[ts] @ Vt[rows].T) @ Ut[rows]           # Eq. 10 on the sampled rows, float64
+        assert_close(Y[torch.from_numpy(ts).to(DEV)].float().cpu().numpy(), Yref, TOL_BF16, f"prompt {p}")
+
+
+# ------------------------------------------------------------------ a7 decode
+@pytest.mark.parametrize("n,m,R,G,k,B,npat", [
+    (1024, 1536, 640, 20, 10, 32, 4),
+    (512, 256, 256, 8, 3, 5, 2),
+    (2752, 1024, 640, 20, 10, 32, 4),      # n/16 not divisible by the slice count
+])
+def test_decode_matches_oracle_and_prefill(n, m, R, G, k, B, npat):
+    say(f"decode n={n} m={m} R={R} G={G} k={k} B={B} patterns={npat}")
+    lay = si.small_layer(601, n, m, R, G, "bf16")
+    rng = np.random.default_rng(602)
+    pats = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(npat)]).astype(np.int32)
+    seq_pat = (np.arange(B) % npat).astype(np.int32)
+    x = si.make_tokens(rng, B, n, "bf16")
+    U0, sg, V = oracle_factors(lay)
+    Yref = po.decode_step(U0, sg, V, lay.gs, si.bf16_bits_to_f32(x).astype(np.float64), pats[seq_pat])
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    xd = upload_tokens(x, "bf16")
+    pt = pa.Patterns(k, npat, subsets=i32(pats))
+    y1 = pa.lowrank_forward(pa.PARSE_DECODE, dl, pt, xd, None, i32(seq_pat))
+    y2 = pa.lowrank_forward(pa.PARSE_DECODE, dl, pt, xd, None, i32(seq_pat))
+    torch.cuda.synchronize()
+    assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+    for b in range(B):
+        assert_close(y1[b:b + 1].float().cpu().numpy(), Yref[b:b + 1], TOL_BF16, f"sequence {b}")
+    # cross-kernel check: the prefill kernel on the same single rows and subsets
+    Vs, Us = pa.pack_patterns(dl, i32(pats), k, k, None, None, npat)
+    yp = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, npat, Vs, Us), xd, i32(np.arange(B + 1)), i32(seq_pat))
+    torch.cuda.synchronize()
+    assert_close(y1.float().cpu().numpy(), yp.float().cpu().numpy(), TOL_BF16, "decode vs prefill kernel")
+
+
+def test_decode_unselected_groups_are_not_needed():
+    say("decode: factors of groups nobody selected may hold anything (they are never read into the result)")
+    lay = si.small_layer(603, 512, 512, 256, 8, "bf16")
+    pats = np.array([[0, 3], [3, 6]], np.int32)
+    seq_pat = np.array([0, 1, 1, 0, 5], np.int32)             # sequence 4: invalid pattern -> zero row
+    x = si.make_tokens(np.random.default_rng(2), 5, 512, "bf16")
+    poisoned = si.Layer(lay.n, lay.m, lay.R, lay.G, "bf16", None, None, None, lay.Vt_store.copy(), lay.Ut_store.copy())
+    for g in (1, 2, 4, 5, 7):
+        poisoned.Vt_store[g * 32:(g + 1) * 32] = 0x7FC0        # NaN bit pattern
+        poisoned.Ut_store[g * 32:(g + 1) * 32] = 0x7FC0
+    outs = []
+    for l in (lay, poisoned):
+        dl = pa.layer_to_mfma16(upload_layer(l))
+        outs.append(pa.lowrank_forward(pa.PARSE_DECODE, dl, pa.Patterns(2, 2, subsets=i32(pats)),
+                                       upload_tokens(x, "bf16"), None, i32(seq_pat)))
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+    assert torch.all(outs[0][4] == 0) and torch.any(outs[0][0] != 0)
