@@ -1,0 +1,280 @@
+#!/usr/bin/env python3
+"""Benchmark of the routed low-rank linear hot path on ONE MI355X.
+
+A "step" is one pass of the whole prefill hot path over one batch of the q_proj-shaped workload
+(bf16, 4096x4096, stored rank 2048 in 16 groups of 128, top-8, 8 prompts x 512 tokens):
+  pool + route -> pattern-cache probe (route-on-miss) -> bucket -> pack (memory aggregation) -> fused forward.
+All inputs are resident in HBM before the timed region.  `value` is whole-step prefill throughput in
+TFLOP/s of algorithmic work 2*T*r_S*(n+m).  The `roofline` object prices the dominant kernel (the fused
+forward) against the bf16 matrix-core peak from HIP-event timings taken inside the timed region; the
+`decode` object reports the bandwidth-bound decode kernels on the MLP-shaped workload (32 sequences, 20
+groups of 128, top-10, 4 patterns) against the HBM peak; `cpu_baseline` is the CPU oracle timed on the host.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-decode] [--tokens T]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--tokens", type=int, default=512, help="tokens per prompt (512 = the named workload)")
+    ap.add_argument("--prompts", type=int, default=8)
+    ap.add_argument("--decode-steps", type=int, default=128)
+    ap.add_argument("--decode-copies", type=int, default=32, help="independent layer copies rotated per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--only-decode", action="store_true")
+    return ap.parse_args()
+
+
+def traffic_from_profiles(name):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE,
+    scaled by a copy kernel of known size); the figure is kept in profiles/traffic.json by hand after a
+    counter run, null until then."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(name)
+    except Exception:
+        return None
+
+
+def bench_prefill(args, torch, pa, si):
+    from helpers import i32, upload_layer, upload_tokens
+    dev = "cuda"
+    w = si.config1(P=args.prompts, T=args.tokens)
+    lay = w.layers[0]
+    k, P, n, m, gs = w.k, w.P, lay.n, lay.m, lay.gs
+    rS = k * gs
+    rows = int(w.tok_offsets[-1])
+    dl = pa.layer_to_mfma16(upload_layer(lay, dev))
+    X = upload_tokens(w.X, "bf16", dev)
+    off = i32(w.tok_offsets, dev)
+    Wr = torch.from_numpy(w.Wr).to(dev)                    # [1][G][d]
+    cache = pa.Cache(1024, w.d, 1, k, max(P, 8))
+    # every buffer of the step is allocated once, outside the timed region
+    emb = torch.empty((P, w.d), dtype=torch.float32, device=dev)
+    sub_route = torch.empty((P, k), dtype=torch.int32, device=dev)
+    ws_route = torch.empty(max(pa.route_workspace_bytes(rows, P, w.d), 256), dtype=torch.uint8, device=dev)
+    entry = torch.empty(P, dtype=torch.int32, device=dev)
+    hit = torch.empty(P, dtype=torch.uint8, device=dev)
+    sim = torch.empty(P, dtype=torch.float32, device=dev)
+    sub = torch.empty((P, 1, k), dtype=torch.int32, device=dev)
+    bucket_out = (torch.empty(P, dtype=torch.int32, device=dev), torch.empty(P, dtype=torch.int32, device=dev),
+                  torch.empty(P + 1, dtype=torch.int32, device=dev), torch.empty(1, dtype=torch.int32, device=dev),
+                  torch.empty(P, dtype=torch.int32, device=dev))
+    Vs = torch.empty((P, rS, n), dtype=torch.bfloat16, device=dev)
+    Us = torch.empty((P, rS, m), dtype=torch.bfloat16, device=dev)
+    Y = torch.empty((rows, m), dtype=torch.bfloat16, device=dev)
+    pt = pa.Patterns(k, P, Vs, Us)
+    names = ["route", "cache", "bucket", "pack", "forward"]
+
+    def step(ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        pa.route(X, off, Wr[0], k, subset_out=sub_route, emb_out=emb, workspace=ws_route)
+        mark(1)
+        cache.lookup_or_route(emb, 0.9, Wr, entry, hit, sim, sub)
+        mark(2)
+        pid, perm, boff, npat, rep = pa.bucket_patterns(sub, k, k, bucket_out)
+        mark(3)
+        pa.pack_patterns(dl, sub, k, k, rep, npat, P, Vs, Us)
+        mark(4)
+        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y)
+        mark(5)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall = t1 - t0
+    per = {nm: sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)) / args.steps * 1e3
+           for i, nm in enumerate(names)}                                  # microseconds
+    hits = int(hit.sum().item())
+    assert torch.equal(sub.view(P, k), sub_route), "cache answered with a subset that differs from the route"
+    flops = 2.0 * rows * rS * (n + m)
+    ms_per_step = wall / args.steps * 1e3
+    value = flops / (wall / args.steps) / 1e12
+    fwd_s = per["forward"] * 1e-6
+    achieved = flops / fwd_s / 1e12
+    cache.close()
+    res = {
+        "value": value, "ms_per_step": ms_per_step, "flops_per_step": flops,
+        "rows_us": {k_: round(v, 2) for k_, v in per.items()},
+        "cache_hits": hits,
+        "roofline": {"bound": "mfma", "kernel": "prefill_fused", "achieved": round(achieved, 2),
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": traffic_from_profiles("prefill_fused_config1"),
+                     "launch_us": round(per["forward"], 2)},
+        "workload": w,
+    }
+    return res
+
+
+def bench_decode(args, torch, pa, si):
+    """MLP-shaped decode: gate/up (4096->11008) and down (11008->4096), R=2560 in 20 groups, top-10, 32
+    sequences, 4 patterns.  `copies` independent layer triples are rotated so that every step streams cold
+    factors from HBM (one triple is about the size of the last-level cache).  Factor values are Gaussian
+    (their layout is irrelevant to timing); parity at these shapes is covered by the tests."""
+    import numpy as np
+    dev = "cuda"
+    B, G, k, R, hidden, inter = 32, 20, 10, 2560, 4096, 11008
+    gs = R // G
+    shapes = [("gate", hidden, inter), ("up", hidden, inter), ("down", inter, hidden)]
+    rng = np.random.default_rng(si.SEED_BASE + 2)
+    pats = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(4)]).astype(np.int32)
+    distinct = len(set(pats.reshape(-1).tolist()))
+    seq_pat = (np.arange(B) % 4).astype(np.int32)
+    subsets = torch.from_numpy(pats).to(dev)
+    pid = torch.from_numpy(seq_pat).to(dev)
+    copies = args.decode_copies
+    layers = []
+    for c in range(copies):
+        trip = []
+        for nm, n, m in shapes:
+            Vt = (torch.randn((R, n), device=dev) * 0.02).to(torch.bfloat16)
+            Ut = (torch.randn((R, m), device=dev) * 0.02).to(torch.bfloat16)
+            trip.append(pa.Layer(Vt, Ut, n, m, R, G, pa.PARSE_MFMA16))
+        layers.append(trip)
+    xs = {hidden: torch.randn((B, hidden), device=dev).to(torch.bfloat16),
+          inter: torch.randn((B, inter), device=dev).to(torch.bfloat16)}
+    ys = {hidden: torch.empty((B, hidden), dtype=torch.bfloat16, device=dev),
+          inter: torch.empty((B, inter), dtype=torch.bfloat16, device=dev)}
+    ws = torch.empty(max(pa.lowrank_workspace_bytes(pa.PARSE_DECODE, layers[0][0], B, k),
+                         pa.lowrank_workspace_bytes(pa.PARSE_DECODE, layers[0][2], B, k)), dtype=torch.uint8, device=dev)
+    pt = pa.Patterns(k, 4, subsets=subsets)
+
+    def step(s, ev=None):
+        trip = layers[s % copies]
+        for i, lay in enumerate(trip):
+            if ev is not None:
+                ev[i].record()
+            pa.lowrank_forward(pa.PARSE_DECODE, lay, pt, xs[lay.n], None, pid, ys[lay.m], ws)
+        if ev is not None:
+            ev[3].record()
+
+    for s in range(min(8, copies)):
+        step(s)
+    torch.cuda.synchronize()
+    steps = args.decode_steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        step(s, evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    out = {"workload": "config2: gate/up 4096->11008, down 11008->4096, R=2560, G=20, k=10, B=32, 4 patterns",
+           "steps": steps, "copies": copies, "distinct_groups": distinct,
+           "ms_per_step": round(wall / steps * 1e3, 4), "layers": {}}
+    tot_bytes, tot_us = 0.0, 0.0
+    for i, (nm, n, m) in enumerate(shapes):
+        us = sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(steps)) / steps * 1e3
+        nbytes = distinct * gs * (n + m) * 2 + B * (n + m) * 2
+        out["layers"][nm] = {"us": round(us, 2), "algorithmic_bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1)}
+        tot_bytes += nbytes; tot_us += us
+    ach = tot_bytes / tot_us / 1e3
+    out["roofline"] = {"bound": "hbm", "kernel": "decode_z + decode_zfin + decode_y (one layer call)",
+                       "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic_from_profiles("decode_config2")}
+    out["end_to_end_GBps"] = round(tot_bytes * steps / wall / 1e9, 1)
+    return out
+
+
+def cpu_baseline(w, flops):
+    """The CPU oracle as it stands, timed on the host cores on the same workload (bounded sample)."""
+    import numpy as np
+    from oracle import parse_oracle as po
+    from helpers import oracle_factors
+    lay = w.layers[0]
+    cores = len(os.sched_getaffinity(0))
+    Xv = w.X_values()
+    U0, sg, V = oracle_factors(lay)
+    # sample: as many whole prompts as fit in roughly 20 s, at least one
+    P_done, t0 = 0, time.perf_counter()
+    budget = 20.0
+    while P_done < w.P:
+        p = P_done
+        off = w.tok_offsets[p:p + 2] - w.tok_offsets[p]
+        a, b = int(w.tok_offsets[p]), int(w.tok_offsets[p + 1])
+        E = po.pool(Xv[a:b], off)
+        subs, _ = po.route(E, w.Wr[0], w.k)
+        po.pack(lay.Vt_store, lay.Ut_store, subs[0], lay.gs)
+        po.forward(U0, sg, V, lay.gs, Xv[a:b], off, subs)
+        P_done += 1
+        if time.perf_counter() - t0 > budget:
+            break
+    dt = time.perf_counter() - t0
+    frac = P_done / w.P
+    return {"value": round(flops * frac / dt / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"{P_done} of {w.P} prompts of the same workload (pool, route, pack, dense reconstruction and "
+                      f"apply in float64), {dt:.1f} s", "seconds": round(dt, 2)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the layer shards by prompts/"
+              "sequences with no exchange step); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2605_08568_amd as pa
+    import synth_inputs as si
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    dec = None
+    if args.only_decode:
+        print(json.dumps({"decode": bench_decode(args, torch, pa, si)}))
+        return
+    pre = bench_prefill(args, torch, pa, si)
+    w = pre.pop("workload")
+    if not args.no_decode:
+        dec = bench_decode(args, torch, pa, si)
+    base = None if args.no_cpu_baseline else cpu_baseline(w, pre["flops_per_step"])
+    lay = w.layers[0]
+    line = {
+        "metric": "routed low-rank linear: prefill TFLOP/s (%MFMA peak); decode GB/s (%HBM peak)",
+        "value": round(pre["value"], 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(pre["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config1: q_proj-shaped prefill, bf16, {lay.m}x{lay.n}, R={lay.R} in {lay.G} groups of "
+                               f"{lay.gs}, top-{w.k}, {w.P} prompts x {args.tokens} tokens, one routed subset per prompt",
+                   "step": "pool+route, cache probe, bucket, pack, fused forward"},
+        "roofline": pre["roofline"],
+        "cpu_baseline": base,
+        "rows_us": pre["rows_us"],
+        "cache_hits_last_step": pre["cache_hits"],
+        "decode": dec,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -10,7 +10,11 @@
 // Both products are computed transposed (factor = A operand with M = ranks / output columns, tokens = N)
 // so that the accumulator layout gives each lane 4 consecutive ranks (phase 1: one 8-byte LDS store) and
 // 4 consecutive output columns (phase 2: one 8-byte global store).
-// A 64-row block of the flat token axis that spans several prompts is processed once per prompt segment.
+// A BM-row block of the flat token axis that spans several prompts is processed once per prompt segment.
+//
+// The inner loops are branch-free: the number of 32-wide operand blocks a wavefront owns in a pass (NB) is a
+// template parameter, prefetches past the end are clamped to the last valid operand instead of being
+// predicated, and shapes that do not fill whole staged tiles take a separate, simpler kernel.
 #include "common.hpp"
 
 namespace parse {
@@ -19,215 +23,342 @@ constexpr int PF_THREADS = 256;
 constexpr int PF_BK = 64;            // reduction indices per staged X tile (4 matrix instructions deep)
 constexpr int PF_XPAD = 8;           // bf16 of padding per LDS row: keeps 16-byte operand reads conflict-free
 constexpr int PF_ZPAD = 8;
+constexpr int PF_DEPTH = 8;          // reduction steps of factor operands in flight per wavefront
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+// two floats -> packed bfloat16 pair, round to nearest even (hardware conversion)
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
+}
+
+// Workgroup ids are dealt round-robin over the 8 accelerator dies (XCDs), each with its own L2.  Token tiles
+// are renumbered so that the tiles one die works on are consecutive: tiles of one prompt share a pattern, so
+// they stream the same packed factors and hit in that die's L2 instead of each die fetching every pattern.
+__device__ __forceinline__ int xcd_tile(int b, int nb) {
+  const int per = nb / 8, rem = nb % 8, x = b % 8, i = b / 8;
+  return x * per + min(x, rem) + i;
+}
+
+struct PfArgs {
+  const uint16_t *X, *Vt_S, *Ut_S;
+  uint16_t *Y;
+  const int32_t *tok_offsets, *pattern_id;
+  int n_patterns, rows, n, m, rS, P;
+};
+
+// ---------------------------------------------------------------------------------------------------------
+// phase 1, one pass: this wavefront's NB rank blocks (first one rb0, then every 4th) x all BM tokens.
+// Requires n % (2*PF_BK) == 0.
+template <int BM, int NB>
+__device__ __forceinline__ void phase1_pass(const PfArgs &a, const uint16_t *Vp, int row0, int rb0, uint16_t *Zs,
+                                            int zld, uint16_t *Xs) {
+  constexpr int NT = BM / 32;
+  constexpr int XP = BM * PF_BK / 8 / PF_THREADS;
+  constexpr int xld = PF_BK + PF_XPAD;
+  const int lane = threadIdx.x & 63, l32 = lane & 31, q = lane >> 5;
+  const int n = a.n, nkb = n / 16, nkt = n / PF_BK;
+  f32x16 acc[NT][NB];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
+  const uint16_t *vbase[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i) vbase[i] = Vp + ((size_t)(rb0 + 4 * i) * nkb * 64 + lane) * 8;
+  // X tile pieces of this lane: piece = i*256 + tid -> row piece/8, column (piece%8)*8
+  const uint16_t *xsrc[XP];
+  int xdst[XP];
+#pragma unroll
+  for (int i = 0; i < XP; ++i) {
+    const int piece = i * PF_THREADS + threadIdx.x;
+    const int r = piece / (PF_BK / 8), c = (piece % (PF_BK / 8)) * 8;
+    xsrc[i] = a.X + (size_t)min(row0 + r, a.rows - 1) * n + c;
+    xdst[i] = r * xld + c;
+  }
+  const int xoff = l32 * xld + q * 8;   // operand read: token l32 (+32 t), reduction offset 16 s + 8 q
+  u32x4 xr[2][XP];
+  u32x4 vr[PF_DEPTH][NB];
+  __syncthreads();  // earlier readers of Xs / Zs are done
+#pragma unroll
+  for (int i = 0; i < XP; ++i) xr[0][i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
+#pragma unroll
+  for (int d = 0; d < PF_DEPTH; ++d)
+#pragma unroll
+    for (int i = 0; i < NB; ++i) vr[d][i] = *reinterpret_cast<const u32x4 *>(vbase[i] + (size_t)d * 512);
+#pragma unroll
+  for (int i = 0; i < XP; ++i) xr[1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + PF_BK);
+#pragma unroll
+  for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(Xs + xdst[i]) = xr[0][i];
+  __syncthreads();
+  for (int kt0 = 0; kt0 < nkt; kt0 += 2) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int kt = kt0 + u;   // LDS buffer = u (kt0 is even)
+      // tile kt+2 replaces tile kt in the register ring (tile kt went to LDS one iteration ago)
+      const int ktn = min(kt + 2, nkt - 1);
+#pragma unroll
+      for (int i = 0; i < XP; ++i) xr[u][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)ktn * PF_BK);
+      bf16x8 xb[2][NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        xb[0][t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + u * BM * xld + t * 32 * xld + xoff));
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (s < 3) {
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            xb[(s + 1) & 1][t] =
+                as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + u * BM * xld + t * 32 * xld + xoff + (s + 1) * 16));
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the next step's LDS reads ahead of this step's matrix work
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vr[u * 4 + s][i]), xb[s & 1][t], acc[t][i], 0, 0, 0);
+        // the slot just consumed is refilled with the operands PF_DEPTH steps ahead
+        const int kbn = min(kt * 4 + s + PF_DEPTH, nkb - 1);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) vr[u * 4 + s][i] = *reinterpret_cast<const u32x4 *>(vbase[i] + (size_t)kbn * 512);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(Xs + (u ^ 1) * BM * xld + xdst[i]) = xr[u ^ 1][i];
+      __syncthreads();
+    }
+  }
+  // accumulators -> bf16 -> Z block.  lane holds token l32 of block t, ranks rb*32 + 8*blk + 4*q + (0..3)
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk) {
+        u32x2 w;
+        w[0] = cvt_pk_bf16(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]);
+        w[1] = cvt_pk_bf16(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]);
+        *reinterpret_cast<u32x2 *>(Zs + (size_t)(t * 32 + l32) * zld + (rb0 + 4 * i) * 32 + blk * 8 + q * 4) = w;
+      }
+}
+
+// phase 2, one pass: NB consecutive 32-column blocks starting at cb0 x all BM tokens; reduction over r_S.
+// Requires rS % (16*PF_DEPTH) == 0.
+template <int BM, int NB>
+__device__ __forceinline__ void phase2_pass(const PfArgs &a, const uint16_t *Up, bool valid, int row0, int seg_lo,
+                                            int seg_hi, int cb0, const uint16_t *Zs, int zld) {
+  constexpr int NT = BM / 32;
+  const int lane = threadIdx.x & 63, l32 = lane & 31, q = lane >> 5;
+  const int m = a.m, ncb = m / 32, nk2 = a.rS / 16;
+  f32x16 acc[NT][NB];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
+  const uint16_t *ubase = Up + ((size_t)cb0 * 64 + lane) * 8;   // + kb * ncb * 512 + i * 512
+  const size_t kstride = (size_t)ncb * 512;
+  const int zoff = l32 * zld + q * 8;
+  u32x4 ua[PF_DEPTH][NB];
+#pragma unroll
+  for (int d = 0; d < PF_DEPTH; ++d)
+#pragma unroll
+    for (int i = 0; i < NB; ++i) ua[d][i] = *reinterpret_cast<const u32x4 *>(ubase + d * kstride + i * 512);
+  bf16x8 zb[2][NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) zb[0][t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(Zs + t * 32 * zld + zoff));
+  for (int kb0 = 0; kb0 < nk2; kb0 += PF_DEPTH) {
+#pragma unroll
+    for (int d = 0; d < PF_DEPTH; ++d) {
+      const int kb = kb0 + d;
+      const int kbz = min(kb + 1, nk2 - 1);
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        zb[(d + 1) & 1][t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(Zs + t * 32 * zld + zoff + kbz * 16));
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ua[d][i]), zb[d & 1][t], acc[t][i], 0, 0, 0);
+      const int kbn = min(kb + PF_DEPTH, nk2 - 1);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) ua[d][i] = *reinterpret_cast<const u32x4 *>(ubase + kbn * kstride + i * 512);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  // store: lane holds token t*32 + l32, columns (cb0+i)*32 + 8*blk + 4*q + (0..3)
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int r = row0 + t * 32 + l32;
+    if (r < seg_lo || r >= seg_hi) continue;
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk) {
+        u32x2 w;
+        w[0] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]) : 0u;
+        w[1] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]) : 0u;
+        *reinterpret_cast<u32x2 *>(a.Y + (size_t)r * m + (cb0 + i) * 32 + blk * 8 + q * 4) = w;
+      }
+  }
+}
 
 template <int BM>
-__global__ __launch_bounds__(PF_THREADS) void prefill_fused(
-    const uint16_t *__restrict__ X, const uint16_t *__restrict__ Vt_S, const uint16_t *__restrict__ Ut_S,
-    int n_patterns, int rows, int n, int m, int rS, const int32_t *__restrict__ tok_offsets,
-    const int32_t *__restrict__ pattern_id, int P, uint16_t *__restrict__ Y) {
-  constexpr int NT = BM / 32;  // 32-token blocks per workgroup
+__global__ __launch_bounds__(PF_THREADS) void prefill_fused(PfArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-  const int zld = rS + PF_ZPAD;
+  const int zld = a.rS + PF_ZPAD;
   constexpr int xld = PF_BK + PF_XPAD;
   uint16_t *Zs = lds;                          // [BM][zld]
   uint16_t *Xs = lds + (size_t)BM * zld;       // [2][BM][xld]
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l32 = lane & 31, q = lane >> 5;
-  const int row0 = blockIdx.x * BM;
-  const int row_end = min(row0 + BM, rows);
-  const int nkb = n / 16;      // 16-wide reduction blocks of phase 1
-  const int nrb = rS / 32;     // 32-rank blocks
-  const int ncb = m / 32;      // 32-column blocks of the output
-  const int nkt = (n + PF_BK - 1) / PF_BK;
-
+  const int wave = threadIdx.x >> 6;
+  const int row0 = xcd_tile(blockIdx.x, gridDim.x) * BM;
+  const int row_end = min(row0 + BM, a.rows);
+  const int nrb = a.rS / 32, ncb = a.m / 32;
   int seg_lo = row0;
   while (seg_lo < row_end) {
-    const int p = prompt_of_row(tok_offsets, P, seg_lo);
-    int seg_hi = (p + 1 < P) ? tok_offsets[p + 1] : rows;
+    const int p = prompt_of_row(a.tok_offsets, a.P, seg_lo);
+    int seg_hi = (p + 1 < a.P) ? a.tok_offsets[p + 1] : a.rows;
     seg_hi = min(max(seg_hi, seg_lo + 1), row_end);
-    const int pid = pattern_id[p];
-    const bool valid = pid >= 0 && pid < n_patterns;
-    const uint16_t *Vp = Vt_S + (valid ? (size_t)pid * rS * n : 0);
-    const uint16_t *Up = Ut_S + (valid ? (size_t)pid * rS * m : 0);
+    const int pid = a.pattern_id[p];
+    const bool valid = pid >= 0 && pid < a.n_patterns;
+    const uint16_t *Vp = a.Vt_S + (valid ? (size_t)pid * a.rS * a.n : 0);
+    const uint16_t *Up = a.Ut_S + (valid ? (size_t)pid * a.rS * a.m : 0);
 
-    // ------------------------------------------------------------ phase 1: Z = X Vt_S^T  -> LDS
-    // wave w owns rank blocks w, w+4, w+8, ...; a pass handles up to 4 of them
-    const int my_nrb = (nrb - wave + 3) / 4;
+    // phase 1: wave w owns rank blocks w, w+4, ...; a pass takes up to 4 of them (all waves run every pass:
+    // the staged X tile is shared and the barriers are collective; a wave with nothing left recomputes its
+    // last block, which rewrites the same Z values)
+    const int my_nrb = max(1, (nrb - wave + 3) / 4);
     const int passes1 = (nrb + 15) / 16;
     for (int pass = 0; pass < passes1; ++pass) {
-      const int nb = max(0, min(4, my_nrb - pass * 4));
-      f32x16 acc[NT][4];
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
-      // operand base of this wave's i-th rank block: rb = (pass*4 + i)*4 + wave
-      const uint16_t *vbase[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int rb = min((pass * 4 + i) * 4 + wave, nrb - 1);
-        vbase[i] = Vp + ((size_t)rb * nkb * 64 + lane) * 8;
+      int first = pass * 4;                       // index into this wave's own list of rank blocks
+      int nb = min(4, my_nrb - first);
+      if (nb <= 0) { first = my_nrb - 1; nb = 1; }
+      const int rb0 = min(first * 4 + wave, nrb - 1);
+      switch (nb) {
+        case 4: phase1_pass<BM, 4>(a, Vp, row0, rb0, Zs, zld, Xs); break;
+        case 3: phase1_pass<BM, 3>(a, Vp, row0, rb0, Zs, zld, Xs); break;
+        case 2: phase1_pass<BM, 2>(a, Vp, row0, rb0, Zs, zld, Xs); break;
+        default: phase1_pass<BM, 1>(a, Vp, row0, rb0, Zs, zld, Xs); break;
       }
-      __syncthreads();  // previous users of Xs (and of Zs in an earlier segment) are done
-      // stage X tile 0
-      auto load_x = [&](int kt, u32x4 *regs) {
-#pragma unroll
-        for (int i = 0; i < BM * PF_BK / 8 / PF_THREADS; ++i) {
-          const int piece = i * PF_THREADS + threadIdx.x;  // 16-byte piece of the BM x 64 tile
-          const int r = piece / (PF_BK / 8), c = (piece % (PF_BK / 8)) * 8;
-          const int gr = min(row0 + r, rows - 1);
-          const int gc = kt * PF_BK + c;
-          regs[i] = (gc < n) ? *reinterpret_cast<const u32x4 *>(X + (size_t)gr * n + gc) : u32x4{0, 0, 0, 0};
-        }
-      };
-      auto store_x = [&](int buf, const u32x4 *regs) {
-#pragma unroll
-        for (int i = 0; i < BM * PF_BK / 8 / PF_THREADS; ++i) {
-          const int piece = i * PF_THREADS + threadIdx.x;
-          const int r = piece / (PF_BK / 8), c = (piece % (PF_BK / 8)) * 8;
-          *reinterpret_cast<u32x4 *>(Xs + ((size_t)buf * BM + r) * xld + c) = regs[i];
-        }
-      };
-      auto load_v = [&](int kt, u32x4 (*regs)[4]) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const int kb = min(kt * 4 + s, nkb - 1);
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (i < nb) regs[s][i] = *reinterpret_cast<const u32x4 *>(vbase[i] + (size_t)kb * 512);
-        }
-      };
-      u32x4 xr[BM * PF_BK / 8 / PF_THREADS];
-      u32x4 va[4][4], vb[4][4];
-      load_x(0, xr);
-      load_v(0, va);
-      store_x(0, xr);
-      __syncthreads();
-      for (int kt = 0; kt < nkt; ++kt) {
-        const int buf = kt & 1;
-        const bool more = kt + 1 < nkt;
-        if (more) {
-          load_x(kt + 1, xr);
-          load_v(kt + 1, vb);
-        }
-        const int ksteps = min(4, nkb - kt * 4);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          if (s < ksteps) {
-            bf16x8 xb[NT];
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-              xb[t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + ((size_t)buf * BM + t * 32 + l32) * xld + s * 16 + q * 8));
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (i < nb) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                  acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[s][i]), xb[t], acc[t][i], 0, 0, 0);
-              }
-          }
-        }
-        if (more) {
-          store_x(buf ^ 1, xr);
-#pragma unroll
-          for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) va[s][i] = vb[s][i];
-        }
-        __syncthreads();
-      }
-      // accumulators -> bf16 -> Z block.  lane holds token l32 of block t, ranks rb*32 + 8*blk + 4*q + (0..3)
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (i < nb) {
-          const int rb = (pass * 4 + i) * 4 + wave;
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int blk = 0; blk < 4; ++blk) {
-              u32x2 w;
-              w[0] = pack_bf16x2(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]);
-              w[1] = pack_bf16x2(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]);
-              *reinterpret_cast<u32x2 *>(Zs + (size_t)(t * 32 + l32) * zld + rb * 32 + blk * 8 + q * 4) = w;
-            }
-        }
     }
     __syncthreads();  // Z block complete
 
-    // ------------------------------------------------------------ phase 2: Y = Z Ut_S
-    const int nk2 = rS / 16;
+    // phase 2: a pass covers 16 column blocks, 4 consecutive ones per wave
     const int passes2 = (ncb + 15) / 16;
     for (int pass = 0; pass < passes2; ++pass) {
       const int cb0 = pass * 16 + wave * 4;
-      const int nb = max(0, min(4, ncb - cb0));
-      if (nb == 0) continue;   // no barriers below: a wave may skip
-      f32x16 acc[NT][4];
+      const int nb = min(4, ncb - cb0);
+      switch (nb) {
+        case 4: phase2_pass<BM, 4>(a, Up, valid, row0, seg_lo, seg_hi, cb0, Zs, zld); break;
+        case 3: phase2_pass<BM, 3>(a, Up, valid, row0, seg_lo, seg_hi, cb0, Zs, zld); break;
+        case 2: phase2_pass<BM, 2>(a, Up, valid, row0, seg_lo, seg_hi, cb0, Zs, zld); break;
+        case 1: phase2_pass<BM, 1>(a, Up, valid, row0, seg_lo, seg_hi, cb0, Zs, zld); break;
+        default: break;
+      }
+    }
+    seg_lo = seg_hi;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Any shape the operand order allows (n % 16 == 0, r_S % 32 == 0, m % 32 == 0): same data flow, one matrix
+// instruction deep, predicated.  Used when n is not a multiple of 128 or r_S not a multiple of 128.
+template <int BM>
+__global__ __launch_bounds__(PF_THREADS) void prefill_fused_any(PfArgs a) {
+  constexpr int NT = BM / 32;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  const int zld = a.rS + PF_ZPAD;
+  constexpr int xld = PF_BK + PF_XPAD;
+  uint16_t *Zs = lds;
+  uint16_t *Xs = lds + (size_t)BM * zld;       // one buffer is enough here
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, q = lane >> 5;
+  const int n = a.n, m = a.m, rS = a.rS;
+  const int row0 = xcd_tile(blockIdx.x, gridDim.x) * BM;
+  const int row_end = min(row0 + BM, a.rows);
+  const int nkb = n / 16, nrb = rS / 32, ncb = m / 32, nk2 = rS / 16;
+  int seg_lo = row0;
+  while (seg_lo < row_end) {
+    const int p = prompt_of_row(a.tok_offsets, a.P, seg_lo);
+    int seg_hi = (p + 1 < a.P) ? a.tok_offsets[p + 1] : a.rows;
+    seg_hi = min(max(seg_hi, seg_lo + 1), row_end);
+    const int pid = a.pattern_id[p];
+    const bool valid = pid >= 0 && pid < a.n_patterns;
+    const uint16_t *Vp = a.Vt_S + (valid ? (size_t)pid * rS * n : 0);
+    const uint16_t *Up = a.Ut_S + (valid ? (size_t)pid * rS * m : 0);
+    // phase 1: a round handles rank blocks rbase + wave
+    for (int rbase = 0; rbase < nrb; rbase += 4) {
+      const int rb = min(rbase + wave, nrb - 1);
+      f32x16 acc[NT];
 #pragma unroll
       for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+      for (int k0 = 0; k0 < n; k0 += PF_BK) {
+        __syncthreads();
+        for (int piece = threadIdx.x; piece < BM * PF_BK / 8; piece += PF_THREADS) {
+          const int r = piece / (PF_BK / 8), c = (piece % (PF_BK / 8)) * 8;
+          const int gr = min(row0 + r, a.rows - 1), gc = k0 + c;
+          const u32x4 v = (gc < n) ? *reinterpret_cast<const u32x4 *>(a.X + (size_t)gr * n + gc) : u32x4{0, 0, 0, 0};
+          *reinterpret_cast<u32x4 *>(Xs + r * xld + c) = v;
+        }
+        __syncthreads();
+        const int steps = min(4, (n - k0) / 16);
+        for (int s = 0; s < steps; ++s) {
+          const int kb = k0 / 16 + s;
+          const bf16x8 va = as_bf16x8(*reinterpret_cast<const u32x4 *>(Vp + (((size_t)rb * nkb + kb) * 64 + lane) * 8));
 #pragma unroll
-          for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
-      const uint16_t *ubase = Up + ((size_t)cb0 * 64 + lane) * 8;   // + kb * ncb * 512 + i * 512
-      auto load_u = [&](int kb, u32x4 *regs) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (i < nb) regs[i] = *reinterpret_cast<const u32x4 *>(ubase + ((size_t)kb * ncb + i) * 512);
-      };
-      constexpr int DEPTH = 4;
-      u32x4 ua[DEPTH][4];
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) load_u(min(d, nk2 - 1), ua[d]);
-      for (int kb0 = 0; kb0 < nk2; kb0 += DEPTH) {
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d) {
-          const int kb = kb0 + d;
-          if (kb < nk2) {
-            bf16x8 zb[NT];
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-              zb[t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(Zs + (size_t)(t * 32 + l32) * zld + kb * 16 + q * 8));
-            u32x4 cur[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) cur[i] = ua[d][i];
-            load_u(min(kb + DEPTH, nk2 - 1), ua[d]);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (i < nb) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                  acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(cur[i]), zb[t], acc[t][i], 0, 0, 0);
-              }
+          for (int t = 0; t < NT; ++t) {
+            const bf16x8 xb = as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + (t * 32 + l32) * xld + s * 16 + q * 8));
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, xb, acc[t], 0, 0, 0);
           }
         }
       }
-      // store: lane holds token t*32 + l32, columns (cb0+i)*32 + 8*blk + 4*q + (0..3)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk) {
+          u32x2 w;
+          w[0] = cvt_pk_bf16(acc[t][blk * 4 + 0], acc[t][blk * 4 + 1]);
+          w[1] = cvt_pk_bf16(acc[t][blk * 4 + 2], acc[t][blk * 4 + 3]);
+          *reinterpret_cast<u32x2 *>(Zs + (size_t)(t * 32 + l32) * zld + rb * 32 + blk * 8 + q * 4) = w;
+        }
+    }
+    __syncthreads();
+    // phase 2
+    for (int cb = wave; cb < ncb; cb += 4) {
+      f32x16 acc[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+      for (int kb = 0; kb < nk2; ++kb) {
+        const bf16x8 ua = as_bf16x8(*reinterpret_cast<const u32x4 *>(Up + (((size_t)kb * ncb + cb) * 64 + lane) * 8));
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const bf16x8 zb = as_bf16x8(*reinterpret_cast<const u32x4 *>(Zs + (size_t)(t * 32 + l32) * zld + kb * 16 + q * 8));
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua, zb, acc[t], 0, 0, 0);
+        }
+      }
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int r = row0 + t * 32 + l32;
         if (r < seg_lo || r >= seg_hi) continue;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (i < nb) {
-#pragma unroll
-            for (int blk = 0; blk < 4; ++blk) {
-              u32x2 w;
-              if (valid) {
-                w[0] = pack_bf16x2(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]);
-                w[1] = pack_bf16x2(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]);
-              } else {
-                w[0] = 0; w[1] = 0;
-              }
-              *reinterpret_cast<u32x2 *>(Y + (size_t)r * m + (cb0 + i) * 32 + blk * 8 + q * 4) = w;
-            }
-          }
+        for (int blk = 0; blk < 4; ++blk) {
+          u32x2 w;
+          w[0] = valid ? cvt_pk_bf16(acc[t][blk * 4 + 0], acc[t][blk * 4 + 1]) : 0u;
+          w[1] = valid ? cvt_pk_bf16(acc[t][blk * 4 + 2], acc[t][blk * 4 + 3]) : 0u;
+          *reinterpret_cast<u32x2 *>(a.Y + (size_t)r * m + cb * 32 + blk * 8 + q * 4) = w;
+        }
       }
     }
+    __syncthreads();   // Zs is rewritten by the next segment
     seg_lo = seg_hi;
   }
 }
@@ -238,6 +369,17 @@ size_t prefill_lds_bytes(int BM, int rS) {
 
 constexpr size_t kLdsLimit = 160 * 1024;
 
+template <typename K>
+static int launch_prefill(K kernel, bool *attr_done, const PfArgs &a, int BM, size_t lds, hipStream_t s) {
+  if (!*attr_done) {
+    PARSE_HIP_TRY(hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit));
+    *attr_done = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3((a.rows + BM - 1) / BM), dim3(PF_THREADS), lds, s, a);
+  PARSE_LAUNCH_CHECK();
+  return PARSE_OK;
+}
+
 int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *X, int rows,
                          const int32_t *tok_offsets, const int32_t *pattern_id, int P, uint16_t *Y, hipStream_t s) {
   const int gs = L->R / L->G, rS = pt->k * gs;
@@ -245,28 +387,16 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
   if (prefill_lds_bytes(64, rS) > kLdsLimit) BM = 32;
   const size_t lds = prefill_lds_bytes(BM, rS);
   if (lds > kLdsLimit) return PARSE_ESHAPE;
-  const dim3 grid((rows + BM - 1) / BM);
-  if (BM == 64) {
-    static bool attr64 = false;
-    if (!attr64) {
-      PARSE_HIP_TRY(hipFuncSetAttribute((const void *)prefill_fused<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)kLdsLimit));
-      attr64 = true;
-    }
-    hipLaunchKernelGGL(prefill_fused<64>, grid, dim3(PF_THREADS), lds, s, X, (const uint16_t *)pt->Vt_S,
-                       (const uint16_t *)pt->Ut_S, pt->n_patterns, rows, L->n, L->m, rS, tok_offsets, pattern_id, P, Y);
-  } else {
-    static bool attr32 = false;
-    if (!attr32) {
-      PARSE_HIP_TRY(hipFuncSetAttribute((const void *)prefill_fused<32>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)kLdsLimit));
-      attr32 = true;
-    }
-    hipLaunchKernelGGL(prefill_fused<32>, grid, dim3(PF_THREADS), lds, s, X, (const uint16_t *)pt->Vt_S,
-                       (const uint16_t *)pt->Ut_S, pt->n_patterns, rows, L->n, L->m, rS, tok_offsets, pattern_id, P, Y);
+  PfArgs a{X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, Y, tok_offsets, pattern_id,
+           pt->n_patterns, rows, L->n, L->m, rS, P};
+  const bool fast = (L->n % (2 * PF_BK) == 0) && (rS % (16 * PF_DEPTH) == 0) && (L->n / 16 >= PF_DEPTH);
+  static bool done[4] = {false, false, false, false};
+  if (fast) {
+    if (BM == 64) return launch_prefill(prefill_fused<64>, &done[0], a, 64, lds, s);
+    return launch_prefill(prefill_fused<32>, &done[1], a, 32, lds, s);
   }
-  PARSE_LAUNCH_CHECK();
-  return PARSE_OK;
+  if (BM == 64) return launch_prefill(prefill_fused_any<64>, &done[2], a, 64, lds, s);
+  return launch_prefill(prefill_fused_any<32>, &done[3], a, 32, lds, s);
 }
 
 }  // namespace parse
