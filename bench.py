@@ -83,6 +83,7 @@ def bench_prefill(args, torch, pa, si):
     Vs = torch.empty((P, rS, n), dtype=torch.bfloat16, device=dev)
     Us = torch.empty((P, rS, m), dtype=torch.bfloat16, device=dev)
     Y = torch.empty((rows, m), dtype=torch.bfloat16, device=dev)
+    ws_fwd = torch.empty(max(pa.lowrank_workspace_bytes(pa.PARSE_PREFILL, dl, rows, k), 256), dtype=torch.uint8, device=dev)
     pt = pa.Patterns(k, P, Vs, Us)
     names = ["route", "cache", "bucket", "pack", "forward"]
 
@@ -99,7 +100,7 @@ def bench_prefill(args, torch, pa, si):
         mark(3)
         pa.pack_patterns(dl, sub, k, k, rep, npat, P, Vs, Us)
         mark(4)
-        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y)
+        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y, ws_fwd)
         mark(5)
 
     for _ in range(args.warmup):
@@ -116,6 +117,20 @@ def bench_prefill(args, torch, pa, si):
     per = {nm: sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)) / args.steps * 1e3
            for i, nm in enumerate(names)}                                  # microseconds
     hits = int(hit.sum().item())
+    # the same forward under each fixed schedule, for the record (not part of the timed steps above)
+    sched_us = {}
+    pid = bucket_out[0]
+    for nm, code in (("fused", 1), ("two_launch", 2)):
+        pa.set_prefill_schedule(code)
+        for _ in range(3):
+            pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y, ws_fwd)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y, ws_fwd)
+        e1.record(); torch.cuda.synchronize()
+        sched_us[nm] = round(e0.elapsed_time(e1) / 20 * 1e3, 2)
+    pa.set_prefill_schedule(0)
     assert torch.equal(sub.view(P, k), sub_route), "cache answered with a subset that differs from the route"
     flops = 2.0 * rows * rS * (n + m)
     ms_per_step = wall / args.steps * 1e3
@@ -126,8 +141,8 @@ def bench_prefill(args, torch, pa, si):
     res = {
         "value": value, "ms_per_step": ms_per_step, "flops_per_step": flops,
         "rows_us": {k_: round(v, 2) for k_, v in per.items()},
-        "cache_hits": hits,
-        "roofline": {"bound": "mfma", "kernel": "prefill_fused", "achieved": round(achieved, 2),
+        "cache_hits": hits, "forward_us_by_schedule": sched_us,
+        "roofline": {"bound": "mfma", "kernel": "gemm_tokens x2 (two-launch schedule)" if sched_us["two_launch"] <= sched_us["fused"] else "prefill_fused", "achieved": round(achieved, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": traffic_from_profiles("prefill_fused_config1"),
                      "launch_us": round(per["forward"], 2)},
@@ -271,6 +286,7 @@ def main():
         "cpu_baseline": base,
         "rows_us": pre["rows_us"],
         "cache_hits_last_step": pre["cache_hits"],
+        "forward_us_by_schedule": pre["forward_us_by_schedule"],
         "decode": dec,
     }
     print(json.dumps(line))

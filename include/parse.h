@@ -197,10 +197,18 @@ typedef enum { PARSE_PREFILL = 0, PARSE_DECODE = 1 } parse_mode;
 
 size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *layer, int32_t rows,
                                      int32_t k);
+/* How the bf16 prefill product is scheduled: 0 = chosen from the batch size (default), 1 = always the fused
+ * kernel, 2 = always two launches (PARSE_EWORKSPACE from the forward call if it got no workspace).
+ * Process-wide; not thread-safe against concurrent forward calls. */
+int parse_set_prefill_schedule(int32_t schedule);
 /* PARSE_PREFILL  Y[t] = A_S (B_S^T x_t) for every token t of prompt p, S = pattern pattern_id[p]
  *                (Eq. 4 / Eq. 10), read from the packed factors.  bf16 layers must be PARSE_MFMA16:
- *                one fused kernel, both products on the bf16 matrix cores with fp32 accumulation, the
- *                r_S-wide intermediate rounded to bf16 and kept in LDS.  f32 layers must be
+ *                both products on the bf16 matrix cores with fp32 accumulation, the r_S-wide
+ *                intermediate rounded to bf16.  Two schedules: ONE fused kernel that keeps the
+ *                intermediate in LDS (a workgroup per 64 token rows; needs no workspace), or TWO launches
+ *                of one tile kernel with the intermediate in the workspace (it stays cache-resident), which
+ *                is what fills the chip when the batch has fewer than a few hundred 64-row tiles.  With
+ *                workspace == NULL the fused kernel is used.  f32 layers must be
  *                PARSE_ROWMAJOR (plain fp32 kernels, intermediate in the workspace).
  *                  X device [rows][n], Y device [rows][m] (layer dtype), tok_offsets device int32 [P+1],
  *                  pattern_id device int32 [P].
@@ -209,7 +217,7 @@ size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *layer, int
  *                once from the layer's own store (layer->Vt / layer->Ut, not the packed copies) and applies
  *                it to the sequences whose pattern holds it (Sec. 4.3, rank reuse: pattern_id is fixed
  *                at prefill).  Bandwidth-bound.
- * workspace: device, >= parse_lowrank_workspace_bytes(mode, layer, rows, k) bytes. */
+ * workspace: device, >= parse_lowrank_workspace_bytes(mode, layer, rows, k) bytes (optional for bf16 prefill). */
 int parse_lowrank_forward(int32_t mode, const parse_layer *layer, const parse_patterns *patterns,
                           const void *X, int32_t rows, const int32_t *tok_offsets,
                           const int32_t *pattern_id, int32_t P, void *Y, void *workspace,

@@ -75,6 +75,7 @@ def lib():
     L.parse_pack_patterns.argtypes = [C.POINTER(_Layer), vp, i32, i32, vp, vp, i32, vp, vp, vp]
     L.parse_lowrank_workspace_bytes.restype = sz
     L.parse_lowrank_workspace_bytes.argtypes = [i32, C.POINTER(_Layer), i32, i32]
+    L.parse_set_prefill_schedule.restype = C.c_int; L.parse_set_prefill_schedule.argtypes = [i32]
     L.parse_lowrank_forward.restype = C.c_int
     L.parse_lowrank_forward.argtypes = [i32, C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, i32, vp, vp,
                                         sz, vp]
@@ -291,15 +292,20 @@ def lowrank_workspace_bytes(mode: int, layer: Layer, rows: int, k: int) -> int:
     return lib().parse_lowrank_workspace_bytes(mode, C.byref(cl), rows, k)
 
 
+def set_prefill_schedule(schedule: int):
+    """parse_set_prefill_schedule: 0 = by size, 1 = fused kernel, 2 = two launches."""
+    _check(lib().parse_set_prefill_schedule(schedule), "parse_set_prefill_schedule")
+
+
 def lowrank_forward(mode: int, layer: Layer, patterns: Patterns, X, tok_offsets, pattern_id, Y=None,
-                    workspace=None):
-    """parse_lowrank_forward.  Returns Y [rows][m]."""
+                    workspace=None, no_workspace=False):
+    """parse_lowrank_forward.  Returns Y [rows][m].  no_workspace=True passes NULL (bf16 prefill: fused kernel)."""
     rows = X.shape[0]
     P = pattern_id.numel()
     if Y is None:
         Y = torch.empty((rows, layer.m), dtype=X.dtype, device=X.device)
     need = lowrank_workspace_bytes(mode, layer, rows, patterns.k)
-    if workspace is None and need > 0:
+    if workspace is None and need > 0 and not no_workspace:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     cl, cp = layer.c(), patterns.c()
     _check(lib().parse_lowrank_forward(mode, C.byref(cl), C.byref(cp), _ptr(X), rows, _ptr(tok_offsets),

@@ -5,7 +5,10 @@ namespace parse {
 int forward_f32(const parse_layer *L, const parse_patterns *pt, const float *X, int rows, const int32_t *tok_offsets,
                 const int32_t *pattern_id, int P, float *Y, void *workspace, hipStream_t s);
 int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *X, int rows,
-                         const int32_t *tok_offsets, const int32_t *pattern_id, int P, uint16_t *Y, hipStream_t s);
+                         const int32_t *tok_offsets, const int32_t *pattern_id, int P, uint16_t *Y, void *workspace,
+                         size_t workspace_bytes, hipStream_t s);
+size_t prefill_split_workspace_bytes(int rows, int rS);
+void set_prefill_schedule(int v);
 size_t prefill_lds_bytes(int BM, int rS);
 size_t decode_workspace_bytes(const parse_layer *L);
 int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *x, int B,
@@ -20,7 +23,13 @@ size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *L, int32_t
   if (!L || rows <= 0 || k <= 0 || L->G <= 0 || L->R <= 0) return 0;
   if (mode == PARSE_DECODE) return decode_workspace_bytes(L);
   if (L->dtype == PARSE_F32) return round_up((size_t)rows * k * (L->R / L->G) * sizeof(float), 256);
-  return 0;
+  return prefill_split_workspace_bytes(rows, k * (L->R / L->G));
+}
+
+int parse_set_prefill_schedule(int32_t schedule) {
+  if (schedule < 0 || schedule > 2) return PARSE_EINVAL;
+  set_prefill_schedule(schedule);
+  return PARSE_OK;
 }
 
 int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patterns *pt, const void *X, int32_t rows,
@@ -34,8 +43,10 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patter
   if (pt->k > L->G || P > rows) return PARSE_ESHAPE;
   if (!aligned16(X) || !aligned16(Y)) return PARSE_EALIGN;
   const size_t need = parse_lowrank_workspace_bytes(mode, L, rows, pt->k);
-  if (need > 0 && (!workspace || workspace_bytes < need)) return PARSE_EWORKSPACE;
-  if (need > 0 && !aligned16(workspace)) return PARSE_EALIGN;
+  // bf16 prefill may run without a workspace (fused kernel only); every other mode needs the queried size
+  const bool optional_ws = mode == PARSE_PREFILL && L->dtype == PARSE_BF16 && workspace == nullptr;
+  if (!optional_ws && need > 0 && (!workspace || workspace_bytes < need)) return PARSE_EWORKSPACE;
+  if (workspace && !aligned16(workspace)) return PARSE_EALIGN;
   hipStream_t s = (hipStream_t)stream;
   const int gs = L->R / L->G, rS = pt->k * gs;
 
@@ -55,7 +66,8 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patter
   if (L->layout != PARSE_MFMA16) return PARSE_ELAYOUT;
   if (rS % 32 != 0) return PARSE_ESHAPE;
   if (prefill_lds_bytes(32, rS) > 160 * 1024) return PARSE_ESHAPE;
-  return forward_prefill_bf16(L, pt, (const uint16_t *)X, rows, tok_offsets, pattern_id, P, (uint16_t *)Y, s);
+  return forward_prefill_bf16(L, pt, (const uint16_t *)X, rows, tok_offsets, pattern_id, P, (uint16_t *)Y, workspace,
+                              workspace_bytes, s);
 }
 
 }  // extern "C"

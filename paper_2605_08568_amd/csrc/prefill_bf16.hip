@@ -15,39 +15,9 @@
 // The inner loops are branch-free: the number of 32-wide operand blocks a wavefront owns in a pass (NB) is a
 // template parameter, prefetches past the end are clamped to the last valid operand instead of being
 // predicated, and shapes that do not fill whole staged tiles take a separate, simpler kernel.
-#include "common.hpp"
+#include "prefill_common.hpp"
 
 namespace parse {
-
-constexpr int PF_THREADS = 256;
-constexpr int PF_BK = 64;            // reduction indices per staged X tile (4 matrix instructions deep)
-constexpr int PF_XPAD = 8;           // bf16 of padding per LDS row: keeps 16-byte operand reads conflict-free
-constexpr int PF_ZPAD = 8;
-constexpr int PF_DEPTH = 8;          // reduction steps of factor operands in flight per wavefront
-
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-typedef __attribute__((ext_vector_type(2))) float f32x2_t;
-
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-// two floats -> packed bfloat16 pair, round to nearest even (hardware conversion)
-__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
-}
-
-// Workgroup ids are dealt round-robin over the 8 accelerator dies (XCDs), each with its own L2.  Token tiles
-// are renumbered so that the tiles one die works on are consecutive: tiles of one prompt share a pattern, so
-// they stream the same packed factors and hit in that die's L2 instead of each die fetching every pattern.
-__device__ __forceinline__ int xcd_tile(int b, int nb) {
-  const int per = nb / 8, rem = nb % 8, x = b % 8, i = b / 8;
-  return x * per + min(x, rem) + i;
-}
-
-struct PfArgs {
-  const uint16_t *X, *Vt_S, *Ut_S;
-  uint16_t *Y;
-  const int32_t *tok_offsets, *pattern_id;
-  int n_patterns, rows, n, m, rS, P;
-};
 
 // ---------------------------------------------------------------------------------------------------------
 // phase 1, one pass: this wavefront's NB rank blocks (first one rb0, then every 4th) x all BM tokens.
@@ -380,15 +350,35 @@ static int launch_prefill(K kernel, bool *attr_done, const PfArgs &a, int BM, si
   return PARSE_OK;
 }
 
+// two-launch form (prefill_split_bf16.hip)
+size_t prefill_split_workspace_bytes(int rows, int rS);
+bool prefill_split_supported(int n, int rS);
+int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s);
+
+static int g_prefill_schedule = 0;   // 0 = choose by size, 1 = fused kernel, 2 = two launches
+void set_prefill_schedule(int v) { g_prefill_schedule = v; }
+
 int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *X, int rows,
-                         const int32_t *tok_offsets, const int32_t *pattern_id, int P, uint16_t *Y, hipStream_t s) {
+                         const int32_t *tok_offsets, const int32_t *pattern_id, int P, uint16_t *Y, void *workspace,
+                         size_t workspace_bytes, hipStream_t s) {
   const int gs = L->R / L->G, rS = pt->k * gs;
+  PfArgs a{X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, Y, tok_offsets, pattern_id,
+           pt->n_patterns, rows, L->n, L->m, rS, P};
+  // The fused kernel runs rows/64 workgroups, one per compute unit: below about two waves of the 256 units
+  // the two-launch form (which needs the Z workspace) fills the chip better.
+  const bool can_split = workspace != nullptr && workspace_bytes >= prefill_split_workspace_bytes(rows, rS) &&
+                         prefill_split_supported(L->n, rS);
+  bool split = can_split && (rows / 64 < 1024);
+  if (g_prefill_schedule == 1) split = false;
+  if (g_prefill_schedule == 2) {
+    if (!can_split) return PARSE_EWORKSPACE;
+    split = true;
+  }
+  if (split) return forward_prefill_split_bf16(a, (uint16_t *)workspace, rows / (P > 0 ? P : 1), s);
   int BM = 64;
   if (prefill_lds_bytes(64, rS) > kLdsLimit) BM = 32;
   const size_t lds = prefill_lds_bytes(BM, rS);
   if (lds > kLdsLimit) return PARSE_ESHAPE;
-  PfArgs a{X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, Y, tok_offsets, pattern_id,
-           pt->n_patterns, rows, L->n, L->m, rS, P};
   const bool fast = (L->n % (2 * PF_BK) == 0) && (rS % (16 * PF_DEPTH) == 0) && (L->n / 16 >= PF_DEPTH);
   static bool done[4] = {false, false, false, false};
   if (fast) {

@@ -1,0 +1,178 @@
+// a6, two-launch form of the bf16 prefill product for batches that give the fused kernel too few token tiles to
+// occupy the chip:  launch 1  Z = X Vt_S^T  (bf16, into the caller's workspace),  launch 2  Y = Z Ut_S.
+// Both launches run ONE kernel, `gemm_tokens`: out^T[M-block, tokens] = sum_k F[M-block, k] * Tk[token, k], where F
+// is a factor matrix in operand order (fetched straight from global memory, 1 KiB per wavefront instruction) and
+// Tk the row-major token operand (X, then Z) staged through LDS.  A workgroup owns BT token rows x 4*NB*32
+// factor rows; wavefront w owns NB consecutive 32-row factor blocks and all BT tokens, so each factor operand is
+// fetched by exactly one wavefront and each staged token operand feeds NB matrix instructions.
+// The intermediate costs 2*T*r_S*2 bytes of extra traffic (it stays in the last-level cache at these sizes) and
+// buys a grid of (T/BT) x (M/(128 NB)) workgroups instead of T/64.
+#include "prefill_common.hpp"
+
+namespace parse {
+
+struct GtArgs {
+  const uint16_t *T;        // token operand [rows][K]
+  const uint16_t *F;        // factor operands of all patterns
+  uint16_t *O;              // output [rows][M]
+  const int32_t *tok_offsets, *pattern_id;
+  size_t pattern_stride;    // elements of F per pattern
+  int mb_stride, kb_stride; // operand (mb, kb) starts at (mb*mb_stride + kb*kb_stride) * 512 elements
+  int K, M, rows, P, n_patterns;
+  int ntiles, nchunks, GT;  // token tiles, factor-row chunks, token tiles per locality group
+};
+
+template <int BT, int NB>
+__global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
+  constexpr int NT = BT / 32;
+  constexpr int XP = BT * PF_BK / 8 / PF_THREADS;
+  constexpr int xld = PF_BK + PF_XPAD;
+  __shared__ __attribute__((aligned(16))) uint16_t Xs[2 * BT * xld];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, q = lane >> 5;
+  // consecutive virtual ids share an XCD; a group of GT token tiles x all chunks is consecutive, so the tiles
+  // of one prompt find their pattern's factors (and each other's token rows) in that die's L2
+  const int v = xcd_tile(blockIdx.x, gridDim.x);
+  const int per_group = a.nchunks * a.GT;
+  const int grp = v / per_group, rem = v % per_group;
+  const int chunk = rem / a.GT, tile = grp * a.GT + rem % a.GT;
+  if (tile >= a.ntiles) return;
+  const int row0 = tile * BT;
+  const int row_end = min(row0 + BT, a.rows);
+  const int K = a.K, nkb = K / 16, nkt = K / PF_BK, nmb = a.M / 32;
+  const int mb0 = chunk * 4 * NB + wave * NB;
+
+  const uint16_t *xsrc[XP];
+  int xdst[XP];
+#pragma unroll
+  for (int i = 0; i < XP; ++i) {
+    const int piece = i * PF_THREADS + threadIdx.x;
+    const int r = piece / (PF_BK / 8), c = (piece % (PF_BK / 8)) * 8;
+    xsrc[i] = a.T + (size_t)min(row0 + r, a.rows - 1) * K + c;
+    xdst[i] = r * xld + c;
+  }
+  const int xoff = l32 * xld + q * 8;
+
+  int seg_lo = row0;
+  while (seg_lo < row_end) {
+    const int p = prompt_of_row(a.tok_offsets, a.P, seg_lo);
+    int seg_hi = (p + 1 < a.P) ? a.tok_offsets[p + 1] : a.rows;
+    seg_hi = min(max(seg_hi, seg_lo + 1), row_end);
+    const int pid = a.pattern_id[p];
+    const bool valid = pid >= 0 && pid < a.n_patterns;
+    const uint16_t *Fp = a.F + (valid ? (size_t)pid * a.pattern_stride : 0);
+    const uint16_t *fbase[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+      fbase[i] = Fp + ((size_t)min(mb0 + i, nmb - 1) * a.mb_stride * 64 + lane) * 8;
+    const size_t kstride = (size_t)a.kb_stride * 512;
+
+    f32x16 acc[NT][NB];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
+    u32x4 xr[2][XP];
+    u32x4 fr[PF_DEPTH][NB];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < XP; ++i) xr[0][i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
+#pragma unroll
+    for (int d = 0; d < PF_DEPTH; ++d)
+#pragma unroll
+      for (int i = 0; i < NB; ++i) fr[d][i] = *reinterpret_cast<const u32x4 *>(fbase[i] + d * kstride);
+#pragma unroll
+    for (int i = 0; i < XP; ++i) xr[1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + PF_BK);
+#pragma unroll
+    for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(Xs + xdst[i]) = xr[0][i];
+    __syncthreads();
+    for (int kt0 = 0; kt0 < nkt; kt0 += 2) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int kt = kt0 + u;
+        const int ktn = min(kt + 2, nkt - 1);
+#pragma unroll
+        for (int i = 0; i < XP; ++i) xr[u][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)ktn * PF_BK);
+        bf16x8 xb[2][NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          xb[0][t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + u * BT * xld + t * 32 * xld + xoff));
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          if (s < 3) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+              xb[(s + 1) & 1][t] =
+                  as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + u * BT * xld + t * 32 * xld + xoff + (s + 1) * 16));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+              acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fr[u * 4 + s][i]), xb[s & 1][t], acc[t][i], 0, 0, 0);
+          const int kbn = min(kt * 4 + s + PF_DEPTH, nkb - 1);
+#pragma unroll
+          for (int i = 0; i < NB; ++i) fr[u * 4 + s][i] = *reinterpret_cast<const u32x4 *>(fbase[i] + kbn * kstride);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(Xs + (u ^ 1) * BT * xld + xdst[i]) = xr[u ^ 1][i];
+        __syncthreads();
+      }
+    }
+    // lane holds token t*32 + l32, factor rows (mb0+i)*32 + 8*blk + 4*q + (0..3)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int r = row0 + t * 32 + l32;
+      if (r < seg_lo || r >= seg_hi) continue;
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        if (mb0 + i >= nmb) continue;
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk) {
+          u32x2 w;
+          w[0] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]) : 0u;
+          w[1] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]) : 0u;
+          *reinterpret_cast<u32x2 *>(a.O + (size_t)r * a.M + (mb0 + i) * 32 + blk * 8 + q * 4) = w;
+        }
+      }
+    }
+    seg_lo = seg_hi;
+  }
+}
+
+template <int BT, int NB>
+static int launch_gemm_tokens(GtArgs a, int GT, hipStream_t s) {
+  a.ntiles = (a.rows + BT - 1) / BT;
+  a.nchunks = (a.M / 32 + 4 * NB - 1) / (4 * NB);
+  a.GT = GT;
+  const int groups = (a.ntiles + GT - 1) / GT;
+  hipLaunchKernelGGL((gemm_tokens<BT, NB>), dim3(groups * GT * a.nchunks), dim3(PF_THREADS), 0, s, a);
+  PARSE_LAUNCH_CHECK();
+  return PARSE_OK;
+}
+
+// Z workspace: rows x rS bf16
+size_t prefill_split_workspace_bytes(int rows, int rS) { return round_up((size_t)rows * rS * sizeof(uint16_t), 256); }
+
+bool prefill_split_supported(int n, int rS) {
+  return n % (2 * PF_BK) == 0 && rS % (2 * PF_BK) == 0 && n / 16 >= PF_DEPTH && rS / 16 >= PF_DEPTH;
+}
+
+int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s) {
+  // launch 1: factor rows = ranks (operand (rb, kb) at rb*(n/16) + kb), tokens = X
+  GtArgs g1{p.X, p.Vt_S, Z, p.tok_offsets, p.pattern_id, (size_t)p.rS * p.n, p.n / 16, 1,
+            p.n, p.rS, p.rows, p.P, p.n_patterns, 0, 0, 0};
+  int gt64 = avg_prompt_rows / 64;  gt64 = gt64 < 1 ? 1 : (gt64 > 8 ? 8 : gt64);
+  int st = launch_gemm_tokens<64, 2>(g1, gt64, s);
+  if (st != PARSE_OK) return st;
+  // launch 2: factor rows = output columns (operand (cb, kb) at kb*(m/32) + cb), tokens = Z
+  GtArgs g2{Z, p.Ut_S, p.Y, p.tok_offsets, p.pattern_id, (size_t)p.rS * p.m, 1, p.m / 32,
+            p.rS, p.m, p.rows, p.P, p.n_patterns, 0, 0, 0};
+  int gt128 = avg_prompt_rows / 128;  gt128 = gt128 < 1 ? 1 : (gt128 > 8 ? 8 : gt128);
+  return launch_gemm_tokens<128, 2>(g2, gt128, s);
+}
+
+}  // namespace parse

@@ -218,7 +218,7 @@ def test_pack_skips_invalid_group_ids():
 
 
 # ------------------------------------------------------------------ a6 prefill forward
-def _run_prefill(lay, lengths, subsets_per_prompt, seed, dtype):
+def _run_prefill(lay, lengths, subsets_per_prompt, seed, dtype, schedule=0):
     rng = np.random.default_rng(seed)
     off = si.offsets_from_lengths(lengths)
     X = si.make_tokens(rng, int(off[-1]), lay.n, dtype)
@@ -233,9 +233,13 @@ def _run_prefill(lay, lengths, subsets_per_prompt, seed, dtype):
     sd = i32(subs)
     pid, perm, boff, npat, rep = pa.bucket_patterns(sd, k)
     Vs, Us = pa.pack_patterns(dl, sd, k, k, rep, npat, len(lengths))
-    Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, len(lengths), Vs, Us), upload_tokens(X, dtype),
-                           i32(off), pid)
-    torch.cuda.synchronize()
+    pa.set_prefill_schedule(schedule)
+    try:
+        Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, len(lengths), Vs, Us), upload_tokens(X, dtype),
+                               i32(off), pid, no_workspace=(schedule == 1))
+        torch.cuda.synchronize()
+    finally:
+        pa.set_prefill_schedule(0)
     Yg = Y.float().cpu().numpy().astype(np.float64)
     return Yg, Yref, off
 
@@ -258,14 +262,18 @@ def test_prefill_config0_fp32():
         assert_close(Y[a:b].cpu().numpy(), Yref[a:b], TOL_F32, f"prompt {p}")
 
 
-@pytest.mark.parametrize("n,m,R,G,k,lengths", [
-    (512, 768, 256, 8, 4, [70, 1, 33, 129, 64]),          # r_S = 128: one rank block per wave, ragged tiles
-    (1024, 1024, 512, 4, 3, [64, 200]),                   # r_S = 384: uneven rank blocks per wave
-    (528, 544, 160, 5, 2, [5, 90]),                       # n not a multiple of the staged tile, r_S = 64
-    (512, 512, 2560, 20, 10, [40, 100]),                  # r_S = 1280: 32-token workgroups
+@pytest.mark.parametrize("n,m,R,G,k,lengths,schedule", [
+    (512, 768, 256, 8, 4, [70, 1, 33, 129, 64], 1),       # r_S = 128: one rank block per wave, ragged tiles
+    (512, 768, 256, 8, 4, [70, 1, 33, 129, 64], 2),
+    (1024, 1024, 512, 4, 3, [64, 200], 1),                # r_S = 384: uneven rank blocks per wave
+    (1024, 1024, 512, 4, 3, [64, 200], 2),
+    (528, 544, 160, 5, 2, [5, 90], 0),                    # n not a multiple of the staged tile, r_S = 64
+    (512, 512, 2560, 20, 10, [40, 100], 1),               # r_S = 1280: 32-token workgroups
+    (512, 800, 2560, 20, 10, [40, 300], 2),               # two launches, output blocks not a multiple of a chunk
+    (1024, 4096, 1024, 8, 4, [512, 512, 37], 0),          # default choice at a size with whole 128-row tiles
 ])
-def test_prefill_bf16_small(n, m, R, G, k, lengths):
-    say(f"prefill bf16 n={n} m={m} R={R} G={G} k={k} lengths={lengths}")
+def test_prefill_bf16_small(n, m, R, G, k, lengths, schedule):
+    say(f"prefill bf16 n={n} m={m} R={R} G={G} k={k} lengths={lengths} schedule={schedule}")
     if R > min(n, m):
         lay = si.make_layer(np.random.default_rng(501), n, m, min(n, m), 1, "bf16")
         # stored rank above min(n, m) cannot be orthonormal: tile independent blocks instead (values only matter
@@ -278,7 +286,7 @@ def test_prefill_bf16_small(n, m, R, G, k, lengths):
         lay = si.small_layer(502, n, m, R, G, "bf16")
     rng = np.random.default_rng(503)
     subs = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in lengths]).astype(np.int32)
-    Yg, Yref, off = _run_prefill(lay, lengths, subs, 504, "bf16")
+    Yg, Yref, off = _run_prefill(lay, lengths, subs, 504, "bf16", schedule)
     for p in range(len(lengths)):
         assert_close(Yg[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"prompt {p}")
 
@@ -310,8 +318,14 @@ def test_prefill_config1_full_size_sampled():
     sub_d = pa.route(Xd, offd, torch.from_numpy(w.Wr[0]).to(DEV), w.k)
     pid, perm, boff, npat, rep = pa.bucket_patterns(sub_d, w.k)
     Vs, Us = pa.pack_patterns(dl, sub_d, w.k, w.k, rep, npat, w.P)
-    Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us), Xd, offd, pid)
-    torch.cuda.synchronize()
+    Ys = {}
+    for schedule in (1, 2):
+        pa.set_prefill_schedule(schedule)
+        try:
+            Ys[schedule] = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us), Xd, offd, pid)
+            torch.cuda.synchronize()
+        finally:
+            pa.set_prefill_schedule(0)
     assert np.all(margin > 1e-4) and np.array_equal(sub_d.cpu().numpy(), subs)
     Vt, Ut = lay.stored_values()
     rng = np.random.default_rng(7)
@@ -319,7 +333,9 @@ def test_prefill_config1_full_size_sampled():
         rows = po.group_rows(subs[p], lay.gs)
         ts = w.tok_offsets[p] + np.concatenate([[0, 63, 64, 511], rng.integers(0, 512, size=4)])
         Yref = (Xv[ts] @ Vt[rows].T) @ Ut[rows]           # Eq. 10 on the sampled rows, float64
-        assert_close(Y[torch.from_numpy(ts).to(DEV)].float().cpu().numpy(), Yref, TOL_BF16, f"prompt {p}")
+        for schedule, Y in Ys.items():
+            assert_close(Y[torch.from_numpy(ts).to(DEV)].float().cpu().numpy(), Yref, TOL_BF16,
+                         f"prompt {p} schedule {schedule}")
 
 
 # ------------------------------------------------------------------ a7 decode
