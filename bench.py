@@ -68,7 +68,8 @@ def bench_prefill(args, torch, pa, si):
     X = upload_tokens(w.X, "bf16", dev)
     off = i32(w.tok_offsets, dev)
     Wr = torch.from_numpy(w.Wr).to(dev)                    # [1][G][d]
-    cache = pa.Cache(1024, w.d, 1, k, max(P, 8))
+    n_slots = 32                                           # aggregated-pattern store, one slot per cache entry
+    cache = pa.Cache(n_slots, w.d, 1, k, max(P, 8))
     # every buffer of the step is allocated once, outside the timed region
     emb = torch.empty((P, w.d), dtype=torch.float32, device=dev)
     sub_route = torch.empty((P, k), dtype=torch.int32, device=dev)
@@ -80,11 +81,11 @@ def bench_prefill(args, torch, pa, si):
     bucket_out = (torch.empty(P, dtype=torch.int32, device=dev), torch.empty(P, dtype=torch.int32, device=dev),
                   torch.empty(P + 1, dtype=torch.int32, device=dev), torch.empty(1, dtype=torch.int32, device=dev),
                   torch.empty(P, dtype=torch.int32, device=dev))
-    Vs = torch.empty((P, rS, n), dtype=torch.bfloat16, device=dev)
-    Us = torch.empty((P, rS, m), dtype=torch.bfloat16, device=dev)
+    Vs = torch.empty((n_slots, rS, n), dtype=torch.bfloat16, device=dev)
+    Us = torch.empty((n_slots, rS, m), dtype=torch.bfloat16, device=dev)
     Y = torch.empty((rows, m), dtype=torch.bfloat16, device=dev)
     ws_fwd = torch.empty(max(pa.lowrank_workspace_bytes(pa.PARSE_PREFILL, dl, rows, k), 256), dtype=torch.uint8, device=dev)
-    pt = pa.Patterns(k, P, Vs, Us)
+    pt = pa.Patterns(k, n_slots, Vs, Us)
     names = ["route", "cache", "bucket", "pack", "forward"]
 
     def step(ev=None):
@@ -96,13 +97,20 @@ def bench_prefill(args, torch, pa, si):
         mark(1)
         cache.lookup_or_route(emb, 0.9, Wr, entry, hit, sim, sub)
         mark(2)
-        pid, perm, boff, npat, rep = pa.bucket_patterns(sub, k, k, bucket_out)
+        pa.bucket_patterns(sub, k, k, bucket_out)          # buckets of equal subsets (execution grouping)
         mark(3)
-        pa.pack_patterns(dl, sub, k, k, rep, npat, P, Vs, Us)
+        pa.pack_new_entries(dl, sub, k, k, entry, hit, Vs, Us)   # aggregation happens once per new cache entry
         mark(4)
-        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y, ws_fwd)
+        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, entry, Y, ws_fwd)   # pattern id = cache entry
         mark(5)
 
+    # cold step: empty cache, every prompt misses, is routed, appended and aggregated
+    step(); torch.cuda.synchronize()
+    cache.clear()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record(); step(); c1.record(); torch.cuda.synchronize()
+    cold_ms = c0.elapsed_time(c1)
+    assert int(hit.sum().item()) == 0 and cache.count() == P
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -119,7 +127,7 @@ def bench_prefill(args, torch, pa, si):
     hits = int(hit.sum().item())
     # the same forward under each fixed schedule, for the record (not part of the timed steps above)
     sched_us = {}
-    pid = bucket_out[0]
+    pid = entry
     for nm, code in (("fused", 1), ("two_launch", 2)):
         pa.set_prefill_schedule(code)
         for _ in range(3):
@@ -141,7 +149,7 @@ def bench_prefill(args, torch, pa, si):
     res = {
         "value": value, "ms_per_step": ms_per_step, "flops_per_step": flops,
         "rows_us": {k_: round(v, 2) for k_, v in per.items()},
-        "cache_hits": hits, "forward_us_by_schedule": sched_us,
+        "cache_hits": hits, "forward_us_by_schedule": sched_us, "cold_step_ms": round(cold_ms, 4),
         "roofline": {"bound": "mfma", "kernel": "gemm_tokens x2 (two-launch schedule)" if sched_us["two_launch"] <= sched_us["fused"] else "prefill_fused", "achieved": round(achieved, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": traffic_from_profiles("prefill_fused_config1"),
@@ -281,12 +289,14 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config1: q_proj-shaped prefill, bf16, {lay.m}x{lay.n}, R={lay.R} in {lay.G} groups of "
                                f"{lay.gs}, top-{w.k}, {w.P} prompts x {args.tokens} tokens, one routed subset per prompt",
-                   "step": "pool+route, cache probe, bucket, pack, fused forward"},
+                   "step": "pool+route, cache probe (route-on-miss), bucket, pack of new cache entries, forward; "
+                           "warm cache in the timed steps, cold_step_ms = the same step with an empty cache"},
         "roofline": pre["roofline"],
         "cpu_baseline": base,
         "rows_us": pre["rows_us"],
         "cache_hits_last_step": pre["cache_hits"],
         "forward_us_by_schedule": pre["forward_us_by_schedule"],
+        "cold_step_ms": pre["cold_step_ms"],
         "decode": dec,
     }
     print(json.dumps(line))

@@ -182,6 +182,16 @@ int parse_pack_patterns(const parse_layer *layer, const int32_t *subset, int32_t
                         int32_t k, const int32_t *rep, const int32_t *n_patterns,
                         int32_t max_patterns, void *Vt_S, void *Ut_S, parse_stream stream);
 
+/* Aggregation keyed by pattern-cache entry (the aggregated copy of a pattern is made once, when the pattern
+ * enters the cache, and reused by every later hit and every decode step): for each of the P prompts of a
+ * parse_cache_lookup_or_route batch with hit[p] == 0 and 0 <= entry[p] < n_slots, prompt p's subset
+ * (subset[p*subset_stride .. +k)) is packed into slot entry[p] of Vt_S [n_slots][k*gs][n] and
+ * Ut_S [n_slots][k*gs][m].  Hits and misses that found the cache full (entry -1) are skipped; the forward
+ * call then takes pattern_id = entry.  entry device int32 [P], hit device uint8 [P]. */
+int parse_pack_new_entries(const parse_layer *layer, const int32_t *subset, int32_t subset_stride,
+                           int32_t k, int32_t P, const int32_t *entry, const uint8_t *hit,
+                           int32_t n_slots, void *Vt_S, void *Ut_S, parse_stream stream);
+
 /* ---- a6 / a7: the routed product ------------------------------------------------------------
  * Patterns of one call.  All patterns of a layer have the same active rank r_S = k*gs. */
 typedef struct {

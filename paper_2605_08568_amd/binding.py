@@ -73,6 +73,8 @@ def lib():
     L.parse_pack_experts.argtypes = [C.POINTER(_Layer), vp, i32, vp, vp, vp]
     L.parse_pack_patterns.restype = C.c_int
     L.parse_pack_patterns.argtypes = [C.POINTER(_Layer), vp, i32, i32, vp, vp, i32, vp, vp, vp]
+    L.parse_pack_new_entries.restype = C.c_int
+    L.parse_pack_new_entries.argtypes = [C.POINTER(_Layer), vp, i32, i32, i32, vp, vp, i32, vp, vp, vp]
     L.parse_lowrank_workspace_bytes.restype = sz
     L.parse_lowrank_workspace_bytes.argtypes = [i32, C.POINTER(_Layer), i32, i32]
     L.parse_set_prefill_schedule.restype = C.c_int; L.parse_set_prefill_schedule.argtypes = [i32]
@@ -284,6 +286,16 @@ def pack_patterns(layer: Layer, subset, subset_stride, k, rep, n_patterns, max_p
     cl = layer.c()
     _check(lib().parse_pack_patterns(C.byref(cl), _ptr(subset), subset_stride, k, _ptr(rep), _ptr(n_patterns),
                                      max_patterns, _ptr(Vt_S), _ptr(Ut_S), _stream()), "parse_pack_patterns")
+    return Vt_S, Ut_S
+
+
+def pack_new_entries(layer: Layer, subset, subset_stride, k, entry, hit, Vt_S, Ut_S):
+    """parse_pack_new_entries: packs the subsets of this batch's new cache entries into their slots of
+    Vt_S [n_slots][k*gs][n] / Ut_S [n_slots][k*gs][m]."""
+    cl = layer.c()
+    _check(lib().parse_pack_new_entries(C.byref(cl), _ptr(subset), subset_stride, k, entry.numel(), _ptr(entry),
+                                        _ptr(hit), Vt_S.shape[0], _ptr(Vt_S), _ptr(Ut_S), _stream()),
+           "parse_pack_new_entries")
     return Vt_S, Ut_S
 
 

@@ -3,14 +3,16 @@
 //
 // Kernels of one batched probe (all on the caller's stream, no host round trip; the entry count lives
 // in device memory):
-//   emb_norms      one wavefront per prompt: ||e_p||
-//   cache_sims     cosine of every prompt with every stored key and, for the sequential variant, with
-//                  every earlier prompt of the batch; one wavefront per (prompt, column)
-//   best_existing  one wavefront per prompt: arg-max over the stored keys (smallest index on ties)
-//   resolve        ONE wavefront walks the batch in arrival order and decides hit / miss / new entry,
-//                  taking earlier misses of the same batch (already appended) into account
-//   route_misses   router scores + top-k for the prompts that missed; appends key and subsets
-//   gather_hits    copies the stored subsets of the answering entry
+//   cache_sims       cosine of every prompt with every stored key and, for the sequential variant, with
+//                    every earlier prompt of the batch; one wavefront per (prompt, column), norms on the fly
+//   resolve          one workgroup: its wavefronts first take the arg-max over the stored keys per prompt
+//                    (smallest index on ties), then ONE wavefront walks the batch in arrival order and
+//                    decides hit / miss / new entry, taking earlier misses of the same batch (already
+//                    appended) into account
+//   route_or_gather  per (layer, prompt): a miss runs the router (scores + top-k) and appends key and
+//                    subsets; a hit on a stored entry copies its subsets; a hit on an entry appended by
+//                    this very batch re-routes that entry's key (same result as the stored value, which
+//                    another workgroup of this launch is still writing)
 #include <new>
 
 #include "common.hpp"
@@ -19,14 +21,11 @@
 struct parse_cache {
   int32_t capacity, d, L, k, max_batch;
   float *keys;      // [capacity][d]
-  float *knorm;     // [capacity]
   int32_t *values;  // [capacity][L][k]
   int32_t *count;   // [1]
   // scratch of one batch
   float *sims;      // [max_batch][capacity + max_batch]
-  float *enorm;     // [max_batch]
-  float *best_sim;  // [max_batch]
-  int32_t *best_idx;  // [max_batch]
+  int32_t *src;     // [max_batch] prompt whose embedding defines the answer's key (in-batch entries), else -1
   int32_t *entry;   // [max_batch] (used when the caller passes no entry_out)
   uint8_t *hit;     // [max_batch]
   int32_t count_ub; // host-side upper bound of *count (exact after count/insert/clear); sizes the probe grid
@@ -34,63 +33,38 @@ struct parse_cache {
 
 namespace parse {
 
-__global__ __launch_bounds__(64) void emb_norms(const float *__restrict__ E, int d, float *__restrict__ enorm) {
-  const int p = blockIdx.x, lane = threadIdx.x;
-  const float4 *e4 = reinterpret_cast<const float4 *>(E + (size_t)p * d);
-  float acc = 0.f;
-  for (int c = lane; c < d / 4; c += 64) {
-    const float4 v = e4[c];
-    acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-  }
-  acc = wave_sum(acc);
-  if (lane == 0) enorm[p] = sqrtf(acc);
-}
-
-// grid (ceil((capacity + peers)/4), P), block 256: wave w of block bx handles column j = 4*bx + w.
-// Columns [0, capacity) are stored keys (skipped beyond *count), columns capacity + q are batch peers
-// (only q < p is needed).
+// grid (ceil((ncols_keys + peers)/4), P), block 256: wave w of block bx handles column j = 4*bx + w.
+// Columns [0, ncols_keys) are stored keys (skipped beyond *count), the next `peers` columns are batch peers
+// (only q < p is needed); similarities land in sims[p][j] (keys) and sims[p][capacity + q] (peers).
 __global__ __launch_bounds__(256) void cache_sims(const float *__restrict__ E, int d, const float *__restrict__ keys,
-                                                  const float *__restrict__ knorm, const float *__restrict__ enorm,
                                                   const int32_t *__restrict__ count, int capacity, int ncols_keys,
                                                   int peers, int ld, float *__restrict__ sims) {
-  // columns [0, ncols_keys) -> stored keys; columns ncols_keys + q -> batch peer q
   const int p = blockIdx.y, lane = threadIdx.x & 63;
   int j = blockIdx.x * 4 + (threadIdx.x >> 6);
   const float *other;
-  float onorm;
   if (j < ncols_keys) {
     if (j >= *count || j >= capacity) return;
     other = keys + (size_t)j * d;
-    onorm = knorm[j];
   } else {
     const int q = j - ncols_keys;
     j = capacity + q;
     if (q >= peers || q >= p) return;
     other = E + (size_t)q * d;
-    onorm = enorm[q];
   }
   const float4 *a4 = reinterpret_cast<const float4 *>(E + (size_t)p * d);
   const float4 *b4 = reinterpret_cast<const float4 *>(other);
-  float acc = 0.f;
+  float ab = 0.f, aa = 0.f, bb = 0.f;
   for (int c = lane; c < d / 4; c += 64) {
     const float4 a = a4[c], b = b4[c];
-    acc += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+    ab += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+    aa += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    bb += b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
   }
-  acc = wave_sum(acc);
-  if (lane == 0) sims[(size_t)p * ld + j] = acc / (enorm[p] * onorm);
+  ab = wave_sum(ab); aa = wave_sum(aa); bb = wave_sum(bb);
+  if (lane == 0) sims[(size_t)p * ld + j] = ab / (sqrtf(aa) * sqrtf(bb));
 }
 
-__global__ __launch_bounds__(64) void best_existing(const float *__restrict__ sims, int ld,
-                                                    const int32_t *__restrict__ count, float *__restrict__ best_sim,
-                                                    int32_t *__restrict__ best_idx) {
-  const int p = blockIdx.x, lane = threadIdx.x;
-  const int n = *count;
-  float bs = -INFINITY;
-  int bi = -1;
-  for (int j = lane; j < n; j += 64) {
-    const float s = sims[(size_t)p * ld + j];
-    if (bi < 0 || s > bs) { bs = s; bi = j; }
-  }
+__device__ __forceinline__ void wave_argmax(float &bs, int &bi) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     const float os = __shfl_xor(bs, o, 64);
@@ -98,31 +72,43 @@ __global__ __launch_bounds__(64) void best_existing(const float *__restrict__ si
     const bool take = (oi >= 0) && (bi < 0 || os > bs || (os == bs && oi < bi));
     if (take) { bs = os; bi = oi; }
   }
-  if (lane == 0) { best_sim[p] = bs; best_idx[p] = bi; }
 }
 
-// Pure lookup: threshold the best stored key.
-__global__ void finish_lookup(const float *__restrict__ best_sim, const int32_t *__restrict__ best_idx, int P,
-                              float tau, int32_t *__restrict__ entry_out, uint8_t *__restrict__ hit,
-                              float *__restrict__ sim_out) {
-  const int p = blockIdx.x * blockDim.x + threadIdx.x;
-  if (p >= P) return;
-  const bool h = best_idx[p] >= 0 && best_sim[p] >= tau;
-  entry_out[p] = h ? best_idx[p] : -1;
-  hit[p] = h ? 1 : 0;
-  if (sim_out) sim_out[p] = best_sim[p];
-}
-
-// One wavefront, arrival order.  ins_list (LDS) holds the prompts appended so far in this batch; the
-// i-th of them became entry count0 + i.
-__global__ __launch_bounds__(64) void resolve(const float *__restrict__ sims, int ld, int capacity, int P,
-                                              float tau, const float *__restrict__ best_sim,
-                                              const int32_t *__restrict__ best_idx, int32_t *__restrict__ count,
-                                              int32_t *__restrict__ entry_out, uint8_t *__restrict__ hit_out,
-                                              float *__restrict__ sim_out) {
-  extern __shared__ int32_t ins_list[];  // [P]
-  const int lane = threadIdx.x;
+// One workgroup of 1024 lanes.  LDS: best_sim[P], best_idx[P], ins_list[P].
+// sequential == 0: pure lookup (threshold the best stored key).  Otherwise arrival-order semantics: ins_list
+// holds the prompts appended so far in this batch; the i-th of them became entry count0 + i.
+__global__ __launch_bounds__(1024) void resolve(const float *__restrict__ sims, int ld, int capacity, int P,
+                                                float tau, int sequential, int32_t *__restrict__ count,
+                                                int32_t *__restrict__ entry_out, uint8_t *__restrict__ hit_out,
+                                                float *__restrict__ sim_out, int32_t *__restrict__ src_out) {
+  extern __shared__ float lds_f[];
+  float *best_sim = lds_f;                                         // [P]
+  int32_t *best_idx = reinterpret_cast<int32_t *>(lds_f + P);      // [P]
+  int32_t *ins_list = best_idx + P;                                // [P]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
   const int count0 = *count;
+  for (int p = wave; p < P; p += nwaves) {
+    float bs = -INFINITY;
+    int bi = -1;
+    for (int j = lane; j < count0; j += 64) {
+      const float s = sims[(size_t)p * ld + j];
+      if (bi < 0 || s > bs) { bs = s; bi = j; }
+    }
+    wave_argmax(bs, bi);
+    if (lane == 0) { best_sim[p] = bs; best_idx[p] = bi; }
+  }
+  __syncthreads();
+  if (!sequential) {
+    for (int p = threadIdx.x; p < P; p += blockDim.x) {
+      const bool h = best_idx[p] >= 0 && best_sim[p] >= tau;
+      entry_out[p] = h ? best_idx[p] : -1;
+      hit_out[p] = h ? 1 : 0;
+      src_out[p] = -1;
+      if (sim_out) sim_out[p] = best_sim[p];
+    }
+    return;
+  }
+  if (wave != 0) return;
   int n_ins = 0;
   for (int p = 0; p < P; ++p) {
     float bs = best_sim[p];
@@ -134,14 +120,9 @@ __global__ __launch_bounds__(64) void resolve(const float *__restrict__ sims, in
       const float s = sims[(size_t)p * ld + capacity + ins_list[i]];
       if (pi < 0 || s > ps) { ps = s; pi = i; }
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const float os = __shfl_xor(ps, o, 64);
-      const int oi = __shfl_xor(pi, o, 64);
-      const bool take = (oi >= 0) && (pi < 0 || os > ps || (os == ps && oi < pi));
-      if (take) { ps = os; pi = oi; }
-    }
-    if (pi >= 0 && (bi < 0 || ps > bs)) { bs = ps; bi = count0 + pi; }
+    wave_argmax(ps, pi);
+    int src = -1;
+    if (pi >= 0 && (bi < 0 || ps > bs)) { bs = ps; bi = count0 + pi; src = ins_list[pi]; }
     const bool h = bi >= 0 && bs >= tau;
     int ent;
     if (h) {
@@ -153,34 +134,42 @@ __global__ __launch_bounds__(64) void resolve(const float *__restrict__ sims, in
     } else {
       ent = -1;
     }
-    __builtin_amdgcn_s_waitcnt(0);  // ins_list write visible to the wave's later reads
+    __builtin_amdgcn_s_waitcnt(0);  // the ins_list write is visible to this wave's later reads
     __builtin_amdgcn_wave_barrier();
     if (lane == 0) {
       entry_out[p] = ent;
       hit_out[p] = h ? 1 : 0;
+      src_out[p] = h ? src : -1;
       if (sim_out) sim_out[p] = bs;
     }
   }
   if (lane == 0) *count = count0 + n_ins;
 }
 
-// grid (L, P), block 256, LDS d + 64 floats.
-__global__ __launch_bounds__(256) void route_misses(const float *__restrict__ E, int d, const float *__restrict__ Wr,
-                                                    int G, int L, int k, const float *__restrict__ enorm,
-                                                    const int32_t *__restrict__ entry, const uint8_t *__restrict__ hit,
-                                                    float *__restrict__ keys, float *__restrict__ knorm,
-                                                    int32_t *__restrict__ values, int32_t *__restrict__ subset_out) {
+// grid (L, P), block 256, LDS d + 128 floats.  do_route == 0 (pure lookup): only the copy for hits.
+__global__ __launch_bounds__(256) void route_or_gather(const float *__restrict__ E, int d, const float *__restrict__ Wr,
+                                                       int G, int L, int k, int capacity, int do_route,
+                                                       const int32_t *__restrict__ entry, const uint8_t *__restrict__ hit,
+                                                       const int32_t *__restrict__ src, float *__restrict__ keys,
+                                                       int32_t *__restrict__ values, int32_t *__restrict__ subset_out) {
   extern __shared__ float lds[];
   float *e = lds, *s = lds + d;
   const int l = blockIdx.x, p = blockIdx.y;
-  if (hit[p]) return;
   const int ent = entry[p];
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    const float v = E[(size_t)p * d + c];
-    e[c] = v;
-    if (l == 0 && ent >= 0) keys[(size_t)ent * d + c] = v;
+  const bool h = hit[p] != 0;
+  if (h && src[p] < 0) {          // answered by an entry stored before this batch
+    if (ent >= 0 && ent < capacity && threadIdx.x < k)
+      subset_out[((size_t)p * L + l) * k + threadIdx.x] = values[((size_t)ent * L + l) * k + threadIdx.x];
+    return;
   }
-  if (l == 0 && ent >= 0 && threadIdx.x == 0) knorm[ent] = enorm[p];
+  if (!do_route) return;
+  const int from = h ? src[p] : p;  // the embedding that defines the key of the answering entry
+  const bool owner = !h && ent >= 0;   // this prompt's miss created entry `ent`
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    const float v = E[(size_t)from * d + c];
+    e[c] = v;
+    if (l == 0 && owner) keys[(size_t)ent * d + c] = v;
+  }
   __syncthreads();
   block_router_scores(Wr + (size_t)l * G * d, e, d, G, s);
   int32_t *sel = reinterpret_cast<int32_t *>(s + 64);  // [64] after the scores
@@ -189,41 +178,19 @@ __global__ __launch_bounds__(256) void route_misses(const float *__restrict__ E,
   if (threadIdx.x < k) {
     const int32_t g = sel[threadIdx.x];
     subset_out[((size_t)p * L + l) * k + threadIdx.x] = g;
-    if (ent >= 0) values[((size_t)ent * L + l) * k + threadIdx.x] = g;
+    if (owner) values[((size_t)ent * L + l) * k + threadIdx.x] = g;
   }
-}
-
-__global__ void gather_hits(const int32_t *__restrict__ entry, const uint8_t *__restrict__ hit,
-                            const int32_t *__restrict__ values, int Lk, int capacity,
-                            int32_t *__restrict__ subset_out) {
-  const int p = blockIdx.x;
-  if (!hit[p]) return;
-  const int ent = entry[p];
-  if (ent < 0 || ent >= capacity) return;
-  for (int i = threadIdx.x; i < Lk; i += blockDim.x) subset_out[(size_t)p * Lk + i] = values[(size_t)ent * Lk + i];
 }
 
 __global__ void append_entry(const float *__restrict__ emb, const int32_t *__restrict__ subsets, int d, int Lk,
                              int32_t *__restrict__ count, int capacity, float *__restrict__ keys,
-                             float *__restrict__ knorm, int32_t *__restrict__ values) {
-  __shared__ float red[4];
+                             int32_t *__restrict__ values) {
   const int ent = *count;
   if (ent >= capacity) return;
-  float acc = 0.f;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    const float v = emb[c];
-    keys[(size_t)ent * d + c] = v;
-    acc += v * v;
-  }
+  for (int c = threadIdx.x; c < d; c += blockDim.x) keys[(size_t)ent * d + c] = emb[c];
   for (int i = threadIdx.x; i < Lk; i += blockDim.x) values[(size_t)ent * Lk + i] = subsets[i];
-  acc = wave_sum(acc);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    knorm[ent] = sqrtf(red[0] + red[1] + red[2] + red[3]);
-    __threadfence();
-    *count = ent + 1;
-  }
+  __syncthreads();   // one workgroup: every lane has read *count before it changes
+  if (threadIdx.x == 0) *count = ent + 1;
 }
 
 __global__ void set_i32(int32_t *p, int32_t v) { *p = v; }
@@ -258,13 +225,10 @@ int parse_cache_create(parse_cache **out, int32_t capacity, int32_t d, int32_t L
     if (e == hipSuccess) e = hipMalloc(p, round_up(bytes, 256));
   };
   alloc((void **)&c->keys, (size_t)capacity * d * sizeof(float));
-  alloc((void **)&c->knorm, (size_t)capacity * sizeof(float));
   alloc((void **)&c->values, (size_t)capacity * L * k * sizeof(int32_t));
   alloc((void **)&c->count, sizeof(int32_t));
   alloc((void **)&c->sims, (size_t)max_batch * ld * sizeof(float));
-  alloc((void **)&c->enorm, (size_t)max_batch * sizeof(float));
-  alloc((void **)&c->best_sim, (size_t)max_batch * sizeof(float));
-  alloc((void **)&c->best_idx, (size_t)max_batch * sizeof(int32_t));
+  alloc((void **)&c->src, (size_t)max_batch * sizeof(int32_t));
   alloc((void **)&c->entry, (size_t)max_batch * sizeof(int32_t));
   alloc((void **)&c->hit, (size_t)max_batch);
   if (e == hipSuccess) e = hipMemset(c->count, 0, sizeof(int32_t));
@@ -281,7 +245,7 @@ int parse_cache_create(parse_cache **out, int32_t capacity, int32_t d, int32_t L
 int parse_cache_destroy(parse_cache *c) {
   if (!c) return PARSE_EINVAL;
   (void)hipDeviceSynchronize();
-  void *ptrs[] = {c->keys, c->knorm, c->values, c->count, c->sims, c->enorm, c->best_sim, c->best_idx, c->entry, c->hit};
+  void *ptrs[] = {c->keys, c->values, c->count, c->sims, c->src, c->entry, c->hit};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   delete c;
@@ -315,7 +279,7 @@ int parse_cache_insert(parse_cache *c, const float *emb, const int32_t *subsets,
   if (n >= c->capacity) return PARSE_ECAPACITY;
   hipStream_t s = (hipStream_t)stream;
   hipLaunchKernelGGL(append_entry, dim3(1), dim3(256), 0, s, emb, subsets, c->d, c->L * c->k, c->count, c->capacity,
-                     c->keys, c->knorm, c->values);
+                     c->keys, c->values);
   PARSE_LAUNCH_CHECK();
   PARSE_HIP_TRY(hipStreamSynchronize(s));
   c->count_ub = n + 1;
@@ -329,22 +293,18 @@ int parse_cache_lookup(parse_cache *c, const float *emb, int32_t P, float tau, i
   if (!entry_out) return PARSE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
   const int ld = c->capacity + c->max_batch;
-  hipLaunchKernelGGL(emb_norms, dim3(P), dim3(64), 0, s, emb, c->d, c->enorm);
-  PARSE_LAUNCH_CHECK();
   const int ncols = c->count_ub < c->capacity ? c->count_ub : c->capacity;
   if (ncols > 0) {
-    hipLaunchKernelGGL(cache_sims, dim3((ncols + 3) / 4, P), dim3(256), 0, s, emb, c->d, c->keys, c->knorm, c->enorm,
-                       c->count, c->capacity, ncols, 0, ld, c->sims);
+    hipLaunchKernelGGL(cache_sims, dim3((ncols + 3) / 4, P), dim3(256), 0, s, emb, c->d, c->keys, c->count, c->capacity,
+                       ncols, 0, ld, c->sims);
     PARSE_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(best_existing, dim3(P), dim3(64), 0, s, c->sims, ld, c->count, c->best_sim, c->best_idx);
-  PARSE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(finish_lookup, dim3((P + 255) / 256), dim3(256), 0, s, c->best_sim, c->best_idx, P, tau,
-                     entry_out, c->hit, sim_out);
+  hipLaunchKernelGGL(resolve, dim3(1), dim3(1024), (size_t)P * 12, s, c->sims, ld, c->capacity, P, tau, 0, c->count,
+                     entry_out, c->hit, sim_out, c->src);
   PARSE_LAUNCH_CHECK();
   if (subset_out) {
-    hipLaunchKernelGGL(gather_hits, dim3(P), dim3(64), 0, s, entry_out, c->hit, c->values, c->L * c->k, c->capacity,
-                       subset_out);
+    hipLaunchKernelGGL(route_or_gather, dim3(c->L, P), dim3(256), 0, s, emb, c->d, (const float *)nullptr, 0, c->L,
+                       c->k, c->capacity, 0, entry_out, c->hit, c->src, c->keys, c->values, subset_out);
     PARSE_LAUNCH_CHECK();
   }
   return PARSE_OK;
@@ -363,23 +323,18 @@ int parse_cache_lookup_or_route(parse_cache *c, const float *emb, int32_t P, flo
   const int ld = c->capacity + c->max_batch;
   int32_t *entry = entry_out ? entry_out : c->entry;
   uint8_t *hit = hit_out ? hit_out : c->hit;
-  hipLaunchKernelGGL(emb_norms, dim3(P), dim3(64), 0, s, emb, c->d, c->enorm);
-  PARSE_LAUNCH_CHECK();
   const int ncols = c->count_ub < c->capacity ? c->count_ub : c->capacity;
-  hipLaunchKernelGGL(cache_sims, dim3((ncols + P + 3) / 4, P), dim3(256), 0, s, emb, c->d, c->keys, c->knorm,
-                     c->enorm, c->count, c->capacity, ncols, P, ld, c->sims);
-  PARSE_LAUNCH_CHECK();
+  if (ncols + P > 1) {   // a single prompt against an empty cache has nothing to compare with
+    hipLaunchKernelGGL(cache_sims, dim3((ncols + P + 3) / 4, P), dim3(256), 0, s, emb, c->d, c->keys, c->count,
+                       c->capacity, ncols, P, ld, c->sims);
+    PARSE_LAUNCH_CHECK();
+  }
   c->count_ub = (c->count_ub + P < c->capacity) ? c->count_ub + P : c->capacity;
-  hipLaunchKernelGGL(best_existing, dim3(P), dim3(64), 0, s, c->sims, ld, c->count, c->best_sim, c->best_idx);
+  hipLaunchKernelGGL(resolve, dim3(1), dim3(1024), (size_t)P * 12, s, c->sims, ld, c->capacity, P, tau, 1, c->count,
+                     entry, hit, sim_out, c->src);
   PARSE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(resolve, dim3(1), dim3(64), (size_t)P * sizeof(int32_t), s, c->sims, ld, c->capacity, P, tau,
-                     c->best_sim, c->best_idx, c->count, entry, hit, sim_out);
-  PARSE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(route_misses, dim3(c->L, P), dim3(256), (size_t)(c->d + 128) * sizeof(float), s, emb, c->d, Wr,
-                     G, c->L, c->k, c->enorm, entry, hit, c->keys, c->knorm, c->values, subset_out);
-  PARSE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(gather_hits, dim3(P), dim3(64), 0, s, entry, hit, c->values, c->L * c->k, c->capacity,
-                     subset_out);
+  hipLaunchKernelGGL(route_or_gather, dim3(c->L, P), dim3(256), (size_t)(c->d + 128) * sizeof(float), s, emb, c->d, Wr,
+                     G, c->L, c->k, c->capacity, 1, entry, hit, c->src, c->keys, c->values, subset_out);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }

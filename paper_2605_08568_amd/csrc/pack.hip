@@ -17,24 +17,29 @@ __global__ __launch_bounds__(kCopyThreads) void pack_slabs(const char *__restric
                                                            size_t v_slab_bytes, size_t u_slab_bytes, int G, int k,
                                                            const int32_t *__restrict__ subset, int subset_stride,
                                                            const int32_t *__restrict__ rep,
+                                                           const int32_t *__restrict__ slot,
+                                                           const uint8_t *__restrict__ skip, int n_slots,
                                                            const int32_t *__restrict__ n_patterns,
                                                            char *__restrict__ Vt_S, char *__restrict__ Ut_S) {
   const int j = blockIdx.z;
   if (n_patterns && j >= *n_patterns) return;
+  if (skip && skip[j]) return;
   int row = j;
   if (rep) {
     row = rep[j];
     if (row < 0) return;
   }
+  const int dst_slot = slot ? slot[j] : j;
+  if (dst_slot < 0 || dst_slot >= n_slots) return;
   const bool is_u = (int)blockIdx.y >= k;
-  const int slot = is_u ? blockIdx.y - k : blockIdx.y;
-  const int g = subset[(size_t)row * subset_stride + slot];
+  const int slot_in = is_u ? blockIdx.y - k : blockIdx.y;
+  const int g = subset[(size_t)row * subset_stride + slot_in];
   if (g < 0 || g >= G) return;
   const size_t slab = is_u ? u_slab_bytes : v_slab_bytes;
   const size_t base = (size_t)blockIdx.x * kCopyChunk;
   if (base >= slab) return;
   const char *src = (is_u ? Ut : Vt) + (size_t)g * slab;
-  char *dst = (is_u ? Ut_S : Vt_S) + ((size_t)j * k + slot) * slab;
+  char *dst = (is_u ? Ut_S : Vt_S) + ((size_t)dst_slot * k + slot_in) * slab;
   u32x4 v[kCopyUnroll];
 #pragma unroll
   for (int i = 0; i < kCopyUnroll; ++i) {
@@ -79,11 +84,12 @@ __global__ void to_mfma16_u(const uint16_t *__restrict__ src, int R, int m, uint
 }
 
 static int launch_pack(const parse_layer *L, const int32_t *subset, int subset_stride, int k, const int32_t *rep,
-                       const int32_t *n_patterns, int max_patterns, void *Vt_S, void *Ut_S, hipStream_t s) {
+                       const int32_t *slot, const uint8_t *skip, int n_slots, const int32_t *n_patterns,
+                       int max_patterns, void *Vt_S, void *Ut_S, hipStream_t s) {
   int st = check_layer(L);
   if (st != PARSE_OK) return st;
   if (!subset || !Vt_S || !Ut_S) return PARSE_EINVAL;
-  if (k <= 0 || max_patterns <= 0) return PARSE_EINVAL;
+  if (k <= 0 || max_patterns <= 0 || n_slots <= 0) return PARSE_EINVAL;
   if (k > L->G || subset_stride < k || max_patterns > 65535 || 2 * k > 65535) return PARSE_ESHAPE;
   if (!aligned16(Vt_S) || !aligned16(Ut_S)) return PARSE_EALIGN;
   const size_t gs = L->R / L->G, es = elem_size(L->dtype);
@@ -91,7 +97,7 @@ static int launch_pack(const parse_layer *L, const int32_t *subset, int subset_s
   const size_t big = vb > ub ? vb : ub;
   dim3 grid((unsigned)((big + kCopyChunk - 1) / kCopyChunk), 2 * k, max_patterns);
   hipLaunchKernelGGL(pack_slabs, grid, dim3(kCopyThreads), 0, s, (const char *)L->Vt, (const char *)L->Ut, vb, ub,
-                     L->G, k, subset, subset_stride, rep, n_patterns, (char *)Vt_S, (char *)Ut_S);
+                     L->G, k, subset, subset_stride, rep, slot, skip, n_slots, n_patterns, (char *)Vt_S, (char *)Ut_S);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }
@@ -104,13 +110,22 @@ extern "C" {
 
 int parse_pack_experts(const parse_layer *L, const int32_t *subset, int32_t k, void *Vt_S, void *Ut_S,
                        parse_stream stream) {
-  return launch_pack(L, subset, k, k, nullptr, nullptr, 1, Vt_S, Ut_S, (hipStream_t)stream);
+  return launch_pack(L, subset, k, k, nullptr, nullptr, nullptr, 1, nullptr, 1, Vt_S, Ut_S, (hipStream_t)stream);
 }
 
 int parse_pack_patterns(const parse_layer *L, const int32_t *subset, int32_t subset_stride, int32_t k,
                         const int32_t *rep, const int32_t *n_patterns, int32_t max_patterns, void *Vt_S, void *Ut_S,
                         parse_stream stream) {
-  return launch_pack(L, subset, subset_stride, k, rep, n_patterns, max_patterns, Vt_S, Ut_S, (hipStream_t)stream);
+  return launch_pack(L, subset, subset_stride, k, rep, nullptr, nullptr, max_patterns, n_patterns, max_patterns, Vt_S,
+                     Ut_S, (hipStream_t)stream);
+}
+
+int parse_pack_new_entries(const parse_layer *L, const int32_t *subset, int32_t subset_stride, int32_t k, int32_t P,
+                           const int32_t *entry, const uint8_t *hit, int32_t n_slots, void *Vt_S, void *Ut_S,
+                           parse_stream stream) {
+  if (!entry || !hit) return PARSE_EINVAL;
+  return launch_pack(L, subset, subset_stride, k, nullptr, entry, hit, n_slots, nullptr, P, Vt_S, Ut_S,
+                     (hipStream_t)stream);
 }
 
 int parse_layer_to_mfma16(const parse_layer *src, void *Vt_out, void *Ut_out, parse_stream stream) {

@@ -54,12 +54,14 @@ __global__ __launch_bounds__(kPoolThreads) void pool_partial(const void *__restr
   for (int i = 0; i < PER; ++i) dst[i] = acc[i];
 }
 
-__global__ __launch_bounds__(256) void route_finish(const float *__restrict__ partial, int Q, int rows, int d,
-                                                    const int32_t *__restrict__ tok_offsets,
-                                                    const float *__restrict__ Wr, int G, int k,
-                                                    int32_t *__restrict__ subset_out, int subset_stride,
-                                                    float *__restrict__ scores_out,
-                                                    float *__restrict__ emb_out) {
+constexpr int kFinishThreads = 1024;
+
+__global__ __launch_bounds__(kFinishThreads) void route_finish(const float *__restrict__ partial, int Q, int rows, int d,
+                                                               const int32_t *__restrict__ tok_offsets,
+                                                               const float *__restrict__ Wr, int G, int k,
+                                                               int32_t *__restrict__ subset_out, int subset_stride,
+                                                               float *__restrict__ scores_out,
+                                                               float *__restrict__ emb_out) {
   extern __shared__ float lds[];
   float *e = lds;          // [d]
   float *s = lds + d;      // [64]
@@ -67,12 +69,18 @@ __global__ __launch_bounds__(256) void route_finish(const float *__restrict__ pa
   const int a = clampi(tok_offsets[p], 0, rows);
   const int b = clampi(tok_offsets[p + 1], a, rows);
   const float inv = (b > a) ? 1.0f / (float)(b - a) : 0.f;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float acc = 0.f;
-    for (int q = 0; q < Q; ++q) acc += partial[((size_t)p * Q + q) * d + c];
-    const float v = acc * inv;
-    e[c] = v;
-    if (emb_out) emb_out[(size_t)p * d + c] = v;
+  // four columns per lane, the Q slice partials added in slice order (independent loads, fixed order of adds)
+  for (int c = threadIdx.x * 4; c < d; c += kFinishThreads * 4) {
+    const float *src = partial + (size_t)p * Q * d + c;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int q = 0; q < Q; ++q) {
+      const float4 v = *reinterpret_cast<const float4 *>(src + (size_t)q * d);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    *reinterpret_cast<float4 *>(e + c) = acc;
+    if (emb_out) *reinterpret_cast<float4 *>(emb_out + (size_t)p * d + c) = acc;
   }
   __syncthreads();
   block_router_scores(Wr, e, d, G, s);
@@ -131,7 +139,7 @@ int parse_route(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_
     hipLaunchKernelGGL(pool_partial<false>, grid, dim3(kPoolThreads), 0, s, X, rows, d, tok_offsets, Q, partial);
   PARSE_LAUNCH_CHECK();
   const size_t lds = (size_t)(d + 64) * sizeof(float);
-  hipLaunchKernelGGL(route_finish, dim3(P), dim3(256), lds, s, partial, Q, rows, d, tok_offsets, Wr, G, k,
+  hipLaunchKernelGGL(route_finish, dim3(P), dim3(kFinishThreads), lds, s, partial, Q, rows, d, tok_offsets, Wr, G, k,
                      subset_out, subset_stride, scores_out, emb_out);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;

@@ -207,6 +207,40 @@ def test_reorder_and_pack_in_operand_order():
         assert pa.bf16_to_bits(Us[j]).tobytes() == mfma16_u(Ur).tobytes()
 
 
+def test_pack_new_cache_entries_only():
+    say("pack keyed by cache entry: only this batch's new entries are packed, into their entry's slot")
+    lay = si.small_layer(404, 256, 512, 256, 8, "bf16")
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    d, L, k, P = 256, 1, 3, 10
+    rng = np.random.default_rng(405)
+    E, cid = si.clustered_embeddings(rng, P, d, 4, 0.05)
+    Wr = si.make_router(rng, L, 8, d)
+    oc = po.PatternCache(16, d, L, k)
+    e_ref, h_ref, s_ref = oc.lookup_or_route(E, 0.9, Wr)
+    cache = pa.Cache(16, d, L, k, P)
+    entry, hit, sim, subs = cache.lookup_or_route(torch.from_numpy(E).to(DEV), 0.9, torch.from_numpy(Wr).to(DEV))
+    Vs = torch.zeros((6, k * lay.gs, lay.n), dtype=torch.bfloat16, device=DEV)
+    Us = torch.zeros((6, k * lay.gs, lay.m), dtype=torch.bfloat16, device=DEV)
+    pa.pack_new_entries(dl, subs, L * k, k, entry, hit, Vs, Us)
+    torch.cuda.synchronize()
+    assert np.array_equal(entry.cpu().numpy(), e_ref) and np.array_equal(hit.cpu().numpy(), h_ref)
+    n_new = int((h_ref == 0).sum())
+    assert n_new == 4
+    for p in range(P):
+        if h_ref[p] == 0:
+            Vr, Ur = po.pack(lay.Vt_store, lay.Ut_store, s_ref[p, 0], lay.gs)
+            assert pa.bf16_to_bits(Vs[e_ref[p]]).tobytes() == mfma16_v(Vr).tobytes()
+            assert pa.bf16_to_bits(Us[e_ref[p]]).tobytes() == mfma16_u(Ur).tobytes()
+    assert torch.all(Vs[n_new:] == 0) and torch.all(Us[n_new:] == 0)     # slots of no new entry stay untouched
+    # a second batch of the same prompts hits everywhere: nothing is packed
+    Vs.zero_()
+    entry, hit, sim, subs = cache.lookup_or_route(torch.from_numpy(E).to(DEV), 0.9, torch.from_numpy(Wr).to(DEV))
+    pa.pack_new_entries(dl, subs, L * k, k, entry, hit, Vs, Us)
+    torch.cuda.synchronize()
+    assert int(hit.sum().item()) == P and torch.all(Vs == 0)
+    cache.close()
+
+
 def test_pack_skips_invalid_group_ids():
     say("pack: an id outside [0, G) leaves its slab untouched")
     lay = si.small_layer(403, 256, 256, 64, 4, "f32")
