@@ -41,7 +41,6 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--only-decode", action="store_true")
-    ap.add_argument("--decode-schedule", type=int, default=0, help="0 = one launch when possible, 1 = three launches")
     return ap.parse_args()
 
 
@@ -192,7 +191,6 @@ def bench_decode(args, torch, pa, si):
     ws = torch.empty(max(pa.lowrank_workspace_bytes(pa.PARSE_DECODE, layers[0][0], B, k),
                          pa.lowrank_workspace_bytes(pa.PARSE_DECODE, layers[0][2], B, k)), dtype=torch.uint8, device=dev)
     pt = pa.Patterns(k, 4, subsets=subsets)
-    pa.set_decode_schedule(args.decode_schedule)
 
     def step(s, ev=None):
         trip = layers[s % copies]

@@ -211,11 +211,6 @@ size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *layer, int
  * kernel, 2 = always two launches (PARSE_EWORKSPACE from the forward call if it got no workspace).
  * Process-wide; not thread-safe against concurrent forward calls. */
 int parse_set_prefill_schedule(int32_t schedule);
-/* How a decode call is scheduled: 0 = ONE launch when the shape allows it (default; rank blocks < half the
- * compute units), 1 = always three launches.  Process-wide.  The one-launch form keeps two counters per call
- * in a library-owned device array of 64 slots used in rotation: decode calls must not overlap on one GPU by
- * more than 64 calls in flight, and calls on different streams of one GPU must not run concurrently. */
-int parse_set_decode_schedule(int32_t schedule);
 /* PARSE_PREFILL  Y[t] = A_S (B_S^T x_t) for every token t of prompt p, S = pattern pattern_id[p]
  *                (Eq. 4 / Eq. 10), read from the packed factors.  bf16 layers must be PARSE_MFMA16:
  *                both products on the bf16 matrix cores with fp32 accumulation, the r_S-wide

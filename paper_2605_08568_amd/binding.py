@@ -78,7 +78,6 @@ def lib():
     L.parse_lowrank_workspace_bytes.restype = sz
     L.parse_lowrank_workspace_bytes.argtypes = [i32, C.POINTER(_Layer), i32, i32]
     L.parse_set_prefill_schedule.restype = C.c_int; L.parse_set_prefill_schedule.argtypes = [i32]
-    L.parse_set_decode_schedule.restype = C.c_int; L.parse_set_decode_schedule.argtypes = [i32]
     L.parse_lowrank_forward.restype = C.c_int
     L.parse_lowrank_forward.argtypes = [i32, C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, i32, vp, vp,
                                         sz, vp]
@@ -308,11 +307,6 @@ def lowrank_workspace_bytes(mode: int, layer: Layer, rows: int, k: int) -> int:
 def set_prefill_schedule(schedule: int):
     """parse_set_prefill_schedule: 0 = by size, 1 = fused kernel, 2 = two launches."""
     _check(lib().parse_set_prefill_schedule(schedule), "parse_set_prefill_schedule")
-
-
-def set_decode_schedule(schedule: int):
-    """parse_set_decode_schedule: 0 = one launch when possible, 1 = three launches."""
-    _check(lib().parse_set_decode_schedule(schedule), "parse_set_decode_schedule")
 
 
 def lowrank_forward(mode: int, layer: Layer, patterns: Patterns, X, tok_offsets, pattern_id, Y=None,

@@ -9,7 +9,6 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
                          size_t workspace_bytes, hipStream_t s);
 size_t prefill_split_workspace_bytes(int rows, int rS);
 void set_prefill_schedule(int v);
-void set_decode_schedule(int v);
 size_t prefill_lds_bytes(int BM, int rS);
 size_t decode_workspace_bytes(const parse_layer *L);
 int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *x, int B,
@@ -25,12 +24,6 @@ size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *L, int32_t
   if (mode == PARSE_DECODE) return decode_workspace_bytes(L);
   if (L->dtype == PARSE_F32) return round_up((size_t)rows * k * (L->R / L->G) * sizeof(float), 256);
   return prefill_split_workspace_bytes(rows, k * (L->R / L->G));
-}
-
-int parse_set_decode_schedule(int32_t schedule) {
-  if (schedule < 0 || schedule > 1) return PARSE_EINVAL;
-  set_decode_schedule(schedule);
-  return PARSE_OK;
 }
 
 int parse_set_prefill_schedule(int32_t schedule) {

@@ -375,21 +375,15 @@ def test_prefill_config1_full_size_sampled():
 # ------------------------------------------------------------------ a7 decode
 @pytest.mark.parametrize("n,m,R,G,k,B,npat,schedule", [
     (1024, 1536, 640, 20, 10, 32, 4, 0),
-    (1024, 1536, 640, 20, 10, 32, 4, 1),
     (512, 256, 256, 8, 3, 5, 2, 0),
-    (512, 256, 256, 8, 3, 5, 2, 1),
-    (2752, 1024, 640, 20, 10, 32, 4, 0),   # n/16 not divisible by the wavefront / slice count
-    (2752, 1024, 640, 20, 10, 32, 4, 1),
-    (4096, 11008, 2560, 20, 10, 32, 4, 0), # the decode workload's gate/up shape, one launch
-    (512, 16384, 256, 8, 3, 32, 3, 0),     # many column blocks per phase-2 worker
+    (2752, 1024, 640, 20, 10, 32, 4, 0),   # n/16 not divisible by the slice count
+    (4096, 11008, 2560, 20, 10, 32, 4, 0), # the decode workload's gate/up shape (two column blocks per workgroup)
+    (11008, 4096, 2560, 20, 10, 32, 4, 0), # the decode workload's down shape
+    (512, 16384, 96, 3, 2, 32, 3, 0),      # three rank blocks (a partial quad), many column blocks
 ])
 def test_decode_matches_oracle_and_prefill(n, m, R, G, k, B, npat, schedule):
     say(f"decode n={n} m={m} R={R} G={G} k={k} B={B} patterns={npat} schedule={schedule}")
-    pa.set_decode_schedule(schedule)
-    try:
-        _decode_case(n, m, R, G, k, B, npat)
-    finally:
-        pa.set_decode_schedule(0)
+    _decode_case(n, m, R, G, k, B, npat)
 
 
 def _decode_case(n, m, R, G, k, B, npat):
