@@ -22,8 +22,9 @@ struct GtArgs {
   int ntiles, nchunks, GT;  // token tiles, factor-row chunks, token tiles per locality group
 };
 
-template <int BT, int NB>
+template <int BT, int NB, int DEPTH>
 __global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
+  constexpr int TPI = DEPTH / 4;   // staged tiles per unrolled loop iteration = ring depth in tiles
   constexpr int NT = BT / 32;
   constexpr int XP = BT * PF_BK / 8 / PF_THREADS;
   constexpr int xld = PF_BK + PF_XPAD;
@@ -74,12 +75,12 @@ __global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
     u32x4 xr[2][XP];
-    u32x4 fr[PF_DEPTH][NB];
+    u32x4 fr[DEPTH][NB];
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < XP; ++i) xr[0][i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
 #pragma unroll
-    for (int d = 0; d < PF_DEPTH; ++d)
+    for (int d = 0; d < DEPTH; ++d)
 #pragma unroll
       for (int i = 0; i < NB; ++i) fr[d][i] = *reinterpret_cast<const u32x4 *>(fbase[i] + d * kstride);
 #pragma unroll
@@ -87,24 +88,24 @@ __global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
 #pragma unroll
     for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(Xs + xdst[i]) = xr[0][i];
     __syncthreads();
-    for (int kt0 = 0; kt0 < nkt; kt0 += 2) {
+    for (int kt0 = 0; kt0 < nkt; kt0 += TPI) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int kt = kt0 + u;
+      for (int u = 0; u < TPI; ++u) {
+        const int kt = kt0 + u;   // LDS buffer = u & 1 (TPI is even)
         const int ktn = min(kt + 2, nkt - 1);
 #pragma unroll
-        for (int i = 0; i < XP; ++i) xr[u][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)ktn * PF_BK);
+        for (int i = 0; i < XP; ++i) xr[u & 1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + (size_t)ktn * PF_BK);
         bf16x8 xb[2][NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-          xb[0][t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + u * BT * xld + t * 32 * xld + xoff));
+          xb[0][t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + (u & 1) * BT * xld + t * 32 * xld + xoff));
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
           if (s < 3) {
 #pragma unroll
             for (int t = 0; t < NT; ++t)
               xb[(s + 1) & 1][t] =
-                  as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + u * BT * xld + t * 32 * xld + xoff + (s + 1) * 16));
+                  as_bf16x8(*reinterpret_cast<const u32x4 *>(Xs + (u & 1) * BT * xld + t * 32 * xld + xoff + (s + 1) * 16));
           }
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -112,13 +113,13 @@ __global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
 #pragma unroll
             for (int t = 0; t < NT; ++t)
               acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fr[u * 4 + s][i]), xb[s & 1][t], acc[t][i], 0, 0, 0);
-          const int kbn = min(kt * 4 + s + PF_DEPTH, nkb - 1);
+          const int kbn = min(kt * 4 + s + DEPTH, nkb - 1);
 #pragma unroll
           for (int i = 0; i < NB; ++i) fr[u * 4 + s][i] = *reinterpret_cast<const u32x4 *>(fbase[i] + kbn * kstride);
           __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(Xs + (u ^ 1) * BT * xld + xdst[i]) = xr[u ^ 1][i];
+        for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(Xs + ((u & 1) ^ 1) * BT * xld + xdst[i]) = xr[(u & 1) ^ 1][i];
         __syncthreads();
       }
     }
@@ -143,13 +144,13 @@ __global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
   }
 }
 
-template <int BT, int NB>
+template <int BT, int NB, int DEPTH>
 static int launch_gemm_tokens(GtArgs a, int GT, hipStream_t s) {
   a.ntiles = (a.rows + BT - 1) / BT;
   a.nchunks = (a.M / 32 + 4 * NB - 1) / (4 * NB);
   a.GT = GT;
   const int groups = (a.ntiles + GT - 1) / GT;
-  hipLaunchKernelGGL((gemm_tokens<BT, NB>), dim3(groups * GT * a.nchunks), dim3(PF_THREADS), 0, s, a);
+  hipLaunchKernelGGL((gemm_tokens<BT, NB, DEPTH>), dim3(groups * GT * a.nchunks), dim3(PF_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }
@@ -166,13 +167,14 @@ int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows
   GtArgs g1{p.X, p.Vt_S, Z, p.tok_offsets, p.pattern_id, (size_t)p.rS * p.n, p.n / 16, 1,
             p.n, p.rS, p.rows, p.P, p.n_patterns, 0, 0, 0};
   int gt64 = avg_prompt_rows / 64;  gt64 = gt64 < 1 ? 1 : (gt64 > 8 ? 8 : gt64);
-  int st = launch_gemm_tokens<64, 2>(g1, gt64, s);
+  // a deeper operand ring when the reduction length is a whole number of ring periods
+  int st = (p.n % (PF_BK * 4) == 0) ? launch_gemm_tokens<64, 2, 16>(g1, gt64, s) : launch_gemm_tokens<64, 2, 8>(g1, gt64, s);
   if (st != PARSE_OK) return st;
   // launch 2: factor rows = output columns (operand (cb, kb) at kb*(m/32) + cb), tokens = Z
   GtArgs g2{Z, p.Ut_S, p.Y, p.tok_offsets, p.pattern_id, (size_t)p.rS * p.m, 1, p.m / 32,
             p.rS, p.m, p.rows, p.P, p.n_patterns, 0, 0, 0};
   int gt128 = avg_prompt_rows / 128;  gt128 = gt128 < 1 ? 1 : (gt128 > 8 ? 8 : gt128);
-  return launch_gemm_tokens<128, 2>(g2, gt128, s);
+  return (p.rS % (PF_BK * 4) == 0) ? launch_gemm_tokens<128, 2, 16>(g2, gt128, s) : launch_gemm_tokens<128, 2, 8>(g2, gt128, s);
 }
 
 }  // namespace parse
