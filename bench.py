@@ -152,7 +152,7 @@ def bench_prefill(args, torch, pa, si):
         "cache_hits": hits, "forward_us_by_schedule": sched_us, "cold_step_ms": round(cold_ms, 4),
         "roofline": {"bound": "mfma", "kernel": "gemm_tokens x2 (two-launch schedule)" if sched_us["two_launch"] <= sched_us["fused"] else "prefill_fused", "achieved": round(achieved, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": traffic_from_profiles("prefill_fused_config1"),
+                     "traffic": traffic_from_profiles("prefill_config1"),
                      "launch_us": round(per["forward"], 2)},
         "workload": w,
     }
