@@ -4,10 +4,10 @@
 // order (1 KiB coalesced per wavefront instruction, no LDS hop, no packed copies), and apply it to all
 // sequences at once on the matrix cores (32 sequences = the N side of a 32x32x16 instruction).  A sequence
 // whose pattern does not hold a group gets a zero in that group's part of z, so it contributes nothing.
-// Three launches: decode_z (Vt stream -> fp32 partials of z per slice of n), decode_zfin (tiny: sum, mask,
-// round, operand order), decode_y (Ut stream -> y).  A compute unit sustains only about 50 GB/s of cache-line
-// fills, so both streams are cut into at least as many workgroups as there are units, and the small operands
-// (x, z) are shared inside a workgroup instead of being re-fetched per factor operand.
+// Three launches: decode_z (Vt stream -> fp32 partials of z per slice of n), decode_zfin (tiny: adds the slices
+// up in slice order, masks, rounds, operand order), decode_y (Ut stream -> y).  A compute unit sustains only
+// about 50 GB/s of cache-line fills, so both streams are cut into about as many workgroups as there are units,
+// and the small operands (x, z) are shared inside a workgroup instead of being re-fetched per factor operand.
 // The streaming loops are branch-free: operand lists are walked in chunks with fetches past the end clamped
 // to the last valid operand and their contribution switched off by zeroing the small operand.
 #include "common.hpp"
@@ -16,12 +16,12 @@ namespace parse {
 
 constexpr int DZ_WAVES = 8, DZ_THREADS = DZ_WAVES * 64;
 constexpr int DY_WAVES = 8, DY_THREADS = DY_WAVES * 64;
-constexpr int DEC_CHUNK = 8;       // operands fetched per chunk; two chunks in flight per wavefront
+constexpr int DEC_CHUNK = 4;       // operands fetched per chunk; four chunks in flight per wavefront
 constexpr int DEC_MAXG = 64;
-constexpr int DZ_MAXSLICE = 32;    // reduction steps (of 16 columns) of x staged per decode_z task
+constexpr int DZ_MAXSLICE = 64;    // reduction steps (of 16 columns) of x staged per decode_z task
 constexpr int DZ_XLD = DZ_MAXSLICE * 16 + 8;
 constexpr int DEC_MAX_SLICES = 64; // slices of n the workspace is sized for
-constexpr int DY_MAXK = 20;        // reduction blocks per wavefront whose operands are requested at once
+constexpr int DY_CHUNK = 4;        // decode_y: operands per chunk after the first block
 constexpr int DY_MAXKB = 1024;     // selected reduction blocks a decode_y workgroup can list
 
 __device__ __forceinline__ bf16x8 dec_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -49,17 +49,21 @@ __device__ __forceinline__ void build_group_masks(const int32_t *__restrict__ su
 // decode_z: z partials.  grid = nquads * S tasks; task = (four consecutive 32-rank blocks, slice s of n).
 // The slice of the token rows x is staged in LDS once (coalesced row reads; the matrix-core operand read
 // pattern is only ever applied to LDS) and shared by the four rank blocks; wavefront w owns rank block w % 4
-// and half w / 4 of the slice; its Vt operands come straight from the store, two chunks in flight; the two
-// halves add up through LDS; fp32 partials go to the workspace.  Rank blocks of groups nobody selected are
-// skipped (nothing of them is read).
+// and half w / 4 of the slice; its Vt operands come straight from the store, four chunks in flight; the two
+// halves add up through LDS; fp32 partials go to the workspace as zp[quad][slice][piece][8], a piece being the
+// 8 ranks x 1 sequence that one lane of the next product holds, so that both this kernel's stores and
+// decode_zfin's loads are contiguous per wavefront.  Rank blocks of groups nobody selected are skipped (nothing
+// of them is read or written).  Workgroup 0 also lists the groups selected by at least one sequence
+// (ascending) for decode_y.
 __global__ __launch_bounds__(DZ_THREADS) void decode_z(const uint16_t *__restrict__ Vt, const uint16_t *__restrict__ x,
                                                        int B, int n, int R, int G, int gs,
                                                        const int32_t *__restrict__ subsets, int stride, int k,
                                                        int n_patterns, const int32_t *__restrict__ pattern_id, int S,
-                                                       float *__restrict__ zp) {
-  __shared__ float red[4][16][64];                                   // 16 KiB
-  __shared__ __attribute__((aligned(16))) uint16_t xs[32 * DZ_XLD];  // 66 KiB
+                                                       float *__restrict__ zp,
+                                                       int32_t *__restrict__ used_out /* [0] = count, [1..] = ids */) {
+  __shared__ __attribute__((aligned(16))) uint16_t xs[32 * DZ_XLD];  // 66 KiB; reused for the halves' sum
   __shared__ uint32_t gmask[DEC_MAXG];
+  float(*red)[16][64] = reinterpret_cast<float(*)[16][64]>(xs);       // [4][16][64] floats = 16 KiB
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, q = lane >> 5;
   const int nkb = n / 16, nrb = R / 32;
@@ -69,12 +73,11 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_z(const uint16_t *__restric
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int rbl = wave_s & 3, half = wave_s >> 2;
   const int rb = quad * 4 + rbl;
-  // Vt operands of the first two chunks are requested before anything else: they depend on nothing
   const int h0 = (len * half) / 2, h1 = (len * (half + 1)) / 2;      // this wavefront's steps of the slice
   const int cnt_all = rb < nrb ? h1 - h0 : 0;
   const char *vblock = reinterpret_cast<const char *>(Vt) + ((size_t)min(rb, nrb - 1) * nkb + w0 + h0) * 1024;
   const uint32_t lane_off = lane * 16;
-  u32x4 V0[DEC_CHUNK], V1[DEC_CHUNK];
+  u32x4 V0[DEC_CHUNK], V1[DEC_CHUNK], V2[DEC_CHUNK], V3[DEC_CHUNK];
   auto load_v = [&](u32x4 *V, int base, int cnt) {
 #pragma unroll
     for (int i = 0; i < DEC_CHUNK; ++i)
@@ -92,6 +95,12 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_z(const uint16_t *__restric
   if (threadIdx.x < DEC_MAXG) gmask[threadIdx.x] = 0;
   __syncthreads();
   build_group_masks(subsets, stride, k, n_patterns, pattern_id, B, G, gmask);
+  if (blockIdx.x == 0 && threadIdx.x < 64) {
+    const bool u = lane < G && gmask[lane] != 0u;
+    const unsigned long long mask = __ballot(u);
+    if (u) used_out[1 + __popcll(mask & ((1ull << lane) - 1ull))] = lane;
+    if (lane == 0) used_out[0] = __popcll(mask);
+  }
   bool any = false;
   for (int i = 0; i < 4; ++i) {
     const int r = quad * 4 + i;
@@ -102,6 +111,8 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_z(const uint16_t *__restric
   const int cnt = live ? cnt_all : 0;
   load_v(V0, 0, cnt);
   load_v(V1, DEC_CHUNK, cnt);
+  load_v(V2, 2 * DEC_CHUNK, cnt);
+  load_v(V3, 3 * DEC_CHUNK, cnt);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int piece = i * DZ_THREADS + threadIdx.x;
@@ -124,94 +135,79 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_z(const uint16_t *__restric
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(V[i]), dec_bf16x8(base + i < cnt ? xv : zero), acc, 0, 0, 0);
     }
   };
-  for (int c0 = 0; c0 < cnt; c0 += 2 * DEC_CHUNK) {
+  for (int c0 = 0; c0 < cnt; c0 += 4 * DEC_CHUNK) {
     compute(V0, c0);
     __builtin_amdgcn_sched_barrier(0);
-    load_v(V0, c0 + 2 * DEC_CHUNK, cnt);
+    load_v(V0, c0 + 4 * DEC_CHUNK, cnt);
     __builtin_amdgcn_sched_barrier(0);
     compute(V1, c0 + DEC_CHUNK);
     __builtin_amdgcn_sched_barrier(0);
-    load_v(V1, c0 + 3 * DEC_CHUNK, cnt);
+    load_v(V1, c0 + 5 * DEC_CHUNK, cnt);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(V2, c0 + 2 * DEC_CHUNK);
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(V2, c0 + 6 * DEC_CHUNK, cnt);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(V3, c0 + 3 * DEC_CHUNK);
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(V3, c0 + 7 * DEC_CHUNK, cnt);
     __builtin_amdgcn_sched_barrier(0);
   }
-  // halves add up: wavefronts 4..7 hand their tile to 0..3
+  __syncthreads();      // every wavefront is done with the x slice; its LDS now holds the halves' sum
   if (half == 1) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) red[rbl][e][lane] = acc[e];
   }
   __syncthreads();
+  float *zq = zp + (size_t)quad * S * 4096;   // this quad's partials: [S][512 pieces][8]
   if (half == 0 && live) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] += red[rbl][e][lane];
-    // lane: sequence l32, ranks rb*32 + 8*blk + 4*q + (0..3)
-    float *dst = zp + ((size_t)sl * 32 + l32) * R + rb * 32 + q * 4;
+    // entries of sequences whose pattern does not hold the rank's group are zero in z
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      const bool member = (gmask[(rb * 32 + 8 * blk + 4 * q) / gs] >> l32) & 1u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[blk * 4 + j] = member ? acc[blk * 4 + j] : 0.f;
+    }
+    // lane: sequence l32, local ranks rbl*32 + 8*blk + 4*q + (0..3) = piece (rbl*4 + blk)*32 + l32, floats 4q..4q+3
+    float *dst = zq + (size_t)sl * 4096 + ((rbl * 4) * 32 + l32) * 8 + q * 4;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
-      *reinterpret_cast<float4 *>(dst + blk * 8) = float4{acc[blk * 4], acc[blk * 4 + 1], acc[blk * 4 + 2], acc[blk * 4 + 3]};
+      *reinterpret_cast<float4 *>(dst + blk * 256) = float4{acc[blk * 4], acc[blk * 4 + 1], acc[blk * 4 + 2], acc[blk * 4 + 3]};
   }
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// decode_zfin: z = sum of the S slices (in slice order), masked by pattern membership, rounded to bf16, stored in
-// operand order: piece o = (kb*2 + q)*32 + b holds z[b][16kb + 8q + (0..7)].  Lane (piece, slice) fetches one
-// 32-byte partial so that all slices of a piece are in flight together.  Block 0 also lists the groups selected
-// by at least one sequence (ascending) for decode_y.  grid = ceil(pieces / (DZF_THREADS / S)).
-constexpr int DZF_THREADS = 512;
-__global__ __launch_bounds__(DZF_THREADS) void decode_zfin(const float *__restrict__ zp, int S, int B, int R, int G,
-                                                           int gs, const int32_t *__restrict__ subsets, int stride,
-                                                           int k, int n_patterns,
-                                                           const int32_t *__restrict__ pattern_id,
-                                                           uint16_t *__restrict__ zf,
-                                                           int32_t *__restrict__ used_out /* [0] = count, [1..] = ids */) {
-  __shared__ uint32_t gmask[DEC_MAXG];
-  __shared__ __attribute__((aligned(16))) float part[DZF_THREADS * 8];
-  if (threadIdx.x < DEC_MAXG) gmask[threadIdx.x] = 0;
-  __syncthreads();
-  build_group_masks(subsets, stride, k, n_patterns, pattern_id, B, G, gmask);
-  if (blockIdx.x == 0 && threadIdx.x < 64) {
-    const int lane = threadIdx.x;
-    const bool u = lane < G && gmask[lane] != 0u;
-    const unsigned long long mask = __ballot(u);
-    if (u) used_out[1 + __popcll(mask & ((1ull << lane) - 1ull))] = lane;
-    if (lane == 0) used_out[0] = __popcll(mask);
+// decode_zfin: z = sum of the S slices (in slice order), rounded to bf16, stored in operand order: piece
+// o = (kb*2 + q)*32 + b holds z[b][16kb + 8q + (0..7)] (the partials use the same piece numbering and are
+// already masked).  One wavefront per workgroup, one piece per lane, the loads of eight slices in flight at
+// once.  Pieces of rank blocks nobody selected hold whatever the workspace held; decode_y never reads them.
+__global__ __launch_bounds__(64) void decode_zfin(const float *__restrict__ zp, int S, int R, uint16_t *__restrict__ zf) {
+  const int o = blockIdx.x * 64 + threadIdx.x;   // piece
+  const int quad = o >> 9, t = o & 511;
+  if ((o >> 5) * 8 >= R) return;
+  float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const float *src = zp + ((size_t)quad * S * 512 + t) * 8;
+#pragma unroll 8
+  for (int s2 = 0; s2 < S; ++s2) {
+    const float4 f0 = *reinterpret_cast<const float4 *>(src + (size_t)s2 * 4096);
+    const float4 f1 = *reinterpret_cast<const float4 *>(src + (size_t)s2 * 4096 + 4);
+    v[0] += f0.x; v[1] += f0.y; v[2] += f0.z; v[3] += f0.w;
+    v[4] += f1.x; v[5] += f1.y; v[6] += f1.z; v[7] += f1.w;
   }
-  const int pieces = R * 4;
-  const int per_block = DZF_THREADS / S;
-  const int pl = threadIdx.x / S, sl = threadIdx.x - pl * S;
-  const int o = blockIdx.x * per_block + pl;
-  float4 f0 = {0, 0, 0, 0}, f1 = {0, 0, 0, 0};
-  if (pl < per_block && o < pieces) {
-    const int b = o & 31, q2 = (o >> 5) & 1, kb = o >> 6;
-    const int r0 = kb * 16 + q2 * 8;
-    if ((gmask[r0 / gs] >> b) & 1u) {
-      const float *src = zp + ((size_t)sl * 32 + b) * R + r0;
-      f0 = *reinterpret_cast<const float4 *>(src);
-      f1 = *reinterpret_cast<const float4 *>(src + 4);
-    }
-  }
-  *reinterpret_cast<float4 *>(part + (size_t)threadIdx.x * 8) = f0;
-  *reinterpret_cast<float4 *>(part + (size_t)threadIdx.x * 8 + 4) = f1;
-  __syncthreads();
-  const int o2 = blockIdx.x * per_block + threadIdx.x;
-  if ((int)threadIdx.x < per_block && o2 < pieces) {
-    float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int s2 = 0; s2 < S; ++s2) {
-      const float *pp = part + ((size_t)threadIdx.x * S + s2) * 8;
+  u32x4 w;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += pp[e];
-    }
-    u32x4 w;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
-    *reinterpret_cast<u32x4 *>(zf + (size_t)o2 * 8) = w;
-  }
+  for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+  *reinterpret_cast<u32x4 *>(zf + (size_t)o * 8) = w;
 }
 
 // ---------------------------------------------------------------------------------------------------------
 // decode_y: y.  grid = ceil(ncb / NC) workgroups, each owns NC (1 or 2) consecutive 32-column output blocks;
 // wavefront w owns an eighth of the selected reduction blocks for all NC column blocks, so one z operand
-// (cache-resident) feeds NC products; all its Ut operands (up to DY_MAXK reduction blocks) are requested at
-// once, the rest is streamed in chunks; the eight wavefronts add up through LDS.
+// (cache-resident) feeds NC products; the Ut operands of its first MAXK reduction blocks are requested at
+// once (MAXK sized so that everything stays in registers), the rest is streamed in chunks; the eight wavefronts
+// add up through LDS.
 template <int NC>
 __global__ __launch_bounds__(DY_THREADS) void decode_y(const uint16_t *__restrict__ Ut, const uint16_t *__restrict__ zf,
                                                        int B, int m, int G, int gs,
@@ -244,6 +240,8 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(const uint16_t *__restric
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
   const u32x4 zero = {0, 0, 0, 0};
+  constexpr int DY_MAXK = NC > 1 ? 16 : 20;
+  constexpr int DEC_CHUNK = DY_CHUNK;
   if (cnt > 0) {
     u32x4 ur[DY_MAXK][NC], zr[DY_MAXK];
 #pragma unroll
@@ -309,21 +307,36 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(const uint16_t *__restric
   }
 }
 
-// slices of n: about two tasks per compute unit, a slice no longer than DZ_MAXSLICE steps, at most DEC_MAX_SLICES
-static int decode_slices(int n, int R, int n_cu) {
+// Slices of n: about one task per compute unit over the rank quads that can be selected at all (the host knows
+// k and the number of patterns, not the subsets), a slice no longer than DZ_MAXSLICE steps, at most
+// DEC_MAX_SLICES slices.
+static int decode_slices(int n, int R, int gs, int G, int k, int n_patterns, int n_cu) {
   const int nkb = n / 16, nquads = (R / 32 + 3) / 4;
-  int S = (2 * n_cu + nquads - 1) / nquads;
+  long long groups = (long long)k * n_patterns;
+  if (groups > G) groups = G;
+  int live = (int)((groups * gs + 127) / 128);
+  if (live > nquads) live = nquads;
+  if (live < 1) live = 1;
+  int S = (n_cu + live - 1) / live;
   const int s_min = (nkb + DZ_MAXSLICE - 1) / DZ_MAXSLICE;
   if (S < s_min) S = s_min;
-  if (S > DEC_MAX_SLICES) S = DEC_MAX_SLICES;
+  if (S > DEC_MAX_SLICES) S = DEC_MAX_SLICES;   // decode_supported() keeps the slice within DZ_MAXSLICE
   if (S > nkb) S = nkb;
   if (S < 1) S = 1;
   return S;
 }
 
+static size_t dec_zp_bytes(const parse_layer *L) {
+  const int nquads = (L->R / 32 + 3) / 4;
+  return round_up((size_t)DEC_MAX_SLICES * nquads * 4096 * sizeof(float), 256);
+}
+static size_t dec_zf_bytes(const parse_layer *L) {
+  const int nquads = (L->R / 32 + 3) / 4;
+  return round_up((size_t)nquads * 4096 * sizeof(uint16_t), 256);
+}
+
 size_t decode_workspace_bytes(const parse_layer *L) {
-  return round_up((size_t)DEC_MAX_SLICES * 32 * L->R * sizeof(float), 256) +
-         round_up((size_t)L->R * 32 * sizeof(uint16_t), 256) + round_up((DEC_MAXG + 1) * sizeof(int32_t), 256);
+  return dec_zp_bytes(L) + dec_zf_bytes(L) + round_up((DEC_MAXG + 1) * sizeof(int32_t), 256);
 }
 
 bool decode_supported(const parse_layer *L) {
@@ -334,26 +347,26 @@ bool decode_supported(const parse_layer *L) {
 int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *x, int B,
                         const int32_t *pattern_id, uint16_t *y, void *workspace, hipStream_t s) {
   const int gs = L->R / L->G;
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0;
+  static int n_cu_of[64] = {0};
+  int dev = 0;
+  PARSE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return PARSE_EINVAL;
+  if (n_cu_of[dev] == 0) {
     hipDeviceProp_t prop;
-    PARSE_HIP_TRY(hipGetDevice(&dev));
     PARSE_HIP_TRY(hipGetDeviceProperties(&prop, dev));
-    n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    n_cu_of[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
+  const int n_cu = n_cu_of[dev];
   if (!decode_supported(L)) return PARSE_ESHAPE;
-  const int S = decode_slices(L->n, L->R, n_cu);
+  const int S = decode_slices(L->n, L->R, gs, L->G, pt->k, pt->n_patterns, n_cu);
   float *zp = reinterpret_cast<float *>(workspace);
-  uint16_t *zf = reinterpret_cast<uint16_t *>((char *)workspace + round_up((size_t)DEC_MAX_SLICES * 32 * L->R * sizeof(float), 256));
-  int32_t *used = reinterpret_cast<int32_t *>((char *)zf + round_up((size_t)L->R * 32 * sizeof(uint16_t), 256));
+  uint16_t *zf = reinterpret_cast<uint16_t *>((char *)workspace + dec_zp_bytes(L));
+  int32_t *used = reinterpret_cast<int32_t *>((char *)zf + dec_zf_bytes(L));
   const int nquads = (L->R / 32 + 3) / 4, ncb = L->m / 32;
   hipLaunchKernelGGL(decode_z, dim3(nquads * S), dim3(DZ_THREADS), 0, s, (const uint16_t *)L->Vt, x, B, L->n, L->R, L->G,
-                     gs, pt->subsets, pt->subset_stride, pt->k, pt->n_patterns, pattern_id, S, zp);
+                     gs, pt->subsets, pt->subset_stride, pt->k, pt->n_patterns, pattern_id, S, zp, used);
   PARSE_LAUNCH_CHECK();
-  const int per_block = DZF_THREADS / S;
-  hipLaunchKernelGGL(decode_zfin, dim3((L->R * 4 + per_block - 1) / per_block), dim3(DZF_THREADS), 0, s, zp, S, B, L->R,
-                     L->G, gs, pt->subsets, pt->subset_stride, pt->k, pt->n_patterns, pattern_id, zf, used);
+  hipLaunchKernelGGL(decode_zfin, dim3(nquads * 8), dim3(64), 0, s, zp, S, L->R, zf);
   PARSE_LAUNCH_CHECK();
   // two column blocks per workgroup (one z operand feeds two products) once that still gives every unit a workgroup
   if (ncb >= n_cu) {
