@@ -42,6 +42,7 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patter
   if (rows <= 0 || P <= 0 || pt->n_patterns <= 0 || pt->k <= 0) return PARSE_EINVAL;
   if (pt->k > L->G || P > rows) return PARSE_ESHAPE;
   if (!aligned16(X) || !aligned16(Y)) return PARSE_EALIGN;
+  if (mode == PARSE_DECODE && (L->dtype != PARSE_BF16 || L->layout != PARSE_MFMA16)) return PARSE_ELAYOUT;
   const size_t need = parse_lowrank_workspace_bytes(mode, L, rows, pt->k);
   // bf16 prefill may run without a workspace (fused kernel only); every other mode needs the queried size
   const bool optional_ws = mode == PARSE_PREFILL && L->dtype == PARSE_BF16 && workspace == nullptr;
@@ -51,7 +52,6 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patter
   const int gs = L->R / L->G, rS = pt->k * gs;
 
   if (mode == PARSE_DECODE) {
-    if (L->dtype != PARSE_BF16 || L->layout != PARSE_MFMA16) return PARSE_ELAYOUT;
     if (!pt->subsets) return PARSE_EINVAL;
     if (rows != P || rows > 32 || L->G > 64 || pt->subset_stride < pt->k) return PARSE_ESHAPE;
     return forward_decode_bf16(L, pt, (const uint16_t *)X, rows, pattern_id, (uint16_t *)Y, workspace, s);
