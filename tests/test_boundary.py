@@ -112,7 +112,7 @@ def test_forward_rejects_bad_arguments():
     L = _layer()
     pt = B._Patterns(FAKE.value, FAKE.value, FAKE.value, 1, 2, 1)
 
-    def call(mode=0, layer=L, pat=pt, X=FAKE, rows=8, off=FAKE, pid=FAKE, P=2, Y=FAKE, ws=FAKE, wsb=1 << 20):
+    def call(mode=0, layer=L, pat=pt, X=FAKE, rows=8, off=FAKE, pid=FAKE, P=2, Y=FAKE, ws=FAKE, wsb=1 << 22):
         return lib.parse_lowrank_forward(mode, C.byref(layer), C.byref(pat), X, rows, off, pid, P, Y, ws, wsb, None)
 
     assert call(mode=3) == -1 and call(X=None) == -1 and call(Y=None) == -1 and call(pid=None) == -1
