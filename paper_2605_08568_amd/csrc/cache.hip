@@ -54,6 +54,7 @@ __global__ __launch_bounds__(256) void cache_sims(const float *__restrict__ E, i
   const float4 *a4 = reinterpret_cast<const float4 *>(E + (size_t)p * d);
   const float4 *b4 = reinterpret_cast<const float4 *>(other);
   float ab = 0.f, aa = 0.f, bb = 0.f;
+#pragma unroll 8
   for (int c = lane; c < d / 4; c += 64) {
     const float4 a = a4[c], b = b4[c];
     ab += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;

@@ -12,44 +12,67 @@ constexpr int kCopyThreads = 256;
 constexpr int kCopyUnroll = 8;                                       // 16-byte pieces per lane per block
 constexpr size_t kCopyChunk = (size_t)kCopyThreads * kCopyUnroll * 16;  // 32 KiB per block
 
-// grid (chunks of the larger slab, 2k, patterns).  blockIdx.y < k: Vt slab, else Ut slab.
+constexpr int kPackWindow = 2048;   // patterns whose work list a workgroup holds in LDS at a time
+
+// A fixed grid walks the work list: every workgroup first lists (in LDS) the patterns that have anything to
+// copy -- a batch whose prompts all hit the cache ends here, after one pass over the hit flags -- then takes
+// every gridDim.x-th task; a task = (listed pattern, one of its 2k slabs, one 32 KiB chunk of the slab).
+// Copies are idempotent, so the order in which the list was filled does not matter.
 __global__ __launch_bounds__(kCopyThreads) void pack_slabs(const char *__restrict__ Vt, const char *__restrict__ Ut,
                                                            size_t v_slab_bytes, size_t u_slab_bytes, int G, int k,
                                                            const int32_t *__restrict__ subset, int subset_stride,
                                                            const int32_t *__restrict__ rep,
                                                            const int32_t *__restrict__ slot,
                                                            const uint8_t *__restrict__ skip, int n_slots,
-                                                           const int32_t *__restrict__ n_patterns,
+                                                           const int32_t *__restrict__ n_patterns, int max_patterns,
                                                            char *__restrict__ Vt_S, char *__restrict__ Ut_S) {
-  const int j = blockIdx.z;
-  if (n_patterns && j >= *n_patterns) return;
-  if (skip && skip[j]) return;
-  int row = j;
-  if (rep) {
-    row = rep[j];
-    if (row < 0) return;
-  }
-  const int dst_slot = slot ? slot[j] : j;
-  if (dst_slot < 0 || dst_slot >= n_slots) return;
-  const bool is_u = (int)blockIdx.y >= k;
-  const int slot_in = is_u ? blockIdx.y - k : blockIdx.y;
-  const int g = subset[(size_t)row * subset_stride + slot_in];
-  if (g < 0 || g >= G) return;
-  const size_t slab = is_u ? u_slab_bytes : v_slab_bytes;
-  const size_t base = (size_t)blockIdx.x * kCopyChunk;
-  if (base >= slab) return;
-  const char *src = (is_u ? Ut : Vt) + (size_t)g * slab;
-  char *dst = (is_u ? Ut_S : Vt_S) + ((size_t)dst_slot * k + slot_in) * slab;
-  u32x4 v[kCopyUnroll];
+  __shared__ int32_t act[kPackWindow];
+  __shared__ int32_t n_act;
+  const int np = n_patterns ? min(*n_patterns, max_patterns) : max_patterns;
+  const size_t big = v_slab_bytes > u_slab_bytes ? v_slab_bytes : u_slab_bytes;
+  const int chunks = (int)((big + kCopyChunk - 1) / kCopyChunk);
+  for (int j0 = 0; j0 < np; j0 += kPackWindow) {
+    if (threadIdx.x == 0) n_act = 0;
+    __syncthreads();
+    for (int j = j0 + threadIdx.x; j < min(np, j0 + kPackWindow); j += kCopyThreads) {
+      bool on = !(skip && skip[j]);
+      if (on && rep) on = rep[j] >= 0;
+      if (on) {
+        const int d = slot ? slot[j] : j;
+        on = d >= 0 && d < n_slots;
+      }
+      if (on) act[atomicAdd(&n_act, 1)] = j;
+    }
+    __syncthreads();
+    const long long total = (long long)n_act * 2 * k * chunks;
+    for (long long t = blockIdx.x; t < total; t += gridDim.x) {
+      const int c = (int)(t % chunks);
+      const int y = (int)((t / chunks) % (2 * k));
+      const int j = act[t / ((long long)chunks * 2 * k)];
+      const int row = rep ? rep[j] : j;
+      const int dst_slot = slot ? slot[j] : j;
+      const bool is_u = y >= k;
+      const int slot_in = is_u ? y - k : y;
+      const int g = subset[(size_t)row * subset_stride + slot_in];
+      if (g < 0 || g >= G) continue;
+      const size_t slab = is_u ? u_slab_bytes : v_slab_bytes;
+      const size_t base = (size_t)c * kCopyChunk;
+      if (base >= slab) continue;
+      const char *src = (is_u ? Ut : Vt) + (size_t)g * slab;
+      char *dst = (is_u ? Ut_S : Vt_S) + ((size_t)dst_slot * k + slot_in) * slab;
+      u32x4 v[kCopyUnroll];
 #pragma unroll
-  for (int i = 0; i < kCopyUnroll; ++i) {
-    const size_t o = base + ((size_t)i * kCopyThreads + threadIdx.x) * 16;
-    if (o < slab) v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
-  }
+      for (int i = 0; i < kCopyUnroll; ++i) {
+        const size_t o = base + ((size_t)i * kCopyThreads + threadIdx.x) * 16;
+        if (o < slab) v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
+      }
 #pragma unroll
-  for (int i = 0; i < kCopyUnroll; ++i) {
-    const size_t o = base + ((size_t)i * kCopyThreads + threadIdx.x) * 16;
-    if (o < slab) *reinterpret_cast<u32x4 *>(dst + o) = v[i];
+      for (int i = 0; i < kCopyUnroll; ++i) {
+        const size_t o = base + ((size_t)i * kCopyThreads + threadIdx.x) * 16;
+        if (o < slab) *reinterpret_cast<u32x4 *>(dst + o) = v[i];
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -90,14 +113,16 @@ static int launch_pack(const parse_layer *L, const int32_t *subset, int subset_s
   if (st != PARSE_OK) return st;
   if (!subset || !Vt_S || !Ut_S) return PARSE_EINVAL;
   if (k <= 0 || max_patterns <= 0 || n_slots <= 0) return PARSE_EINVAL;
-  if (k > L->G || subset_stride < k || max_patterns > 65535 || 2 * k > 65535) return PARSE_ESHAPE;
+  if (k > L->G || subset_stride < k || max_patterns > (1 << 24)) return PARSE_ESHAPE;
   if (!aligned16(Vt_S) || !aligned16(Ut_S)) return PARSE_EALIGN;
   const size_t gs = L->R / L->G, es = elem_size(L->dtype);
   const size_t vb = gs * L->n * es, ub = gs * L->m * es;  // multiples of 16 (checked by check_layer)
   const size_t big = vb > ub ? vb : ub;
-  dim3 grid((unsigned)((big + kCopyChunk - 1) / kCopyChunk), 2 * k, max_patterns);
-  hipLaunchKernelGGL(pack_slabs, grid, dim3(kCopyThreads), 0, s, (const char *)L->Vt, (const char *)L->Ut, vb, ub,
-                     L->G, k, subset, subset_stride, rep, slot, skip, n_slots, n_patterns, (char *)Vt_S, (char *)Ut_S);
+  const long long tasks = (long long)((big + kCopyChunk - 1) / kCopyChunk) * 2 * k * max_patterns;
+  const unsigned grid = (unsigned)(tasks < 1024 ? tasks : 1024);   // four workgroups per compute unit walk the list
+  hipLaunchKernelGGL(pack_slabs, dim3(grid), dim3(kCopyThreads), 0, s, (const char *)L->Vt, (const char *)L->Ut, vb, ub,
+                     L->G, k, subset, subset_stride, rep, slot, skip, n_slots, n_patterns, max_patterns, (char *)Vt_S,
+                     (char *)Ut_S);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }

@@ -1,8 +1,9 @@
 // a1 + a2: prompt pooling and the linear router with top-k (Sec. 4.1, Eq. 5).
 //
 // Two launches, both deterministic:
-//   pool_partial  grid (column blocks, Q token slices, P prompts): fp32 partial sums of a slice of the
-//                 prompt's token rows, 16 bytes per lane per row, rows streamed once.
+//   pool_partial  grid (column blocks of 64 lanes x 16 bytes, Q token slices, P prompts): the four wavefronts
+//                 of a workgroup take a quarter of the slice's rows each for the same columns and add up
+//                 through LDS in wavefront order; fp32 partial sums per slice, rows streamed once.
 //   route_finish  one block per prompt: adds the Q partials in slice order, divides by the length,
 //                 scores the G groups (one wavefront per group, butterfly reduction) and selects the
 //                 top k with a rank count inside one wavefront.
@@ -11,7 +12,7 @@
 
 namespace parse {
 
-constexpr int kPoolThreads = 256;
+constexpr int kPoolThreads = 256, kPoolWaves = kPoolThreads / 64;
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
@@ -20,38 +21,54 @@ __global__ __launch_bounds__(kPoolThreads) void pool_partial(const void *__restr
                                                              const int32_t *__restrict__ tok_offsets,
                                                              int Q, float *__restrict__ partial) {
   constexpr int PER = BF16 ? 8 : 4;  // columns per lane = 16 bytes
+  __shared__ float red[kPoolWaves - 1][64][PER];
   const int p = blockIdx.z, q = blockIdx.y;
-  const int c0 = (blockIdx.x * kPoolThreads + threadIdx.x) * PER;
-  if (c0 >= d) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c0 = (blockIdx.x * 64 + lane) * PER;
+  const bool in = c0 < d;
   const int a = clampi(tok_offsets[p], 0, rows);
   const int b = clampi(tok_offsets[p + 1], a, rows);
   const long long len = b - a;
-  const int r0 = a + (int)((len * q) / Q), r1 = a + (int)((len * (q + 1)) / Q);
+  const int s0 = a + (int)((len * q) / Q), s1 = a + (int)((len * (q + 1)) / Q);
+  const long long sl = s1 - s0;
+  const int r0 = s0 + (int)((sl * wave) / kPoolWaves), r1 = s0 + (int)((sl * (wave + 1)) / kPoolWaves);
   float acc[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) acc[i] = 0.f;
-  if constexpr (BF16) {
-    const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
-#pragma unroll 4
-    for (int r = r0; r < r1; ++r) {
-      const u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)r * d + c0);
+  if (in) {
+    if constexpr (BF16) {
+      const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
+#pragma unroll 8
+      for (int r = r0; r < r1; ++r) {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)r * d + c0);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        acc[2 * i] += __uint_as_float(v[i] << 16);
-        acc[2 * i + 1] += __uint_as_float(v[i] & 0xFFFF0000u);
+        for (int i = 0; i < 4; ++i) {
+          acc[2 * i] += __uint_as_float(v[i] << 16);
+          acc[2 * i + 1] += __uint_as_float(v[i] & 0xFFFF0000u);
+        }
+      }
+    } else {
+      const float *x = reinterpret_cast<const float *>(X);
+#pragma unroll 8
+      for (int r = r0; r < r1; ++r) {
+        const float4 v = *reinterpret_cast<const float4 *>(x + (size_t)r * d + c0);
+        acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
       }
     }
-  } else {
-    const float *x = reinterpret_cast<const float *>(X);
-#pragma unroll 4
-    for (int r = r0; r < r1; ++r) {
-      const float4 v = *reinterpret_cast<const float4 *>(x + (size_t)r * d + c0);
-      acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
-    }
   }
-  float *dst = partial + ((size_t)p * Q + q) * d + c0;
+  if (wave > 0) {
 #pragma unroll
-  for (int i = 0; i < PER; ++i) dst[i] = acc[i];
+    for (int i = 0; i < PER; ++i) red[wave - 1][lane][i] = acc[i];
+  }
+  __syncthreads();
+  if (wave == 0 && in) {
+    for (int w = 0; w < kPoolWaves - 1; ++w)
+#pragma unroll
+      for (int i = 0; i < PER; ++i) acc[i] += red[w][lane][i];
+    float *dst = partial + ((size_t)p * Q + q) * d + c0;
+#pragma unroll
+    for (int i = 0; i < PER; i += 4) *reinterpret_cast<float4 *>(dst + i) = float4{acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
+  }
 }
 
 constexpr int kFinishThreads = 1024;
@@ -89,12 +106,14 @@ __global__ __launch_bounds__(kFinishThreads) void route_finish(const float *__re
   if (threadIdx.x < 64) wave_topk_ascending(s, G, k, subset_out + (size_t)p * subset_stride);
 }
 
+// Slices per prompt: enough workgroups to keep every compute unit streaming (about two per unit), a slice of
+// at least 32 rows (8 per wavefront), at most 32 slices.
 static int pool_slices(int rows, int P, int d, bool bf16) {
-  const int per_block = kPoolThreads * (bf16 ? 8 : 4);
+  const int per_block = 64 * (bf16 ? 8 : 4);
   const int colblocks = (d + per_block - 1) / per_block;
-  long long want = (2048 + (long long)P * colblocks - 1) / ((long long)P * colblocks);
+  long long want = (512 + (long long)P * colblocks - 1) / ((long long)P * colblocks);
   long long avg = rows / (P > 0 ? P : 1);
-  long long by_len = avg / 8 > 0 ? avg / 8 : 1;
+  long long by_len = avg / 32 > 0 ? avg / 32 : 1;
   long long q = want < by_len ? want : by_len;
   if (q > 32) q = 32;
   if (q < 1) q = 1;
@@ -129,7 +148,7 @@ int parse_route(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_
   if (!workspace || workspace_bytes < parse_route_workspace_bytes(rows, P, d)) return PARSE_EWORKSPACE;
   const bool bf16 = xdtype == PARSE_BF16;
   const int Q = pool_slices(rows, P, d, bf16);
-  const int per_block = kPoolThreads * (bf16 ? 8 : 4);
+  const int per_block = 64 * (bf16 ? 8 : 4);
   dim3 grid((d + per_block - 1) / per_block, Q, P);
   hipStream_t s = (hipStream_t)stream;
   float *partial = reinterpret_cast<float *>(workspace);

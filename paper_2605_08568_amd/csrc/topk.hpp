@@ -14,6 +14,7 @@ __device__ __forceinline__ void block_router_scores(const float *__restrict__ Wr
     const float4 *w4 = reinterpret_cast<const float4 *>(Wr + (size_t)g * d);
     const float4 *e4 = reinterpret_cast<const float4 *>(e_lds);
     float acc = 0.f;
+#pragma unroll 8
     for (int c = lane; c < d / 4; c += 64) {
       const float4 w = w4[c];
       const float4 e = e4[c];
