@@ -368,7 +368,7 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
   // the two-launch form (which needs the Z workspace) fills the chip better.
   const bool can_split = workspace != nullptr && workspace_bytes >= prefill_split_workspace_bytes(rows, rS) &&
                          prefill_split_supported(L->n, rS);
-  bool split = can_split && (rows / 64 < 1024);
+  bool split = can_split && (rows / 64 < 512);
   if (g_prefill_schedule == 1) split = false;
   if (g_prefill_schedule == 2) {
     if (!can_split) return PARSE_EWORKSPACE;

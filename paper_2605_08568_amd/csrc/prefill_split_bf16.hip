@@ -22,14 +22,23 @@ struct GtArgs {
   int ntiles, nchunks, GT;  // token tiles, factor-row chunks, token tiles per locality group
 };
 
-template <int BT, int NB, int DEPTH>
-__global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
+// KG = 1: four wavefronts, the whole reduction.  KG = 2: eight wavefronts, two groups of four that each run the
+// same loop over one half of the reduction range with their own staged tiles and add their accumulators through
+// LDS at the end.  The tile and the bytes fetched per workgroup are the same; what the second group buys is a
+// second, independent instruction stream on every SIMD, so a wait of one wavefront is covered by the other.
+template <int BT, int NB, int DEPTH, int KG>
+__global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   constexpr int TPI = DEPTH / 4;   // staged tiles per unrolled loop iteration = ring depth in tiles
   constexpr int NT = BT / 32;
   constexpr int XP = BT * PF_BK / 8 / PF_THREADS;
   constexpr int xld = PF_BK + PF_XPAD;
-  __shared__ __attribute__((aligned(16))) uint16_t Xs[2 * BT * xld];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, q = lane >> 5;
+  constexpr int XS_ELEMS = 2 * KG * BT * xld;
+  constexpr int RED_ELEMS = KG > 1 ? PF_THREADS * 16 * NB * 2 : 0;   // one token block of accumulators, as bf16 units
+  __shared__ __attribute__((aligned(16))) uint16_t lds_raw[XS_ELEMS > RED_ELEMS ? XS_ELEMS : RED_ELEMS];
+  const int tid = threadIdx.x & (PF_THREADS - 1);
+  const int kg = __builtin_amdgcn_readfirstlane((int)threadIdx.x / PF_THREADS);
+  uint16_t *Xs = lds_raw + kg * 2 * BT * xld;
+  const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, q = lane >> 5;
   // consecutive virtual ids share an XCD; a group of GT token tiles x all chunks is consecutive, so the tiles
   // of one prompt find their pattern's factors (and each other's token rows) in that die's L2
   const int v = xcd_tile(blockIdx.x, gridDim.x);
@@ -39,16 +48,17 @@ __global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
   if (tile >= a.ntiles) return;
   const int row0 = tile * BT;
   const int row_end = min(row0 + BT, a.rows);
-  const int K = a.K, nkb = K / 16, nkt = K / PF_BK, nmb = a.M / 32;
+  const int K = a.K, Kg = K / KG, nkb = Kg / 16, nkt = Kg / PF_BK, nmb = a.M / 32;
+  const int kbeg = kg * Kg;        // this group's part of the reduction range
   const int mb0 = chunk * 4 * NB + wave * NB;
 
   const uint16_t *xsrc[XP];
   int xdst[XP];
 #pragma unroll
   for (int i = 0; i < XP; ++i) {
-    const int piece = i * PF_THREADS + threadIdx.x;
+    const int piece = i * PF_THREADS + tid;
     const int r = piece / (PF_BK / 8), c = (piece % (PF_BK / 8)) * 8;
-    xsrc[i] = a.T + (size_t)min(row0 + r, a.rows - 1) * K + c;
+    xsrc[i] = a.T + (size_t)min(row0 + r, a.rows - 1) * K + kbeg + c;
     xdst[i] = r * xld + c;
   }
   const int xoff = l32 * xld + q * 8;
@@ -61,11 +71,11 @@ __global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
     const int pid = a.pattern_id[p];
     const bool valid = pid >= 0 && pid < a.n_patterns;
     const uint16_t *Fp = a.F + (valid ? (size_t)pid * a.pattern_stride : 0);
+    const size_t kstride = (size_t)a.kb_stride * 512;
     const uint16_t *fbase[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i)
-      fbase[i] = Fp + ((size_t)min(mb0 + i, nmb - 1) * a.mb_stride * 64 + lane) * 8;
-    const size_t kstride = (size_t)a.kb_stride * 512;
+      fbase[i] = Fp + ((size_t)min(mb0 + i, nmb - 1) * a.mb_stride * 64 + lane) * 8 + (size_t)(kbeg / 16) * kstride;
 
     f32x16 acc[NT][NB];
 #pragma unroll
@@ -123,20 +133,43 @@ __global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
         __syncthreads();
       }
     }
+    if constexpr (KG > 1) {
+      // the second group hands its accumulators over, one token block at a time (the staged tiles are dead)
+      float *red = reinterpret_cast<float *>(lds_raw);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        if (kg == 1) {
+#pragma unroll
+          for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[(i * 16 + e) * PF_THREADS + tid] = acc[t][i][e];
+        }
+        __syncthreads();
+        if (kg == 0) {
+#pragma unroll
+          for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[t][i][e] += red[(i * 16 + e) * PF_THREADS + tid];
+        }
+        __syncthreads();
+      }
+    }
     // lane holds token t*32 + l32, factor rows (mb0+i)*32 + 8*blk + 4*q + (0..3)
+    if (kg == 0) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int r = row0 + t * 32 + l32;
-      if (r < seg_lo || r >= seg_hi) continue;
+      for (int t = 0; t < NT; ++t) {
+        const int r = row0 + t * 32 + l32;
+        if (r < seg_lo || r >= seg_hi) continue;
 #pragma unroll
-      for (int i = 0; i < NB; ++i) {
-        if (mb0 + i >= nmb) continue;
+        for (int i = 0; i < NB; ++i) {
+          if (mb0 + i >= nmb) continue;
 #pragma unroll
-        for (int blk = 0; blk < 4; ++blk) {
-          u32x2 w;
-          w[0] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]) : 0u;
-          w[1] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]) : 0u;
-          *reinterpret_cast<u32x2 *>(a.O + (size_t)r * a.M + (mb0 + i) * 32 + blk * 8 + q * 4) = w;
+          for (int blk = 0; blk < 4; ++blk) {
+            u32x2 w;
+            w[0] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]) : 0u;
+            w[1] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]) : 0u;
+            *reinterpret_cast<u32x2 *>(a.O + (size_t)r * a.M + (mb0 + i) * 32 + blk * 8 + q * 4) = w;
+          }
         }
       }
     }
@@ -144,13 +177,13 @@ __global__ __launch_bounds__(PF_THREADS) void gemm_tokens(GtArgs a) {
   }
 }
 
-template <int BT, int NB, int DEPTH>
+template <int BT, int NB, int DEPTH, int KG = 1>
 static int launch_gemm_tokens(GtArgs a, int GT, hipStream_t s) {
   a.ntiles = (a.rows + BT - 1) / BT;
   a.nchunks = (a.M / 32 + 4 * NB - 1) / (4 * NB);
   a.GT = GT;
   const int groups = (a.ntiles + GT - 1) / GT;
-  hipLaunchKernelGGL((gemm_tokens<BT, NB, DEPTH>), dim3(groups * GT * a.nchunks), dim3(PF_THREADS), 0, s, a);
+  hipLaunchKernelGGL((gemm_tokens<BT, NB, DEPTH, KG>), dim3(groups * GT * a.nchunks), dim3(PF_THREADS * KG), 0, s, a);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }
@@ -167,13 +200,16 @@ int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows
   GtArgs g1{p.X, p.Vt_S, Z, p.tok_offsets, p.pattern_id, (size_t)p.rS * p.n, p.n / 16, 1,
             p.n, p.rS, p.rows, p.P, p.n_patterns, 0, 0, 0};
   int gt64 = avg_prompt_rows / 64;  gt64 = gt64 < 1 ? 1 : (gt64 > 8 ? 8 : gt64);
-  // a deeper operand ring when the reduction length is a whole number of ring periods
-  int st = (p.n % (PF_BK * 4) == 0) ? launch_gemm_tokens<64, 2, 16>(g1, gt64, s) : launch_gemm_tokens<64, 2, 8>(g1, gt64, s);
+  // a long reduction over few output tiles: eight wavefronts per workgroup (two reduction halves) when each
+  // half is a whole number of ring periods, else four wavefronts
+  const int st = (p.n % (PF_BK * 4) == 0) ? launch_gemm_tokens<64, 2, 8, 2>(g1, gt64, s)
+                                          : launch_gemm_tokens<64, 2, 8>(g1, gt64, s);
   if (st != PARSE_OK) return st;
   // launch 2: factor rows = output columns (operand (cb, kb) at kb*(m/32) + cb), tokens = Z
   GtArgs g2{Z, p.Ut_S, p.Y, p.tok_offsets, p.pattern_id, (size_t)p.rS * p.m, 1, p.m / 32,
             p.rS, p.m, p.rows, p.P, p.n_patterns, 0, 0, 0};
   int gt128 = avg_prompt_rows / 128;  gt128 = gt128 < 1 ? 1 : (gt128 > 8 ? 8 : gt128);
+  // a deeper operand ring when the reduction length is a whole number of ring periods
   return (p.rS % (PF_BK * 4) == 0) ? launch_gemm_tokens<128, 2, 16>(g2, gt128, s) : launch_gemm_tokens<128, 2, 8>(g2, gt128, s);
 }
 
