@@ -34,7 +34,12 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   constexpr int xld = PF_BK + PF_XPAD;
   constexpr int XS_ELEMS = 2 * KG * BT * xld;
   constexpr int RED_ELEMS = KG > 1 ? PF_THREADS * 16 * NB * 2 : 0;   // one token block of accumulators, as bf16 units
-  __shared__ __attribute__((aligned(16))) uint16_t lds_raw[XS_ELEMS > RED_ELEMS ? XS_ELEMS : RED_ELEMS];
+  constexpr int OC = 4 * NB * 32, OLD = OC + 8;                      // output columns of the tile, padded LDS row
+  static_assert(NT % 2 == 0, "token tiles are written out 64 rows at a time");
+  constexpr int OUT_ELEMS = 64 * OLD;
+  constexpr int LDS_ELEMS = XS_ELEMS > RED_ELEMS ? (XS_ELEMS > OUT_ELEMS ? XS_ELEMS : OUT_ELEMS)
+                                                 : (RED_ELEMS > OUT_ELEMS ? RED_ELEMS : OUT_ELEMS);
+  __shared__ __attribute__((aligned(16))) uint16_t lds_raw[LDS_ELEMS];
   const int tid = threadIdx.x & (PF_THREADS - 1);
   const int kg = __builtin_amdgcn_readfirstlane((int)threadIdx.x / PF_THREADS);
   uint16_t *Xs = lds_raw + kg * 2 * BT * xld;
@@ -154,22 +159,37 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
         __syncthreads();
       }
     }
-    // lane holds token t*32 + l32, factor rows (mb0+i)*32 + 8*blk + 4*q + (0..3)
-    if (kg == 0) {
+    // Output: lane holds token t*32 + l32, factor rows (mb0+i)*32 + 8*blk + 4*q + (0..3).  Tiles go through LDS,
+    // 64 tokens at a time, so that every store instruction writes whole output rows (OC*2 contiguous bytes
+    // per token) instead of 8-byte pieces of 32 different rows.
+    uint16_t *Ot = lds_raw;
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        const int r = row0 + t * 32 + l32;
-        if (r < seg_lo || r >= seg_hi) continue;
+    for (int tp = 0; tp < NT; tp += 2) {
+      if (tp > 0) __syncthreads();   // the previous pass has been read out
+      if (kg == 0) {
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-          if (mb0 + i >= nmb) continue;
+        for (int t = tp; t < tp + 2 && t < NT; ++t)
 #pragma unroll
-          for (int blk = 0; blk < 4; ++blk) {
-            u32x2 w;
-            w[0] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]) : 0u;
-            w[1] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]) : 0u;
-            *reinterpret_cast<u32x2 *>(a.O + (size_t)r * a.M + (mb0 + i) * 32 + blk * 8 + q * 4) = w;
-          }
+          for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int blk = 0; blk < 4; ++blk) {
+              u32x2 w;
+              w[0] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]) : 0u;
+              w[1] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]) : 0u;
+              *reinterpret_cast<u32x2 *>(Ot + ((t - tp) * 32 + l32) * OLD + (wave * NB + i) * 32 + blk * 8 + q * 4) = w;
+            }
+      }
+      __syncthreads();
+      if (kg == 0) {
+        constexpr int PPR = OC / 8;                 // 16-byte pieces per token row of the tile
+        constexpr int ROWS = 64;
+#pragma unroll
+        for (int it = 0; it < ROWS * PPR / PF_THREADS; ++it) {
+          const int piece = it * PF_THREADS + tid;
+          const int r = piece / PPR, c = (piece % PPR) * 8;
+          const int grow = row0 + tp * 32 + r, gcol = chunk * OC + c;
+          if (grow >= seg_lo && grow < seg_hi && gcol < a.M)
+            *reinterpret_cast<u32x4 *>(a.O + (size_t)grow * a.M + gcol) = *reinterpret_cast<const u32x4 *>(Ot + r * OLD + c);
         }
       }
     }
