@@ -188,41 +188,58 @@ def bench_decode(args, torch, pa, si):
           inter: torch.randn((B, inter), device=dev).to(torch.bfloat16)}
     ys = {hidden: torch.empty((B, hidden), dtype=torch.bfloat16, device=dev),
           inter: torch.empty((B, inter), dtype=torch.bfloat16, device=dev)}
-    ws = torch.empty(max(pa.lowrank_workspace_bytes(pa.PARSE_DECODE, layers[0][0], B, k),
+    ws = torch.empty(max(pa.lowrank_decode_multi_workspace_bytes(layers[0][:2]),
                          pa.lowrank_workspace_bytes(pa.PARSE_DECODE, layers[0][2], B, k)), dtype=torch.uint8, device=dev)
     pt = pa.Patterns(k, 4, subsets=subsets)
 
-    def step(s, ev=None):
-        trip = layers[s % copies]
-        for i, lay in enumerate(trip):
-            if ev is not None:
-                ev[i].record()
-            pa.lowrank_forward(pa.PARSE_DECODE, lay, pt, xs[lay.n], None, pid, ys[lay.m], ws)
+    def step(s, ev=None, fused=True):
+        gate, up, down = layers[s % copies]
         if ev is not None:
-            ev[3].record()
+            ev[0].record()
+        if fused:   # gate and up read the same x: one horizontally fused call (Sec. 4.4, Eq. 11-12)
+            pa.lowrank_decode_multi([gate, up], [pt, pt], xs[hidden], pid, [ys[inter], ys2], ws)
+        else:
+            pa.lowrank_forward(pa.PARSE_DECODE, gate, pt, xs[hidden], None, pid, ys[inter], ws)
+            pa.lowrank_forward(pa.PARSE_DECODE, up, pt, xs[hidden], None, pid, ys2, ws)
+        if ev is not None:
+            ev[1].record()
+        pa.lowrank_forward(pa.PARSE_DECODE, down, pt, xs[inter], None, pid, ys[hidden], ws)
+        if ev is not None:
+            ev[2].record()
 
-    for s in range(min(8, copies)):
-        step(s)
-    torch.cuda.synchronize()
+    ys2 = torch.empty((B, inter), dtype=torch.bfloat16, device=dev)
     steps = args.decode_steps
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(steps):
-        step(s, evs[s])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    out = {"workload": "config2: gate/up 4096->11008, down 11008->4096, R=2560, G=20, k=10, B=32, 4 patterns",
+
+    def run(fused):
+        for s in range(min(8, copies)):
+            step(s, fused=fused)
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            step(s, evs[s], fused)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        us = [sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(steps)) / steps * 1e3 for i in range(2)]
+        return wall, us
+
+    wall_sep, us_sep = run(False)
+    wall, us = run(True)
+    out = {"workload": "config2: gate/up 4096->11008 (one horizontally fused call), down 11008->4096, R=2560, G=20, "
+                       "k=10, B=32, 4 patterns",
            "steps": steps, "copies": copies, "distinct_groups": distinct,
-           "ms_per_step": round(wall / steps * 1e3, 4), "layers": {}}
-    tot_bytes, tot_us = 0.0, 0.0
-    for i, (nm, n, m) in enumerate(shapes):
-        us = sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(steps)) / steps * 1e3
-        nbytes = distinct * gs * (n + m) * 2 + B * (n + m) * 2
-        out["layers"][nm] = {"us": round(us, 2), "algorithmic_bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1)}
-        tot_bytes += nbytes; tot_us += us
+           "ms_per_step": round(wall / steps * 1e3, 4), "calls": {}}
+    fac = lambda n, m: distinct * gs * (n + m) * 2
+    b_gu = 2 * fac(hidden, inter) + B * hidden * 2 + 2 * B * inter * 2      # x is read once for both layers
+    b_dn = fac(inter, hidden) + B * (inter + hidden) * 2
+    out["calls"]["gate+up"] = {"us": round(us[0], 2), "algorithmic_bytes": b_gu, "GBps": round(b_gu / us[0] / 1e3, 1)}
+    out["calls"]["down"] = {"us": round(us[1], 2), "algorithmic_bytes": b_dn, "GBps": round(b_dn / us[1] / 1e3, 1)}
+    out["separate_calls"] = {"gate,up_us": round(us_sep[0], 2), "down_us": round(us_sep[1], 2),
+                             "ms_per_step": round(wall_sep / steps * 1e3, 4)}
+    tot_bytes, tot_us = b_gu + b_dn, us[0] + us[1]
     ach = tot_bytes / tot_us / 1e3
-    out["roofline"] = {"bound": "hbm", "kernel": "decode_z + decode_zfin + decode_y (one layer call)",
+    out["roofline"] = {"bound": "hbm", "kernel": "decode_z + decode_zfin + decode_y (two calls per step: gate+up fused, down)",
                        "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic_from_profiles("decode_config2")}
     out["end_to_end_GBps"] = round(tot_bytes * steps / wall / 1e9, 1)

@@ -233,6 +233,21 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *layer, const parse_pa
                           const int32_t *pattern_id, int32_t P, void *Y, void *workspace,
                           size_t workspace_bytes, parse_stream stream);
 
+/* Horizontal fusion for decode (Sec. 4.4, Eq. 11-12: projections that share their input run as one stacked
+ * first product and one batched second product).  n_layers (1..4) layers that read the SAME token rows X
+ * (equal n; m, R, G and the patterns may differ per layer) take ONE decode step together: the result equals
+ * n_layers separate PARSE_DECODE calls, at the launch count of one.
+ *   layers, patterns  host arrays [n_layers]; layer l uses patterns[l] (its own subsets, k, n_patterns)
+ *   X                 device [rows][n] bf16, rows <= 32, one token per sequence
+ *   pattern_id        device int32 [rows], shared by all layers (a sequence's cache entry)
+ *   Y                 host array [n_layers] of device pointers, Y[l] = [rows][layers[l].m] bf16
+ *   workspace         device, >= parse_lowrank_decode_multi_workspace_bytes(layers, n_layers), caller-owned
+ * Errors as parse_lowrank_forward; nothing is launched on error.  Same inputs, same bits. */
+size_t parse_lowrank_decode_multi_workspace_bytes(const parse_layer *layers, int32_t n_layers);
+int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
+                               const void *X, int32_t rows, const int32_t *pattern_id, void *const *Y,
+                               void *workspace, size_t workspace_bytes, parse_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

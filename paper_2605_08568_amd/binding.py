@@ -78,6 +78,11 @@ def lib():
     L.parse_lowrank_workspace_bytes.restype = sz
     L.parse_lowrank_workspace_bytes.argtypes = [i32, C.POINTER(_Layer), i32, i32]
     L.parse_set_prefill_schedule.restype = C.c_int; L.parse_set_prefill_schedule.argtypes = [i32]
+    L.parse_lowrank_decode_multi_workspace_bytes.restype = sz
+    L.parse_lowrank_decode_multi_workspace_bytes.argtypes = [C.POINTER(_Layer), i32]
+    L.parse_lowrank_decode_multi.restype = C.c_int
+    L.parse_lowrank_decode_multi.argtypes = [C.POINTER(_Layer), C.POINTER(_Patterns), i32, vp, i32, vp,
+                                             C.POINTER(C.c_void_p), vp, sz, vp]
     L.parse_lowrank_forward.restype = C.c_int
     L.parse_lowrank_forward.argtypes = [i32, C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, i32, vp, vp,
                                         sz, vp]
@@ -325,3 +330,24 @@ def lowrank_forward(mode: int, layer: Layer, patterns: Patterns, X, tok_offsets,
                                        0 if workspace is None else workspace.numel(), _stream()),
            "parse_lowrank_forward")
     return Y
+
+
+def lowrank_decode_multi_workspace_bytes(layers) -> int:
+    arr = (_Layer * len(layers))(*[l.c() for l in layers])
+    return int(lib().parse_lowrank_decode_multi_workspace_bytes(arr, len(layers)))
+
+
+def lowrank_decode_multi(layers, patterns, X, pattern_id, Ys=None, workspace=None):
+    """parse_lowrank_decode_multi: one decode step of several layers that share X.  Returns the list of Y."""
+    rows = X.shape[0]
+    nl = len(layers)
+    if Ys is None:
+        Ys = [torch.empty((rows, l.m), dtype=X.dtype, device=X.device) for l in layers]
+    if workspace is None:
+        workspace = torch.empty(max(lowrank_decode_multi_workspace_bytes(layers), 256), dtype=torch.uint8, device=X.device)
+    larr = (_Layer * nl)(*[l.c() for l in layers])
+    parr = (_Patterns * nl)(*[p.c() for p in patterns])
+    yarr = (C.c_void_p * nl)(*[y.data_ptr() for y in Ys])
+    _check(lib().parse_lowrank_decode_multi(larr, parr, nl, _ptr(X), rows, _ptr(pattern_id), yarr, _ptr(workspace),
+                                            workspace.numel(), _stream()), "parse_lowrank_decode_multi")
+    return Ys

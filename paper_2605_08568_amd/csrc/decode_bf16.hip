@@ -10,6 +10,9 @@
 // and the small operands (x, z) are shared inside a workgroup instead of being re-fetched per factor operand.
 // The streaming loops are branch-free: operand lists are walked in chunks with fetches past the end clamped
 // to the last valid operand and their contribution switched off by zeroing the small operand.
+// Horizontal fusion (Sec. 4.4, Eq. 11-12): up to DEC_MAX_LAYERS layers that read the SAME x (Q/K/V, gate/up)
+// go through the same three launches together -- each launch's grid is the concatenation of the layers' task
+// lists, so the per-launch floor is paid once and x is staged once per task whichever layer the task belongs to.
 #include "common.hpp"
 
 namespace parse {
@@ -23,6 +26,27 @@ constexpr int DZ_XLD = DZ_MAXSLICE * 16 + 8;
 constexpr int DEC_MAX_SLICES = 64; // slices of n the workspace is sized for
 constexpr int DY_CHUNK = 4;        // decode_y: operands per chunk after the first block
 constexpr int DY_MAXKB = 1024;     // selected reduction blocks a decode_y workgroup can list
+
+constexpr int DEC_MAX_LAYERS = 4;
+
+struct DecLayer {
+  const uint16_t *Vt, *Ut;
+  uint16_t *y;
+  const int32_t *subsets;      // this layer's patterns
+  int stride, k, n_patterns;
+  float *zp;                   // workspace parts of this layer
+  uint16_t *zf;
+  int32_t *used;
+  int R, G, gs, m;
+  int z_first, f_first, y_first;   // first workgroup of this layer in decode_z / decode_zfin / decode_y
+};
+struct DecArgs {
+  DecLayer L[DEC_MAX_LAYERS];
+  int n_layers;
+  const uint16_t *x;
+  const int32_t *pattern_id;
+  int B, n, S;                 // sequences, input width, slices of n (the same for every layer)
+};
 
 __device__ __forceinline__ bf16x8 dec_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -55,19 +79,27 @@ __device__ __forceinline__ void build_group_masks(const int32_t *__restrict__ su
 // decode_zfin's loads are contiguous per wavefront.  Rank blocks of groups nobody selected are skipped (nothing
 // of them is read or written).  Workgroup 0 also lists the groups selected by at least one sequence
 // (ascending) for decode_y.
-__global__ __launch_bounds__(DZ_THREADS) void decode_z(const uint16_t *__restrict__ Vt, const uint16_t *__restrict__ x,
-                                                       int B, int n, int R, int G, int gs,
-                                                       const int32_t *__restrict__ subsets, int stride, int k,
-                                                       int n_patterns, const int32_t *__restrict__ pattern_id, int S,
-                                                       float *__restrict__ zp,
-                                                       int32_t *__restrict__ used_out /* [0] = count, [1..] = ids */) {
+__global__ __launch_bounds__(DZ_THREADS) void decode_z(DecArgs a) {
+  int li = 0;
+#pragma unroll
+  for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].z_first) ? 1 : 0;
+  const DecLayer &ly = a.L[li];
+  const uint16_t *__restrict__ Vt = ly.Vt;
+  const uint16_t *__restrict__ x = a.x;
+  const int32_t *__restrict__ subsets = ly.subsets;
+  const int32_t *__restrict__ pattern_id = a.pattern_id;
+  float *__restrict__ zp = ly.zp;
+  int32_t *__restrict__ used_out = ly.used;   // [0] = count, [1..] = ids
+  const int B = a.B, n = a.n, R = ly.R, G = ly.G, gs = ly.gs, stride = ly.stride, k = ly.k, n_patterns = ly.n_patterns;
+  const int S = a.S;
+  const int bid = blockIdx.x - ly.z_first;    // task within the layer
   __shared__ __attribute__((aligned(16))) uint16_t xs[32 * DZ_XLD];  // 66 KiB; reused for the halves' sum
   __shared__ uint32_t gmask[DEC_MAXG];
   float(*red)[16][64] = reinterpret_cast<float(*)[16][64]>(xs);       // [4][16][64] floats = 16 KiB
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, q = lane >> 5;
   const int nkb = n / 16, nrb = R / 32;
-  const int quad = blockIdx.x / S, sl = blockIdx.x - quad * S;
+  const int quad = bid / S, sl = bid - quad * S;
   const int w0 = (int)(((long long)nkb * sl) / S), w1 = (int)(((long long)nkb * (sl + 1)) / S);
   const int len = w1 - w0;                                           // <= DZ_MAXSLICE (host)
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -95,7 +127,7 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_z(const uint16_t *__restric
   if (threadIdx.x < DEC_MAXG) gmask[threadIdx.x] = 0;
   __syncthreads();
   build_group_masks(subsets, stride, k, n_patterns, pattern_id, B, G, gmask);
-  if (blockIdx.x == 0 && threadIdx.x < 64) {
+  if (bid == 0 && threadIdx.x < 64) {
     const bool u = lane < G && gmask[lane] != 0u;
     const unsigned long long mask = __ballot(u);
     if (u) used_out[1 + __popcll(mask & ((1ull << lane) - 1ull))] = lane;
@@ -183,8 +215,15 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_z(const uint16_t *__restric
 // o = (kb*2 + q)*32 + b holds z[b][16kb + 8q + (0..7)] (the partials use the same piece numbering and are
 // already masked).  One wavefront per workgroup, one piece per lane, the loads of eight slices in flight at
 // once.  Pieces of rank blocks nobody selected hold whatever the workspace held; decode_y never reads them.
-__global__ __launch_bounds__(64) void decode_zfin(const float *__restrict__ zp, int S, int R, uint16_t *__restrict__ zf) {
-  const int o = blockIdx.x * 64 + threadIdx.x;   // piece
+__global__ __launch_bounds__(64) void decode_zfin(DecArgs a) {
+  int li = 0;
+#pragma unroll
+  for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].f_first) ? 1 : 0;
+  const DecLayer &ly = a.L[li];
+  const float *__restrict__ zp = ly.zp;
+  uint16_t *__restrict__ zf = ly.zf;
+  const int S = a.S, R = ly.R;
+  const int o = ((int)blockIdx.x - ly.f_first) * 64 + threadIdx.x;   // piece
   const int quad = o >> 9, t = o & 511;
   if ((o >> 5) * 8 >= R) return;
   float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -209,17 +248,24 @@ __global__ __launch_bounds__(64) void decode_zfin(const float *__restrict__ zp, 
 // once (MAXK sized so that everything stays in registers), the rest is streamed in chunks; the eight wavefronts
 // add up through LDS.
 template <int NC>
-__global__ __launch_bounds__(DY_THREADS) void decode_y(const uint16_t *__restrict__ Ut, const uint16_t *__restrict__ zf,
-                                                       int B, int m, int G, int gs,
-                                                       const int32_t *__restrict__ used_in,
-                                                       uint16_t *__restrict__ y) {
+__global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
+  int li = 0;
+#pragma unroll
+  for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].y_first) ? 1 : 0;
+  const DecLayer &ly = a.L[li];
+  const uint16_t *__restrict__ Ut = ly.Ut;
+  const uint16_t *__restrict__ zf = ly.zf;
+  const int32_t *__restrict__ used_in = ly.used;
+  uint16_t *__restrict__ y = ly.y;
+  const int B = a.B, m = ly.m, G = ly.G, gs = ly.gs;
+  const int bid = blockIdx.x - ly.y_first;
   __shared__ float red[DY_WAVES][16][64];
   __shared__ int32_t kb_list[DY_MAXKB];
   __shared__ int32_t used[DEC_MAXG];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, q = lane >> 5;
   const int ncb = m / 32;
-  const int c0 = blockIdx.x * NC;
+  const int c0 = bid * NC;
   const int nc = min(NC, ncb - c0);
   const int n_used = min(used_in[0], G);
   if ((int)threadIdx.x < n_used) used[threadIdx.x] = used_in[1 + threadIdx.x];
@@ -307,16 +353,20 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(const uint16_t *__restric
   }
 }
 
-// Slices of n: about one task per compute unit over the rank quads that can be selected at all (the host knows
-// k and the number of patterns, not the subsets), a slice no longer than DZ_MAXSLICE steps, at most
-// DEC_MAX_SLICES slices.
-static int decode_slices(int n, int R, int gs, int G, int k, int n_patterns, int n_cu) {
-  const int nkb = n / 16, nquads = (R / 32 + 3) / 4;
-  long long groups = (long long)k * n_patterns;
-  if (groups > G) groups = G;
-  int live = (int)((groups * gs + 127) / 128);
+// Slices of n: about one task per compute unit over the rank quads (of all layers of the call) that can be
+// selected at all (the host knows k and the number of patterns, not the subsets), a slice no longer than
+// DZ_MAXSLICE steps, at most DEC_MAX_SLICES slices.
+static int live_quads_bound(const parse_layer *L, const parse_patterns *pt) {
+  const int gs = L->R / L->G, nquads = (L->R / 32 + 3) / 4;
+  long long groups = (long long)pt->k * pt->n_patterns;
+  if (groups > L->G) groups = L->G;
+  long long live = (groups * gs + 127) / 128;
   if (live > nquads) live = nquads;
-  if (live < 1) live = 1;
+  return live < 1 ? 1 : (int)live;
+}
+
+static int decode_slices(int n, int live, int n_cu) {
+  const int nkb = n / 16;
   int S = (n_cu + live - 1) / live;
   const int s_min = (nkb + DZ_MAXSLICE - 1) / DZ_MAXSLICE;
   if (S < s_min) S = s_min;
@@ -344,9 +394,10 @@ bool decode_supported(const parse_layer *L) {
   return s_min <= DEC_MAX_SLICES && L->R / 16 <= DY_MAXKB && L->G <= DEC_MAXG;
 }
 
-int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *x, int B,
-                        const int32_t *pattern_id, uint16_t *y, void *workspace, hipStream_t s) {
-  const int gs = L->R / L->G;
+// n_layers layers that share x (same n); Y[l] and the workspace part of layer l follow the order of `layers`.
+int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *pts, int n_layers, const uint16_t *x,
+                              int B, const int32_t *pattern_id, uint16_t *const *Y, void *workspace, hipStream_t s) {
+  if (n_layers < 1 || n_layers > DEC_MAX_LAYERS) return PARSE_ESHAPE;
   static int n_cu_of[64] = {0};
   int dev = 0;
   PARSE_HIP_TRY(hipGetDevice(&dev));
@@ -357,27 +408,58 @@ int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const ui
     n_cu_of[dev] = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
   const int n_cu = n_cu_of[dev];
-  if (!decode_supported(L)) return PARSE_ESHAPE;
-  const int S = decode_slices(L->n, L->R, gs, L->G, pt->k, pt->n_patterns, n_cu);
-  float *zp = reinterpret_cast<float *>(workspace);
-  uint16_t *zf = reinterpret_cast<uint16_t *>((char *)workspace + dec_zp_bytes(L));
-  int32_t *used = reinterpret_cast<int32_t *>((char *)zf + dec_zf_bytes(L));
-  const int nquads = (L->R / 32 + 3) / 4, ncb = L->m / 32;
-  hipLaunchKernelGGL(decode_z, dim3(nquads * S), dim3(DZ_THREADS), 0, s, (const uint16_t *)L->Vt, x, B, L->n, L->R, L->G,
-                     gs, pt->subsets, pt->subset_stride, pt->k, pt->n_patterns, pattern_id, S, zp, used);
-  PARSE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(decode_zfin, dim3(nquads * 8), dim3(64), 0, s, zp, S, L->R, zf);
-  PARSE_LAUNCH_CHECK();
-  // two column blocks per workgroup (one z operand feeds two products) once that still gives every unit a workgroup
-  if (ncb >= n_cu) {
-    hipLaunchKernelGGL(decode_y<2>, dim3((ncb + 1) / 2), dim3(DY_THREADS), 0, s, (const uint16_t *)L->Ut, zf, B, L->m,
-                       L->G, gs, used, y);
-  } else {
-    hipLaunchKernelGGL(decode_y<1>, dim3(ncb), dim3(DY_THREADS), 0, s, (const uint16_t *)L->Ut, zf, B, L->m, L->G, gs,
-                       used, y);
+  DecArgs a{};
+  a.n_layers = n_layers;
+  a.x = x;
+  a.pattern_id = pattern_id;
+  a.B = B;
+  a.n = layers[0].n;
+  int live = 0, total_cb = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (!decode_supported(&layers[l])) return PARSE_ESHAPE;
+    if (layers[l].n != a.n) return PARSE_ESHAPE;
+    live += live_quads_bound(&layers[l], &pts[l]);
+    total_cb += layers[l].m / 32;
   }
+  a.S = decode_slices(a.n, live, n_cu);
+  // two column blocks per workgroup (one z operand feeds two products) once that still gives every unit a workgroup
+  const int NC = total_cb >= n_cu ? 2 : 1;
+  char *ws = reinterpret_cast<char *>(workspace);
+  int zb = 0, fb = 0, yb = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    const parse_layer *L = &layers[l];
+    DecLayer &d = a.L[l];
+    d.Vt = (const uint16_t *)L->Vt;
+    d.Ut = (const uint16_t *)L->Ut;
+    d.y = Y[l];
+    d.subsets = pts[l].subsets;
+    d.stride = pts[l].subset_stride;
+    d.k = pts[l].k;
+    d.n_patterns = pts[l].n_patterns;
+    d.zp = reinterpret_cast<float *>(ws);
+    d.zf = reinterpret_cast<uint16_t *>(ws + dec_zp_bytes(L));
+    d.used = reinterpret_cast<int32_t *>(ws + dec_zp_bytes(L) + dec_zf_bytes(L));
+    ws += decode_workspace_bytes(L);
+    d.R = L->R; d.G = L->G; d.gs = L->R / L->G; d.m = L->m;
+    const int nquads = (L->R / 32 + 3) / 4, ncb = L->m / 32;
+    d.z_first = zb; zb += nquads * a.S;
+    d.f_first = fb; fb += nquads * 8;
+    d.y_first = yb; yb += (ncb + NC - 1) / NC;
+  }
+  hipLaunchKernelGGL(decode_z, dim3(zb), dim3(DZ_THREADS), 0, s, a);
+  PARSE_LAUNCH_CHECK();
+  hipLaunchKernelGGL(decode_zfin, dim3(fb), dim3(64), 0, s, a);
+  PARSE_LAUNCH_CHECK();
+  if (NC == 2) hipLaunchKernelGGL(decode_y<2>, dim3(yb), dim3(DY_THREADS), 0, s, a);
+  else hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
+}
+
+int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *x, int B,
+                        const int32_t *pattern_id, uint16_t *y, void *workspace, hipStream_t s) {
+  uint16_t *Y[1] = {y};
+  return forward_decode_multi_bf16(L, pt, 1, x, B, pattern_id, Y, workspace, s);
 }
 
 }  // namespace parse

@@ -11,6 +11,8 @@ size_t prefill_split_workspace_bytes(int rows, int rS);
 void set_prefill_schedule(int v);
 size_t prefill_lds_bytes(int BM, int rS);
 size_t decode_workspace_bytes(const parse_layer *L);
+int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *pts, int n_layers, const uint16_t *x,
+                              int B, const int32_t *pattern_id, uint16_t *const *Y, void *workspace, hipStream_t s);
 int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *x, int B,
                         const int32_t *pattern_id, uint16_t *y, void *workspace, hipStream_t s);
 }  // namespace parse
@@ -68,6 +70,41 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patter
   if (prefill_lds_bytes(32, rS) > 160 * 1024) return PARSE_ESHAPE;
   return forward_prefill_bf16(L, pt, (const uint16_t *)X, rows, tok_offsets, pattern_id, P, (uint16_t *)Y, workspace,
                               workspace_bytes, s);
+}
+
+size_t parse_lowrank_decode_multi_workspace_bytes(const parse_layer *layers, int32_t n_layers) {
+  if (!layers || n_layers < 1 || n_layers > 4) return 0;
+  size_t total = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (layers[l].G <= 0 || layers[l].R <= 0) return 0;
+    total += decode_workspace_bytes(&layers[l]);
+  }
+  return total;
+}
+
+int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
+                               const void *X, int32_t rows, const int32_t *pattern_id, void *const *Y,
+                               void *workspace, size_t workspace_bytes, parse_stream stream) {
+  if (!layers || !patterns || !X || !pattern_id || !Y) return PARSE_EINVAL;
+  if (n_layers < 1 || rows <= 0) return PARSE_EINVAL;
+  if (n_layers > 4 || rows > 32) return PARSE_ESHAPE;
+  if (!aligned16(X)) return PARSE_EALIGN;
+  for (int l = 0; l < n_layers; ++l) {
+    const parse_layer *L = &layers[l];
+    const parse_patterns *pt = &patterns[l];
+    int st = check_layer(L);
+    if (st != PARSE_OK) return st;
+    if (L->dtype != PARSE_BF16 || L->layout != PARSE_MFMA16) return PARSE_ELAYOUT;
+    if (!Y[l] || !pt->subsets) return PARSE_EINVAL;
+    if (pt->n_patterns <= 0 || pt->k <= 0) return PARSE_EINVAL;
+    if (pt->k > L->G || L->G > 64 || pt->subset_stride < pt->k || L->n != layers[0].n) return PARSE_ESHAPE;
+    if (!aligned16(Y[l])) return PARSE_EALIGN;
+  }
+  const size_t need = parse_lowrank_decode_multi_workspace_bytes(layers, n_layers);
+  if (!workspace || workspace_bytes < need) return PARSE_EWORKSPACE;
+  if (!aligned16(workspace)) return PARSE_EALIGN;
+  return forward_decode_multi_bf16(layers, patterns, n_layers, (const uint16_t *)X, rows, pattern_id,
+                                   (uint16_t *const *)Y, workspace, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -126,3 +126,26 @@ def test_forward_rejects_bad_arguments():
     assert call(mode=1, layer=Lb, rows=40, P=40) == -2                  # more than 32 sequences
     assert call(mode=1, layer=Lb, rows=8, P=4) == -2                    # decode: one row per sequence
     assert lib.parse_lowrank_workspace_bytes(0, C.byref(L), 8, 1) >= 8 * 16 * 4
+
+
+def test_decode_multi_rejects_bad_arguments():
+    lib = pa.lib()
+    La = _layer(n=64, m=64, R=64, G=2, dtype=1, layout=1)
+    Lb = _layer(n=128, m=64, R=64, G=2, dtype=1, layout=1)
+    pt = B._Patterns(None, None, FAKE.value, 1, 2, 1)
+
+    def call(layers, pats, nl, X=FAKE, rows=8, pid=FAKE, ys=None, ws=FAKE, wsb=1 << 24):
+        larr = (B._Layer * len(layers))(*layers)
+        parr = (B._Patterns * len(pats))(*pats)
+        yarr = (C.c_void_p * len(layers))(*(ys if ys is not None else [FAKE.value] * len(layers)))
+        return lib.parse_lowrank_decode_multi(larr, parr, nl, X, rows, pid, yarr, ws, wsb, None)
+
+    assert call([La, La], [pt, pt], 0) == -1 and call([La, La], [pt, pt], 2, X=None) == -1
+    assert call([La] * 5, [pt] * 5, 5) == -2                       # at most four layers
+    assert call([La, La], [pt, pt], 2, rows=33) == -2              # at most 32 sequences
+    assert call([La, Lb], [pt, pt], 2) == -2                       # the layers must share the input width
+    assert call([La, _layer(n=64, m=64, R=64, G=2, dtype=1, layout=0)], [pt, pt], 2) == -7
+    assert call([La, La], [pt, pt], 2, ys=[FAKE.value, None]) == -1
+    assert call([La, La], [pt, pt], 2, wsb=64) == -5
+    larr = (B._Layer * 2)(La, La)
+    assert lib.parse_lowrank_decode_multi_workspace_bytes(larr, 2) == 2 * lib.parse_lowrank_workspace_bytes(1, C.byref(La), 8, 1)

@@ -431,3 +431,40 @@ def test_decode_unselected_groups_are_not_needed():
     torch.cuda.synchronize()
     assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
     assert torch.all(outs[0][4] == 0) and torch.any(outs[0][0] != 0)
+
+
+@pytest.mark.parametrize("shapes,n,B", [
+    ([(1536, 640, 20, 10), (1536, 640, 20, 10)], 1024, 32),                      # gate/up-like pair
+    ([(512, 256, 8, 3), (256, 128, 4, 2), (768, 256, 8, 4)], 512, 7),           # Q/K/V-like, different m, R, G, k
+    ([(11008, 2560, 20, 10), (11008, 2560, 20, 10)], 4096, 32),                  # the decode workload's gate + up
+])
+def test_decode_multi_matches_oracle_and_single_calls(shapes, n, B):
+    """Horizontal fusion (Sec. 4.4, Eq. 11-12): layers sharing x in one decode step = the separate steps."""
+    say(f"decode_multi n={n} B={B} layers={shapes}")
+    rng = np.random.default_rng(611)
+    x = si.make_tokens(rng, B, n, "bf16")
+    xd = upload_tokens(x, "bf16")
+    npat = 4 if B >= 4 else 1
+    seq_pat = (np.arange(B) % npat).astype(np.int32)
+    layers, patterns, refs, rows_of = [], [], [], []
+    for li, (m, R, G, k) in enumerate(shapes):
+        lay = si.make_layer(np.random.default_rng(620 + li), n, m, R, G, "bf16", fast=(R > 1024))
+        pats = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(npat)]).astype(np.int32)
+        U0, sg, V = oracle_factors(lay)
+        rows = np.arange(B) if R <= 1024 else np.array([0, B - 1])
+        refs.append(po.decode_step(U0, sg, V, lay.gs, si.bf16_bits_to_f32(x[rows]).astype(np.float64), pats[seq_pat[rows]]))
+        rows_of.append(rows)
+        layers.append(pa.layer_to_mfma16(upload_layer(lay)))
+        patterns.append(pa.Patterns(k, npat, subsets=i32(pats)))
+    pid = i32(seq_pat)
+    ys = pa.lowrank_decode_multi(layers, patterns, xd, pid)
+    ys2 = pa.lowrank_decode_multi(layers, patterns, xd, pid)
+    torch.cuda.synchronize()
+    for li in range(len(shapes)):
+        assert torch.equal(ys[li].view(torch.int16), ys2[li].view(torch.int16))
+        yn = ys[li].float().cpu().numpy()
+        for i, b in enumerate(rows_of[li]):
+            assert_close(yn[b:b + 1], refs[li][i:i + 1], TOL_BF16, f"layer {li} sequence {b}")
+        single = pa.lowrank_forward(pa.PARSE_DECODE, layers[li], patterns[li], xd, None, pid)
+        torch.cuda.synchronize()
+        assert_close(yn, single.float().cpu().numpy(), TOL_BF16, f"layer {li}: fused vs separate call")
