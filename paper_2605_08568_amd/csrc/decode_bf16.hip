@@ -279,22 +279,24 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
   const uint16_t *ubase = Ut + ((size_t)c0 * 64 + lane) * 8;
   const uint16_t *zbase = zf + (size_t)lane * 8;
   const size_t ustep = (size_t)ncb * 512;
-  const int second_off = (NC > 1 && nc > 1) ? 512 : 0;
+  int coff[NC];   // element offset of column block j's operand; blocks past the end re-read block 0 (result unused)
+#pragma unroll
+  for (int j = 0; j < NC; ++j) coff[j] = j < nc ? j * 512 : 0;
   f32x16 acc[NC];
 #pragma unroll
   for (int j = 0; j < NC; ++j)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
   const u32x4 zero = {0, 0, 0, 0};
-  constexpr int DY_MAXK = NC > 1 ? 16 : 20;
+  constexpr int DY_MAXK = NC == 1 ? 20 : (NC == 2 ? 16 : (NC == 3 ? 12 : 8));
   constexpr int DEC_CHUNK = DY_CHUNK;
   if (cnt > 0) {
     u32x4 ur[DY_MAXK][NC], zr[DY_MAXK];
 #pragma unroll
     for (int i = 0; i < DY_MAXK; ++i) {
       const int kb = kb_list[k0 + min(i, cnt - 1)];
-      ur[i][0] = *reinterpret_cast<const u32x4 *>(ubase + (size_t)kb * ustep);
-      if (NC > 1) ur[i][NC - 1] = *reinterpret_cast<const u32x4 *>(ubase + (size_t)kb * ustep + second_off);
+#pragma unroll
+      for (int j = 0; j < NC; ++j) ur[i][j] = *reinterpret_cast<const u32x4 *>(ubase + (size_t)kb * ustep + coff[j]);
       zr[i] = *reinterpret_cast<const u32x4 *>(zbase + (size_t)kb * 512);
     }
     __builtin_amdgcn_sched_barrier(0);   // every fetch above is in flight before the first product
@@ -310,8 +312,8 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
 #pragma unroll
       for (int i = 0; i < DEC_CHUNK; ++i) {
         const int kb = kb_list[k0 + min(c + i, cnt - 1)];
-        uu[i][0] = *reinterpret_cast<const u32x4 *>(ubase + (size_t)kb * ustep);
-        if (NC > 1) uu[i][NC - 1] = *reinterpret_cast<const u32x4 *>(ubase + (size_t)kb * ustep + second_off);
+#pragma unroll
+        for (int j = 0; j < NC; ++j) uu[i][j] = *reinterpret_cast<const u32x4 *>(ubase + (size_t)kb * ustep + coff[j]);
         zz[i] = *reinterpret_cast<const u32x4 *>(zbase + (size_t)kb * 512);
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -353,7 +355,7 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
   }
 }
 
-// Slices of n: about one task per compute unit over the rank quads (of all layers of the call) that can be
+// Slices of n: at most one task per compute unit over the rank quads (of all layers of the call) that can be
 // selected at all (the host knows k and the number of patterns, not the subsets), a slice no longer than
 // DZ_MAXSLICE steps, at most DEC_MAX_SLICES slices.
 static int live_quads_bound(const parse_layer *L, const parse_patterns *pt) {
@@ -367,7 +369,7 @@ static int live_quads_bound(const parse_layer *L, const parse_patterns *pt) {
 
 static int decode_slices(int n, int live, int n_cu) {
   const int nkb = n / 16;
-  int S = (n_cu + live - 1) / live;
+  int S = n_cu / live;   // rounded down: a unit that gets two tasks runs both at half the rate
   const int s_min = (nkb + DZ_MAXSLICE - 1) / DZ_MAXSLICE;
   if (S < s_min) S = s_min;
   if (S > DEC_MAX_SLICES) S = DEC_MAX_SLICES;   // decode_supported() keeps the slice within DZ_MAXSLICE
@@ -414,16 +416,21 @@ int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *p
   a.pattern_id = pattern_id;
   a.B = B;
   a.n = layers[0].n;
-  int live = 0, total_cb = 0;
+  int live = 0;
   for (int l = 0; l < n_layers; ++l) {
     if (!decode_supported(&layers[l])) return PARSE_ESHAPE;
     if (layers[l].n != a.n) return PARSE_ESHAPE;
     live += live_quads_bound(&layers[l], &pts[l]);
-    total_cb += layers[l].m / 32;
   }
   a.S = decode_slices(a.n, live, n_cu);
-  // two column blocks per workgroup (one z operand feeds two products) once that still gives every unit a workgroup
-  const int NC = total_cb >= n_cu ? 2 : 1;
+  // column blocks per workgroup (one z operand feeds NC products): the smallest count that puts at most one
+  // workgroup on a compute unit -- a unit with two streams at half the rate and sets the kernel's time
+  int NC = 1;
+  for (; NC < 4; ++NC) {
+    int wgs = 0;
+    for (int l = 0; l < n_layers; ++l) wgs += (layers[l].m / 32 + NC - 1) / NC;
+    if (wgs <= n_cu) break;
+  }
   char *ws = reinterpret_cast<char *>(workspace);
   int zb = 0, fb = 0, yb = 0;
   for (int l = 0; l < n_layers; ++l) {
@@ -450,8 +457,10 @@ int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *p
   PARSE_LAUNCH_CHECK();
   hipLaunchKernelGGL(decode_zfin, dim3(fb), dim3(64), 0, s, a);
   PARSE_LAUNCH_CHECK();
-  if (NC == 2) hipLaunchKernelGGL(decode_y<2>, dim3(yb), dim3(DY_THREADS), 0, s, a);
-  else hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
+  if (NC == 1) hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
+  else if (NC == 2) hipLaunchKernelGGL(decode_y<2>, dim3(yb), dim3(DY_THREADS), 0, s, a);
+  else if (NC == 3) hipLaunchKernelGGL(decode_y<3>, dim3(yb), dim3(DY_THREADS), 0, s, a);
+  else hipLaunchKernelGGL(decode_y<4>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }
