@@ -35,8 +35,9 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   constexpr int XS_ELEMS = 2 * KG * BT * xld;
   constexpr int RED_ELEMS = KG > 1 ? PF_THREADS * 16 * NB * 2 : 0;   // one token block of accumulators, as bf16 units
   constexpr int OC = 4 * NB * 32, OLD = OC + 8;                      // output columns of the tile, padded LDS row
-  static_assert(NT % 2 == 0, "token tiles are written out 64 rows at a time");
-  constexpr int OUT_ELEMS = 64 * OLD;
+  constexpr int EPT = OC > 256 ? 1 : 2;                              // token blocks written out per pass
+  static_assert(NT % EPT == 0, "token tiles are written out EPT blocks at a time");
+  constexpr int OUT_ELEMS = EPT * 32 * OLD;
   constexpr int LDS_ELEMS = XS_ELEMS > RED_ELEMS ? (XS_ELEMS > OUT_ELEMS ? XS_ELEMS : OUT_ELEMS)
                                                  : (RED_ELEMS > OUT_ELEMS ? RED_ELEMS : OUT_ELEMS);
   __shared__ __attribute__((aligned(16))) uint16_t lds_raw[LDS_ELEMS];
@@ -160,15 +161,15 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
       }
     }
     // Output: lane holds token t*32 + l32, factor rows (mb0+i)*32 + 8*blk + 4*q + (0..3).  Tiles go through LDS,
-    // 64 tokens at a time, so that every store instruction writes whole output rows (OC*2 contiguous bytes
+    // EPT*32 tokens at a time, so that every store instruction writes whole output rows (OC*2 contiguous bytes
     // per token) instead of 8-byte pieces of 32 different rows.
     uint16_t *Ot = lds_raw;
 #pragma unroll
-    for (int tp = 0; tp < NT; tp += 2) {
+    for (int tp = 0; tp < NT; tp += EPT) {
       if (tp > 0) __syncthreads();   // the previous pass has been read out
       if (kg == 0) {
 #pragma unroll
-        for (int t = tp; t < tp + 2 && t < NT; ++t)
+        for (int t = tp; t < tp + EPT; ++t)
 #pragma unroll
           for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
       __syncthreads();
       if (kg == 0) {
         constexpr int PPR = OC / 8;                 // 16-byte pieces per token row of the tile
-        constexpr int ROWS = 64;
+        constexpr int ROWS = EPT * 32;
 #pragma unroll
         for (int it = 0; it < ROWS * PPR / PF_THREADS; ++it) {
           const int piece = it * PF_THREADS + tid;
