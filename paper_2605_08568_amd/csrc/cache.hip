@@ -22,7 +22,8 @@ struct parse_cache {
   int32_t capacity, d, L, k, max_batch;
   float *keys;      // [capacity][d]
   int32_t *values;  // [capacity][L][k]
-  int32_t *count;   // [1]
+  int32_t *count;   // [2]: the live counter is count[cur]; a fused probe reads it and writes the other one
+  int32_t cur;
   // scratch of one batch
   float *sims;      // [max_batch][capacity + max_batch]
   int32_t *src;     // [max_batch] prompt whose embedding defines the answer's key (in-batch entries), else -1
@@ -183,6 +184,109 @@ __global__ __launch_bounds__(256) void route_or_gather(const float *__restrict__
   }
 }
 
+// Small batches (P <= kSmallBatch): resolve and route_or_gather in one launch.  grid (L, P), block 256.  Every
+// workgroup repeats the (cheap, deterministic) decision walk for prompts 0..p from the similarity matrix, so no
+// workgroup waits for another; it then routes / gathers for its own (layer, prompt).  The entry count is read
+// from count_in and the new one written to count_out (a different word: workgroups still starting must see the
+// old value) by the workgroup of the last prompt, which has walked the whole batch.
+constexpr int kSmallBatch = 64;
+__global__ __launch_bounds__(256) void resolve_route_or_gather(
+    const float *__restrict__ sims, int ld, int capacity, int P, float tau, const int32_t *__restrict__ count_in,
+    int32_t *__restrict__ count_out, const float *__restrict__ E, int d, const float *__restrict__ Wr, int G, int L, int k,
+    int32_t *__restrict__ entry_out, uint8_t *__restrict__ hit_out, float *__restrict__ sim_out,
+    float *__restrict__ keys, int32_t *__restrict__ values, int32_t *__restrict__ subset_out) {
+  extern __shared__ float lds[];
+  float *e = lds, *s = lds + d;
+  __shared__ float best_sim[kSmallBatch];
+  __shared__ int32_t best_idx[kSmallBatch], ins_list[kSmallBatch];
+  __shared__ int32_t my_ent, my_src, my_hit, total_ins;
+  __shared__ float peer[kSmallBatch][kSmallBatch + 1];   // peer[q][i] = similarity of prompt q with earlier prompt i
+  const int l = blockIdx.x, p = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  const int count0 = min(*count_in, capacity);
+  // the walk below is sequential: everything it reads is fetched here, all at once
+  for (int t = threadIdx.x; t < (p + 1) * P; t += blockDim.x) {
+    const int q = t / P, i = t - q * P;
+    if (i < q) peer[q][i] = sims[(size_t)q * ld + capacity + i];
+  }
+  for (int q = wave; q <= p; q += nwaves) {
+    float bs = -INFINITY;
+    int bi = -1;
+    for (int j = lane; j < count0; j += 64) {
+      const float v = sims[(size_t)q * ld + j];
+      if (bi < 0 || v > bs) { bs = v; bi = j; }
+    }
+    wave_argmax(bs, bi);
+    if (lane == 0) { best_sim[q] = bs; best_idx[q] = bi; }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int n_ins = 0;
+    for (int q = 0; q <= p; ++q) {
+      float bs = best_sim[q];
+      int bi = best_idx[q];
+      // best among the peers appended so far: larger similarity wins, equal similarity keeps the lower entry
+      float ps = -INFINITY;
+      int pi = -1;
+      for (int i = lane; i < n_ins; i += 64) {
+        const float v = peer[q][ins_list[i]];
+        if (pi < 0 || v > ps) { ps = v; pi = i; }
+      }
+      wave_argmax(ps, pi);
+      int src = -1;
+      if (pi >= 0 && (bi < 0 || ps > bs)) { bs = ps; bi = count0 + pi; src = ins_list[pi]; }
+      const bool h = bi >= 0 && bs >= tau;
+      int ent;
+      if (h) {
+        ent = bi;
+      } else if (count0 + n_ins < capacity) {
+        ent = count0 + n_ins;
+        if (lane == 0) ins_list[n_ins] = q;
+        ++n_ins;
+      } else {
+        ent = -1;
+      }
+      __builtin_amdgcn_s_waitcnt(0);  // the ins_list write is visible to this wave's later reads
+      __builtin_amdgcn_wave_barrier();
+      if (q == p && lane == 0) {
+        my_ent = ent; my_hit = h ? 1 : 0; my_src = h ? src : -1;
+        if (l == 0) {
+          entry_out[p] = ent;
+          hit_out[p] = h ? 1 : 0;
+          if (sim_out) sim_out[p] = bs;
+        }
+      }
+    }
+    if (lane == 0) total_ins = n_ins;
+  }
+  __syncthreads();
+  if (l == 0 && p == P - 1 && threadIdx.x == 0) *count_out = count0 + total_ins;
+  const int ent = my_ent;
+  const bool h = my_hit != 0;
+  if (h && my_src < 0) {          // answered by an entry stored before this batch
+    if (ent >= 0 && ent < capacity && (int)threadIdx.x < k)
+      subset_out[((size_t)p * L + l) * k + threadIdx.x] = values[((size_t)ent * L + l) * k + threadIdx.x];
+    return;
+  }
+  const int from = h ? my_src : p;     // the embedding that defines the key of the answering entry
+  const bool owner = !h && ent >= 0;   // this prompt's miss created entry `ent`
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    const float v = E[(size_t)from * d + c];
+    e[c] = v;
+    if (l == 0 && owner) keys[(size_t)ent * d + c] = v;
+  }
+  __syncthreads();
+  block_router_scores(Wr + (size_t)l * G * d, e, d, G, s);
+  int32_t *sel = reinterpret_cast<int32_t *>(s + 64);  // [64] after the scores
+  if (threadIdx.x < 64) wave_topk_ascending(s, G, k, sel);
+  __syncthreads();
+  if ((int)threadIdx.x < k) {
+    const int32_t g = sel[threadIdx.x];
+    subset_out[((size_t)p * L + l) * k + threadIdx.x] = g;
+    if (owner) values[((size_t)ent * L + l) * k + threadIdx.x] = g;
+  }
+}
+
 __global__ void append_entry(const float *__restrict__ emb, const int32_t *__restrict__ subsets, int d, int Lk,
                              int32_t *__restrict__ count, int capacity, float *__restrict__ keys,
                              int32_t *__restrict__ values) {
@@ -220,6 +324,7 @@ int parse_cache_create(parse_cache **out, int32_t capacity, int32_t d, int32_t L
   if (!c) return PARSE_EINVAL;
   c->capacity = capacity; c->d = d; c->L = L; c->k = k; c->max_batch = max_batch;
   c->count_ub = 0;
+  c->cur = 0;
   const size_t ld = (size_t)capacity + max_batch;
   hipError_t e = hipSuccess;
   auto alloc = [&](void **p, size_t bytes) {
@@ -227,12 +332,12 @@ int parse_cache_create(parse_cache **out, int32_t capacity, int32_t d, int32_t L
   };
   alloc((void **)&c->keys, (size_t)capacity * d * sizeof(float));
   alloc((void **)&c->values, (size_t)capacity * L * k * sizeof(int32_t));
-  alloc((void **)&c->count, sizeof(int32_t));
+  alloc((void **)&c->count, 2 * sizeof(int32_t));
   alloc((void **)&c->sims, (size_t)max_batch * ld * sizeof(float));
   alloc((void **)&c->src, (size_t)max_batch * sizeof(int32_t));
   alloc((void **)&c->entry, (size_t)max_batch * sizeof(int32_t));
   alloc((void **)&c->hit, (size_t)max_batch);
-  if (e == hipSuccess) e = hipMemset(c->count, 0, sizeof(int32_t));
+  if (e == hipSuccess) e = hipMemset(c->count, 0, 2 * sizeof(int32_t));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     set_hip_error(e, "parse_cache_create");
@@ -256,7 +361,7 @@ int parse_cache_destroy(parse_cache *c) {
 int parse_cache_clear(parse_cache *c, parse_stream stream) {
   if (!c) return PARSE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(set_i32, dim3(1), dim3(1), 0, s, c->count, 0);
+  hipLaunchKernelGGL(set_i32, dim3(1), dim3(1), 0, s, c->count + c->cur, 0);
   PARSE_LAUNCH_CHECK();
   PARSE_HIP_TRY(hipStreamSynchronize(s));
   c->count_ub = 0;
@@ -266,7 +371,7 @@ int parse_cache_clear(parse_cache *c, parse_stream stream) {
 int parse_cache_count(parse_cache *c, int32_t *count_out, parse_stream stream) {
   if (!c || !count_out) return PARSE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
-  PARSE_HIP_TRY(hipMemcpyAsync(count_out, c->count, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  PARSE_HIP_TRY(hipMemcpyAsync(count_out, c->count + c->cur, sizeof(int32_t), hipMemcpyDeviceToHost, s));
   PARSE_HIP_TRY(hipStreamSynchronize(s));
   c->count_ub = *count_out;
   return PARSE_OK;
@@ -279,7 +384,7 @@ int parse_cache_insert(parse_cache *c, const float *emb, const int32_t *subsets,
   if (st != PARSE_OK) return st;
   if (n >= c->capacity) return PARSE_ECAPACITY;
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(append_entry, dim3(1), dim3(256), 0, s, emb, subsets, c->d, c->L * c->k, c->count, c->capacity,
+  hipLaunchKernelGGL(append_entry, dim3(1), dim3(256), 0, s, emb, subsets, c->d, c->L * c->k, c->count + c->cur, c->capacity,
                      c->keys, c->values);
   PARSE_LAUNCH_CHECK();
   PARSE_HIP_TRY(hipStreamSynchronize(s));
@@ -296,11 +401,11 @@ int parse_cache_lookup(parse_cache *c, const float *emb, int32_t P, float tau, i
   const int ld = c->capacity + c->max_batch;
   const int ncols = c->count_ub < c->capacity ? c->count_ub : c->capacity;
   if (ncols > 0) {
-    hipLaunchKernelGGL(cache_sims, dim3((ncols + 3) / 4, P), dim3(256), 0, s, emb, c->d, c->keys, c->count, c->capacity,
+    hipLaunchKernelGGL(cache_sims, dim3((ncols + 3) / 4, P), dim3(256), 0, s, emb, c->d, c->keys, c->count + c->cur, c->capacity,
                        ncols, 0, ld, c->sims);
     PARSE_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(resolve, dim3(1), dim3(1024), (size_t)P * 12, s, c->sims, ld, c->capacity, P, tau, 0, c->count,
+  hipLaunchKernelGGL(resolve, dim3(1), dim3(1024), (size_t)P * 12, s, c->sims, ld, c->capacity, P, tau, 0, c->count + c->cur,
                      entry_out, c->hit, sim_out, c->src);
   PARSE_LAUNCH_CHECK();
   if (subset_out) {
@@ -326,12 +431,22 @@ int parse_cache_lookup_or_route(parse_cache *c, const float *emb, int32_t P, flo
   uint8_t *hit = hit_out ? hit_out : c->hit;
   const int ncols = c->count_ub < c->capacity ? c->count_ub : c->capacity;
   if (ncols + P > 1) {   // a single prompt against an empty cache has nothing to compare with
-    hipLaunchKernelGGL(cache_sims, dim3((ncols + P + 3) / 4, P), dim3(256), 0, s, emb, c->d, c->keys, c->count,
+    hipLaunchKernelGGL(cache_sims, dim3((ncols + P + 3) / 4, P), dim3(256), 0, s, emb, c->d, c->keys, c->count + c->cur,
                        c->capacity, ncols, P, ld, c->sims);
     PARSE_LAUNCH_CHECK();
   }
   c->count_ub = (c->count_ub + P < c->capacity) ? c->count_ub + P : c->capacity;
-  hipLaunchKernelGGL(resolve, dim3(1), dim3(1024), (size_t)P * 12, s, c->sims, ld, c->capacity, P, tau, 1, c->count,
+  if (P <= kSmallBatch) {
+    // small batch: every (layer, prompt) workgroup works out the batch's decisions itself, then does its own part;
+    // the new entry count goes to the other counter slot, which becomes the live one
+    hipLaunchKernelGGL(resolve_route_or_gather, dim3(c->L, P), dim3(256), (size_t)(c->d + 128) * sizeof(float), s, c->sims,
+                       ld, c->capacity, P, tau, c->count + c->cur, c->count + (c->cur ^ 1), emb, c->d, Wr, G, c->L, c->k,
+                       entry, hit, sim_out, c->keys, c->values, subset_out);
+    PARSE_LAUNCH_CHECK();
+    c->cur ^= 1;
+    return PARSE_OK;
+  }
+  hipLaunchKernelGGL(resolve, dim3(1), dim3(1024), (size_t)P * 12, s, c->sims, ld, c->capacity, P, tau, 1, c->count + c->cur,
                      entry, hit, sim_out, c->src);
   PARSE_LAUNCH_CHECK();
   hipLaunchKernelGGL(route_or_gather, dim3(c->L, P), dim3(256), (size_t)(c->d + 128) * sizeof(float), s, emb, c->d, Wr,
