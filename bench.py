@@ -141,6 +141,22 @@ def bench_prefill(args, torch, pa, si):
         e1.record(); torch.cuda.synchronize()
         sched_us[nm] = round(e0.elapsed_time(e1) / 20 * 1e3, 2)
     pa.set_prefill_schedule(0)
+    # horizontal fusion, for the record: two layers of this shape that share X, in one call vs two calls
+    # (the same factors stand in for the second layer; its output and intermediate are its own)
+    Y2 = torch.empty_like(Y)
+    ws2 = torch.empty(2 * ws_fwd.numel(), dtype=torch.uint8, device=dev)
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return round(e0.elapsed_time(e1) / reps * 1e3, 2)
+    sched_us["two_layers_one_call"] = timed(lambda: pa.lowrank_prefill_multi([dl, dl], [pt, pt], X, off, pid, [Y, Y2], ws2))
+    sched_us["two_layers_two_calls"] = timed(lambda: (pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y, ws_fwd),
+                                                      pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y2, ws_fwd)))
     assert torch.equal(sub.view(P, k), sub_route), "cache answered with a subset that differs from the route"
     flops = 2.0 * rows * rS * (n + m)
     ms_per_step = wall / args.steps * 1e3

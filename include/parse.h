@@ -248,6 +248,22 @@ int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *
                                const void *X, int32_t rows, const int32_t *pattern_id, void *const *Y,
                                void *workspace, size_t workspace_bytes, parse_stream stream);
 
+/* Horizontal fusion for prefill (Sec. 4.4, Eq. 11-12): n_layers (1..4) bf16 PARSE_MFMA16 layers that read the
+ * SAME token rows X (equal n) in two launches for all of them -- one stacked first product over the selected
+ * ranks of every layer, one batched second product.  The result equals n_layers separate PARSE_PREFILL calls
+ * in their two-launch schedule, bit for bit.
+ *   layers, patterns  host arrays [n_layers]; patterns[l] holds layer l's packed factors (Vt_S, Ut_S, k)
+ *   X                 device [rows][n] bf16; tok_offsets device int32 [P+1]; pattern_id device int32 [P]
+ *   Y                 host array [n_layers] of device pointers, Y[l] = [rows][layers[l].m] bf16
+ *   workspace         device, >= parse_lowrank_prefill_multi_workspace_bytes(...) (the intermediates), required
+ * PARSE_ESHAPE when n or k*gs of a layer is not a multiple of 128 (use separate calls then). */
+size_t parse_lowrank_prefill_multi_workspace_bytes(const parse_layer *layers, const parse_patterns *patterns,
+                                                   int32_t n_layers, int32_t rows);
+int parse_lowrank_prefill_multi(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
+                                const void *X, int32_t rows, const int32_t *tok_offsets,
+                                const int32_t *pattern_id, int32_t P, void *const *Y, void *workspace,
+                                size_t workspace_bytes, parse_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -83,6 +83,11 @@ def lib():
     L.parse_lowrank_decode_multi.restype = C.c_int
     L.parse_lowrank_decode_multi.argtypes = [C.POINTER(_Layer), C.POINTER(_Patterns), i32, vp, i32, vp,
                                              C.POINTER(C.c_void_p), vp, sz, vp]
+    L.parse_lowrank_prefill_multi_workspace_bytes.restype = sz
+    L.parse_lowrank_prefill_multi_workspace_bytes.argtypes = [C.POINTER(_Layer), C.POINTER(_Patterns), i32, i32]
+    L.parse_lowrank_prefill_multi.restype = C.c_int
+    L.parse_lowrank_prefill_multi.argtypes = [C.POINTER(_Layer), C.POINTER(_Patterns), i32, vp, i32, vp, vp, i32,
+                                              C.POINTER(C.c_void_p), vp, sz, vp]
     L.parse_lowrank_forward.restype = C.c_int
     L.parse_lowrank_forward.argtypes = [i32, C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, i32, vp, vp,
                                         sz, vp]
@@ -350,4 +355,21 @@ def lowrank_decode_multi(layers, patterns, X, pattern_id, Ys=None, workspace=Non
     yarr = (C.c_void_p * nl)(*[y.data_ptr() for y in Ys])
     _check(lib().parse_lowrank_decode_multi(larr, parr, nl, _ptr(X), rows, _ptr(pattern_id), yarr, _ptr(workspace),
                                             workspace.numel(), _stream()), "parse_lowrank_decode_multi")
+    return Ys
+
+
+def lowrank_prefill_multi(layers, patterns, X, tok_offsets, pattern_id, Ys=None, workspace=None):
+    """parse_lowrank_prefill_multi: prefill of several layers that share X in two launches.  Returns the list of Y."""
+    rows, nl = X.shape[0], len(layers)
+    P = pattern_id.numel()
+    if Ys is None:
+        Ys = [torch.empty((rows, l.m), dtype=X.dtype, device=X.device) for l in layers]
+    larr = (_Layer * nl)(*[l.c() for l in layers])
+    parr = (_Patterns * nl)(*[p.c() for p in patterns])
+    if workspace is None:
+        need = int(lib().parse_lowrank_prefill_multi_workspace_bytes(larr, parr, nl, rows))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    yarr = (C.c_void_p * nl)(*[y.data_ptr() for y in Ys])
+    _check(lib().parse_lowrank_prefill_multi(larr, parr, nl, _ptr(X), rows, _ptr(tok_offsets), _ptr(pattern_id), P, yarr,
+                                             _ptr(workspace), workspace.numel(), _stream()), "parse_lowrank_prefill_multi")
     return Ys

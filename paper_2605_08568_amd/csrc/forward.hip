@@ -1,5 +1,5 @@
 // parse_lowrank_forward: argument checks and dispatch to the fp32 / bf16 prefill kernels and the decode kernels.
-#include "common.hpp"
+#include "prefill_common.hpp"
 
 namespace parse {
 int forward_f32(const parse_layer *L, const parse_patterns *pt, const float *X, int rows, const int32_t *tok_offsets,
@@ -8,6 +8,8 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
                          const int32_t *tok_offsets, const int32_t *pattern_id, int P, uint16_t *Y, void *workspace,
                          size_t workspace_bytes, hipStream_t s);
 size_t prefill_split_workspace_bytes(int rows, int rS);
+bool prefill_split_supported(int n, int rS);
+int forward_prefill_split_multi_bf16(const PfArgs *p, int n_layers, uint16_t *const *Z, int avg_prompt_rows, hipStream_t s);
 void set_prefill_schedule(int v);
 size_t prefill_lds_bytes(int BM, int rS);
 size_t decode_workspace_bytes(const parse_layer *L);
@@ -105,6 +107,52 @@ int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *
   if (!aligned16(workspace)) return PARSE_EALIGN;
   return forward_decode_multi_bf16(layers, patterns, n_layers, (const uint16_t *)X, rows, pattern_id,
                                    (uint16_t *const *)Y, workspace, (hipStream_t)stream);
+}
+
+size_t parse_lowrank_prefill_multi_workspace_bytes(const parse_layer *layers, const parse_patterns *patterns,
+                                                   int32_t n_layers, int32_t rows) {
+  if (!layers || !patterns || n_layers < 1 || n_layers > 4 || rows <= 0) return 0;
+  size_t total = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (layers[l].G <= 0 || layers[l].R <= 0 || patterns[l].k <= 0) return 0;
+    total += prefill_split_workspace_bytes(rows, patterns[l].k * (layers[l].R / layers[l].G));
+  }
+  return total;
+}
+
+int parse_lowrank_prefill_multi(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
+                                const void *X, int32_t rows, const int32_t *tok_offsets, const int32_t *pattern_id,
+                                int32_t P, void *const *Y, void *workspace, size_t workspace_bytes,
+                                parse_stream stream) {
+  if (!layers || !patterns || !X || !tok_offsets || !pattern_id || !Y) return PARSE_EINVAL;
+  if (n_layers < 1 || rows <= 0 || P <= 0) return PARSE_EINVAL;
+  if (n_layers > 4 || P > rows) return PARSE_ESHAPE;
+  if (!aligned16(X)) return PARSE_EALIGN;
+  PfArgs args[4];
+  for (int l = 0; l < n_layers; ++l) {
+    const parse_layer *L = &layers[l];
+    const parse_patterns *pt = &patterns[l];
+    int st = check_layer(L);
+    if (st != PARSE_OK) return st;
+    if (L->dtype != PARSE_BF16 || L->layout != PARSE_MFMA16) return PARSE_ELAYOUT;
+    if (!Y[l] || !pt->Vt_S || !pt->Ut_S) return PARSE_EINVAL;
+    if (pt->n_patterns <= 0 || pt->k <= 0) return PARSE_EINVAL;
+    const int rS = pt->k * (L->R / L->G);
+    if (pt->k > L->G || L->n != layers[0].n || !prefill_split_supported(L->n, rS)) return PARSE_ESHAPE;
+    if (!aligned16(Y[l]) || !aligned16(pt->Vt_S) || !aligned16(pt->Ut_S)) return PARSE_EALIGN;
+    args[l] = PfArgs{(const uint16_t *)X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, (uint16_t *)Y[l],
+                     tok_offsets, pattern_id, pt->n_patterns, rows, L->n, L->m, rS, P};
+  }
+  const size_t need = parse_lowrank_prefill_multi_workspace_bytes(layers, patterns, n_layers, rows);
+  if (!workspace || workspace_bytes < need) return PARSE_EWORKSPACE;
+  if (!aligned16(workspace)) return PARSE_EALIGN;
+  uint16_t *Z[4];
+  char *ws = reinterpret_cast<char *>(workspace);
+  for (int l = 0; l < n_layers; ++l) {
+    Z[l] = reinterpret_cast<uint16_t *>(ws);
+    ws += prefill_split_workspace_bytes(rows, args[l].rS);
+  }
+  return forward_prefill_split_multi_bf16(args, n_layers, Z, rows / P, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -7,19 +7,33 @@
 // fetched by exactly one wavefront and each staged token operand feeds NB matrix instructions.
 // The intermediate costs 2*T*r_S*2 bytes of extra traffic (it stays in the last-level cache at these sizes) and
 // buys a grid of (T/BT) x (M/(128 NB)) workgroups instead of T/64.
+// Horizontal fusion (Sec. 4.4, Eq. 11-12): layers that read the same token rows share the two launches -- the
+// first is the stacked product over the ranks of all layers, the second the batched product of every layer's own
+// intermediate with its own left factor; a launch's grid is the layers' chunk lists laid end to end.
 #include "prefill_common.hpp"
 
 namespace parse {
 
-struct GtArgs {
+constexpr int GT_MAX_LAYERS = 4;
+
+// One product of one layer.  A launch covers up to GT_MAX_LAYERS of them (layers that share their token rows:
+// the stacked first product and the batched second product of Sec. 4.4, Eq. 11-12): the factor-row chunks of the
+// layers are numbered through, chunk_first is a layer's first.
+struct GtLayer {
   const uint16_t *T;        // token operand [rows][K]
   const uint16_t *F;        // factor operands of all patterns
   uint16_t *O;              // output [rows][M]
-  const int32_t *tok_offsets, *pattern_id;
   size_t pattern_stride;    // elements of F per pattern
   int mb_stride, kb_stride; // operand (mb, kb) starts at (mb*mb_stride + kb*kb_stride) * 512 elements
-  int K, M, rows, P, n_patterns;
-  int ntiles, nchunks, GT;  // token tiles, factor-row chunks, token tiles per locality group
+  int K, M, n_patterns;
+  int chunk_first;
+};
+struct GtArgs {
+  GtLayer L[GT_MAX_LAYERS];
+  int n_layers;
+  const int32_t *tok_offsets, *pattern_id;
+  int rows, P;
+  int ntiles, nchunks, GT;  // token tiles, factor-row chunks (all layers), token tiles per locality group
 };
 
 // KG = 1: four wavefronts, the whole reduction.  KG = 2: eight wavefronts, two groups of four that each run the
@@ -50,11 +64,16 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   const int v = xcd_tile(blockIdx.x, gridDim.x);
   const int per_group = a.nchunks * a.GT;
   const int grp = v / per_group, rem = v % per_group;
-  const int chunk = rem / a.GT, tile = grp * a.GT + rem % a.GT;
+  const int gchunk = rem / a.GT, tile = grp * a.GT + rem % a.GT;
   if (tile >= a.ntiles) return;
+  int li = 0;
+#pragma unroll
+  for (int i = 1; i < GT_MAX_LAYERS; ++i) li += (i < a.n_layers && gchunk >= a.L[i].chunk_first) ? 1 : 0;
+  const GtLayer &ly = a.L[li];
+  const int chunk = gchunk - ly.chunk_first;
   const int row0 = tile * BT;
   const int row_end = min(row0 + BT, a.rows);
-  const int K = a.K, Kg = K / KG, nkb = Kg / 16, nkt = Kg / PF_BK, nmb = a.M / 32;
+  const int K = ly.K, Kg = K / KG, nkb = Kg / 16, nkt = Kg / PF_BK, nmb = ly.M / 32;
   const int kbeg = kg * Kg;        // this group's part of the reduction range
   const int mb0 = chunk * 4 * NB + wave * NB;
 
@@ -64,7 +83,7 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   for (int i = 0; i < XP; ++i) {
     const int piece = i * PF_THREADS + tid;
     const int r = piece / (PF_BK / 8), c = (piece % (PF_BK / 8)) * 8;
-    xsrc[i] = a.T + (size_t)min(row0 + r, a.rows - 1) * K + kbeg + c;
+    xsrc[i] = ly.T + (size_t)min(row0 + r, a.rows - 1) * K + kbeg + c;
     xdst[i] = r * xld + c;
   }
   const int xoff = l32 * xld + q * 8;
@@ -75,13 +94,13 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
     int seg_hi = (p + 1 < a.P) ? a.tok_offsets[p + 1] : a.rows;
     seg_hi = min(max(seg_hi, seg_lo + 1), row_end);
     const int pid = a.pattern_id[p];
-    const bool valid = pid >= 0 && pid < a.n_patterns;
-    const uint16_t *Fp = a.F + (valid ? (size_t)pid * a.pattern_stride : 0);
-    const size_t kstride = (size_t)a.kb_stride * 512;
+    const bool valid = pid >= 0 && pid < ly.n_patterns;
+    const uint16_t *Fp = ly.F + (valid ? (size_t)pid * ly.pattern_stride : 0);
+    const size_t kstride = (size_t)ly.kb_stride * 512;
     const uint16_t *fbase[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i)
-      fbase[i] = Fp + ((size_t)min(mb0 + i, nmb - 1) * a.mb_stride * 64 + lane) * 8 + (size_t)(kbeg / 16) * kstride;
+      fbase[i] = Fp + ((size_t)min(mb0 + i, nmb - 1) * ly.mb_stride * 64 + lane) * 8 + (size_t)(kbeg / 16) * kstride;
 
     f32x16 acc[NT][NB];
 #pragma unroll
@@ -189,8 +208,8 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
           const int piece = it * PF_THREADS + tid;
           const int r = piece / PPR, c = (piece % PPR) * 8;
           const int grow = row0 + tp * 32 + r, gcol = chunk * OC + c;
-          if (grow >= seg_lo && grow < seg_hi && gcol < a.M)
-            *reinterpret_cast<u32x4 *>(a.O + (size_t)grow * a.M + gcol) = *reinterpret_cast<const u32x4 *>(Ot + r * OLD + c);
+          if (grow >= seg_lo && grow < seg_hi && gcol < ly.M)
+            *reinterpret_cast<u32x4 *>(ly.O + (size_t)grow * ly.M + gcol) = *reinterpret_cast<const u32x4 *>(Ot + r * OLD + c);
         }
       }
     }
@@ -201,7 +220,12 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
 template <int BT, int NB, int DEPTH, int KG = 1>
 static int launch_gemm_tokens(GtArgs a, int GT, hipStream_t s) {
   a.ntiles = (a.rows + BT - 1) / BT;
-  a.nchunks = (a.M / 32 + 4 * NB - 1) / (4 * NB);
+  int chunks = 0;
+  for (int l = 0; l < a.n_layers; ++l) {
+    a.L[l].chunk_first = chunks;
+    chunks += (a.L[l].M / 32 + 4 * NB - 1) / (4 * NB);
+  }
+  a.nchunks = chunks;
   a.GT = GT;
   const int groups = (a.ntiles + GT - 1) / GT;
   hipLaunchKernelGGL((gemm_tokens<BT, NB, DEPTH, KG>), dim3(groups * GT * a.nchunks), dim3(PF_THREADS * KG), 0, s, a);
@@ -216,22 +240,35 @@ bool prefill_split_supported(int n, int rS) {
   return n % (2 * PF_BK) == 0 && rS % (2 * PF_BK) == 0 && n / 16 >= PF_DEPTH && rS / 16 >= PF_DEPTH;
 }
 
-int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s) {
-  // launch 1: factor rows = ranks (operand (rb, kb) at rb*(n/16) + kb), tokens = X
-  GtArgs g1{p.X, p.Vt_S, Z, p.tok_offsets, p.pattern_id, (size_t)p.rS * p.n, p.n / 16, 1,
-            p.n, p.rS, p.rows, p.P, p.n_patterns, 0, 0, 0};
+// n_layers layers that share X (same n); p[l].X is the same pointer for all; Z[l] = layer l's part of the workspace.
+int forward_prefill_split_multi_bf16(const PfArgs *p, int n_layers, uint16_t *const *Z, int avg_prompt_rows, hipStream_t s) {
+  if (n_layers < 1 || n_layers > GT_MAX_LAYERS) return PARSE_ESHAPE;
+  // launch 1 (stacked): factor rows = ranks of every layer (operand (rb, kb) at rb*(n/16) + kb), tokens = X
+  GtArgs g1{};
+  g1.n_layers = n_layers;
+  g1.tok_offsets = p[0].tok_offsets; g1.pattern_id = p[0].pattern_id; g1.rows = p[0].rows; g1.P = p[0].P;
+  GtArgs g2 = g1;
+  bool deep2 = true;
+  for (int l = 0; l < n_layers; ++l) {
+    g1.L[l] = GtLayer{p[l].X, p[l].Vt_S, Z[l], (size_t)p[l].rS * p[l].n, p[l].n / 16, 1, p[l].n, p[l].rS, p[l].n_patterns, 0};
+    // launch 2 (batched): factor rows = output columns (operand (cb, kb) at kb*(m/32) + cb), tokens = Z of the layer
+    g2.L[l] = GtLayer{Z[l], p[l].Ut_S, p[l].Y, (size_t)p[l].rS * p[l].m, 1, p[l].m / 32, p[l].rS, p[l].m, p[l].n_patterns, 0};
+    deep2 = deep2 && (p[l].rS % (PF_BK * 4) == 0);
+  }
   int gt64 = avg_prompt_rows / 64;  gt64 = gt64 < 1 ? 1 : (gt64 > 8 ? 8 : gt64);
   // a long reduction over few output tiles: eight wavefronts per workgroup (two reduction halves) when each
   // half is a whole number of ring periods, else four wavefronts
-  const int st = (p.n % (PF_BK * 4) == 0) ? launch_gemm_tokens<64, 2, 8, 2>(g1, gt64, s)
-                                          : launch_gemm_tokens<64, 2, 8>(g1, gt64, s);
+  const int st = (p[0].n % (PF_BK * 4) == 0) ? launch_gemm_tokens<64, 2, 8, 2>(g1, gt64, s)
+                                             : launch_gemm_tokens<64, 2, 8>(g1, gt64, s);
   if (st != PARSE_OK) return st;
-  // launch 2: factor rows = output columns (operand (cb, kb) at kb*(m/32) + cb), tokens = Z
-  GtArgs g2{Z, p.Ut_S, p.Y, p.tok_offsets, p.pattern_id, (size_t)p.rS * p.m, 1, p.m / 32,
-            p.rS, p.m, p.rows, p.P, p.n_patterns, 0, 0, 0};
   int gt128 = avg_prompt_rows / 128;  gt128 = gt128 < 1 ? 1 : (gt128 > 8 ? 8 : gt128);
-  // a deeper operand ring when the reduction length is a whole number of ring periods
-  return (p.rS % (PF_BK * 4) == 0) ? launch_gemm_tokens<128, 2, 16>(g2, gt128, s) : launch_gemm_tokens<128, 2, 8>(g2, gt128, s);
+  // a deeper operand ring when every reduction length is a whole number of ring periods
+  return deep2 ? launch_gemm_tokens<128, 2, 16>(g2, gt128, s) : launch_gemm_tokens<128, 2, 8>(g2, gt128, s);
+}
+
+int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s) {
+  uint16_t *Zs[1] = {Z};
+  return forward_prefill_split_multi_bf16(&p, 1, Zs, avg_prompt_rows, s);
 }
 
 }  // namespace parse

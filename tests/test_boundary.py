@@ -149,3 +149,25 @@ def test_decode_multi_rejects_bad_arguments():
     assert call([La, La], [pt, pt], 2, wsb=64) == -5
     larr = (B._Layer * 2)(La, La)
     assert lib.parse_lowrank_decode_multi_workspace_bytes(larr, 2) == 2 * lib.parse_lowrank_workspace_bytes(1, C.byref(La), 8, 1)
+
+
+def test_prefill_multi_rejects_bad_arguments():
+    lib = pa.lib()
+    La = _layer(n=256, m=256, R=256, G=2, dtype=1, layout=1)          # k*gs = 128
+    Lb = _layer(n=512, m=256, R=256, G=2, dtype=1, layout=1)
+    Lc = _layer(n=256, m=256, R=128, G=2, dtype=1, layout=1)          # k*gs = 64: not a multiple of 128
+    pt = B._Patterns(FAKE.value, FAKE.value, None, 1, 2, 1)
+
+    def call(layers, pats, nl, X=FAKE, rows=8, off=FAKE, pid=FAKE, P=2, ys=None, ws=FAKE, wsb=1 << 24):
+        larr = (B._Layer * len(layers))(*layers)
+        parr = (B._Patterns * len(pats))(*pats)
+        yarr = (C.c_void_p * len(layers))(*(ys if ys is not None else [FAKE.value] * len(layers)))
+        return lib.parse_lowrank_prefill_multi(larr, parr, nl, X, rows, off, pid, P, yarr, ws, wsb, None)
+
+    assert call([La, La], [pt, pt], 0) == -1 and call([La, La], [pt, pt], 2, off=None) == -1
+    assert call([La] * 5, [pt] * 5, 5) == -2 and call([La, La], [pt, pt], 2, P=9) == -2
+    assert call([La, Lb], [pt, pt], 2) == -2                       # the layers must share the input width
+    assert call([La, Lc], [pt, pt], 2) == -2                       # selected ranks not a multiple of 128
+    assert call([La, _layer(n=256, m=256, R=256, G=2, dtype=1, layout=0)], [pt, pt], 2) == -7
+    assert call([La, La], [pt, pt], 2, ys=[FAKE.value, None]) == -1
+    assert call([La, La], [pt, pt], 2, wsb=64) == -5 and call([La, La], [pt, pt], 2, ws=None) == -5

@@ -469,3 +469,42 @@ def test_decode_multi_matches_oracle_and_single_calls(shapes, n, B):
         single = pa.lowrank_forward(pa.PARSE_DECODE, layers[li], patterns[li], xd, None, pid)
         torch.cuda.synchronize()
         assert_close(yn, single.float().cpu().numpy(), TOL_BF16, f"layer {li}: fused vs separate call")
+
+
+@pytest.mark.parametrize("shapes,n,lengths", [
+    ([(768, 256, 8, 4), (512, 256, 4, 2), (1024, 512, 4, 3)], 512, [70, 1, 33, 129, 64]),   # Q/K/V-like, ragged
+    ([(1024, 1024, 8, 4), (1024, 1024, 8, 4)], 1024, [512, 300]),                            # gate/up-like
+])
+def test_prefill_multi_matches_oracle_and_single_calls(shapes, n, lengths):
+    """Horizontal fusion (Sec. 4.4, Eq. 11-12): layers sharing X in two launches = the separate two-launch calls."""
+    say(f"prefill_multi n={n} lengths={lengths} layers={shapes}")
+    rng = np.random.default_rng(711)
+    off = si.offsets_from_lengths(lengths)
+    X = si.make_tokens(rng, int(off[-1]), n, "bf16")
+    Xv = si.bf16_bits_to_f32(X).astype(np.float64)
+    Xd, offd = upload_tokens(X, "bf16"), i32(off)
+    P = len(lengths)
+    pid = i32(np.arange(P, dtype=np.int32))
+    layers, patterns, refs = [], [], []
+    for li, (m, R, G, k) in enumerate(shapes):
+        lay = si.small_layer(720 + li, n, m, R, G, "bf16")
+        subs = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in lengths]).astype(np.int32)
+        U0, sg, V = oracle_factors(lay)
+        refs.append(po.forward(U0, sg, V, lay.gs, Xv, off, subs))
+        dl = pa.layer_to_mfma16(upload_layer(lay))
+        Vs, Us = pa.pack_patterns(dl, i32(subs), k, k, None, None, P)
+        layers.append(dl)
+        patterns.append(pa.Patterns(k, P, Vs, Us))
+    ys = pa.lowrank_prefill_multi(layers, patterns, Xd, offd, pid)
+    torch.cuda.synchronize()
+    pa.set_prefill_schedule(2)
+    try:
+        for li in range(len(shapes)):
+            yn = ys[li].float().cpu().numpy().astype(np.float64)
+            for p in range(P):
+                assert_close(yn[off[p]:off[p + 1]], refs[li][off[p]:off[p + 1]], TOL_BF16, f"layer {li} prompt {p}")
+            single = pa.lowrank_forward(pa.PARSE_PREFILL, layers[li], patterns[li], Xd, offd, pid)
+            torch.cuda.synchronize()
+            assert torch.equal(single.view(torch.int16), ys[li].view(torch.int16)), f"layer {li}: fused vs separate call"
+    finally:
+        pa.set_prefill_schedule(0)
