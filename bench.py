@@ -157,6 +157,14 @@ def bench_prefill(args, torch, pa, si):
     sched_us["two_layers_one_call"] = timed(lambda: pa.lowrank_prefill_multi([dl, dl], [pt, pt], X, off, pid, [Y, Y2], ws2))
     sched_us["two_layers_two_calls"] = timed(lambda: (pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y, ws_fwd),
                                                       pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y2, ws_fwd)))
+    # shared head, for the record (timing only: groups 0,1 stand in as the shared block, the per-pattern blocks
+    # hold each prompt's last k-2 groups; parity of this layout is covered by the tests)
+    ns = 2
+    Vsh, Ush = pa.pack_experts(dl, torch.arange(ns, dtype=torch.int32, device=dev))
+    Vp, Up = pa.pack_patterns(dl, sub.view(P, k)[:, ns:], k, k - ns, None, None, P)
+    pt_sh = pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns)
+    pid_seq = torch.arange(P, dtype=torch.int32, device=dev)
+    sched_us["shared_head_2_of_8"] = timed(lambda: pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh, X, off, pid_seq, Y, ws_fwd))
     assert torch.equal(sub.view(P, k), sub_route), "cache answered with a subset that differs from the route"
     flops = 2.0 * rows * rS * (n + m)
     ms_per_step = wall / args.steps * 1e3

@@ -119,6 +119,14 @@ int parse_route(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_
                 int32_t d, const float *Wr, int32_t G, int32_t k, int32_t *subset_out,
                 int32_t subset_stride, float *scores_out, float *emb_out, void *workspace,
                 size_t workspace_bytes, parse_stream stream);
+/* The same with a shared head (Sec. 4.4, expert memory aggregation: the components with the largest singular
+ * values are used by nearly all prompts and sit at the head of memory): groups 0..n_shared-1 are in every
+ * subset, the router picks the k - n_shared best of the groups n_shared..G-1.  0 <= n_shared <= k;
+ * n_shared = 0 is parse_route. */
+int parse_route_shared(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_offsets, int32_t P,
+                       int32_t d, const float *Wr, int32_t G, int32_t k, int32_t n_shared,
+                       int32_t *subset_out, int32_t subset_stride, float *scores_out, float *emb_out,
+                       void *workspace, size_t workspace_bytes, parse_stream stream);
 
 /* ---- a3: pattern cache (Sec. 4.3, "Rank Retrieval for Prefilling") -------------------------
  * Maps prompt embeddings to the rank subsets of all L routed matrices of a model.  The only
@@ -133,6 +141,9 @@ int parse_cache_create(parse_cache **cache, int32_t capacity, int32_t d, int32_t
                        int32_t max_batch);
 int parse_cache_destroy(parse_cache *cache);
 int parse_cache_clear(parse_cache *cache, parse_stream stream);
+/* Routing on a miss (parse_cache_lookup_or_route) keeps groups 0..n_shared-1 in every subset, as
+ * parse_route_shared does.  Host-side setting, 0 by default; 0 <= n_shared <= k. */
+int parse_cache_set_shared(parse_cache *cache, int32_t n_shared);
 /* count_out: host int32. */
 int parse_cache_count(parse_cache *cache, int32_t *count_out, parse_stream stream);
 /* Appends one entry.  emb device float [d]; subsets device int32 [L][k].  PARSE_ECAPACITY when full. */
@@ -193,14 +204,23 @@ int parse_pack_new_entries(const parse_layer *layer, const int32_t *subset, int3
                            int32_t n_slots, void *Vt_S, void *Ut_S, parse_stream stream);
 
 /* ---- a6 / a7: the routed product ------------------------------------------------------------
- * Patterns of one call.  All patterns of a layer have the same active rank r_S = k*gs. */
+ * Patterns of one call.  All patterns of a layer have the same active rank r_S = k*gs.
+ * Shared head (Sec. 4.4): with n_shared > 0 the first n_shared groups of every pattern are the layer's
+ * groups 0..n_shared-1; they are stored ONCE (Vt_shared, Ut_shared = parse_pack_experts of the ids
+ * 0..n_shared-1) and the per-pattern blocks hold only the other k - n_shared groups (parse_pack_patterns /
+ * parse_pack_new_entries on `subset + n_shared` with k - n_shared ids and the full row stride), so a prompt
+ * reads two contiguous blocks.  bf16 prefill in the two-launch schedule only (a workspace is then required);
+ * decode reads the layer's own store by group id and ignores these three fields. */
 typedef struct {
-  const void *Vt_S;       /* device, packed [n_patterns][k*gs][n] in the layer's layout; prefill only */
-  const void *Ut_S;       /* device, packed [n_patterns][k*gs][m];                       prefill only */
+  const void *Vt_S;       /* device, packed [n_patterns][(k-n_shared)*gs][n] in the layer's layout; prefill only */
+  const void *Ut_S;       /* device, packed [n_patterns][(k-n_shared)*gs][m];                       prefill only */
   const int32_t *subsets; /* device int32, pattern j's ids at subsets[j*subset_stride .. +k); decode only */
   int32_t subset_stride;
   int32_t n_patterns;     /* capacity of the arrays above; pattern ids outside [0, n_patterns) give zero rows */
   int32_t k;
+  const void *Vt_shared;  /* device [n_shared*gs][n], or NULL when n_shared == 0 */
+  const void *Ut_shared;  /* device [n_shared*gs][m], or NULL when n_shared == 0 */
+  int32_t n_shared;
 } parse_patterns;
 
 typedef enum { PARSE_PREFILL = 0, PARSE_DECODE = 1 } parse_mode;

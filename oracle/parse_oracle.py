@@ -99,12 +99,29 @@ def topk_ascending(scores, k: int):
     return np.asarray(chosen, dtype=np.int32), margin
 
 
-def route(E, Wr, k: int):
-    """subset[P][k] (ascending ids) and per-prompt margins for embeddings E."""
+def topk_with_shared(scores, k: int, n_shared: int = 0):
+    """Subset of one score vector when groups 0..n_shared-1 are always active (Sec. 4.4, shared experts at
+    the head of memory): those, plus the k - n_shared best of the other groups; ascending ids and the margin
+    of the routed part."""
+    if n_shared <= 0:
+        return topk_ascending(scores, k)
+    if n_shared >= k:
+        return np.arange(k, dtype=np.int32), float("inf")
+    s = np.asarray(scores, F64).reshape(-1)
+    rest, mg = topk_ascending(s[n_shared:], k - n_shared)
+    return np.concatenate([np.arange(n_shared, dtype=np.int32), rest + n_shared]).astype(np.int32), mg
+
+
+def route(E, Wr, k: int, n_shared: int = 0):
+    """subset[P][k] (ascending ids) and per-prompt margins for embeddings E.
+
+    n_shared > 0 (Sec. 4.4, expert memory aggregation: the components with the largest singular values are
+    shared by all prompts and sit at the head of memory): groups 0..n_shared-1 are always active, the router
+    chooses the k - n_shared best of the remaining groups; the margin is that of the routed part."""
     S = route_scores(E, Wr)
     subs, margins = [], []
     for p in range(S.shape[0]):
-        c, mg = topk_ascending(S[p], k)
+        c, mg = topk_with_shared(S[p], k, n_shared)
         subs.append(c); margins.append(mg)
     return np.asarray(subs, dtype=np.int32).reshape(S.shape[0], k), np.asarray(margins, F64)
 
@@ -123,8 +140,8 @@ class PatternCache:
     a hit needs similarity >= tau.  lookup_or_route: a miss routes every layer's
     subset, and appends (embedding, subsets) while there is room (no eviction)."""
 
-    def __init__(self, capacity: int, d: int, L: int, k: int):
-        self.capacity, self.d, self.L, self.k = capacity, d, L, k
+    def __init__(self, capacity: int, d: int, L: int, k: int, n_shared: int = 0):
+        self.capacity, self.d, self.L, self.k, self.n_shared = capacity, d, L, k, n_shared
         self.keys = np.zeros((0, d), F64)
         self.values = np.zeros((0, L, k), np.int32)
 
@@ -173,7 +190,7 @@ class PatternCache:
                 continue
             S = np.zeros((self.L, self.k), np.int32)
             for l in range(self.L):
-                c, mg = topk_ascending(Wr[l] @ E[p], self.k)
+                c, mg = topk_with_shared(Wr[l] @ E[p], self.k, self.n_shared)
                 S[l] = c
                 route_margin[p] = min(route_margin[p], mg)
             subs[p] = S

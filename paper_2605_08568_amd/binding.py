@@ -31,7 +31,8 @@ class _Layer(C.Structure):
 
 class _Patterns(C.Structure):
     _fields_ = [("Vt_S", C.c_void_p), ("Ut_S", C.c_void_p), ("subsets", C.c_void_p),
-                ("subset_stride", C.c_int32), ("n_patterns", C.c_int32), ("k", C.c_int32)]
+                ("subset_stride", C.c_int32), ("n_patterns", C.c_int32), ("k", C.c_int32),
+                ("Vt_shared", C.c_void_p), ("Ut_shared", C.c_void_p), ("n_shared", C.c_int32)]
 
 
 _lib = None
@@ -57,6 +58,9 @@ def lib():
     L.parse_route_workspace_bytes.restype = sz; L.parse_route_workspace_bytes.argtypes = [i32, i32, i32]
     L.parse_route.restype = C.c_int
     L.parse_route.argtypes = [vp, i32, i32, vp, i32, i32, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+    L.parse_route_shared.restype = C.c_int
+    L.parse_route_shared.argtypes = [vp, i32, i32, vp, i32, i32, vp, i32, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+    L.parse_cache_set_shared.restype = C.c_int; L.parse_cache_set_shared.argtypes = [vp, i32]
     L.parse_cache_create.restype = C.c_int
     L.parse_cache_create.argtypes = [C.POINTER(vp), i32, i32, i32, i32, i32]
     L.parse_cache_destroy.restype = C.c_int; L.parse_cache_destroy.argtypes = [vp]
@@ -153,15 +157,19 @@ class Layer:
 class Patterns:
     """parse_patterns."""
 
-    def __init__(self, k: int, n_patterns: int, Vt_S=None, Ut_S=None, subsets=None, subset_stride=None):
+    def __init__(self, k: int, n_patterns: int, Vt_S=None, Ut_S=None, subsets=None, subset_stride=None,
+                 Vt_shared=None, Ut_shared=None, n_shared: int = 0):
         self.k, self.n_patterns, self.Vt_S, self.Ut_S, self.subsets = k, n_patterns, Vt_S, Ut_S, subsets
         self.subset_stride = k if subset_stride is None else subset_stride
+        self.Vt_shared, self.Ut_shared, self.n_shared = Vt_shared, Ut_shared, n_shared
 
     def c(self) -> _Patterns:
         return _Patterns(None if self.Vt_S is None else self.Vt_S.data_ptr(),
                          None if self.Ut_S is None else self.Ut_S.data_ptr(),
                          None if self.subsets is None else self.subsets.data_ptr(),
-                         self.subset_stride, self.n_patterns, self.k)
+                         self.subset_stride, self.n_patterns, self.k,
+                         None if self.Vt_shared is None else self.Vt_shared.data_ptr(),
+                         None if self.Ut_shared is None else self.Ut_shared.data_ptr(), self.n_shared)
 
 
 def check_offsets(tok_offsets_host: np.ndarray, rows: int) -> int:
@@ -186,8 +194,9 @@ def route_workspace_bytes(rows: int, P: int, d: int) -> int:
 
 
 def route(X, tok_offsets, Wr, k, subset_out=None, subset_stride=None, scores_out=None, emb_out=None,
-          workspace=None):
-    """parse_route.  X [rows][d], tok_offsets int32 device [P+1], Wr float device [G][d]."""
+          workspace=None, n_shared=None):
+    """parse_route (parse_route_shared when n_shared is given).  X [rows][d], tok_offsets int32 device [P+1],
+    Wr float device [G][d]."""
     rows, d = X.shape
     P = tok_offsets.numel() - 1
     G = Wr.shape[0]
@@ -196,9 +205,14 @@ def route(X, tok_offsets, Wr, k, subset_out=None, subset_stride=None, scores_out
         subset_out = torch.empty((P, stride), dtype=torch.int32, device=X.device)
     if workspace is None:
         workspace = torch.empty(max(route_workspace_bytes(rows, P, d), 256), dtype=torch.uint8, device=X.device)
-    _check(lib().parse_route(_ptr(X), _dtype_code(X), rows, _ptr(tok_offsets), P, d, _ptr(Wr), G, k,
-                             _ptr(subset_out), stride, _ptr(scores_out), _ptr(emb_out), _ptr(workspace),
-                             workspace.numel(), _stream()), "parse_route")
+    if n_shared is None:
+        _check(lib().parse_route(_ptr(X), _dtype_code(X), rows, _ptr(tok_offsets), P, d, _ptr(Wr), G, k,
+                                 _ptr(subset_out), stride, _ptr(scores_out), _ptr(emb_out), _ptr(workspace),
+                                 workspace.numel(), _stream()), "parse_route")
+    else:
+        _check(lib().parse_route_shared(_ptr(X), _dtype_code(X), rows, _ptr(tok_offsets), P, d, _ptr(Wr), G, k, n_shared,
+                                        _ptr(subset_out), stride, _ptr(scores_out), _ptr(emb_out), _ptr(workspace),
+                                        workspace.numel(), _stream()), "parse_route_shared")
     return subset_out
 
 
@@ -224,6 +238,9 @@ class Cache:
 
     def clear(self):
         _check(lib().parse_cache_clear(self._h, _stream()), "parse_cache_clear")
+
+    def set_shared(self, n_shared: int):
+        _check(lib().parse_cache_set_shared(self._h, n_shared), "parse_cache_set_shared")
 
     def count(self) -> int:
         n = C.c_int32(0)

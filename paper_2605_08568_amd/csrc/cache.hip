@@ -29,6 +29,7 @@ struct parse_cache {
   int32_t *src;     // [max_batch] prompt whose embedding defines the answer's key (in-batch entries), else -1
   int32_t *entry;   // [max_batch] (used when the caller passes no entry_out)
   uint8_t *hit;     // [max_batch]
+  int32_t n_shared; // leading groups every routed subset holds (route-on-miss uses it)
   int32_t count_ub; // host-side upper bound of *count (exact after count/insert/clear); sizes the probe grid
 };
 
@@ -153,7 +154,8 @@ __global__ __launch_bounds__(256) void route_or_gather(const float *__restrict__
                                                        int G, int L, int k, int capacity, int do_route,
                                                        const int32_t *__restrict__ entry, const uint8_t *__restrict__ hit,
                                                        const int32_t *__restrict__ src, float *__restrict__ keys,
-                                                       int32_t *__restrict__ values, int32_t *__restrict__ subset_out) {
+                                                       int32_t *__restrict__ values, int32_t *__restrict__ subset_out,
+                                                       int n_shared) {
   extern __shared__ float lds[];
   float *e = lds, *s = lds + d;
   const int l = blockIdx.x, p = blockIdx.y;
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(256) void route_or_gather(const float *__restrict__
   __syncthreads();
   block_router_scores(Wr + (size_t)l * G * d, e, d, G, s);
   int32_t *sel = reinterpret_cast<int32_t *>(s + 64);  // [64] after the scores
-  if (threadIdx.x < 64) wave_topk_ascending(s, G, k, sel);
+  if (threadIdx.x < 64) wave_topk_ascending(s, G, k, sel, n_shared);
   __syncthreads();
   if (threadIdx.x < k) {
     const int32_t g = sel[threadIdx.x];
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(256) void resolve_route_or_gather(
     const float *__restrict__ sims, int ld, int capacity, int P, float tau, const int32_t *__restrict__ count_in,
     int32_t *__restrict__ count_out, const float *__restrict__ E, int d, const float *__restrict__ Wr, int G, int L, int k,
     int32_t *__restrict__ entry_out, uint8_t *__restrict__ hit_out, float *__restrict__ sim_out,
-    float *__restrict__ keys, int32_t *__restrict__ values, int32_t *__restrict__ subset_out) {
+    float *__restrict__ keys, int32_t *__restrict__ values, int32_t *__restrict__ subset_out, int n_shared) {
   extern __shared__ float lds[];
   float *e = lds, *s = lds + d;
   __shared__ float best_sim[kSmallBatch];
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(256) void resolve_route_or_gather(
   __syncthreads();
   block_router_scores(Wr + (size_t)l * G * d, e, d, G, s);
   int32_t *sel = reinterpret_cast<int32_t *>(s + 64);  // [64] after the scores
-  if (threadIdx.x < 64) wave_topk_ascending(s, G, k, sel);
+  if (threadIdx.x < 64) wave_topk_ascending(s, G, k, sel, n_shared);
   __syncthreads();
   if ((int)threadIdx.x < k) {
     const int32_t g = sel[threadIdx.x];
@@ -325,6 +327,7 @@ int parse_cache_create(parse_cache **out, int32_t capacity, int32_t d, int32_t L
   c->capacity = capacity; c->d = d; c->L = L; c->k = k; c->max_batch = max_batch;
   c->count_ub = 0;
   c->cur = 0;
+  c->n_shared = 0;
   const size_t ld = (size_t)capacity + max_batch;
   hipError_t e = hipSuccess;
   auto alloc = [&](void **p, size_t bytes) {
@@ -355,6 +358,13 @@ int parse_cache_destroy(parse_cache *c) {
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   delete c;
+  return PARSE_OK;
+}
+
+int parse_cache_set_shared(parse_cache *c, int32_t n_shared) {
+  if (!c || n_shared < 0) return PARSE_EINVAL;
+  if (n_shared > c->k) return PARSE_ESHAPE;
+  c->n_shared = n_shared;
   return PARSE_OK;
 }
 
@@ -410,7 +420,7 @@ int parse_cache_lookup(parse_cache *c, const float *emb, int32_t P, float tau, i
   PARSE_LAUNCH_CHECK();
   if (subset_out) {
     hipLaunchKernelGGL(route_or_gather, dim3(c->L, P), dim3(256), 0, s, emb, c->d, (const float *)nullptr, 0, c->L,
-                       c->k, c->capacity, 0, entry_out, c->hit, c->src, c->keys, c->values, subset_out);
+                       c->k, c->capacity, 0, entry_out, c->hit, c->src, c->keys, c->values, subset_out, 0);
     PARSE_LAUNCH_CHECK();
   }
   return PARSE_OK;
@@ -441,7 +451,7 @@ int parse_cache_lookup_or_route(parse_cache *c, const float *emb, int32_t P, flo
     // the new entry count goes to the other counter slot, which becomes the live one
     hipLaunchKernelGGL(resolve_route_or_gather, dim3(c->L, P), dim3(256), (size_t)(c->d + 128) * sizeof(float), s, c->sims,
                        ld, c->capacity, P, tau, c->count + c->cur, c->count + (c->cur ^ 1), emb, c->d, Wr, G, c->L, c->k,
-                       entry, hit, sim_out, c->keys, c->values, subset_out);
+                       entry, hit, sim_out, c->keys, c->values, subset_out, c->n_shared);
     PARSE_LAUNCH_CHECK();
     c->cur ^= 1;
     return PARSE_OK;
@@ -450,7 +460,7 @@ int parse_cache_lookup_or_route(parse_cache *c, const float *emb, int32_t P, flo
                      entry, hit, sim_out, c->src);
   PARSE_LAUNCH_CHECK();
   hipLaunchKernelGGL(route_or_gather, dim3(c->L, P), dim3(256), (size_t)(c->d + 128) * sizeof(float), s, emb, c->d, Wr,
-                     G, c->L, c->k, c->capacity, 1, entry, hit, c->src, c->keys, c->values, subset_out);
+                     G, c->L, c->k, c->capacity, 1, entry, hit, c->src, c->keys, c->values, subset_out, c->n_shared);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }

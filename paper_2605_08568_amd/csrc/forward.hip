@@ -63,6 +63,13 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patter
 
   if (!tok_offsets || !pt->Vt_S || !pt->Ut_S) return PARSE_EINVAL;
   if (!aligned16(pt->Vt_S) || !aligned16(pt->Ut_S)) return PARSE_EALIGN;
+  if (pt->n_shared < 0) return PARSE_EINVAL;
+  if (pt->n_shared > 0) {   // shared head: bf16 operand-order layers, two-launch schedule
+    if (L->dtype != PARSE_BF16 || L->layout != PARSE_MFMA16) return PARSE_ELAYOUT;
+    if (!pt->Vt_shared || !pt->Ut_shared) return PARSE_EINVAL;
+    if (pt->n_shared >= pt->k) return PARSE_ESHAPE;
+    if (!aligned16(pt->Vt_shared) || !aligned16(pt->Ut_shared)) return PARSE_EALIGN;
+  }
   if (L->dtype == PARSE_F32) {
     if (L->layout != PARSE_ROWMAJOR) return PARSE_ELAYOUT;
     return forward_f32(L, pt, (const float *)X, rows, tok_offsets, pattern_id, P, (float *)Y, workspace, s);
@@ -142,6 +149,15 @@ int parse_lowrank_prefill_multi(const parse_layer *layers, const parse_patterns 
     if (!aligned16(Y[l]) || !aligned16(pt->Vt_S) || !aligned16(pt->Ut_S)) return PARSE_EALIGN;
     args[l] = PfArgs{(const uint16_t *)X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, (uint16_t *)Y[l],
                      tok_offsets, pattern_id, pt->n_patterns, rows, L->n, L->m, rS, P};
+    if (pt->n_shared < 0) return PARSE_EINVAL;
+    if (pt->n_shared > 0) {
+      if (!pt->Vt_shared || !pt->Ut_shared) return PARSE_EINVAL;
+      if (pt->n_shared >= pt->k) return PARSE_ESHAPE;
+      if (!aligned16(pt->Vt_shared) || !aligned16(pt->Ut_shared)) return PARSE_EALIGN;
+      args[l].Vt_sh = (const uint16_t *)pt->Vt_shared;
+      args[l].Ut_sh = (const uint16_t *)pt->Ut_shared;
+      args[l].sh_ranks = pt->n_shared * (L->R / L->G);
+    }
   }
   const size_t need = parse_lowrank_prefill_multi_workspace_bytes(layers, patterns, n_layers, rows);
   if (!workspace || workspace_bytes < need) return PARSE_EWORKSPACE;

@@ -364,14 +364,19 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
   const int gs = L->R / L->G, rS = pt->k * gs;
   PfArgs a{X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, Y, tok_offsets, pattern_id,
            pt->n_patterns, rows, L->n, L->m, rS, P};
+  if (pt->n_shared > 0) {   // shared head: operands from two blocks, built into the two-launch kernels only
+    a.Vt_sh = (const uint16_t *)pt->Vt_shared;
+    a.Ut_sh = (const uint16_t *)pt->Ut_shared;
+    a.sh_ranks = pt->n_shared * gs;
+  }
   // The fused kernel runs rows/64 workgroups, one per compute unit: below about two waves of the 256 units
   // the two-launch form (which needs the Z workspace) fills the chip better.
   const bool can_split = workspace != nullptr && workspace_bytes >= prefill_split_workspace_bytes(rows, rS) &&
                          prefill_split_supported(L->n, rS);
   bool split = can_split && (rows / 64 < 512);
   if (g_prefill_schedule == 1) split = false;
-  if (g_prefill_schedule == 2) {
-    if (!can_split) return PARSE_EWORKSPACE;
+  if (g_prefill_schedule == 2 || a.sh_ranks > 0) {
+    if (!can_split) return prefill_split_supported(L->n, rS) ? PARSE_EWORKSPACE : PARSE_ESHAPE;
     split = true;
   }
   if (split) return forward_prefill_split_bf16(a, (uint16_t *)workspace, rows / (P > 0 ? P : 1), s);

@@ -32,6 +32,10 @@ struct PfArgs {
   uint16_t *Y;
   const int32_t *tok_offsets, *pattern_id;
   int n_patterns, rows, n, m, rS, P;
+  // shared head (Sec. 4.4): the first sh_ranks of the rS selected ranks live once in Vt_sh / Ut_sh, the packed
+  // per-pattern blocks hold the other rS - sh_ranks; 0 = everything per pattern
+  const uint16_t *Vt_sh = nullptr, *Ut_sh = nullptr;
+  int sh_ranks = 0;
 };
 
 

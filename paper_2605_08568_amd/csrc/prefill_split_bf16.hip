@@ -27,6 +27,8 @@ struct GtLayer {
   int mb_stride, kb_stride; // operand (mb, kb) starts at (mb*mb_stride + kb*kb_stride) * 512 elements
   int K, M, n_patterns;
   int chunk_first;
+  const uint16_t *Fsh;      // shared head: operands of the first sh_blocks factor-row blocks (SH == 1) or
+  int sh_blocks;            // reduction blocks (SH == 2) come from here, the rest from F, renumbered from 0
 };
 struct GtArgs {
   GtLayer L[GT_MAX_LAYERS];
@@ -40,7 +42,10 @@ struct GtArgs {
 // same loop over one half of the reduction range with their own staged tiles and add their accumulators through
 // LDS at the end.  The tile and the bytes fetched per workgroup are the same; what the second group buys is a
 // second, independent instruction stream on every SIMD, so a wait of one wavefront is covered by the other.
-template <int BT, int NB, int DEPTH, int KG>
+// SH = 0: all factor operands from the pattern's block.  SH = 1: the leading factor-row blocks, SH = 2: the
+// leading reduction blocks come from the layer's shared block (Sec. 4.4: shared experts at the head of memory,
+// stored once) -- "two contiguous reads" per prompt instead of one.
+template <int BT, int NB, int DEPTH, int KG, int SH>
 __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   constexpr int TPI = DEPTH / 4;   // staged tiles per unrolled loop iteration = ring depth in tiles
   constexpr int NT = BT / 32;
@@ -97,10 +102,26 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
     const bool valid = pid >= 0 && pid < ly.n_patterns;
     const uint16_t *Fp = ly.F + (valid ? (size_t)pid * ly.pattern_stride : 0);
     const size_t kstride = (size_t)ly.kb_stride * 512;
-    const uint16_t *fbase[NB];
+    const uint16_t *fbase[NB], *fshared[NB];
+    const int shb = SH == 2 ? ly.sh_blocks : 0;
 #pragma unroll
-    for (int i = 0; i < NB; ++i)
-      fbase[i] = Fp + ((size_t)min(mb0 + i, nmb - 1) * ly.mb_stride * 64 + lane) * 8 + (size_t)(kbeg / 16) * kstride;
+    for (int i = 0; i < NB; ++i) {
+      const int mb = min(mb0 + i, nmb - 1);
+      if (SH == 1) {
+        const bool in_head = mb < ly.sh_blocks;
+        fbase[i] = (in_head ? ly.Fsh : Fp) + ((size_t)(in_head ? mb : mb - ly.sh_blocks) * ly.mb_stride * 64 + lane) * 8 +
+                   (size_t)(kbeg / 16) * kstride;
+      } else {
+        fbase[i] = Fp + ((size_t)mb * ly.mb_stride * 64 + lane) * 8 + (size_t)(kbeg / 16) * kstride;
+      }
+      // SH == 2: reduction block kb < shb is operand kb of the shared block, else operand kb - shb of the pattern's
+      fshared[i] = SH == 2 ? ly.Fsh + ((size_t)mb * ly.mb_stride * 64 + lane) * 8 : nullptr;
+      if (SH == 2) fbase[i] -= (size_t)shb * kstride;
+    }
+    auto fptr = [&](int i, int kb) -> const uint16_t * {
+      if (SH == 2) return (kb < shb ? fshared[i] : fbase[i]) + (size_t)kb * kstride;
+      return fbase[i] + (size_t)kb * kstride;
+    };
 
     f32x16 acc[NT][NB];
 #pragma unroll
@@ -117,7 +138,7 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
 #pragma unroll
-      for (int i = 0; i < NB; ++i) fr[d][i] = *reinterpret_cast<const u32x4 *>(fbase[i] + d * kstride);
+      for (int i = 0; i < NB; ++i) fr[d][i] = *reinterpret_cast<const u32x4 *>(fptr(i, d));
 #pragma unroll
     for (int i = 0; i < XP; ++i) xr[1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + PF_BK);
 #pragma unroll
@@ -150,7 +171,7 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
               acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fr[u * 4 + s][i]), xb[s & 1][t], acc[t][i], 0, 0, 0);
           const int kbn = min(kt * 4 + s + DEPTH, nkb - 1);
 #pragma unroll
-          for (int i = 0; i < NB; ++i) fr[u * 4 + s][i] = *reinterpret_cast<const u32x4 *>(fbase[i] + kbn * kstride);
+          for (int i = 0; i < NB; ++i) fr[u * 4 + s][i] = *reinterpret_cast<const u32x4 *>(fptr(i, kbn));
           __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -217,7 +238,7 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   }
 }
 
-template <int BT, int NB, int DEPTH, int KG = 1>
+template <int BT, int NB, int DEPTH, int KG, int SH>
 static int launch_gemm_tokens(GtArgs a, int GT, hipStream_t s) {
   a.ntiles = (a.rows + BT - 1) / BT;
   int chunks = 0;
@@ -228,7 +249,7 @@ static int launch_gemm_tokens(GtArgs a, int GT, hipStream_t s) {
   a.nchunks = chunks;
   a.GT = GT;
   const int groups = (a.ntiles + GT - 1) / GT;
-  hipLaunchKernelGGL((gemm_tokens<BT, NB, DEPTH, KG>), dim3(groups * GT * a.nchunks), dim3(PF_THREADS * KG), 0, s, a);
+  hipLaunchKernelGGL((gemm_tokens<BT, NB, DEPTH, KG, SH>), dim3(groups * GT * a.nchunks), dim3(PF_THREADS * KG), 0, s, a);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }
@@ -248,22 +269,28 @@ int forward_prefill_split_multi_bf16(const PfArgs *p, int n_layers, uint16_t *co
   g1.n_layers = n_layers;
   g1.tok_offsets = p[0].tok_offsets; g1.pattern_id = p[0].pattern_id; g1.rows = p[0].rows; g1.P = p[0].P;
   GtArgs g2 = g1;
-  bool deep2 = true;
+  bool deep2 = true, shared = false;
   for (int l = 0; l < n_layers; ++l) {
-    g1.L[l] = GtLayer{p[l].X, p[l].Vt_S, Z[l], (size_t)p[l].rS * p[l].n, p[l].n / 16, 1, p[l].n, p[l].rS, p[l].n_patterns, 0};
+    const int rp = p[l].rS - p[l].sh_ranks;   // ranks in the per-pattern blocks
+    g1.L[l] = GtLayer{p[l].X, p[l].Vt_S, Z[l], (size_t)rp * p[l].n, p[l].n / 16, 1, p[l].n, p[l].rS, p[l].n_patterns, 0,
+                      p[l].Vt_sh, p[l].sh_ranks / 32};
     // launch 2 (batched): factor rows = output columns (operand (cb, kb) at kb*(m/32) + cb), tokens = Z of the layer
-    g2.L[l] = GtLayer{Z[l], p[l].Ut_S, p[l].Y, (size_t)p[l].rS * p[l].m, 1, p[l].m / 32, p[l].rS, p[l].m, p[l].n_patterns, 0};
+    g2.L[l] = GtLayer{Z[l], p[l].Ut_S, p[l].Y, (size_t)rp * p[l].m, 1, p[l].m / 32, p[l].rS, p[l].m, p[l].n_patterns, 0,
+                      p[l].Ut_sh, p[l].sh_ranks / 16};
     deep2 = deep2 && (p[l].rS % (PF_BK * 4) == 0);
+    shared = shared || p[l].sh_ranks > 0;
   }
   int gt64 = avg_prompt_rows / 64;  gt64 = gt64 < 1 ? 1 : (gt64 > 8 ? 8 : gt64);
   // a long reduction over few output tiles: eight wavefronts per workgroup (two reduction halves) when each
   // half is a whole number of ring periods, else four wavefronts
-  const int st = (p[0].n % (PF_BK * 4) == 0) ? launch_gemm_tokens<64, 2, 8, 2>(g1, gt64, s)
-                                             : launch_gemm_tokens<64, 2, 8>(g1, gt64, s);
+  const bool halves = p[0].n % (PF_BK * 4) == 0;
+  const int st = shared ? (halves ? launch_gemm_tokens<64, 2, 8, 2, 1>(g1, gt64, s) : launch_gemm_tokens<64, 2, 8, 1, 1>(g1, gt64, s))
+                        : (halves ? launch_gemm_tokens<64, 2, 8, 2, 0>(g1, gt64, s) : launch_gemm_tokens<64, 2, 8, 1, 0>(g1, gt64, s));
   if (st != PARSE_OK) return st;
   int gt128 = avg_prompt_rows / 128;  gt128 = gt128 < 1 ? 1 : (gt128 > 8 ? 8 : gt128);
   // a deeper operand ring when every reduction length is a whole number of ring periods
-  return deep2 ? launch_gemm_tokens<128, 2, 16>(g2, gt128, s) : launch_gemm_tokens<128, 2, 8>(g2, gt128, s);
+  if (shared) return deep2 ? launch_gemm_tokens<128, 2, 16, 1, 2>(g2, gt128, s) : launch_gemm_tokens<128, 2, 8, 1, 2>(g2, gt128, s);
+  return deep2 ? launch_gemm_tokens<128, 2, 16, 1, 0>(g2, gt128, s) : launch_gemm_tokens<128, 2, 8, 1, 0>(g2, gt128, s);
 }
 
 int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s) {

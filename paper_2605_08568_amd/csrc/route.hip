@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kFinishThreads) void route_finish(const float *__re
                                                                const float *__restrict__ Wr, int G, int k,
                                                                int32_t *__restrict__ subset_out, int subset_stride,
                                                                float *__restrict__ scores_out,
-                                                               float *__restrict__ emb_out) {
+                                                               float *__restrict__ emb_out, int n_shared) {
   extern __shared__ float lds[];
   float *e = lds;          // [d]
   float *s = lds + d;      // [64]
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kFinishThreads) void route_finish(const float *__re
   block_router_scores(Wr, e, d, G, s);
   if (scores_out)
     for (int g = threadIdx.x; g < G; g += blockDim.x) scores_out[(size_t)p * G + g] = s[g];
-  if (threadIdx.x < 64) wave_topk_ascending(s, G, k, subset_out + (size_t)p * subset_stride);
+  if (threadIdx.x < 64) wave_topk_ascending(s, G, k, subset_out + (size_t)p * subset_stride, n_shared);
 }
 
 // Slices per prompt: enough workgroups to keep every compute unit streaming (about two per unit), a slice of
@@ -138,10 +138,19 @@ int parse_route(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_
                 const float *Wr, int32_t G, int32_t k, int32_t *subset_out, int32_t subset_stride,
                 float *scores_out, float *emb_out, void *workspace, size_t workspace_bytes,
                 parse_stream stream) {
+  return parse_route_shared(X, xdtype, rows, tok_offsets, P, d, Wr, G, k, 0, subset_out, subset_stride, scores_out,
+                            emb_out, workspace, workspace_bytes, stream);
+}
+
+int parse_route_shared(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_offsets, int32_t P, int32_t d,
+                       const float *Wr, int32_t G, int32_t k, int32_t n_shared, int32_t *subset_out,
+                       int32_t subset_stride, float *scores_out, float *emb_out, void *workspace,
+                       size_t workspace_bytes, parse_stream stream) {
   if (!X || !tok_offsets || !Wr || !subset_out) return PARSE_EINVAL;
   if (xdtype != PARSE_F32 && xdtype != PARSE_BF16) return PARSE_EINVAL;
   if (rows <= 0 || P <= 0 || d <= 0 || G <= 0 || k <= 0) return PARSE_EINVAL;
-  if (k > G || G > 64 || d > 16384 || P > rows || subset_stride < k) return PARSE_ESHAPE;
+  if (n_shared < 0) return PARSE_EINVAL;
+  if (k > G || G > 64 || d > 16384 || P > rows || subset_stride < k || n_shared > k) return PARSE_ESHAPE;
   if (d % 8 != 0) return PARSE_EALIGN;
   if (!aligned16(X) || !aligned16(Wr) || !aligned16(workspace)) return PARSE_EALIGN;
   if (emb_out && !aligned16(emb_out)) return PARSE_EALIGN;
@@ -159,7 +168,7 @@ int parse_route(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_
   PARSE_LAUNCH_CHECK();
   const size_t lds = (size_t)(d + 64) * sizeof(float);
   hipLaunchKernelGGL(route_finish, dim3(P), dim3(kFinishThreads), lds, s, partial, Q, rows, d, tok_offsets, Wr, G, k,
-                     subset_out, subset_stride, scores_out, emb_out);
+                     subset_out, subset_stride, scores_out, emb_out, n_shared);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }

@@ -26,19 +26,25 @@ __device__ __forceinline__ void block_router_scores(const float *__restrict__ Wr
   __syncthreads();
 }
 
-// Top-k of s_lds[0..G), G <= 64, by ONE wavefront (call with the 64 lanes of wave 0): lane g ranks its
-// score (larger first, equal scores by lower id), the k best ids are written ascending to out[0..k).
-__device__ __forceinline__ void wave_topk_ascending(const float *s_lds, int G, int k, int32_t *out) {
+// Top-k of s_lds[0..G), G <= 64, by ONE wavefront (call with the 64 lanes of wave 0): groups 0..n_shared-1 are
+// always taken (the shared head, Sec. 4.4); lane g >= n_shared ranks its score among the other routed groups
+// (larger first, equal scores by lower id) and is taken when its rank is below k - n_shared; the k ids are
+// written ascending to out[0..k).
+__device__ __forceinline__ void wave_topk_ascending(const float *s_lds, int G, int k, int32_t *out, int n_shared = 0) {
   const int g = threadIdx.x & 63;
   bool sel = false;
   if (g < G) {
-    const float s = s_lds[g];
-    int rank = 0;
-    for (int h = 0; h < G; ++h) {
-      const float t = s_lds[h];
-      rank += (t > s || (t == s && h < g)) ? 1 : 0;
+    if (g < n_shared) {
+      sel = g < k;
+    } else {
+      const float s = s_lds[g];
+      int rank = 0;
+      for (int h = n_shared; h < G; ++h) {
+        const float t = s_lds[h];
+        rank += (t > s || (t == s && h < g)) ? 1 : 0;
+      }
+      sel = rank < k - n_shared;
     }
-    sel = rank < k;
   }
   const unsigned long long mask = __ballot(sel);
   if (sel) {

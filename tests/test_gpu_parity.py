@@ -508,3 +508,71 @@ def test_prefill_multi_matches_oracle_and_single_calls(shapes, n, lengths):
             assert torch.equal(single.view(torch.int16), ys[li].view(torch.int16)), f"layer {li}: fused vs separate call"
     finally:
         pa.set_prefill_schedule(0)
+
+
+def test_shared_head_route_cache_pack_and_prefill():
+    """Shared experts at the head of memory (Sec. 4.4): groups 0..n_shared-1 in every subset, stored once; the
+    per-pattern blocks hold the rest.  Route and cache give the oracle's subsets; the product equals the oracle
+    and is bit-identical to the same subsets packed whole."""
+    say("shared head: route, cache route-on-miss, two-block pack, prefill")
+    n, m, R, G, k, ns = 512, 768, 512, 8, 4, 2
+    lengths = [70, 1, 200, 129]
+    lay = si.small_layer(801, n, m, R, G, "bf16")
+    rng = np.random.default_rng(802)
+    off = si.offsets_from_lengths(lengths)
+    X = si.make_tokens(rng, int(off[-1]), n, "bf16")
+    Xv = si.bf16_bits_to_f32(X).astype(np.float64)
+    Wr = (rng.standard_normal((1, G, n)) / np.sqrt(n)).astype(np.float32)
+    E = po.pool(Xv, off)
+    subs_ref, margin = po.route(E, Wr[0], k, n_shared=ns)
+    assert np.all(margin > 1e-4 * np.abs(E @ Wr[0].T.astype(np.float64)).max())
+    assert np.all(subs_ref[:, :ns] == np.arange(ns))
+    Xd, offd, Wrd = upload_tokens(X, "bf16"), i32(off), torch.from_numpy(Wr).to(DEV)
+    P = len(lengths)
+    emb = torch.empty((P, n), dtype=torch.float32, device=DEV)
+    subs = pa.route(Xd, offd, Wrd[0], k, emb_out=emb, n_shared=ns)
+    torch.cuda.synchronize()
+    assert np.array_equal(subs.cpu().numpy(), subs_ref)
+    # the cache routes its misses the same way
+    cache = pa.Cache(16, n, 1, k, P)
+    cache.set_shared(ns)
+    oc = po.PatternCache(16, n, 1, k, n_shared=ns)
+    ent_ref, hit_ref, sub_ref = oc.lookup_or_route(E, 0.9, Wr.astype(np.float64))
+    ent = torch.empty(P, dtype=torch.int32, device=DEV); hit = torch.empty(P, dtype=torch.uint8, device=DEV)
+    sim = torch.empty(P, dtype=torch.float32, device=DEV); sub = torch.empty((P, 1, k), dtype=torch.int32, device=DEV)
+    cache.lookup_or_route(emb, 0.9, Wrd, ent, hit, sim, sub)
+    torch.cuda.synchronize()
+    assert np.array_equal(ent.cpu().numpy(), ent_ref) and np.array_equal(hit.cpu().numpy(), hit_ref)
+    assert np.array_equal(sub.cpu().numpy(), sub_ref)
+    cache.close()
+    # two-block pack: shared block once, per-pattern blocks with the other k - ns groups
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    sd = i32(subs_ref)
+    Vsh, Ush = pa.pack_experts(dl, i32(np.arange(ns, dtype=np.int32)))
+    Vp, Up = pa.pack_patterns(dl, sd[:, ns:], k, k - ns, None, None, P)
+    Vw, Uw = pa.pack_patterns(dl, sd, k, k, None, None, P)
+    torch.cuda.synchronize()
+    gs = lay.gs
+    for p in range(P):   # whole block = shared block followed by the pattern's own block (slabs stay contiguous)
+        assert torch.equal(Vw[p, :ns * gs].view(torch.int16), Vsh.view(torch.int16))
+        assert torch.equal(Vw[p, ns * gs:].view(torch.int16), Vp[p].view(torch.int16))
+        assert torch.equal(Uw[p, ns * gs:].view(torch.int16), Up[p].view(torch.int16))
+    pid = i32(np.arange(P, dtype=np.int32))
+    pa.set_prefill_schedule(2)
+    try:
+        y_sh = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns),
+                                  Xd, offd, pid)
+        y_whole = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw), Xd, offd, pid)
+        torch.cuda.synchronize()
+    finally:
+        pa.set_prefill_schedule(0)
+    assert torch.equal(y_sh.view(torch.int16), y_whole.view(torch.int16))
+    U0, sg, V = oracle_factors(lay)
+    Yref = po.forward(U0, sg, V, lay.gs, Xv, off, subs_ref)
+    yn = y_sh.float().cpu().numpy().astype(np.float64)
+    for p in range(P):
+        assert_close(yn[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"prompt {p}")
+    # a shared head without the two-launch schedule's workspace is refused, not silently ignored
+    with pytest.raises(pa.ParseError):
+        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns),
+                           Xd, offd, pid, no_workspace=True)

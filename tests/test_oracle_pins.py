@@ -380,3 +380,24 @@ def test_generator_recipe(lay):
     back = si.bf16_bits_to_f32(bits)
     assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.015625   # ties to even, then up
     assert np.all(np.abs(back - x) <= np.abs(x) * 2.0 ** -8)
+
+
+def test_route_with_shared_head_is_the_best_superset_of_the_shared_groups():
+    """Shared experts (Sec. 4.4): the routed subset is the k-subset of largest total score among those that
+    contain groups 0..n_shared-1 (brute force over all subsets), and n_shared = 0 is the plain top-k."""
+    import itertools
+    rng = np.random.default_rng(31)
+    G, d, k = 7, 12, 4
+    Wr = rng.standard_normal((G, d))
+    E = rng.standard_normal((5, d))
+    S = E @ Wr.T
+    plain, _ = po.route(E, Wr, k)
+    same, _ = po.route(E, Wr, k, n_shared=0)
+    assert np.array_equal(plain, same)
+    for n_shared in (1, 2, 3, 4):
+        subs, _ = po.route(E, Wr, k, n_shared=n_shared)
+        for p in range(E.shape[0]):
+            best = max((c for c in itertools.combinations(range(G), k) if set(range(n_shared)) <= set(c)),
+                       key=lambda c: sum(S[p][g] for g in c))
+            assert tuple(subs[p]) == tuple(sorted(best))
+            assert list(subs[p]) == sorted(subs[p]) and len(set(subs[p])) == k
