@@ -66,7 +66,8 @@ def bench_prefill(args, torch, pa, si):
     k, P, n, m, gs = w.k, w.P, lay.n, lay.m, lay.gs
     rS = k * gs
     rows = int(w.tok_offsets[-1])
-    dl = pa.layer_to_mfma16(upload_layer(lay, dev))
+    dl_rm = upload_layer(lay, dev)                         # row-major store (rank-granular aggregation reads it)
+    dl = pa.layer_to_mfma16(dl_rm)
     X = upload_tokens(w.X, "bf16", dev)
     off = i32(w.tok_offsets, dev)
     Wr = torch.from_numpy(w.Wr).to(dev)                    # [1][G][d]
@@ -165,6 +166,16 @@ def bench_prefill(args, torch, pa, si):
     pt_sh = pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns)
     pid_seq = torch.arange(P, dtype=torch.int32, device=dev)
     sched_us["shared_head_2_of_8"] = timed(lambda: pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh, X, off, pid_seq, Y, ws_fwd))
+    # rank-granular mode, for the record (the paper's own formulation: a router over all R ranks, top-K ranks,
+    # K scattered rank rows aggregated per prompt); the forward then runs on blocks of the same shape as above
+    K_r = rS
+    Wr_r = torch.randn((lay.R, w.d), device=dev) / 64.0
+    sub_r = torch.empty((P, K_r), dtype=torch.int32, device=dev)
+    ws_r = torch.empty(int(pa.lib().parse_route_ranks_workspace_bytes(rows, P, w.d, lay.R)), dtype=torch.uint8, device=dev)
+    Vr = torch.empty((P, K_r, n), dtype=torch.bfloat16, device=dev); Ur = torch.empty((P, K_r, m), dtype=torch.bfloat16, device=dev)
+    rank_us = {"route_ranks": timed(lambda: pa.route_ranks(X, off, Wr_r, K_r, subset_out=sub_r, workspace=ws_r)),
+               "pack_ranks_8_patterns": timed(lambda: pa.pack_ranks(dl_rm, sub_r, K_r, P, Vt_S=Vr, Ut_S=Ur)),
+               "R": lay.R, "K": K_r}
     assert torch.equal(sub.view(P, k), sub_route), "cache answered with a subset that differs from the route"
     flops = 2.0 * rows * rS * (n + m)
     ms_per_step = wall / args.steps * 1e3
@@ -176,6 +187,7 @@ def bench_prefill(args, torch, pa, si):
         "value": value, "ms_per_step": ms_per_step, "flops_per_step": flops,
         "rows_us": {k_: round(v, 2) for k_, v in per.items()},
         "cache_hits": hits, "forward_us_by_schedule": sched_us, "cold_step_ms": round(cold_ms, 4),
+        "rank_granular_us": rank_us,
         "roofline": {"bound": "mfma", "kernel": "gemm_tokens x2 (two-launch schedule)" if sched_us["two_launch"] <= sched_us["fused"] else "prefill_fused", "achieved": round(achieved, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": traffic_from_profiles("prefill_config1"),
@@ -340,6 +352,7 @@ def main():
         "cache_hits_last_step": pre["cache_hits"],
         "forward_us_by_schedule": pre["forward_us_by_schedule"],
         "cold_step_ms": pre["cold_step_ms"],
+        "rank_granular_us": pre["rank_granular_us"],
         "decode": dec,
     }
     print(json.dumps(line))

@@ -253,6 +253,27 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *layer, const parse_pa
                           const int32_t *pattern_id, int32_t P, void *Y, void *workspace,
                           size_t workspace_bytes, parse_stream stream);
 
+/* ---- rank-granular routing (Sec. 4.1, Eq. 4-5 as written: one expert per rank component) ----------------
+ * The router maps the prompt embedding to one score per rank, R^d -> R^G with G = the stored rank (up to 8192),
+ * and the K best ranks are active.  parse_route_ranks = pool -> scores = Wr e -> exact top-K (ties to the lower
+ * rank id), ids ascending in subset_out[p][0..K).  Arguments as parse_route, with
+ *   Wr device float [G][d];  1 <= K <= G <= 8192;  scores_out device float [P][G] or NULL (16-byte aligned);
+ *   workspace >= parse_route_ranks_workspace_bytes(rows, P, d, G).
+ * parse_pack_ranks = the memory aggregation of Sec. 4.4 for single ranks: the K selected rank rows of a
+ * ROW-MAJOR bf16 layer are gathered into one contiguous block per pattern, written directly in PARSE_MFMA16
+ * operand order (K % 32 == 0, n % 16 == 0, m % 32 == 0):
+ *   subset device int32 [n_patterns][subset_stride] (K ids per row; ids outside [0, R) give zero rows),
+ *   Vt_S device [n_patterns][K][n], Ut_S device [n_patterns][K][m].
+ * The packed blocks feed parse_lowrank_forward(PARSE_PREFILL) unchanged: describe the layer to it with
+ * PARSE_MFMA16 layout and G = R/32 (32-rank units) and the patterns with k = K/32. */
+size_t parse_route_ranks_workspace_bytes(int32_t rows, int32_t P, int32_t d, int32_t G);
+int parse_route_ranks(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_offsets, int32_t P,
+                      int32_t d, const float *Wr, int32_t G, int32_t K, int32_t *subset_out,
+                      int32_t subset_stride, float *scores_out, float *emb_out, void *workspace,
+                      size_t workspace_bytes, parse_stream stream);
+int parse_pack_ranks(const parse_layer *layer, const int32_t *subset, int32_t subset_stride, int32_t K,
+                     int32_t n_patterns, void *Vt_S, void *Ut_S, parse_stream stream);
+
 /* Horizontal fusion for decode (Sec. 4.4, Eq. 11-12: projections that share their input run as one stacked
  * first product and one batched second product).  n_layers (1..4) layers that read the SAME token rows X
  * (equal n; m, R, G and the patterns may differ per layer) take ONE decode step together: the result equals

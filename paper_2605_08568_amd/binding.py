@@ -61,6 +61,12 @@ def lib():
     L.parse_route_shared.restype = C.c_int
     L.parse_route_shared.argtypes = [vp, i32, i32, vp, i32, i32, vp, i32, i32, i32, vp, i32, vp, vp, vp, sz, vp]
     L.parse_cache_set_shared.restype = C.c_int; L.parse_cache_set_shared.argtypes = [vp, i32]
+    L.parse_route_ranks_workspace_bytes.restype = sz
+    L.parse_route_ranks_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    L.parse_route_ranks.restype = C.c_int
+    L.parse_route_ranks.argtypes = [vp, i32, i32, vp, i32, i32, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+    L.parse_pack_ranks.restype = C.c_int
+    L.parse_pack_ranks.argtypes = [C.POINTER(_Layer), vp, i32, i32, i32, vp, vp, vp]
     L.parse_cache_create.restype = C.c_int
     L.parse_cache_create.argtypes = [C.POINTER(vp), i32, i32, i32, i32, i32]
     L.parse_cache_destroy.restype = C.c_int; L.parse_cache_destroy.argtypes = [vp]
@@ -390,3 +396,34 @@ def lowrank_prefill_multi(layers, patterns, X, tok_offsets, pattern_id, Ys=None,
     _check(lib().parse_lowrank_prefill_multi(larr, parr, nl, _ptr(X), rows, _ptr(tok_offsets), _ptr(pattern_id), P, yarr,
                                              _ptr(workspace), workspace.numel(), _stream()), "parse_lowrank_prefill_multi")
     return Ys
+
+
+def route_ranks(X, tok_offsets, Wr, K, subset_out=None, subset_stride=None, scores_out=None, emb_out=None,
+                workspace=None):
+    """parse_route_ranks: rank-granular routing.  Wr float device [G][d] -> subset int32 [P][K] ascending."""
+    rows, d = X.shape
+    P = tok_offsets.numel() - 1
+    G = Wr.shape[0]
+    stride = K if subset_stride is None else subset_stride
+    if subset_out is None:
+        subset_out = torch.empty((P, stride), dtype=torch.int32, device=X.device)
+    if workspace is None:
+        need = int(lib().parse_route_ranks_workspace_bytes(rows, P, d, G))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    _check(lib().parse_route_ranks(_ptr(X), _dtype_code(X), rows, _ptr(tok_offsets), P, d, _ptr(Wr), G, K,
+                                   _ptr(subset_out), stride, _ptr(scores_out), _ptr(emb_out), _ptr(workspace),
+                                   workspace.numel(), _stream()), "parse_route_ranks")
+    return subset_out
+
+
+def pack_ranks(layer: Layer, subset, K, n_patterns, subset_stride=None, Vt_S=None, Ut_S=None):
+    """parse_pack_ranks: gathers K rank rows per pattern of a row-major bf16 layer into operand-order blocks."""
+    stride = K if subset_stride is None else subset_stride
+    if Vt_S is None:
+        Vt_S = torch.empty((n_patterns, K, layer.n), dtype=layer.Vt.dtype, device=layer.Vt.device)
+    if Ut_S is None:
+        Ut_S = torch.empty((n_patterns, K, layer.m), dtype=layer.Ut.dtype, device=layer.Ut.device)
+    cl = layer.c()
+    _check(lib().parse_pack_ranks(C.byref(cl), _ptr(subset), stride, K, n_patterns, _ptr(Vt_S), _ptr(Ut_S), _stream()),
+           "parse_pack_ranks")
+    return Vt_S, Ut_S

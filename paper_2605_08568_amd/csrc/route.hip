@@ -120,6 +120,22 @@ static int pool_slices(int rows, int P, int d, bool bf16) {
   return (int)q;
 }
 
+// Launches pool_partial into `partial` ([P][Q][d] floats, Q returned); shared with the rank-granular router.
+int launch_pool_partials(const void *X, int xdtype, int rows, const int32_t *tok_offsets, int P, int d, float *partial,
+                         int *Q_out, hipStream_t s) {
+  const bool bf16 = xdtype == PARSE_BF16;
+  const int Q = pool_slices(rows, P, d, bf16);
+  const int per_block = 64 * (bf16 ? 8 : 4);
+  dim3 grid((d + per_block - 1) / per_block, Q, P);
+  if (bf16)
+    hipLaunchKernelGGL(pool_partial<true>, grid, dim3(kPoolThreads), 0, s, X, rows, d, tok_offsets, Q, partial);
+  else
+    hipLaunchKernelGGL(pool_partial<false>, grid, dim3(kPoolThreads), 0, s, X, rows, d, tok_offsets, Q, partial);
+  PARSE_LAUNCH_CHECK();
+  *Q_out = Q;
+  return PARSE_OK;
+}
+
 }  // namespace parse
 
 using namespace parse;
@@ -155,17 +171,11 @@ int parse_route_shared(const void *X, int32_t xdtype, int32_t rows, const int32_
   if (!aligned16(X) || !aligned16(Wr) || !aligned16(workspace)) return PARSE_EALIGN;
   if (emb_out && !aligned16(emb_out)) return PARSE_EALIGN;
   if (!workspace || workspace_bytes < parse_route_workspace_bytes(rows, P, d)) return PARSE_EWORKSPACE;
-  const bool bf16 = xdtype == PARSE_BF16;
-  const int Q = pool_slices(rows, P, d, bf16);
-  const int per_block = 64 * (bf16 ? 8 : 4);
-  dim3 grid((d + per_block - 1) / per_block, Q, P);
   hipStream_t s = (hipStream_t)stream;
   float *partial = reinterpret_cast<float *>(workspace);
-  if (bf16)
-    hipLaunchKernelGGL(pool_partial<true>, grid, dim3(kPoolThreads), 0, s, X, rows, d, tok_offsets, Q, partial);
-  else
-    hipLaunchKernelGGL(pool_partial<false>, grid, dim3(kPoolThreads), 0, s, X, rows, d, tok_offsets, Q, partial);
-  PARSE_LAUNCH_CHECK();
+  int Q = 0;
+  const int st = launch_pool_partials(X, xdtype, rows, tok_offsets, P, d, partial, &Q, s);
+  if (st != PARSE_OK) return st;
   const size_t lds = (size_t)(d + 64) * sizeof(float);
   hipLaunchKernelGGL(route_finish, dim3(P), dim3(kFinishThreads), lds, s, partial, Q, rows, d, tok_offsets, Wr, G, k,
                      subset_out, subset_stride, scores_out, emb_out, n_shared);

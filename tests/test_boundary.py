@@ -171,3 +171,22 @@ def test_prefill_multi_rejects_bad_arguments():
     assert call([La, _layer(n=256, m=256, R=256, G=2, dtype=1, layout=0)], [pt, pt], 2) == -7
     assert call([La, La], [pt, pt], 2, ys=[FAKE.value, None]) == -1
     assert call([La, La], [pt, pt], 2, wsb=64) == -5 and call([La, La], [pt, pt], 2, ws=None) == -5
+
+
+def test_rank_granular_entry_points_reject_bad_arguments():
+    lib = pa.lib()
+
+    def route(X=FAKE, xdt=1, rows=64, off=FAKE, P=2, d=64, Wr=FAKE, G=128, K=32, out=FAKE, stride=32, ws=FAKE, wsb=1 << 24):
+        return lib.parse_route_ranks(X, xdt, rows, off, P, d, Wr, G, K, out, stride, None, None, ws, wsb, None)
+
+    assert route(X=None) == -1 and route(K=0) == -1 and route(xdt=5) == -1
+    assert route(K=256) == -2 and route(G=9000, K=32) == -2 and route(stride=16) == -2 and route(P=100) == -2
+    assert route(d=68) == -3 and route(X=ODD) == -3
+    assert route(ws=None) == -5 and route(wsb=64) == -5
+    assert lib.parse_route_ranks_workspace_bytes(64, 2, 64, 128) >= 2 * 64 * 4 + 2 * 128 * 4
+    rm = _layer(n=64, m=64, R=128, G=128, dtype=1, layout=0)
+    assert lib.parse_pack_ranks(C.byref(rm), None, 32, 32, 2, FAKE, FAKE, None) == -1
+    assert lib.parse_pack_ranks(C.byref(rm), FAKE, 32, 48, 2, FAKE, FAKE, None) == -2              # K % 32
+    assert lib.parse_pack_ranks(C.byref(rm), FAKE, 16, 32, 2, FAKE, FAKE, None) == -2              # stride < K
+    assert lib.parse_pack_ranks(C.byref(_layer(n=64, m=64, R=128, G=4, dtype=1, layout=1)), FAKE, 32, 32, 2, FAKE, FAKE, None) == -7
+    assert lib.parse_pack_ranks(C.byref(_layer(n=64, m=64, R=128, G=128, dtype=0, layout=0)), FAKE, 32, 32, 2, FAKE, FAKE, None) == -7
