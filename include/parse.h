@@ -237,8 +237,8 @@ int parse_set_prefill_schedule(int32_t schedule);
  *                intermediate rounded to bf16.  Two schedules: ONE fused kernel that keeps the
  *                intermediate in LDS (a workgroup per 64 token rows; needs no workspace), or TWO launches
  *                of one tile kernel with the intermediate in the workspace (it stays cache-resident), which
- *                is what fills the chip when the batch has fewer than a few hundred 64-row tiles.  With
- *                workspace == NULL the fused kernel is used.  f32 layers must be
+ *                is the faster form and the one used whenever a workspace is given and n and r_S are
+ *                multiples of 128.  With workspace == NULL the fused kernel is used.  f32 layers must be
  *                PARSE_ROWMAJOR (plain fp32 kernels, intermediate in the workspace).
  *                  X device [rows][n], Y device [rows][m] (layer dtype), tok_offsets device int32 [P+1],
  *                  pattern_id device int32 [P].

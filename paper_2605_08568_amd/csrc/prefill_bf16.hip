@@ -369,11 +369,11 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
     a.Ut_sh = (const uint16_t *)pt->Ut_shared;
     a.sh_ranks = pt->n_shared * gs;
   }
-  // The fused kernel runs rows/64 workgroups, one per compute unit: below about two waves of the 256 units
-  // the two-launch form (which needs the Z workspace) fills the chip better.
+  // The two-launch form is the faster one whenever its workspace is there: at small batches the fused kernel
+  // (rows/64 workgroups) cannot fill the chip, at large ones the two-launch tiles move fewer bytes per flop.
   const bool can_split = workspace != nullptr && workspace_bytes >= prefill_split_workspace_bytes(rows, rS) &&
                          prefill_split_supported(L->n, rS);
-  bool split = can_split && (rows / 64 < 512);
+  bool split = can_split;
   if (g_prefill_schedule == 1) split = false;
   if (g_prefill_schedule == 2 || a.sh_ranks > 0) {
     if (!can_split) return prefill_split_supported(L->n, rS) ? PARSE_EWORKSPACE : PARSE_ESHAPE;

@@ -305,6 +305,7 @@ def test_prefill_config0_fp32():
     (512, 512, 2560, 20, 10, [40, 100], 1),               # r_S = 1280: 32-token workgroups
     (512, 800, 2560, 20, 10, [40, 300], 2),               # two launches, output blocks not a multiple of a chunk
     (1024, 4096, 1024, 8, 4, [512, 512, 37], 0),          # default choice at a size with whole 128-row tiles
+    (256, 256, 1024, 8, 8, [9000, 7400], 0),              # many token tiles: 128-token tiles in both launches
 ])
 def test_prefill_bf16_small(n, m, R, G, k, lengths, schedule):
     say(f"prefill bf16 n={n} m={m} R={R} G={G} k={k} lengths={lengths} schedule={schedule}")
