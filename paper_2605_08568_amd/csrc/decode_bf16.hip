@@ -267,8 +267,10 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
   const int ncb = m / 32;
   const int c0 = bid * NC;
   const int nc = min(NC, ncb - c0);
-  const int n_used = min(used_in[0], G);
-  if ((int)threadIdx.x < n_used) used[threadIdx.x] = used_in[1 + threadIdx.x];
+  // count and ids are fetched together (ids past the count are whatever the list held; they are not used)
+  const int n_used_raw = used_in[0];
+  if (threadIdx.x < DEC_MAXG) used[threadIdx.x] = used_in[1 + threadIdx.x];
+  const int n_used = max(0, min(n_used_raw, G));
   __syncthreads();
   const int kpg = gs / 16;                 // reduction blocks per group
   const int total_kb = n_used * kpg;       // selected reduction blocks
