@@ -202,5 +202,31 @@ def config4_embeddings(seed: int = SEED_BASE + 4, P: int = 256, d: int = 4096,
     return E, cid, offsets_from_lengths(lengths), Wr
 
 
+def pad_groups(lay: Layer, multiple: int = 32) -> Layer:
+    """The same layer with every rank group padded with zero ranks to a multiple of `multiple` ranks (the
+    operand-order layout wants groups of whole 32-rank blocks; a zero rank contributes nothing).  Pure data
+    movement: stored rows are copied, padding rows are zero; U0 / sigma / V are padded alike."""
+    gs, G = lay.gs, lay.G
+    gp = (gs + multiple - 1) // multiple * multiple
+    if gp == gs:
+        return lay
+    def pad_rows(a):      # [R][w] -> [G*gp][w]
+        out = np.zeros((G, gp) + a.shape[1:], dtype=a.dtype)
+        out[:, :gs] = a.reshape((G, gs) + a.shape[1:])
+        return out.reshape((G * gp,) + a.shape[1:])
+    U0 = None if lay.U0 is None else pad_rows(np.ascontiguousarray(lay.U0.T)).T.copy()
+    sigma = None if lay.sigma is None else pad_rows(lay.sigma.reshape(-1, 1)).reshape(-1)
+    V = None if lay.V is None else pad_rows(lay.V)
+    return Layer(lay.n, lay.m, G * gp, G, lay.dtype, U0, sigma, V, pad_rows(lay.Vt_store), pad_rows(lay.Ut_store))
+
+
+def config3_ranks(n: int, m: int, G: int = 16, kept: float = 0.6):
+    """Stored rank of one projection of the full-stack workload: the factors keep `kept` of the dense parameter
+    count, R = kept*m*n/(m+n), rounded so that a group holds a multiple of 16 ranks.  Returns (R, gs)."""
+    R = kept * m * n / (m + n)
+    gs = 16 * int(round(R / G / 16))
+    return gs * G, gs
+
+
 def small_layer(seed: int, n: int, m: int, R: int, G: int, dtype: str) -> Layer:
     return make_layer(np.random.default_rng(seed), n, m, R, G, dtype)

@@ -639,3 +639,54 @@ def test_rank_granular_route_pack_and_prefill():
         yn = y.float().cpu().numpy().astype(np.float64)
         for p in range(P):
             assert_close(yn[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"schedule {schedule} prompt {p}")
+
+
+def test_config3_layer_projections_with_padded_groups():
+    """One layer of the full-stack workload at its real shapes: q/k/v (4096x4096, 16 groups of 80 ranks padded to
+    96), gate/up (4096->11008, groups of 112 padded to 128) and down, top-8 of 16; q/k/v and gate/up go through
+    the horizontally fused calls.  Prefill on one 192-token prompt and one decode token, oracle on sampled rows."""
+    say("config3 layer: q,k,v fused; gate,up fused; down; prefill (192 tokens) + decode (1 sequence)")
+    hidden, inter, G, k, T = 4096, 11008, 16, 8, 192
+    rng = np.random.default_rng(931)
+    shapes = {"q": (hidden, hidden), "k": (hidden, hidden), "v": (hidden, hidden),
+              "gate": (hidden, inter), "up": (hidden, inter), "down": (inter, hidden)}
+    lays, dls, pats, subsets = {}, {}, {}, {}
+    for i, (nm, (n, m)) in enumerate(shapes.items()):
+        R, gs = si.config3_ranks(n, m, G)
+        lay = si.pad_groups(si.make_layer(np.random.default_rng(940 + i), n, m, R, G, "bf16", fast=True), 32)
+        assert lay.gs % 32 == 0
+        sub = np.sort(rng.choice(G, size=k, replace=False)).astype(np.int32)[None, :]
+        lays[nm], subsets[nm] = lay, sub
+        dls[nm] = pa.layer_to_mfma16(upload_layer(lay))
+        Vs, Us = pa.pack_patterns(dls[nm], i32(sub), k, k, None, None, 1)
+        pats[nm] = pa.Patterns(k, 1, Vs, Us, subsets=i32(sub))
+    off = np.array([0, T], np.int32)
+    pid = i32(np.zeros(1, np.int32))
+    sample = np.array([0, 77, T - 1])
+
+    def check(nm, y, Xbits, rows, what):
+        U0, sg, V = oracle_factors(lays[nm])
+        Xv = si.bf16_bits_to_f32(Xbits[rows]).astype(np.float64)
+        ref = po.forward(U0, sg, V, lays[nm].gs, Xv, np.array([0, len(rows)], np.int32), subsets[nm])
+        assert_close(y.float().cpu().numpy()[rows].astype(np.float64), ref, TOL_BF16, f"{what} {nm}")
+
+    Xh = si.make_tokens(rng, T, hidden, "bf16"); Xi = si.make_tokens(rng, T, inter, "bf16")
+    Xhd, Xid, offd = upload_tokens(Xh, "bf16"), upload_tokens(Xi, "bf16"), i32(off)
+    for group, Xb, Xd in ((["q", "k", "v"], Xh, Xhd), (["gate", "up"], Xh, Xhd)):
+        ys = pa.lowrank_prefill_multi([dls[g] for g in group], [pats[g] for g in group], Xd, offd, pid)
+        torch.cuda.synchronize()
+        for g, y in zip(group, ys):
+            check(g, y, Xb, sample, "prefill")
+    y = pa.lowrank_forward(pa.PARSE_PREFILL, dls["down"], pats["down"], Xid, offd, pid)
+    torch.cuda.synchronize()
+    check("down", y, Xi, sample, "prefill")
+    # decode: one sequence, one token
+    one = np.array([0])
+    for group, Xb, Xd in ((["q", "k", "v"], Xh, Xhd), (["gate", "up"], Xh, Xhd)):
+        ys = pa.lowrank_decode_multi([dls[g] for g in group], [pats[g] for g in group], Xd[:1].contiguous(), pid)
+        torch.cuda.synchronize()
+        for g, yv in zip(group, ys):
+            check(g, yv, Xb, one, "decode")
+    yv = pa.lowrank_forward(pa.PARSE_DECODE, dls["down"], pats["down"], Xid[:1].contiguous(), None, pid)
+    torch.cuda.synchronize()
+    check("down", yv, Xi, one, "decode")

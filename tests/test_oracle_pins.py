@@ -401,3 +401,24 @@ def test_route_with_shared_head_is_the_best_superset_of_the_shared_groups():
                        key=lambda c: sum(S[p][g] for g in c))
             assert tuple(subs[p]) == tuple(sorted(best))
             assert list(subs[p]) == sorted(subs[p]) and len(set(subs[p])) == k
+
+
+def test_zero_padded_groups_change_nothing():
+    """Padding every rank group with zero ranks (what the operand-order layout needs when a group is not a whole
+    number of 32-rank blocks) leaves the routed product unchanged; the full-stack workload's ranks come out as
+    the ratio says (4096x4096: 16 groups of 80; 4096<->11008: 16 groups of 112)."""
+    assert si.config3_ranks(4096, 4096) == (1280, 80)
+    assert si.config3_ranks(4096, 11008) == (1792, 112) and si.config3_ranks(11008, 4096) == (1792, 112)
+    lay = si.small_layer(41, 96, 64, 40, 4, "f32")            # groups of 10 ranks
+    pad = si.pad_groups(lay, 16)
+    assert pad.R == 64 and pad.gs == 16 and pad.G == 4
+    rng = np.random.default_rng(42)
+    X = rng.standard_normal((9, 96))
+    off = np.array([0, 4, 9], np.int32)
+    subs = np.array([[0, 2], [1, 3]], np.int32)
+    Y0 = po.forward(lay.U0, lay.sigma, lay.V, lay.gs, X, off, subs)
+    Y1 = po.forward(pad.U0, pad.sigma, pad.V, pad.gs, X, off, subs)
+    assert np.allclose(Y0, Y1, rtol=0, atol=1e-13)
+    V0, U0p = po.pack(lay.Vt_store, lay.Ut_store, subs[0], lay.gs)
+    V1, U1p = po.pack(pad.Vt_store, pad.Ut_store, subs[0], pad.gs)
+    assert np.array_equal(V1.reshape(2, 16, -1)[:, :10].reshape(20, -1), V0) and np.all(V1.reshape(2, 16, -1)[:, 10:] == 0)
