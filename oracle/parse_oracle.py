@@ -21,6 +21,9 @@ What each function follows:
                           shared across prompts), so one launch serves one pattern.
   decode                  Sec. 4.3 "Rank Reuse for Decoding": the prefill subset is fixed
                           for every later step; same product with one row per sequence.
+  soft_mask / router_grad Sec. 4.2 Eq. 6-9: reconstruction loss against the dense output,
+                          hard top-k mask forward, K-normalised sigmoid mask backward
+                          (straight-through), gradient with respect to the router matrix.
 
 Pins (tests/test_oracle_pins.py): full selection == truncated-SVD product and
 numpy.linalg.svd recovers sigma; Eckart-Young residual closed form; orthonormal
@@ -199,6 +202,47 @@ class PatternCache:
         if return_detail:
             return entry, hit, subs, sims, route_margin
         return entry, hit, subs
+
+
+# ------------------------------------------------------------------ router training step
+def soft_mask(scores, k: int, temperature: float, eps: float) -> np.ndarray:
+    """Sec. 4.2 Eq. 9: m_i = K sigmoid(s_i / tau) / (sum_j sigmoid(s_j / tau) + eps)."""
+    a = 1.0 / (1.0 + np.exp(-np.asarray(scores, F64) / temperature))
+    return k * a / (a.sum() + eps)
+
+
+def router_grad(U0, sigma, V, gs: int, X, tok_offsets, Y_dense, Wr, k: int, temperature: float, eps: float):
+    """One training step of the router (Sec. 4.2), groups as experts, one embedding per prompt.
+
+    Forward (Eq. 7): y_hat = sum_g m_g^hard W_g x with m^hard the top-k indicator of s = Wr e_p.
+    Loss (Eq. 6): sum over the prompt's tokens of ||y_hat - y_dense||^2.
+    Backward (Eq. 8-9): the mask's value is the hard one, its derivative the soft one's:
+      dL/dm_g = sum_t 2 (y_hat_t - y_t)^T W_g x_t,   dL/ds = J^T dL/dm with J = d m^soft / d s,
+      dL/dWr = sum_p dL/ds(p) e_p^T.
+    Returns (loss[P], grad_Wr[G][d], dL/dm[P][G])."""
+    X = np.asarray(X, F64); Yd = np.asarray(Y_dense, F64); Wr = np.asarray(Wr, F64)
+    G = Wr.shape[0]
+    P = len(tok_offsets) - 1
+    E = pool(X, tok_offsets)
+    Wg = [reconstruct(U0, sigma, V, [g], gs) for g in range(G)]          # m x n each
+    loss = np.zeros(P, F64); grad = np.zeros_like(Wr); dm_all = np.zeros((P, G), F64)
+    for p in range(P):
+        a, b = int(tok_offsets[p]), int(tok_offsets[p + 1])
+        s = Wr @ E[p]
+        hard, _ = topk_ascending(s, k)
+        Yh = sum(X[a:b] @ Wg[g].T for g in hard)
+        res = Yh - Yd[a:b]
+        loss[p] = float((res ** 2).sum())
+        dm = np.array([2.0 * float((res * (X[a:b] @ Wg[g].T)).sum()) for g in range(G)])
+        sg = 1.0 / (1.0 + np.exp(-s / temperature))
+        A = sg.sum() + eps
+        dsg = sg * (1.0 - sg) / temperature
+        # J[g][j] = d m_g / d s_j = k (delta_gj dsg_j / A - sg_g dsg_j / A^2)
+        J = k * (np.diag(dsg) / A - np.outer(sg, dsg) / A ** 2)
+        ds = J.T @ dm
+        grad += np.outer(ds, E[p])
+        dm_all[p] = dm
+    return loss, grad, dm_all
 
 
 # ------------------------------------------------------------------ pack / bucket

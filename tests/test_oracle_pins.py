@@ -422,3 +422,44 @@ def test_zero_padded_groups_change_nothing():
     V0, U0p = po.pack(lay.Vt_store, lay.Ut_store, subs[0], lay.gs)
     V1, U1p = po.pack(pad.Vt_store, pad.Ut_store, subs[0], pad.gs)
     assert np.array_equal(V1.reshape(2, 16, -1)[:, :10].reshape(20, -1), V0) and np.all(V1.reshape(2, 16, -1)[:, 10:] == 0)
+
+
+def test_router_training_step_against_finite_differences():
+    """Sec. 4.2: dL/dm is checked by perturbing the mask of the (quadratic) loss, d m_soft / d Wr by perturbing
+    the router matrix in the soft-mask formula; their composition is the straight-through gradient.  The soft
+    mask sums to K (up to eps) as the K-normalisation promises."""
+    rng = np.random.default_rng(51)
+    n, m, R, G, k, tau, eps = 24, 20, 12, 4, 2, 0.7, 1e-6
+    lay = si.small_layer(52, n, m, R, G, "f32")
+    gs = lay.gs
+    off = np.array([0, 5, 9], np.int32)
+    X = rng.standard_normal((9, n))
+    Wd = rng.standard_normal((m, n)) * 0.3
+    Yd = X @ Wd.T
+    Wr = rng.standard_normal((G, n)) * 0.5
+    loss, grad, dm = po.router_grad(lay.U0, lay.sigma, lay.V, gs, X, off, Yd, Wr, k, tau, eps)
+    E = po.pool(X, off)
+    Wg = [po.reconstruct(lay.U0, lay.sigma, lay.V, [g], gs) for g in range(G)]
+
+    def loss_of_mask(p, mvec):
+        a, b = off[p], off[p + 1]
+        Yh = sum(mvec[g] * (X[a:b] @ Wg[g].T) for g in range(G))
+        return float(((Yh - Yd[a:b]) ** 2).sum())
+
+    h = 1e-6
+    grad_fd = np.zeros_like(Wr)
+    for p in range(2):
+        s = Wr @ E[p]
+        hard = np.zeros(G); hard[po.topk_ascending(s, k)[0]] = 1.0
+        assert abs(loss_of_mask(p, hard) - loss[p]) < 1e-9 * max(1.0, loss[p])
+        dm_fd = np.array([(loss_of_mask(p, hard + h * np.eye(G)[g]) - loss_of_mask(p, hard - h * np.eye(G)[g])) / (2 * h)
+                          for g in range(G)])
+        assert np.allclose(dm_fd, dm[p], rtol=1e-5, atol=1e-6)
+        assert abs(po.soft_mask(s, k, tau, eps).sum() - k) < 1e-4
+        for j in range(G):
+            for c in range(n):
+                Wp = Wr.copy(); Wp[j, c] += h
+                Wm = Wr.copy(); Wm[j, c] -= h
+                dmsoft = (po.soft_mask(Wp @ E[p], k, tau, eps) - po.soft_mask(Wm @ E[p], k, tau, eps)) / (2 * h)
+                grad_fd[j, c] += float(dm[p] @ dmsoft)
+    assert np.allclose(grad_fd, grad, rtol=1e-4, atol=1e-7)
