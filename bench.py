@@ -15,6 +15,7 @@ groups of 128, top-10, 4 patterns) against the HBM peak; `cpu_baseline` is the C
 from __future__ import annotations
 
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -183,6 +184,14 @@ def bench_prefill(args, torch, pa, si):
         rank_us = {"route_ranks": timed(lambda: pa.route_ranks(X, off, Wr_r, K_r, subset_out=sub_r, workspace=ws_r)),
                    "pack_ranks_8_patterns": timed(lambda: pa.pack_ranks(dl_rm, sub_r, K_r, P, Vt_S=Vr, Ut_S=Ur)),
                    "R": lay.R, "K": K_r}
+        # router training step, for the record (Sec. 4.2): loss and gradient of Wr for this batch against a random
+        # "dense" target; two full-rank products (137 GFLOP) plus small reductions
+        scores_t = torch.empty((P, lay.G), dtype=torch.float32, device=dev)
+        pa.route(X, off, Wr[0], k, subset_out=sub_route, scores_out=scores_t, emb_out=emb, workspace=ws_route)
+        Yd_t = torch.randn((rows, m), device=dev).to(torch.bfloat16)
+        Utr = pa.rankmajor_left_factor(dl_rm)
+        ws_t = torch.empty(int(pa.lib().parse_router_grad_workspace_bytes(C.byref(dl.c()), rows, P)), dtype=torch.uint8, device=dev)
+        sched_us["router_training_step"] = timed(lambda: pa.router_grad(dl, Utr, X, off, Y, Yd_t, emb, scores_t, k, 1.0, 1e-6, ws_t))
     assert torch.equal(sub.view(P, k), sub_route), "cache answered with a subset that differs from the route"
     flops = 2.0 * rows * rS * (n + m)
     ms_per_step = wall / args.steps * 1e3

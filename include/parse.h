@@ -274,6 +274,27 @@ int parse_route_ranks(const void *X, int32_t xdtype, int32_t rows, const int32_t
 int parse_pack_ranks(const parse_layer *layer, const int32_t *subset, int32_t subset_stride, int32_t K,
                      int32_t n_patterns, void *Vt_S, void *Ut_S, parse_stream stream);
 
+/* ---- router training step (Sec. 4.2, Eq. 6-9) ---------------------------------------------------------------
+ * The factors stay fixed; the router matrix Wr is trained against the dense model's output.  For one batch:
+ *   loss_p   = sum over prompt p's tokens of || y_hat - y_dense ||^2                         (Eq. 6)
+ *   y_hat    = the routed output with the hard top-k mask (parse_lowrank_forward)              (Eq. 7)
+ *   backward = straight-through: the mask's derivative is that of the K-normalised sigmoid mask
+ *              m_g = k sigmoid(s_g / temperature) / (sum_j sigmoid(s_j / temperature) + eps)    (Eq. 8-9)
+ *   grad_Wr[j][:] = sum_p dL/ds_j(p) e_p,  s = Wr e_p (groups as experts, one embedding per prompt).
+ * layer          bf16 PARSE_MFMA16, n % 128 == 0, m % 128 == 0, G <= 64, P*G <= 8192
+ * Ut_rankmajor   device: the layer's Ut ([R][m] row-major) reordered like a RIGHT factor, i.e. the Vt output of
+ *                parse_layer_to_mfma16 for a row-major layer whose Vt is that Ut and whose n is m
+ * X [rows][n], Y_hat, Y_dense [rows][m]  device bf16;  tok_offsets device int32 [P+1]
+ * emb [P][d], scores [P][G]             device float, as written by parse_route (emb_out, scores_out)
+ * loss_out       device float [P] or NULL;  grad_Wr device float [G][d] (overwritten)
+ * workspace      device, >= parse_router_grad_workspace_bytes(layer, rows, P) */
+size_t parse_router_grad_workspace_bytes(const parse_layer *layer, int32_t rows, int32_t P);
+int parse_router_grad(const parse_layer *layer, const void *Ut_rankmajor, const void *X, int32_t rows,
+                      const int32_t *tok_offsets, int32_t P, const void *Y_hat, const void *Y_dense,
+                      const float *emb, const float *scores, int32_t d, int32_t k, float temperature,
+                      float eps, float *loss_out, float *grad_Wr, void *workspace, size_t workspace_bytes,
+                      parse_stream stream);
+
 /* Horizontal fusion for decode (Sec. 4.4, Eq. 11-12: projections that share their input run as one stacked
  * first product and one batched second product).  n_layers (1..4) layers that read the SAME token rows X
  * (equal n; m, R, G and the patterns may differ per layer) take ONE decode step together: the result equals

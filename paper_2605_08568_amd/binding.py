@@ -67,6 +67,11 @@ def lib():
     L.parse_route_ranks.argtypes = [vp, i32, i32, vp, i32, i32, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
     L.parse_pack_ranks.restype = C.c_int
     L.parse_pack_ranks.argtypes = [C.POINTER(_Layer), vp, i32, i32, i32, vp, vp, vp]
+    L.parse_router_grad_workspace_bytes.restype = sz
+    L.parse_router_grad_workspace_bytes.argtypes = [C.POINTER(_Layer), i32, i32]
+    L.parse_router_grad.restype = C.c_int
+    L.parse_router_grad.argtypes = [C.POINTER(_Layer), vp, vp, i32, vp, i32, vp, vp, vp, vp, i32, i32, f32, f32, vp, vp,
+                                    vp, sz, vp]
     L.parse_cache_create.restype = C.c_int
     L.parse_cache_create.argtypes = [C.POINTER(vp), i32, i32, i32, i32, i32]
     L.parse_cache_destroy.restype = C.c_int; L.parse_cache_destroy.argtypes = [vp]
@@ -427,3 +432,26 @@ def pack_ranks(layer: Layer, subset, K, n_patterns, subset_stride=None, Vt_S=Non
     _check(lib().parse_pack_ranks(C.byref(cl), _ptr(subset), stride, K, n_patterns, _ptr(Vt_S), _ptr(Ut_S), _stream()),
            "parse_pack_ranks")
     return Vt_S, Ut_S
+
+
+def rankmajor_left_factor(layer_rowmajor: Layer):
+    """Ut ([R][m] row-major bf16) reordered like a right factor (what parse_router_grad takes as Ut_rankmajor)."""
+    tmp = Layer(layer_rowmajor.Ut, layer_rowmajor.Ut, layer_rowmajor.m, layer_rowmajor.m, layer_rowmajor.R,
+                layer_rowmajor.G, PARSE_ROWMAJOR)
+    return layer_to_mfma16(tmp).Vt
+
+
+def router_grad(layer: Layer, Ut_rankmajor, X, tok_offsets, Y_hat, Y_dense, emb, scores, k, temperature, eps,
+                workspace=None):
+    """parse_router_grad -> (loss [P], grad_Wr [G][d])."""
+    rows, P, d = X.shape[0], tok_offsets.numel() - 1, emb.shape[1]
+    cl = layer.c()
+    if workspace is None:
+        need = int(lib().parse_router_grad_workspace_bytes(C.byref(cl), rows, P))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    loss = torch.empty(P, dtype=torch.float32, device=X.device)
+    grad = torch.empty((layer.G, d), dtype=torch.float32, device=X.device)
+    _check(lib().parse_router_grad(C.byref(cl), _ptr(Ut_rankmajor), _ptr(X), rows, _ptr(tok_offsets), P, _ptr(Y_hat),
+                                   _ptr(Y_dense), _ptr(emb), _ptr(scores), d, k, temperature, eps, _ptr(loss), _ptr(grad),
+                                   _ptr(workspace), workspace.numel(), _stream()), "parse_router_grad")
+    return loss, grad

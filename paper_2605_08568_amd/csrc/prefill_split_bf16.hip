@@ -300,6 +300,19 @@ int forward_prefill_split_multi_bf16(const PfArgs *p, int n_layers, uint16_t *co
   return deep2 ? launch_gemm_tokens<128, 2, 16, 1, 0>(g2, gt128, s) : launch_gemm_tokens<128, 2, 8, 1, 0>(g2, gt128, s);
 }
 
+// O[rows][M] = Tk[rows][K] . F^T for ONE factor matrix F of M rows in the right factor's operand order (operand
+// (rb, kb) at rb*(K/16) + kb), the same for every row: the first-product kernel with a single "pattern" that
+// starts at F.  one_offsets = device {0, rows}, zero_id = device {0}.  K % 128 == 0, M % 32 == 0, K >= 128.
+int tokens_times_factor_bf16(const uint16_t *Tk, const uint16_t *F, uint16_t *O, int rows, int K, int M,
+                             const int32_t *one_offsets, const int32_t *zero_id, hipStream_t s) {
+  if (K % (2 * PF_BK) != 0 || M % 32 != 0 || K / 16 < PF_DEPTH) return PARSE_ESHAPE;
+  GtArgs g{};
+  g.n_layers = 1;
+  g.tok_offsets = one_offsets; g.pattern_id = zero_id; g.rows = rows; g.P = 1;
+  g.L[0] = GtLayer{Tk, F, O, 0, K / 16, 1, K, M, 1, 0, nullptr, 0};
+  return (K % (PF_BK * 4) == 0) ? launch_gemm_tokens<64, 2, 8, 2, 0>(g, 8, s) : launch_gemm_tokens<64, 2, 8, 1, 0>(g, 8, s);
+}
+
 int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s) {
   uint16_t *Zs[1] = {Z};
   return forward_prefill_split_multi_bf16(&p, 1, Zs, avg_prompt_rows, s);

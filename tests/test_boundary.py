@@ -190,3 +190,20 @@ def test_rank_granular_entry_points_reject_bad_arguments():
     assert lib.parse_pack_ranks(C.byref(rm), FAKE, 16, 32, 2, FAKE, FAKE, None) == -2              # stride < K
     assert lib.parse_pack_ranks(C.byref(_layer(n=64, m=64, R=128, G=4, dtype=1, layout=1)), FAKE, 32, 32, 2, FAKE, FAKE, None) == -7
     assert lib.parse_pack_ranks(C.byref(_layer(n=64, m=64, R=128, G=128, dtype=0, layout=0)), FAKE, 32, 32, 2, FAKE, FAKE, None) == -7
+
+
+def test_router_grad_rejects_bad_arguments():
+    lib = pa.lib()
+    L = _layer(n=256, m=128, R=64, G=2, dtype=1, layout=1)
+
+    def call(layer=L, U=FAKE, X=FAKE, rows=16, off=FAKE, P=2, yh=FAKE, yd=FAKE, emb=FAKE, sc=FAKE, d=256, k=1,
+             tau=1.0, eps=1e-6, grad=FAKE, ws=FAKE, wsb=1 << 24):
+        return lib.parse_router_grad(C.byref(layer), U, X, rows, off, P, yh, yd, emb, sc, d, k, tau, eps, None, grad, ws,
+                                     wsb, None)
+
+    assert call(U=None) == -1 and call(grad=None) == -1 and call(tau=0.0) == -1 and call(k=0) == -1
+    assert call(k=3) == -2 and call(P=17) == -2
+    assert call(layer=_layer(n=200, m=128, R=64, G=2, dtype=1, layout=1)) == -2        # n not a multiple of 128
+    assert call(layer=_layer(n=256, m=128, R=64, G=2, dtype=1, layout=0)) == -7
+    assert call(X=ODD) == -3 and call(ws=None) == -5 and call(wsb=64) == -5
+    assert lib.parse_router_grad_workspace_bytes(C.byref(L), 16, 2) >= 16 * 128 * 2 + 2 * 16 * 64 * 2

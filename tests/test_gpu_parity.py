@@ -690,3 +690,42 @@ def test_config3_layer_projections_with_padded_groups():
     yv = pa.lowrank_forward(pa.PARSE_DECODE, dls["down"], pats["down"], Xid[:1].contiguous(), None, pid)
     torch.cuda.synchronize()
     check("down", yv, Xi, one, "decode")
+
+
+def test_router_training_step_matches_oracle():
+    """Sec. 4.2: loss and straight-through gradient of the router matrix for one batch, against the oracle on the
+    same rounded inputs (bf16 factors, tokens and dense targets)."""
+    say("router training step: loss and gradient of Wr")
+    n, m, R, G, k, tau, eps = 512, 384, 256, 8, 3, 0.5, 1e-6
+    lengths = [70, 1, 130]
+    lay = si.small_layer(951, n, m, R, G, "bf16")
+    rng = np.random.default_rng(952)
+    off = si.offsets_from_lengths(lengths)
+    X = si.make_tokens(rng, int(off[-1]), n, "bf16")
+    Xv = si.bf16_bits_to_f32(X).astype(np.float64)
+    Wd = rng.standard_normal((m, n)) / np.sqrt(n)
+    Yd_bits = si.f32_to_bf16_bits((Xv @ Wd.T).astype(np.float32))
+    Yd = si.bf16_bits_to_f32(Yd_bits).astype(np.float64)
+    Wr = (rng.standard_normal((G, n)) / np.sqrt(n) * 4.0).astype(np.float32)
+    U0, sg, V = oracle_factors(lay)
+    loss_ref, grad_ref, dm_ref = po.router_grad(U0, sg, V, lay.gs, Xv, off, Yd, Wr.astype(np.float64), k, tau, eps)
+    # GPU: route (embedding, scores, hard subset), routed output, then the training step
+    P = len(lengths)
+    dl_rm = upload_layer(lay)
+    dl = pa.layer_to_mfma16(dl_rm)
+    Xd, offd, Wrd = upload_tokens(X, "bf16"), i32(off), torch.from_numpy(Wr).to(DEV)
+    emb = torch.empty((P, n), dtype=torch.float32, device=DEV)
+    scores = torch.empty((P, G), dtype=torch.float32, device=DEV)
+    subs = pa.route(Xd, offd, Wrd, k, scores_out=scores, emb_out=emb)
+    Vs, Us = pa.pack_patterns(dl, subs, k, k, None, None, P)
+    yhat = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vs, Us), Xd, offd, i32(np.arange(P, dtype=np.int32)))
+    ydd = upload_tokens(Yd_bits, "bf16")
+    loss, grad = pa.router_grad(dl, pa.rankmajor_left_factor(dl_rm), Xd, offd, yhat, ydd, emb, scores, k, tau, eps)
+    loss2, grad2 = pa.router_grad(dl, pa.rankmajor_left_factor(dl_rm), Xd, offd, yhat, ydd, emb, scores, k, tau, eps)
+    torch.cuda.synchronize()
+    assert torch.equal(grad, grad2) and torch.equal(loss, loss2)
+    assert np.allclose(loss.cpu().numpy(), loss_ref, rtol=1e-2)
+    gg = grad.cpu().numpy().astype(np.float64)
+    err = np.linalg.norm(gg - grad_ref) / np.linalg.norm(grad_ref)
+    assert err < 2e-2, f"gradient relative error {err:.3e}"
+    assert np.abs(gg - grad_ref).max() <= 2e-2 * np.abs(grad_ref).max()
