@@ -64,6 +64,18 @@ int check_layer(const parse_layer *L);
 }  // namespace parse
 
 namespace parse {
+// The same answer as prompt_of_row below, found by a whole wavefront at once (every lane must call it with the same
+// row): for P <= 64 lane l reads tok_offsets[l] and the lanes vote, one memory round trip instead of log2(P)
+// dependent ones; longer tables fall back to the binary search.
+__device__ __forceinline__ int prompt_of_row(const int32_t *__restrict__ tok_offsets, int P, int row);
+__device__ __forceinline__ int prompt_of_row_wave(const int32_t *__restrict__ tok_offsets, int P, int row) {
+  if (P > 64) return prompt_of_row(tok_offsets, P, row);
+  const int lane = threadIdx.x & 63;
+  const bool le = lane < P && tok_offsets[lane] <= row;
+  const int n = __popcll(__ballot(le));
+  return n > 0 ? n - 1 : 0;
+}
+
 // Largest p in [0, P) with tok_offsets[p] <= row (tok_offsets ascending, tok_offsets[0] == 0).
 __device__ __forceinline__ int prompt_of_row(const int32_t *__restrict__ tok_offsets, int P, int row) {
   int lo = 0, hi = P - 1;

@@ -93,9 +93,16 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   }
   const int xoff = l32 * xld + q * 8;
 
+  // the first two token tiles do not depend on the prompt's pattern: they are requested before the prompt is
+  // looked up, so that the lookup's memory round trips are not added in front of them
+  u32x4 xr[2][XP];
+#pragma unroll
+  for (int i = 0; i < XP; ++i) xr[0][i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
+#pragma unroll
+  for (int i = 0; i < XP; ++i) xr[1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + PF_BK);
   int seg_lo = row0;
   while (seg_lo < row_end) {
-    const int p = prompt_of_row(a.tok_offsets, a.P, seg_lo);
+    const int p = prompt_of_row_wave(a.tok_offsets, a.P, seg_lo);
     int seg_hi = (p + 1 < a.P) ? a.tok_offsets[p + 1] : a.rows;
     seg_hi = min(max(seg_hi, seg_lo + 1), row_end);
     const int pid = a.pattern_id[p];
@@ -130,17 +137,18 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
       for (int i = 0; i < NB; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
-    u32x4 xr[2][XP];
     u32x4 fr[DEPTH][NB];
     __syncthreads();
+    if (seg_lo != row0) {   // a later segment of the same tile (a prompt boundary inside it): fetch the tiles again
 #pragma unroll
-    for (int i = 0; i < XP; ++i) xr[0][i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
+      for (int i = 0; i < XP; ++i) xr[0][i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
+#pragma unroll
+      for (int i = 0; i < XP; ++i) xr[1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + PF_BK);
+    }
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
 #pragma unroll
       for (int i = 0; i < NB; ++i) fr[d][i] = *reinterpret_cast<const u32x4 *>(fptr(i, d));
-#pragma unroll
-    for (int i = 0; i < XP; ++i) xr[1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + PF_BK);
 #pragma unroll
     for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(Xs + xdst[i]) = xr[0][i];
     __syncthreads();
