@@ -135,7 +135,7 @@ def bench_prefill(args, torch, pa, si):
     per = {nm: sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)) / args.steps * 1e3
            for i, nm in enumerate(names)}                                  # microseconds
     hits = int(hit.sum().item())
-    sched_us, rank_us = {}, None
+    sched_us, rank_us, pipelined = {}, None, None
     if not args.no_extras:
         # the same forward under each fixed schedule, for the record (not part of the timed steps above)
         pid = entry
@@ -184,6 +184,41 @@ def bench_prefill(args, torch, pa, si):
         rank_us = {"route_ranks": timed(lambda: pa.route_ranks(X, off, Wr_r, K_r, subset_out=sub_r, workspace=ws_r)),
                    "pack_ranks_8_patterns": timed(lambda: pa.pack_ranks(dl_rm, sub_r, K_r, P, Vt_S=Vr, Ut_S=Ur)),
                    "R": lay.R, "K": K_r}
+        # two batches in flight, for the record: the control path (pool+route, cache, bucket, pack) of batch i+1 runs
+        # on a second stream while batch i's forward runs; per-batch buffers are double-buffered, events order the
+        # two streams (default priorities).  Every batch still does every row of the path; only the throughput of a
+        # stream of batches changes, a single batch's latency does not.
+        bufs = []
+        for _ in range(2):
+            bufs.append(dict(emb=torch.empty_like(emb), sub_route=torch.empty_like(sub_route), entry=torch.empty_like(entry),
+                             hit=torch.empty_like(hit), sim=torch.empty_like(sim), sub=torch.empty_like(sub),
+                             bucket=tuple(torch.empty_like(t) for t in bucket_out), Y=torch.empty_like(Y),
+                             ready=torch.cuda.Event(), done=torch.cuda.Event()))
+        s_ctl, s_fwd = torch.cuda.Stream(), torch.cuda.Stream()
+        ws_route2 = torch.empty_like(ws_route)
+        def run_pipelined(n_batches):
+            for i in range(n_batches):
+                b = bufs[i & 1]
+                with torch.cuda.stream(s_ctl):
+                    if i >= 2:
+                        s_ctl.wait_event(b["done"])            # batch i-2 has finished reading this buffer set
+                    pa.route(X, off, Wr[0], k, subset_out=b["sub_route"], emb_out=b["emb"], workspace=ws_route2)
+                    cache.lookup_or_route(b["emb"], 0.9, Wr, b["entry"], b["hit"], b["sim"], b["sub"])
+                    pa.bucket_patterns(b["sub"], k, k, b["bucket"])
+                    pa.pack_new_entries(dl, b["sub"], k, k, b["entry"], b["hit"], Vs, Us)
+                    b["ready"].record(s_ctl)
+                with torch.cuda.stream(s_fwd):
+                    s_fwd.wait_event(b["ready"])
+                    pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, b["entry"], b["Y"], ws_fwd)
+                    b["done"].record(s_fwd)
+        torch.cuda.synchronize()
+        run_pipelined(6); torch.cuda.synchronize()
+        nb = max(args.steps, 10)
+        tp0 = time.perf_counter(); run_pipelined(nb); torch.cuda.synchronize(); tp1 = time.perf_counter()
+        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, entry, Y, ws_fwd); torch.cuda.synchronize()
+        pipelined = {"batches": nb, "ms_per_batch": round((tp1 - tp0) / nb * 1e3, 4),
+                     "TFLOPs": round(2.0 * rows * rS * (n + m) / ((tp1 - tp0) / nb) / 1e12, 1),
+                     "same_output_as_sequential": bool(torch.equal(bufs[0]["Y"], Y) and torch.equal(bufs[1]["Y"], Y))}
         # router training step, for the record (Sec. 4.2): loss and gradient of Wr for this batch against a random
         # "dense" target; two full-rank products (137 GFLOP) plus small reductions
         scores_t = torch.empty((P, lay.G), dtype=torch.float32, device=dev)
@@ -203,7 +238,7 @@ def bench_prefill(args, torch, pa, si):
         "value": value, "ms_per_step": ms_per_step, "flops_per_step": flops,
         "rows_us": {k_: round(v, 2) for k_, v in per.items()},
         "cache_hits": hits, "forward_us_by_schedule": sched_us, "cold_step_ms": round(cold_ms, 4),
-        "rank_granular_us": rank_us,
+        "rank_granular_us": rank_us, "two_batches_in_flight": pipelined,
         # the timed steps pass a workspace, so the forward is the two gemm_tokens launches
         "roofline": {"bound": "mfma", "kernel": "gemm_tokens<64,2,8,2> + gemm_tokens<128,2,16,1> (one forward call)",
                      "achieved": round(achieved, 2),
@@ -482,6 +517,7 @@ def main():
         "forward_us_by_schedule": pre["forward_us_by_schedule"],
         "cold_step_ms": pre["cold_step_ms"],
         "rank_granular_us": pre["rank_granular_us"],
+        "two_batches_in_flight": pre["two_batches_in_flight"],
         "decode": dec,
     }
     if stack is not None:
