@@ -729,3 +729,80 @@ def test_router_training_step_matches_oracle():
     err = np.linalg.norm(gg - grad_ref) / np.linalg.norm(grad_ref)
     assert err < 2e-2, f"gradient relative error {err:.3e}"
     assert np.abs(gg - grad_ref).max() <= 2e-2 * np.abs(grad_ref).max()
+
+
+def test_multi_calls_with_four_layers_and_a_shared_head():
+    """Four layers in one decode call (different widths, one needing several column blocks per workgroup) and
+    four layers in one prefill call of which one uses a shared head."""
+    say("decode_multi x4 and prefill_multi x4 (one layer with a shared head)")
+    n, B = 512, 32
+    rng = np.random.default_rng(961)
+    shapes = [(256, 128, 4, 2), (16384, 96, 3, 2), (768, 256, 8, 3), (512, 512, 4, 4)]     # (m, R, G, k)
+    x = si.make_tokens(rng, B, n, "bf16")
+    xd = upload_tokens(x, "bf16")
+    seq_pat = (np.arange(B) % 3).astype(np.int32)
+    layers, pats, refs = [], [], []
+    for li, (m, R, G, k) in enumerate(shapes):
+        lay = si.small_layer(970 + li, n, m, R, G, "bf16")
+        sub = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(3)]).astype(np.int32)
+        U0, sg, V = oracle_factors(lay)
+        refs.append(po.decode_step(U0, sg, V, lay.gs, si.bf16_bits_to_f32(x).astype(np.float64), sub[seq_pat]))
+        layers.append(pa.layer_to_mfma16(upload_layer(lay)))
+        pats.append(pa.Patterns(k, 3, subsets=i32(sub)))
+    ys = pa.lowrank_decode_multi(layers, pats, xd, i32(seq_pat))
+    torch.cuda.synchronize()
+    for li in range(4):
+        assert_close(ys[li].float().cpu().numpy().astype(np.float64), refs[li], TOL_BF16, f"decode layer {li}")
+    # prefill: four layers sharing X, layer 2 with a shared head of one group
+    lengths = [130, 64, 7]
+    off = si.offsets_from_lengths(lengths)
+    X = si.make_tokens(rng, int(off[-1]), n, "bf16")
+    Xv = si.bf16_bits_to_f32(X).astype(np.float64)
+    Xd, offd = upload_tokens(X, "bf16"), i32(off)
+    P = len(lengths)
+    pshapes = [(256, 256, 2, 1), (768, 512, 4, 2), (512, 512, 4, 3), (1024, 256, 2, 2)]     # k*gs multiples of 128
+    layers, pats, refs = [], [], []
+    for li, (m, R, G, k) in enumerate(pshapes):
+        lay = si.small_layer(980 + li, n, m, R, G, "bf16")
+        ns = 1 if li == 2 else 0
+        sub = np.stack([np.concatenate([np.arange(ns), ns + np.sort(rng.choice(G - ns, size=k - ns, replace=False))])
+                        for _ in lengths]).astype(np.int32)
+        U0, sg, V = oracle_factors(lay)
+        refs.append(po.forward(U0, sg, V, lay.gs, Xv, off, sub))
+        dl = pa.layer_to_mfma16(upload_layer(lay))
+        sd = i32(sub)
+        if ns:
+            Vsh, Ush = pa.pack_experts(dl, i32(np.arange(ns, dtype=np.int32)))
+            Vp, Up = pa.pack_patterns(dl, sd[:, ns:], k, k - ns, None, None, P)
+            pats.append(pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns))
+        else:
+            Vp, Up = pa.pack_patterns(dl, sd, k, k, None, None, P)
+            pats.append(pa.Patterns(k, P, Vp, Up))
+        layers.append(dl)
+    ys = pa.lowrank_prefill_multi(layers, pats, Xd, offd, i32(np.arange(P, dtype=np.int32)))
+    torch.cuda.synchronize()
+    for li in range(4):
+        yn = ys[li].float().cpu().numpy().astype(np.float64)
+        for p in range(P):
+            assert_close(yn[off[p]:off[p + 1]], refs[li][off[p]:off[p + 1]], TOL_BF16, f"prefill layer {li} prompt {p}")
+
+
+def test_rank_router_at_its_limits():
+    """8192 ranks (the selection kernel's limit), 40 prompts (five scoring blocks), K = 32."""
+    say("route_ranks: G=8192, P=40, K=32")
+    d, G, K, P = 256, 8192, 32, 40
+    rng = np.random.default_rng(991)
+    E = rng.standard_normal((P, d)).astype(np.float32)
+    Wr = (rng.standard_normal((G, d)) / np.sqrt(d)).astype(np.float32)
+    S = E.astype(np.float64) @ Wr.T.astype(np.float64)
+    ref = np.stack([po.topk_ascending(S[p], K)[0] for p in range(P)])
+    off = i32(np.arange(P + 1, dtype=np.int32))            # ready-made embeddings: prompts of length 1
+    subs = pa.route_ranks(torch.from_numpy(E).to(DEV), off, torch.from_numpy(Wr).to(DEV), K)
+    torch.cuda.synchronize()
+    sg = subs.cpu().numpy()
+    for p in range(P):
+        if not np.array_equal(sg[p], ref[p]):             # only a swap at a near-tie of the cut is acceptable
+            a, b = set(sg[p]) - set(ref[p]), set(ref[p]) - set(sg[p])
+            cut = np.sort(S[p])[::-1][K - 1]
+            assert len(a) == len(b) and all(abs(S[p][g] - cut) < 1e-5 * np.abs(S).max() for g in a | b), f"prompt {p}"
+        assert list(sg[p]) == sorted(set(sg[p]))
