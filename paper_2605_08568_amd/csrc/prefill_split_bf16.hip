@@ -36,6 +36,7 @@ struct GtArgs {
   const int32_t *tok_offsets, *pattern_id;
   int rows, P;
   int ntiles, nchunks, GT;  // token tiles, factor-row chunks (all layers), token tiles per locality group
+  int ngroups;              // locality groups: virtual ids run over ngroups * GT * nchunks
 };
 
 // KG = 1: four wavefronts, the whole reduction.  KG = 2: eight wavefronts, two groups of four that each run the
@@ -45,6 +46,10 @@ struct GtArgs {
 // SH = 0: all factor operands from the pattern's block.  SH = 1: the leading factor-row blocks, SH = 2: the
 // leading reduction blocks come from the layer's shared block (Sec. 4.4: shared experts at the head of memory,
 // stored once) -- "two contiguous reads" per prompt instead of one.
+// A workgroup walks a list of work items -- (token tile, chunk of factor rows, prompt segment of the tile) --
+// one after the other; with a grid of one workgroup per compute unit and several items each, the operand
+// requests of the next item are in flight while the finished item's tile is converted and written out, so neither
+// the start-up round trips nor the output stores of an item sit between two reduction loops.
 template <int BT, int NB, int DEPTH, int KG, int SH>
 __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   constexpr int TPI = DEPTH / 4;   // staged tiles per unrolled loop iteration = ring depth in tiles
@@ -65,71 +70,113 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
   uint16_t *Xs = lds_raw + kg * 2 * BT * xld;
   const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, q = lane >> 5;
   // consecutive virtual ids share an XCD; a group of GT token tiles x all chunks is consecutive, so the tiles
-  // of one prompt find their pattern's factors (and each other's token rows) in that die's L2
-  const int v = xcd_tile(blockIdx.x, gridDim.x);
+  // of one prompt find their pattern's factors (and each other's token rows) in that die's L2.  A workgroup
+  // takes `items` consecutive virtual ids.
   const int per_group = a.nchunks * a.GT;
-  const int grp = v / per_group, rem = v % per_group;
-  const int gchunk = rem / a.GT, tile = grp * a.GT + rem % a.GT;
-  if (tile >= a.ntiles) return;
-  int li = 0;
-#pragma unroll
-  for (int i = 1; i < GT_MAX_LAYERS; ++i) li += (i < a.n_layers && gchunk >= a.L[i].chunk_first) ? 1 : 0;
-  const GtLayer &ly = a.L[li];
-  const int chunk = gchunk - ly.chunk_first;
-  const int row0 = tile * BT;
-  const int row_end = min(row0 + BT, a.rows);
-  const int K = ly.K, Kg = K / KG, nkb = Kg / 16, nkt = Kg / PF_BK, nmb = ly.M / 32;
-  const int kbeg = kg * Kg;        // this group's part of the reduction range
-  const int mb0 = chunk * 4 * NB + wave * NB;
+  const int total = a.ngroups * per_group;
+  const int items = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int v_first = xcd_tile(blockIdx.x, gridDim.x) * items;
+  int v_next = v_first;                       // next virtual id to look at
+  const int v_end = min(v_first + items, total);
 
-  const uint16_t *xsrc[XP];
   int xdst[XP];
 #pragma unroll
   for (int i = 0; i < XP; ++i) {
     const int piece = i * PF_THREADS + tid;
-    const int r = piece / (PF_BK / 8), c = (piece % (PF_BK / 8)) * 8;
-    xsrc[i] = ly.T + (size_t)min(row0 + r, a.rows - 1) * K + kbeg + c;
-    xdst[i] = r * xld + c;
+    xdst[i] = (piece / (PF_BK / 8)) * xld + (piece % (PF_BK / 8)) * 8;
   }
   const int xoff = l32 * xld + q * 8;
 
-  // the first two token tiles do not depend on the prompt's pattern: they are requested before the prompt is
-  // looked up, so that the lookup's memory round trips are not added in front of them
+  // ---- state of the item whose reduction loop runs (set by advance()) ----
+  const uint16_t *xsrc[XP];
+  const uint16_t *fbase[NB], *fshared[NB];
+  const uint16_t *lyT = nullptr, *lyF = nullptr, *lyFsh = nullptr;
+  uint16_t *lyO = nullptr;
+  size_t pattern_stride = 0, kstride = 0;
+  int mb_stride = 0, K = 0, M = 0, n_patterns = 0, sh_blocks = 0, shb = 0;
+  int nkb = 0, nkt = 0, nmb = 0, kbeg = 0, chunk = 0, mb0 = 0, row0 = 0, row_end = 0, seg_lo = 0, seg_hi = 0;
+  bool valid = false, in_tile = false;        // in_tile: the current tile has another prompt segment to do
   u32x4 xr[2][XP];
+  u32x4 fr[DEPTH][NB];
+
+  auto fptr = [&](int i, int kb) -> const uint16_t * {
+    if (SH == 2) return (kb < shb ? fshared[i] : fbase[i]) + (size_t)kb * kstride;
+    return fbase[i] + (size_t)kb * kstride;
+  };
+
+  // Moves to the next item (the next prompt segment of the tile, else the next tile/chunk of this workgroup's
+  // list), works out its operands and requests the first of them.  Returns false at the end of the list.
+  auto advance = [&]() -> bool {
+    if (in_tile) {
+      seg_lo = seg_hi;
+    } else {
+      int tile = 0, gchunk = 0;
+      for (;;) {
+        if (v_next >= v_end) return false;
+        const int v = v_next++;
+        const int grp = v / per_group, rem = v % per_group;
+        gchunk = rem / a.GT;
+        tile = grp * a.GT + rem % a.GT;
+        if (tile < a.ntiles) break;           // ids past the last token tile pad the last locality group
+      }
+      int li = 0;
 #pragma unroll
-  for (int i = 0; i < XP; ++i) xr[0][i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
+      for (int i = 1; i < GT_MAX_LAYERS; ++i) li += (i < a.n_layers && gchunk >= a.L[i].chunk_first) ? 1 : 0;
+      const GtLayer &ly = a.L[li];
+      lyT = ly.T; lyF = ly.F; lyO = ly.O; lyFsh = ly.Fsh;
+      pattern_stride = ly.pattern_stride; mb_stride = ly.mb_stride; kstride = (size_t)ly.kb_stride * 512;
+      K = ly.K; M = ly.M; n_patterns = ly.n_patterns; sh_blocks = ly.sh_blocks;
+      chunk = gchunk - ly.chunk_first;
+      row0 = tile * BT;
+      row_end = min(row0 + BT, a.rows);
+      const int Kg = K / KG;
+      nkb = Kg / 16; nkt = Kg / PF_BK; nmb = M / 32;
+      kbeg = kg * Kg;                         // this wavefront group's part of the reduction range
+      mb0 = chunk * 4 * NB + wave * NB;
+      shb = SH == 2 ? sh_blocks : 0;
 #pragma unroll
-  for (int i = 0; i < XP; ++i) xr[1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + PF_BK);
-  int seg_lo = row0;
-  while (seg_lo < row_end) {
+      for (int i = 0; i < XP; ++i) {
+        const int piece = i * PF_THREADS + tid;
+        const int r = piece / (PF_BK / 8), c = (piece % (PF_BK / 8)) * 8;
+        xsrc[i] = lyT + (size_t)min(row0 + r, a.rows - 1) * K + kbeg + c;
+      }
+      seg_lo = row0;
+    }
+    // the first two token tiles do not depend on the prompt's pattern: requested before the prompt is looked up
+#pragma unroll
+    for (int i = 0; i < XP; ++i) xr[0][i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
+#pragma unroll
+    for (int i = 0; i < XP; ++i) xr[1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + PF_BK);
     const int p = prompt_of_row_wave(a.tok_offsets, a.P, seg_lo);
-    int seg_hi = (p + 1 < a.P) ? a.tok_offsets[p + 1] : a.rows;
-    seg_hi = min(max(seg_hi, seg_lo + 1), row_end);
+    int hi = (p + 1 < a.P) ? a.tok_offsets[p + 1] : a.rows;
+    seg_hi = min(max(hi, seg_lo + 1), row_end);
+    in_tile = seg_hi < row_end;
     const int pid = a.pattern_id[p];
-    const bool valid = pid >= 0 && pid < ly.n_patterns;
-    const uint16_t *Fp = ly.F + (valid ? (size_t)pid * ly.pattern_stride : 0);
-    const size_t kstride = (size_t)ly.kb_stride * 512;
-    const uint16_t *fbase[NB], *fshared[NB];
-    const int shb = SH == 2 ? ly.sh_blocks : 0;
+    valid = pid >= 0 && pid < n_patterns;
+    const uint16_t *Fp = lyF + (valid ? (size_t)pid * pattern_stride : 0);
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
       const int mb = min(mb0 + i, nmb - 1);
       if (SH == 1) {
-        const bool in_head = mb < ly.sh_blocks;
-        fbase[i] = (in_head ? ly.Fsh : Fp) + ((size_t)(in_head ? mb : mb - ly.sh_blocks) * ly.mb_stride * 64 + lane) * 8 +
+        const bool in_head = mb < sh_blocks;
+        fbase[i] = (in_head ? lyFsh : Fp) + ((size_t)(in_head ? mb : mb - sh_blocks) * mb_stride * 64 + lane) * 8 +
                    (size_t)(kbeg / 16) * kstride;
       } else {
-        fbase[i] = Fp + ((size_t)mb * ly.mb_stride * 64 + lane) * 8 + (size_t)(kbeg / 16) * kstride;
+        fbase[i] = Fp + ((size_t)mb * mb_stride * 64 + lane) * 8 + (size_t)(kbeg / 16) * kstride;
       }
       // SH == 2: reduction block kb < shb is operand kb of the shared block, else operand kb - shb of the pattern's
-      fshared[i] = SH == 2 ? ly.Fsh + ((size_t)mb * ly.mb_stride * 64 + lane) * 8 : nullptr;
+      fshared[i] = SH == 2 ? lyFsh + ((size_t)mb * mb_stride * 64 + lane) * 8 : nullptr;
       if (SH == 2) fbase[i] -= (size_t)shb * kstride;
     }
-    auto fptr = [&](int i, int kb) -> const uint16_t * {
-      if (SH == 2) return (kb < shb ? fshared[i] : fbase[i]) + (size_t)kb * kstride;
-      return fbase[i] + (size_t)kb * kstride;
-    };
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+#pragma unroll
+      for (int i = 0; i < NB; ++i) fr[d][i] = *reinterpret_cast<const u32x4 *>(fptr(i, d));
+    return true;
+  };
 
+  bool have = advance();
+  while (have) {
     f32x16 acc[NT][NB];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -137,18 +184,7 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
       for (int i = 0; i < NB; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
-    u32x4 fr[DEPTH][NB];
-    __syncthreads();
-    if (seg_lo != row0) {   // a later segment of the same tile (a prompt boundary inside it): fetch the tiles again
-#pragma unroll
-      for (int i = 0; i < XP; ++i) xr[0][i] = *reinterpret_cast<const u32x4 *>(xsrc[i]);
-#pragma unroll
-      for (int i = 0; i < XP; ++i) xr[1][i] = *reinterpret_cast<const u32x4 *>(xsrc[i] + PF_BK);
-    }
-#pragma unroll
-    for (int d = 0; d < DEPTH; ++d)
-#pragma unroll
-      for (int i = 0; i < NB; ++i) fr[d][i] = *reinterpret_cast<const u32x4 *>(fptr(i, d));
+    __syncthreads();     // the previous item's output passes are done with the LDS
 #pragma unroll
     for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(Xs + xdst[i]) = xr[0][i];
     __syncthreads();
@@ -208,6 +244,11 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
         __syncthreads();
       }
     }
+    // what the output passes of THIS item need, before advance() moves the state on to the next one
+    uint16_t *const oO = lyO;
+    const int oM = M, o_row0 = row0, o_lo = seg_lo, o_hi = seg_hi, o_chunk = chunk;
+    const bool o_valid = valid;
+    have = advance();    // the next item's first operands are in flight from here on
     // Output: lane holds token t*32 + l32, factor rows (mb0+i)*32 + 8*blk + 4*q + (0..3).  Tiles go through LDS,
     // EPT*32 tokens at a time, so that every store instruction writes whole output rows (OC*2 contiguous bytes
     // per token) instead of 8-byte pieces of 32 different rows.
@@ -223,8 +264,8 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
 #pragma unroll
             for (int blk = 0; blk < 4; ++blk) {
               u32x2 w;
-              w[0] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]) : 0u;
-              w[1] = valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]) : 0u;
+              w[0] = o_valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 0], acc[t][i][blk * 4 + 1]) : 0u;
+              w[1] = o_valid ? cvt_pk_bf16(acc[t][i][blk * 4 + 2], acc[t][i][blk * 4 + 3]) : 0u;
               *reinterpret_cast<u32x2 *>(Ot + ((t - tp) * 32 + l32) * OLD + (wave * NB + i) * 32 + blk * 8 + q * 4) = w;
             }
       }
@@ -236,14 +277,24 @@ __global__ __launch_bounds__(PF_THREADS * KG) void gemm_tokens(GtArgs a) {
         for (int it = 0; it < ROWS * PPR / PF_THREADS; ++it) {
           const int piece = it * PF_THREADS + tid;
           const int r = piece / PPR, c = (piece % PPR) * 8;
-          const int grow = row0 + tp * 32 + r, gcol = chunk * OC + c;
-          if (grow >= seg_lo && grow < seg_hi && gcol < ly.M)
-            *reinterpret_cast<u32x4 *>(ly.O + (size_t)grow * ly.M + gcol) = *reinterpret_cast<const u32x4 *>(Ot + r * OLD + c);
+          const int grow = o_row0 + tp * 32 + r, gcol = o_chunk * OC + c;
+          if (grow >= o_lo && grow < o_hi && gcol < oM)
+            *reinterpret_cast<u32x4 *>(oO + (size_t)grow * oM + gcol) = *reinterpret_cast<const u32x4 *>(Ot + r * OLD + c);
         }
       }
     }
-    seg_lo = seg_hi;
   }
+}
+
+static int compute_units() {
+  static int n_cu_of[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (n_cu_of[dev] == 0) {
+    hipDeviceProp_t prop;
+    n_cu_of[dev] = (hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0) ? prop.multiProcessorCount : 256;
+  }
+  return n_cu_of[dev];
 }
 
 template <int BT, int NB, int DEPTH, int KG, int SH>
@@ -256,8 +307,13 @@ static int launch_gemm_tokens(GtArgs a, int GT, hipStream_t s) {
   }
   a.nchunks = chunks;
   a.GT = GT;
-  const int groups = (a.ntiles + GT - 1) / GT;
-  hipLaunchKernelGGL((gemm_tokens<BT, NB, DEPTH, KG, SH>), dim3(groups * GT * a.nchunks), dim3(PF_THREADS * KG), 0, s, a);
+  a.ngroups = (a.ntiles + GT - 1) / GT;
+  const int total = a.ngroups * GT * a.nchunks;
+  // From two rounds of workgroups on, a fixed grid of one workgroup per compute unit walks the list (the next
+  // item's operands are requested while the finished one is written out); below that, one item per workgroup.
+  const int n_cu = compute_units();
+  const int grid = total >= 2 * n_cu ? n_cu : total;
+  hipLaunchKernelGGL((gemm_tokens<BT, NB, DEPTH, KG, SH>), dim3(grid), dim3(PF_THREADS * KG), 0, s, a);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }
