@@ -30,8 +30,9 @@ numpy.linalg.svd recovers sigma; Eckart-Young residual closed form; orthonormal
 energy identity; brute-force rank-1 loops; group-order invariance; left-out group
 contributes exactly its own term; hand-built routers with known top-k; cache
 special cases and the clustered-workload hit-rate closed form; pack/bucket
-identities.  The FORM of the error metric (`rel_errors`) is this build's choice:
-the paper states none -- parity unpinned for that one helper.
+identities; `rel_errors` and `soft_mask` on hand-computed values.  The FORM of the
+error metric (`rel_errors`: Frobenius and max-abs, both relative to the reference) is
+this build's choice: the paper states none; what the helper computes is pinned.
 """
 from __future__ import annotations
 

@@ -17,7 +17,8 @@ constexpr int kPackWindow = 2048;   // patterns whose work list a workgroup hold
 // A fixed grid walks the work list: every workgroup first lists (in LDS) the patterns that have anything to
 // copy -- a batch whose prompts all hit the cache ends here, after one pass over the hit flags -- then takes
 // every gridDim.x-th task; a task = (listed pattern, one of its 2k slabs, one 32 KiB chunk of the slab).
-// Copies are idempotent, so the order in which the list was filled does not matter.
+// The list is in ascending pattern order in every workgroup (a strided walk over lists that differ from
+// workgroup to workgroup would copy some tasks twice and others never).
 __global__ __launch_bounds__(kCopyThreads) void pack_slabs(const char *__restrict__ Vt, const char *__restrict__ Ut,
                                                            size_t v_slab_bytes, size_t u_slab_bytes, int G, int k,
                                                            const int32_t *__restrict__ subset, int subset_stride,
@@ -28,22 +29,39 @@ __global__ __launch_bounds__(kCopyThreads) void pack_slabs(const char *__restric
                                                            char *__restrict__ Vt_S, char *__restrict__ Ut_S) {
   __shared__ int32_t act[kPackWindow];
   __shared__ int32_t n_act;
+  __shared__ int32_t wave_cnt[kCopyThreads / 64];
   const int np = n_patterns ? min(*n_patterns, max_patterns) : max_patterns;
   const size_t big = v_slab_bytes > u_slab_bytes ? v_slab_bytes : u_slab_bytes;
   const int chunks = (int)((big + kCopyChunk - 1) / kCopyChunk);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int j0 = 0; j0 < np; j0 += kPackWindow) {
     if (threadIdx.x == 0) n_act = 0;
     __syncthreads();
-    for (int j = j0 + threadIdx.x; j < min(np, j0 + kPackWindow); j += kCopyThreads) {
-      bool on = !(skip && skip[j]);
+    // the list is filled in ascending pattern order (per-wavefront vote + prefix over the wavefronts), so every
+    // workgroup holds the SAME list and the strided walk below covers every task exactly once
+    const int wend = min(np, j0 + kPackWindow);
+    for (int r0 = j0; r0 < wend; r0 += kCopyThreads) {
+      const int j = r0 + (int)threadIdx.x;
+      bool on = j < wend && !(skip && skip[j]);
       if (on && rep) on = rep[j] >= 0;
       if (on) {
         const int d = slot ? slot[j] : j;
         on = d >= 0 && d < n_slots;
       }
-      if (on) act[atomicAdd(&n_act, 1)] = j;
+      const unsigned long long votes = __ballot(on);
+      if (lane == 0) wave_cnt[wave] = __popcll(votes);
+      __syncthreads();
+      int base = n_act;
+      for (int w2 = 0; w2 < wave; ++w2) base += wave_cnt[w2];
+      if (on) act[base + __popcll(votes & ((1ull << lane) - 1ull))] = j;
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        int add = 0;
+        for (int w2 = 0; w2 < kCopyThreads / 64; ++w2) add += wave_cnt[w2];
+        n_act += add;
+      }
+      __syncthreads();
     }
-    __syncthreads();
     const long long total = (long long)n_act * 2 * k * chunks;
     for (long long t = blockIdx.x; t < total; t += gridDim.x) {
       const int c = (int)(t % chunks);

@@ -463,3 +463,63 @@ def test_router_training_step_against_finite_differences():
                 dmsoft = (po.soft_mask(Wp @ E[p], k, tau, eps) - po.soft_mask(Wm @ E[p], k, tau, eps)) / (2 * h)
                 grad_fd[j, c] += float(dm[p] @ dmsoft)
     assert np.allclose(grad_fd, grad, rtol=1e-4, atol=1e-7)
+
+
+# ----------------------------------------------------------------- error metric and soft mask pins
+def _rel_errors_pins_hold(fn) -> bool:
+    """Hand-computed cases of the two error figures.  Y = [[3, 4]], Yref = [[0, 5]]: difference (3, -1), Frobenius
+    sqrt(10) over 5, max-abs 3 over 5.  Second case: 99 exact entries of value 1 and one entry off by 1, so the two
+    figures differ tenfold (0.1 against 1) and neither can stand in for the other.  Third case: the result is twice
+    the reference, so both errors are 1 relative to the REFERENCE (they would be 0.5 relative to the result)."""
+    ok = True
+    fro, mx = fn([[3.0, 4.0]], [[0.0, 5.0]])
+    ok &= abs(fro - np.sqrt(10.0) / 5.0) < 1e-15 and abs(mx - 3.0 / 5.0) < 1e-15
+    Yref = np.ones((10, 10)); Y = Yref.copy(); Y[3, 7] = 2.0
+    fro, mx = fn(Y, Yref)
+    ok &= abs(fro - 0.1) < 1e-15 and abs(mx - 1.0) < 1e-15
+    fro, mx = fn([[2.0, -4.0, 6.0]], [[1.0, -2.0, 3.0]])
+    ok &= abs(fro - 1.0) < 1e-15 and abs(mx - 1.0) < 1e-15
+    fro, mx = fn([[1.0, -1.0]], [[1.0, 2.0]])          # the only error is negative: (0, -3)
+    ok &= abs(fro - 3.0 / np.sqrt(5.0)) < 1e-15 and abs(mx - 1.5) < 1e-15
+    fro, mx = fn([[1.5, -2.0]], [[1.5, -2.0]])
+    ok &= fro == 0.0 and mx == 0.0
+    return bool(ok)
+
+
+def test_rel_errors_on_hand_computed_arrays():
+    """The helper every float tolerance goes through gives the hand-computed figures, does not divide by zero on a
+    zero reference, and the same cases reject the plausible wrong forms: dividing by the result's norm, by the
+    wrong kind of norm, or a signed maximum."""
+    assert _rel_errors_pins_hold(po.rel_errors)
+    assert np.isfinite(po.rel_errors([[0.0]], [[0.0]])).all()
+    d = lambda Y, Yr: np.asarray(Y, float) - np.asarray(Yr, float)
+    by_result = lambda Y, Yr: (np.linalg.norm(d(Y, Yr)) / np.linalg.norm(Y), np.max(np.abs(d(Y, Yr))) / np.max(np.abs(Y)))
+    max_over_fro = lambda Y, Yr: (np.linalg.norm(d(Y, Yr)) / np.linalg.norm(Yr), np.max(np.abs(d(Y, Yr))) / np.linalg.norm(Yr))
+    signed_max = lambda Y, Yr: (np.linalg.norm(d(Y, Yr)) / np.linalg.norm(Yr), np.max(d(Y, Yr)) / np.max(Yr))
+    mean_not_norm = lambda Y, Yr: (np.abs(d(Y, Yr)).mean() / np.abs(Yr).mean(), np.max(np.abs(d(Y, Yr))) / np.max(np.abs(Yr)))
+    for bad in (by_result, max_over_fro, signed_max, mean_not_norm):
+        assert not _rel_errors_pins_hold(bad)
+
+
+def test_soft_mask_values_fixed_by_the_formula():
+    """Eq. 9 on inputs whose value is known without the oracle: equal scores give K/G each (times 1/(1+eps G/..));
+    two scores have their sigmoids written out by hand; a lower temperature sharpens the mask (the score is DIVIDED
+    by it), a higher one flattens it towards K/G."""
+    G, K = 5, 2
+    m = po.soft_mask(np.full(G, 0.3), K, 0.7, 0.0)
+    assert np.allclose(m, K / G, atol=1e-15)
+    # eps enters the denominator only: sum of sigmoids A = G*a, m = K a / (G a + eps)
+    a = 1.0 / (1.0 + np.exp(-0.3 / 0.7)); eps = 1e-3
+    assert np.allclose(po.soft_mask(np.full(G, 0.3), K, 0.7, eps), K * a / (G * a + eps), atol=1e-15)
+    # two scores, temperature 2: sigmoid(ln3) = 3/4, sigmoid(-ln3) = 1/4 -> mask = K * (3/4, 1/4) / 1
+    s = np.array([2.0 * np.log(3.0), -2.0 * np.log(3.0)])
+    assert np.allclose(po.soft_mask(s, 1, 2.0, 0.0), [0.75, 0.25], atol=1e-15)
+    assert np.allclose(po.soft_mask(s, 2, 2.0, 0.0), [1.5, 0.5], atol=1e-15)
+    # temperature 1 on the same scores: sigmoid(2 ln 3) = 9/10, sigmoid(-2 ln 3) = 1/10 -> sharper
+    assert np.allclose(po.soft_mask(s, 1, 1.0, 0.0), [0.9, 0.1], atol=1e-15)
+    # multiplying by the temperature instead of dividing would give (0.9, 0.1) at temperature 2 and fail the line above
+    s3 = np.array([1.0, 0.0, -1.0])
+    sharp, flat = po.soft_mask(s3, 1, 0.1, 0.0), po.soft_mask(s3, 1, 10.0, 0.0)
+    assert sharp[0] > 0.6 and sharp[2] < 1e-4 and np.all(np.abs(flat - 1.0 / 3.0) < 0.02)
+    # the largest score always gets the largest mask entry; the entries sum to K when eps = 0
+    assert np.argmax(sharp) == 0 and abs(po.soft_mask(s3, 2, 0.5, 0.0).sum() - 2.0) < 1e-15
