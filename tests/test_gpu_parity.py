@@ -247,7 +247,7 @@ def test_pack_many_patterns_spread_over_a_large_batch():
     list, else some slabs are copied twice and others never: byte equality with the oracle's pack per slot, and
     canary slots stay untouched."""
     say("pack: 300-prompt batch with scattered new entries; 200 patterns in one call")
-    lay = si.small_layer(406, 128, 96, 256, 8, "bf16")
+    lay = si.small_layer(406, 256, 288, 256, 8, "bf16")
     dl = pa.layer_to_mfma16(upload_layer(lay))
     k, P, n_slots = 3, 300, 160
     rng = np.random.default_rng(407)
