@@ -777,8 +777,8 @@ def test_router_training_step_matches_oracle():
     err = np.linalg.norm(gg - grad_ref) / np.linalg.norm(grad_ref)
     say(f"    gradient: fro {err:.3e} max {np.abs(gg - grad_ref).max() / np.abs(grad_ref).max():.3e}; "
         f"loss rel {np.abs(loss.cpu().numpy() - loss_ref).max() / np.abs(loss_ref).max():.3e}")
-    assert err < 2e-2, f"gradient relative error {err:.3e}"
-    assert np.abs(gg - grad_ref).max() <= 2e-2 * np.abs(grad_ref).max()
+    assert err <= TOL_BF16, f"gradient relative error {err:.3e}"          # measured 2.7e-4 / 2.3e-4
+    assert np.abs(gg - grad_ref).max() <= TOL_BF16 * np.abs(grad_ref).max()
 
 
 def test_multi_calls_with_four_layers_and_a_shared_head():
