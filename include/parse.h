@@ -310,6 +310,25 @@ int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *
                                const void *X, int32_t rows, const int32_t *pattern_id, void *const *Y,
                                void *workspace, size_t workspace_bytes, parse_stream stream);
 
+/* ---- decode without allocation ---------------------------------------------------------------------------
+ * For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  The same step as parse_lowrank_forward(PARSE_DECODE, ...) -- same kernels, same bits --
+ * but the memory the kernels need beyond inputs and outputs (slice partials of the intermediate, its rounded
+ * copy, the list of used groups) is a fixed array of PARSE_DECODE_STATIC_SCRATCH_BYTES inside the library's
+ * device image instead of a caller's workspace.  The call allocates and frees nothing, on any call, and calls no
+ * allocating routine; every GPU the library runs on holds its own copy of the array until the process ends.
+ *   layer, patterns, X, rows, pattern_id, Y   as for PARSE_DECODE (device pointers, rows <= 32, bf16 PARSE_MFMA16)
+ * PARSE_EWORKSPACE when the layer needs more than the array holds (the need grows with the stored rank R:
+ * parse_lowrank_workspace_bytes(PARSE_DECODE, layer, rows, k) tells; R <= 2560 fits); other errors as
+ * parse_lowrank_forward.  Nothing is launched on error.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two threads) race;
+ * issue them on one stream or order them.  The array keeps the last call's contents; the kernels read only what
+ * the same call wrote, so nothing needs clearing between calls. */
+#define PARSE_DECODE_STATIC_SCRATCH_BYTES (24u << 20)
+size_t parse_lowrank_decode_static_capacity(void);
+int parse_lowrank_decode_static(const parse_layer *layer, const parse_patterns *patterns, const void *X,
+                                int32_t rows, const int32_t *pattern_id, void *Y, parse_stream stream);
+
 /* Horizontal fusion for prefill (Sec. 4.4, Eq. 11-12): n_layers (1..4) bf16 PARSE_MFMA16 layers that read the
  * SAME token rows X (equal n) in two launches for all of them -- one stacked first product over the selected
  * ranks of every layer, one batched second product.  The result equals n_layers separate PARSE_PREFILL calls

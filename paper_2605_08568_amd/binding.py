@@ -106,6 +106,9 @@ def lib():
     L.parse_lowrank_forward.restype = C.c_int
     L.parse_lowrank_forward.argtypes = [i32, C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, i32, vp, vp,
                                         sz, vp]
+    L.parse_lowrank_decode_static_capacity.restype = sz; L.parse_lowrank_decode_static_capacity.argtypes = []
+    L.parse_lowrank_decode_static.restype = C.c_int
+    L.parse_lowrank_decode_static.argtypes = [C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, vp]
     _lib = L
     return L
 
@@ -362,6 +365,14 @@ def lowrank_forward(mode: int, layer: Layer, patterns: Patterns, X, tok_offsets,
                                        _ptr(pattern_id), P, _ptr(Y), _ptr(workspace),
                                        0 if workspace is None else workspace.numel(), _stream()),
            "parse_lowrank_forward")
+    return Y
+
+
+def lowrank_decode_static(layer: Layer, patterns: Patterns, X, pattern_id, Y):
+    """parse_lowrank_decode_static: the decode step on the library's fixed scratch array; Y is the caller's."""
+    cl, cp = layer.c(), patterns.c()
+    _check(lib().parse_lowrank_decode_static(C.byref(cl), C.byref(cp), _ptr(X), X.shape[0], _ptr(pattern_id), _ptr(Y),
+                                             _stream()), "parse_lowrank_decode_static")
     return Y
 
 
