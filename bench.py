@@ -94,9 +94,11 @@ def bench_prefill(args, torch, pa, si):
     Vs = torch.empty((n_slots, rS, n), dtype=torch.bfloat16, device=dev)
     Us = torch.empty((n_slots, rS, m), dtype=torch.bfloat16, device=dev)
     Y = torch.empty((rows, m), dtype=torch.bfloat16, device=dev)
-    ws_fwd = torch.empty(max(pa.lowrank_workspace_bytes(pa.PARSE_PREFILL, dl, rows, k), 256), dtype=torch.uint8, device=dev)
+    ws_fwd = torch.empty(max(pa.lowrank_workspace_bytes(pa.PARSE_PREFILL, dl, rows, k, P, n_slots), 256), dtype=torch.uint8, device=dev)
     pt = pa.Patterns(k, n_slots, Vs, Us)
-    names = ["route", "cache", "bucket", "pack", "forward"]
+    plan = torch.empty(pa.prefill_plan_bytes(rows, P, n_slots), dtype=torch.uint8, device=dev)
+    ws_plan = torch.empty(max(pa.lowrank_prefill_planned_workspace_bytes(dl, rows, P, k, n_slots), 256), dtype=torch.uint8, device=dev)
+    names = ["route", "cache", "bucket", "plan", "pack", "forward"]
 
     def step(ev=None):
         def mark(i):
@@ -109,10 +111,12 @@ def bench_prefill(args, torch, pa, si):
         mark(2)
         pa.bucket_patterns(sub, k, k, bucket_out)          # buckets of equal subsets (execution grouping)
         mark(3)
-        pa.pack_new_entries(dl, sub, k, k, entry, hit, Vs, Us)   # aggregation happens once per new cache entry
+        pa.prefill_plan(off, entry, rows, n_slots, plan)    # token rows grouped by pattern (= cache entry); serves every layer
         mark(4)
-        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, entry, Y, ws_fwd)   # pattern id = cache entry
+        pa.pack_new_entries(dl, sub, k, k, entry, hit, Vs, Us)   # aggregation happens once per new cache entry
         mark(5)
+        pa.lowrank_prefill_planned(dl, pt, X, off, entry, plan, Y, ws_plan)   # two launches over the plan
+        mark(6)
 
     # cold step: empty cache, every prompt misses, is routed, appended and aggregated
     step(); torch.cuda.synchronize()
@@ -124,7 +128,7 @@ def bench_prefill(args, torch, pa, si):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -139,17 +143,17 @@ def bench_prefill(args, torch, pa, si):
     if not args.no_extras:
         # the same forward under each fixed schedule, for the record (not part of the timed steps above)
         pid = entry
-        for nm, code in (("fused", 1), ("two_launch", 2)):
-            pa.set_prefill_schedule(code)
+        for nm, code in (("fused", pa.PARSE_SCHED_FUSED), ("tiles_two_launch", pa.PARSE_SCHED_TILES),
+                         ("planned_incl_plan_launch", pa.PARSE_SCHED_PLANNED)):
+            pts = pt.with_schedule(code)
             for _ in range(3):
-                pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y, ws_fwd)
+                pa.lowrank_forward(pa.PARSE_PREFILL, dl, pts, X, off, pid, Y, ws_fwd)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(20):
-                pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid, Y, ws_fwd)
+                pa.lowrank_forward(pa.PARSE_PREFILL, dl, pts, X, off, pid, Y, ws_fwd)
             e1.record(); torch.cuda.synchronize()
             sched_us[nm] = round(e0.elapsed_time(e1) / 20 * 1e3, 2)
-        pa.set_prefill_schedule(0)
         # horizontal fusion, for the record: two layers of this shape that share X, in one call vs two calls
         # (the same factors stand in for the second layer; its output and intermediate are its own)
         Y2 = torch.empty_like(Y)
@@ -193,6 +197,7 @@ def bench_prefill(args, torch, pa, si):
             bufs.append(dict(emb=torch.empty_like(emb), sub_route=torch.empty_like(sub_route), entry=torch.empty_like(entry),
                              hit=torch.empty_like(hit), sim=torch.empty_like(sim), sub=torch.empty_like(sub),
                              bucket=tuple(torch.empty_like(t) for t in bucket_out), Y=torch.empty_like(Y),
+                             plan=torch.empty_like(plan),
                              ready=torch.cuda.Event(), done=torch.cuda.Event()))
         s_ctl, s_fwd = torch.cuda.Stream(), torch.cuda.Stream()
         ws_route2 = torch.empty_like(ws_route)
@@ -205,17 +210,18 @@ def bench_prefill(args, torch, pa, si):
                     pa.route(X, off, Wr[0], k, subset_out=b["sub_route"], emb_out=b["emb"], workspace=ws_route2)
                     cache.lookup_or_route(b["emb"], 0.9, Wr, b["entry"], b["hit"], b["sim"], b["sub"])
                     pa.bucket_patterns(b["sub"], k, k, b["bucket"])
+                    pa.prefill_plan(off, b["entry"], rows, n_slots, b["plan"])
                     pa.pack_new_entries(dl, b["sub"], k, k, b["entry"], b["hit"], Vs, Us)
                     b["ready"].record(s_ctl)
                 with torch.cuda.stream(s_fwd):
                     s_fwd.wait_event(b["ready"])
-                    pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, b["entry"], b["Y"], ws_fwd)
+                    pa.lowrank_prefill_planned(dl, pt, X, off, b["entry"], b["plan"], b["Y"], ws_plan)
                     b["done"].record(s_fwd)
         torch.cuda.synchronize()
         run_pipelined(6); torch.cuda.synchronize()
         nb = max(args.steps, 10)
         tp0 = time.perf_counter(); run_pipelined(nb); torch.cuda.synchronize(); tp1 = time.perf_counter()
-        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, entry, Y, ws_fwd); torch.cuda.synchronize()
+        pa.lowrank_prefill_planned(dl, pt, X, off, entry, plan, Y, ws_plan); torch.cuda.synchronize()
         pipelined = {"batches": nb, "ms_per_batch": round((tp1 - tp0) / nb * 1e3, 4),
                      "TFLOPs": round(2.0 * rows * rS * (n + m) / ((tp1 - tp0) / nb) / 1e12, 1),
                      "same_output_as_sequential": bool(torch.equal(bufs[0]["Y"], Y) and torch.equal(bufs[1]["Y"], Y))}
@@ -239,8 +245,9 @@ def bench_prefill(args, torch, pa, si):
         "rows_us": {k_: round(v, 2) for k_, v in per.items()},
         "cache_hits": hits, "forward_us_by_schedule": sched_us, "cold_step_ms": round(cold_ms, 4),
         "rank_granular_us": rank_us, "two_batches_in_flight": pipelined,
-        # the timed steps pass a workspace, so the forward is the two gemm_tokens launches
-        "roofline": {"bound": "mfma", "kernel": "gemm_tokens<64,2,8,2> + gemm_tokens<128,2,16,1> (one forward call)",
+        # the forward of the timed steps is parse_lowrank_prefill_planned: first product on 64-token register-operand
+        # tiles (Z row-major), second product on 256 x 256 LDS-staged tiles over the plan
+        "roofline": {"bound": "mfma", "kernel": "gemm_tokens<64,2,8,2> + gemm_lds<256,256,2x4,BK32,S4> (one planned forward call)",
                      "achieved": round(achieved, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": traffic_from_profiles("prefill_config1"),

@@ -221,25 +221,34 @@ typedef struct {
   const void *Vt_shared;  /* device [n_shared*gs][n], or NULL when n_shared == 0 */
   const void *Ut_shared;  /* device [n_shared*gs][m], or NULL when n_shared == 0 */
   int32_t n_shared;
+  int32_t schedule;       /* parse_prefill_schedule for bf16 prefill; 0 = chosen by the library */
 } parse_patterns;
+
+/* How the bf16 prefill product of a call is scheduled (field `schedule` of parse_patterns; there is no process-wide
+ * setting).  PARSE_SCHED_AUTO: planned when the workspace allows it, else two-launch, else fused.
+ * PARSE_SCHED_FUSED: ONE kernel, a workgroup owns 64 token rows and keeps the r_S-wide intermediate in LDS (no
+ *   workspace needed; few workgroups on short batches).
+ * PARSE_SCHED_TILES: two launches of a tile kernel that takes factor operands straight from memory into registers;
+ *   the intermediate goes through the workspace; a tile that spans several prompts is redone per prompt.
+ * PARSE_SCHED_PLANNED: a prefill plan (parse_prefill_plan) renumbers the token rows by pattern, then two launches of
+ *   an LDS-staged tile kernel over 256- or 128-row tiles that each belong to one pattern.
+ * A forced schedule that the shapes or the workspace do not allow gives PARSE_ESHAPE / PARSE_EWORKSPACE. */
+typedef enum { PARSE_SCHED_AUTO = 0, PARSE_SCHED_FUSED = 1, PARSE_SCHED_TILES = 2, PARSE_SCHED_PLANNED = 3 } parse_prefill_schedule;
 
 typedef enum { PARSE_PREFILL = 0, PARSE_DECODE = 1 } parse_mode;
 
-size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *layer, int32_t rows,
-                                     int32_t k);
-/* How the bf16 prefill product is scheduled: 0 = chosen from the batch size (default), 1 = always the fused
- * kernel, 2 = always two launches (PARSE_EWORKSPACE from the forward call if it got no workspace).
- * Process-wide; not thread-safe against concurrent forward calls. */
-int parse_set_prefill_schedule(int32_t schedule);
+/* Workspace of parse_lowrank_forward.  P and n_patterns size the planned prefill schedule (its plan and its padded
+ * intermediate); with P == 0 or n_patterns == 0 the answer covers the other schedules only (the forward call then
+ * does not use the planned one). */
+size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *layer, int32_t rows, int32_t k,
+                                     int32_t P, int32_t n_patterns);
 /* PARSE_PREFILL  Y[t] = A_S (B_S^T x_t) for every token t of prompt p, S = pattern pattern_id[p]
  *                (Eq. 4 / Eq. 10), read from the packed factors.  bf16 layers must be PARSE_MFMA16:
  *                both products on the bf16 matrix cores with fp32 accumulation, the r_S-wide
- *                intermediate rounded to bf16.  Two schedules: ONE fused kernel that keeps the
- *                intermediate in LDS (a workgroup per 64 token rows; needs no workspace), or TWO launches
- *                of one tile kernel with the intermediate in the workspace (it stays cache-resident), which
- *                is the faster form and the one used whenever a workspace is given and n and r_S are
- *                multiples of 128.  With workspace == NULL the fused kernel is used.  f32 layers must be
- *                PARSE_ROWMAJOR (plain fp32 kernels, intermediate in the workspace).
+ *                intermediate rounded to bf16.  Schedules: see parse_prefill_schedule (patterns->schedule).
+ *                With workspace == NULL the fused kernel is used.  The planned schedule builds its plan inside the
+ *                call (one extra small launch); parse_lowrank_prefill_planned takes a ready plan instead.  f32
+ *                layers must be PARSE_ROWMAJOR (plain fp32 kernels, intermediate in the workspace).
  *                  X device [rows][n], Y device [rows][m] (layer dtype), tok_offsets device int32 [P+1],
  *                  pattern_id device int32 [P].
  * PARSE_DECODE   one token per sequence (rows == P, tok_offsets ignored, may be NULL), bf16 PARSE_MFMA16
@@ -247,11 +256,40 @@ int parse_set_prefill_schedule(int32_t schedule);
  *                once from the layer's own store (layer->Vt / layer->Ut, not the packed copies) and applies
  *                it to the sequences whose pattern holds it (Sec. 4.3, rank reuse: pattern_id is fixed
  *                at prefill).  Bandwidth-bound.
- * workspace: device, >= parse_lowrank_workspace_bytes(mode, layer, rows, k) bytes (optional for bf16 prefill). */
+ * workspace: device, >= parse_lowrank_workspace_bytes(mode, layer, rows, k, P, n_patterns) bytes (optional for
+ *            bf16 prefill). */
 int parse_lowrank_forward(int32_t mode, const parse_layer *layer, const parse_patterns *patterns,
                           const void *X, int32_t rows, const int32_t *tok_offsets,
                           const int32_t *pattern_id, int32_t P, void *Y, void *workspace,
                           size_t workspace_bytes, parse_stream stream);
+
+/* ---- prefill plan (Sec. 4.3: prompts that share a pattern are executed together) -----------------------------
+ * Renumbers the token rows of a batch so that the rows of one pattern are consecutive (prompts in arrival order)
+ * and every pattern starts on a 256-row boundary; a tile of such "virtual rows" belongs to one pattern whatever the
+ * prompt lengths are.  The plan depends only on (tok_offsets, pattern_id): one plan serves every layer of the batch.
+ *   tok_offsets device int32 [P+1], ascending, tok_offsets[0] = 0, tok_offsets[P] = rows (rows outside every prompt
+ *               are in no tile: their output rows are not written)
+ *   pattern_id  device int32 [P]; ids outside [0, n_patterns) mark prompts whose output rows become zero
+ *   plan        device, >= parse_prefill_plan_bytes(rows, P, n_patterns) bytes, 16-byte aligned, caller-owned.
+ *               int32 words: [0] virtual tiles of 256 rows, [1] virtual rows, [2] 256, [3] capacity in tiles,
+ *               [16 ..) pattern of each tile (-1 = zero rows), then (from word 16 + capacity rounded up to 16)
+ *               the actual row of each virtual row, -1 for padding.
+ * 1 <= P <= 2048, n_patterns <= 2048.  Only enqueues. */
+size_t parse_prefill_plan_bytes(int32_t rows, int32_t P, int32_t n_patterns);
+int parse_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, int32_t P, int32_t rows,
+                       int32_t n_patterns, void *plan, size_t plan_bytes, parse_stream stream);
+/* The bf16 prefill product (Eq. 10) of one layer over a ready plan: two launches, no prompt-dependent work on the
+ * host.  layer bf16 PARSE_MFMA16 with n % 64 == 0; patterns as for PARSE_PREFILL (no shared head); the plan must
+ * have been built from the same tok_offsets, pattern_id, rows, P and patterns->n_patterns (short batches run their
+ * first product on prompt-order tiles, which read the two arrays directly).
+ *   workspace  device, >= parse_lowrank_prefill_planned_workspace_bytes(layer, rows, P, k, n_patterns): the
+ *              intermediate of the padded virtual rows, in operand order. */
+size_t parse_lowrank_prefill_planned_workspace_bytes(const parse_layer *layer, int32_t rows, int32_t P, int32_t k,
+                                                     int32_t n_patterns);
+int parse_lowrank_prefill_planned(const parse_layer *layer, const parse_patterns *patterns, const void *X,
+                                  int32_t rows, const int32_t *tok_offsets, const int32_t *pattern_id, int32_t P,
+                                  const void *plan, void *Y, void *workspace, size_t workspace_bytes,
+                                  parse_stream stream);
 
 /* ---- rank-granular routing (Sec. 4.1, Eq. 4-5 as written: one expert per rank component) ----------------
  * The router maps the prompt embedding to one score per rank, R^d -> R^G with G = the stored rank (up to 8192),

@@ -17,8 +17,9 @@ What each function follows:
                           threshold and insert-on-miss are this build's reading.
   pack                    Sec. 4.4 "Expert Memory Aggregation": selected components moved
                           into one contiguous block, forward unchanged.
-  bucket                  grouping of prompts that share a subset (Sec. 4.3: patterns are
-                          shared across prompts), so one launch serves one pattern.
+  bucket / plan_rows      grouping of prompts (and of their token rows) that share a subset
+                          (Sec. 4.3: patterns are shared across prompts), so one launch or
+                          tile serves one pattern.
   decode                  Sec. 4.3 "Rank Reuse for Decoding": the prefill subset is fixed
                           for every later step; same product with one row per sequence.
   soft_mask / router_grad Sec. 4.2 Eq. 6-9: reconstruction loss against the dense output,
@@ -273,6 +274,28 @@ def bucket(subsets):
         off[pid[p] + 1] += 1
     off = np.cumsum(off).astype(np.int32)
     return pid, perm, off, len(seen), np.asarray(rep, np.int32)
+
+
+def plan_rows(tok_offsets, pattern_id, n_patterns: int, tile: int = 256):
+    """Execution grouping at row granularity (Sec. 4.3: prompts that share a pattern run together): the token rows of
+    all prompts with pattern 0 (arrival order), padded with -1 to a multiple of `tile`, then pattern 1, ... and last the
+    prompts whose id is outside [0, n_patterns).  -> (rowmap [n_tiles * tile], tile_pattern [n_tiles] with -1 for the
+    last bucket)."""
+    tok_offsets = np.asarray(tok_offsets, dtype=np.int64)
+    pattern_id = np.asarray(pattern_id, dtype=np.int64)
+    rowmap, tile_pat = [], []
+    for b in list(range(n_patterns)) + [-1]:
+        rows = []
+        for p in range(len(pattern_id)):
+            pid = int(pattern_id[p]) if 0 <= pattern_id[p] < n_patterns else -1
+            if pid == b:
+                rows.extend(range(int(tok_offsets[p]), int(tok_offsets[p + 1])))
+        if not rows:
+            continue
+        pad = (-len(rows)) % tile
+        rowmap.extend(rows + [-1] * pad)
+        tile_pat.extend([b] * ((len(rows) + pad) // tile))
+    return np.asarray(rowmap, np.int32), np.asarray(tile_pat, np.int32)
 
 
 # ------------------------------------------------------------------ error metric

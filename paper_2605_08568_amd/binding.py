@@ -10,6 +10,7 @@ import torch
 PARSE_F32, PARSE_BF16 = 0, 1
 PARSE_ROWMAJOR, PARSE_MFMA16 = 0, 1
 PARSE_PREFILL, PARSE_DECODE = 0, 1
+PARSE_SCHED_AUTO, PARSE_SCHED_FUSED, PARSE_SCHED_TILES, PARSE_SCHED_PLANNED = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libparse.so")
@@ -32,7 +33,8 @@ class _Layer(C.Structure):
 class _Patterns(C.Structure):
     _fields_ = [("Vt_S", C.c_void_p), ("Ut_S", C.c_void_p), ("subsets", C.c_void_p),
                 ("subset_stride", C.c_int32), ("n_patterns", C.c_int32), ("k", C.c_int32),
-                ("Vt_shared", C.c_void_p), ("Ut_shared", C.c_void_p), ("n_shared", C.c_int32)]
+                ("Vt_shared", C.c_void_p), ("Ut_shared", C.c_void_p), ("n_shared", C.c_int32),
+                ("schedule", C.c_int32)]
 
 
 _lib = None
@@ -91,8 +93,14 @@ def lib():
     L.parse_pack_new_entries.restype = C.c_int
     L.parse_pack_new_entries.argtypes = [C.POINTER(_Layer), vp, i32, i32, i32, vp, vp, i32, vp, vp, vp]
     L.parse_lowrank_workspace_bytes.restype = sz
-    L.parse_lowrank_workspace_bytes.argtypes = [i32, C.POINTER(_Layer), i32, i32]
-    L.parse_set_prefill_schedule.restype = C.c_int; L.parse_set_prefill_schedule.argtypes = [i32]
+    L.parse_lowrank_workspace_bytes.argtypes = [i32, C.POINTER(_Layer), i32, i32, i32, i32]
+    L.parse_prefill_plan_bytes.restype = sz; L.parse_prefill_plan_bytes.argtypes = [i32, i32, i32]
+    L.parse_prefill_plan.restype = C.c_int; L.parse_prefill_plan.argtypes = [vp, vp, i32, i32, i32, vp, sz, vp]
+    L.parse_lowrank_prefill_planned_workspace_bytes.restype = sz
+    L.parse_lowrank_prefill_planned_workspace_bytes.argtypes = [C.POINTER(_Layer), i32, i32, i32, i32]
+    L.parse_lowrank_prefill_planned.restype = C.c_int
+    L.parse_lowrank_prefill_planned.argtypes = [C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, i32, vp, vp, vp,
+                                                sz, vp]
     L.parse_lowrank_decode_multi_workspace_bytes.restype = sz
     L.parse_lowrank_decode_multi_workspace_bytes.argtypes = [C.POINTER(_Layer), i32]
     L.parse_lowrank_decode_multi.restype = C.c_int
@@ -172,10 +180,16 @@ class Patterns:
     """parse_patterns."""
 
     def __init__(self, k: int, n_patterns: int, Vt_S=None, Ut_S=None, subsets=None, subset_stride=None,
-                 Vt_shared=None, Ut_shared=None, n_shared: int = 0):
+                 Vt_shared=None, Ut_shared=None, n_shared: int = 0, schedule: int = PARSE_SCHED_AUTO):
         self.k, self.n_patterns, self.Vt_S, self.Ut_S, self.subsets = k, n_patterns, Vt_S, Ut_S, subsets
         self.subset_stride = k if subset_stride is None else subset_stride
         self.Vt_shared, self.Ut_shared, self.n_shared = Vt_shared, Ut_shared, n_shared
+        self.schedule = schedule
+
+    def with_schedule(self, schedule: int) -> "Patterns":
+        """The same patterns with another prefill schedule (parse_prefill_schedule)."""
+        return Patterns(self.k, self.n_patterns, self.Vt_S, self.Ut_S, self.subsets, self.subset_stride,
+                        self.Vt_shared, self.Ut_shared, self.n_shared, schedule)
 
     def c(self) -> _Patterns:
         return _Patterns(None if self.Vt_S is None else self.Vt_S.data_ptr(),
@@ -183,7 +197,8 @@ class Patterns:
                          None if self.subsets is None else self.subsets.data_ptr(),
                          self.subset_stride, self.n_patterns, self.k,
                          None if self.Vt_shared is None else self.Vt_shared.data_ptr(),
-                         None if self.Ut_shared is None else self.Ut_shared.data_ptr(), self.n_shared)
+                         None if self.Ut_shared is None else self.Ut_shared.data_ptr(), self.n_shared,
+                         self.schedule)
 
 
 def check_offsets(tok_offsets_host: np.ndarray, rows: int) -> int:
@@ -340,14 +355,45 @@ def pack_new_entries(layer: Layer, subset, subset_stride, k, entry, hit, Vt_S, U
     return Vt_S, Ut_S
 
 
-def lowrank_workspace_bytes(mode: int, layer: Layer, rows: int, k: int) -> int:
+def lowrank_workspace_bytes(mode: int, layer: Layer, rows: int, k: int, P: int = 0, n_patterns: int = 0) -> int:
+    """parse_lowrank_workspace_bytes; P and n_patterns size the planned prefill schedule (0: the other schedules only)."""
     cl = layer.c()
-    return lib().parse_lowrank_workspace_bytes(mode, C.byref(cl), rows, k)
+    return lib().parse_lowrank_workspace_bytes(mode, C.byref(cl), rows, k, P, n_patterns)
 
 
-def set_prefill_schedule(schedule: int):
-    """parse_set_prefill_schedule: 0 = by size, 1 = fused kernel, 2 = two launches."""
-    _check(lib().parse_set_prefill_schedule(schedule), "parse_set_prefill_schedule")
+def prefill_plan_bytes(rows: int, P: int, n_patterns: int) -> int:
+    return int(lib().parse_prefill_plan_bytes(rows, P, n_patterns))
+
+
+def prefill_plan(tok_offsets, pattern_id, rows: int, n_patterns: int, plan=None):
+    """parse_prefill_plan -> the plan buffer (uint8 device tensor)."""
+    P = pattern_id.numel()
+    if plan is None:
+        plan = torch.empty(prefill_plan_bytes(rows, P, n_patterns), dtype=torch.uint8, device=pattern_id.device)
+    _check(lib().parse_prefill_plan(_ptr(tok_offsets), _ptr(pattern_id), P, rows, n_patterns, _ptr(plan), plan.numel(),
+                                    _stream()), "parse_prefill_plan")
+    return plan
+
+
+def lowrank_prefill_planned_workspace_bytes(layer: Layer, rows: int, P: int, k: int, n_patterns: int) -> int:
+    cl = layer.c()
+    return int(lib().parse_lowrank_prefill_planned_workspace_bytes(C.byref(cl), rows, P, k, n_patterns))
+
+
+def lowrank_prefill_planned(layer: Layer, patterns: Patterns, X, tok_offsets, pattern_id, plan, Y=None, workspace=None):
+    """parse_lowrank_prefill_planned.  Returns Y [rows][m]."""
+    rows, P = X.shape[0], pattern_id.numel()
+    if Y is None:
+        Y = torch.empty((rows, layer.m), dtype=X.dtype, device=X.device)
+    if workspace is None:
+        need = lowrank_prefill_planned_workspace_bytes(layer, rows, P, patterns.k, patterns.n_patterns)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    cl, cp = layer.c(), patterns.c()
+    _check(lib().parse_lowrank_prefill_planned(C.byref(cl), C.byref(cp), _ptr(X), rows, _ptr(tok_offsets), _ptr(pattern_id), P,
+                                               _ptr(plan), _ptr(Y),
+                                               _ptr(workspace), workspace.numel(), _stream()),
+           "parse_lowrank_prefill_planned")
+    return Y
 
 
 def lowrank_forward(mode: int, layer: Layer, patterns: Patterns, X, tok_offsets, pattern_id, Y=None,
@@ -357,7 +403,7 @@ def lowrank_forward(mode: int, layer: Layer, patterns: Patterns, X, tok_offsets,
     P = pattern_id.numel()
     if Y is None:
         Y = torch.empty((rows, layer.m), dtype=X.dtype, device=X.device)
-    need = lowrank_workspace_bytes(mode, layer, rows, patterns.k)
+    need = lowrank_workspace_bytes(mode, layer, rows, patterns.k, P, patterns.n_patterns)
     if workspace is None and need > 0 and not no_workspace:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     cl, cp = layer.c(), patterns.c()

@@ -10,7 +10,15 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
 size_t prefill_split_workspace_bytes(int rows, int rS);
 bool prefill_split_supported(int n, int rS);
 int forward_prefill_split_multi_bf16(const PfArgs *p, int n_layers, uint16_t *const *Z, int avg_prompt_rows, hipStream_t s);
-void set_prefill_schedule(int v);
+size_t prefill_plan_bytes(int rows, int P, int n_patterns);
+int prefill_plan_capacity(int rows, int P, int n_patterns);
+bool prefill_plan_supported(int P, int n_patterns);
+int build_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, int P, int rows, int n_patterns,
+                       int32_t *plan, hipStream_t s);
+size_t prefill_planned_z_bytes(int cap_tiles, int rS);
+bool prefill_planned_supported(int n, int m, int rS);
+int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, uint16_t *Z, int avg_prompt_rows,
+                                 hipStream_t s);
 size_t prefill_lds_bytes(int BM, int rS);
 size_t decode_workspace_bytes(const parse_layer *L);
 int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *pts, int n_layers, const uint16_t *x,
@@ -23,17 +31,52 @@ using namespace parse;
 
 extern "C" {
 
-size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *L, int32_t rows, int32_t k) {
+// workspace of the planned schedule inside parse_lowrank_forward: the intermediate, then the plan
+static size_t planned_total_bytes(const parse_layer *L, int rows, int P, int k, int n_patterns) {
+  const int rS = k * (L->R / L->G);
+  return prefill_planned_z_bytes(prefill_plan_capacity(rows, P, n_patterns), rS) + prefill_plan_bytes(rows, P, n_patterns);
+}
+
+size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *L, int32_t rows, int32_t k, int32_t P,
+                                     int32_t n_patterns) {
   if (!L || rows <= 0 || k <= 0 || L->G <= 0 || L->R <= 0) return 0;
   if (mode == PARSE_DECODE) return decode_workspace_bytes(L);
   if (L->dtype == PARSE_F32) return round_up((size_t)rows * k * (L->R / L->G) * sizeof(float), 256);
-  return prefill_split_workspace_bytes(rows, k * (L->R / L->G));
+  const int rS = k * (L->R / L->G);
+  size_t need = prefill_split_workspace_bytes(rows, rS);
+  if (P > 0 && n_patterns > 0 && P <= rows && prefill_plan_supported(P, n_patterns) &&
+      prefill_planned_supported(L->n, L->m, rS)) {
+    const size_t planned = planned_total_bytes(L, rows, P, k, n_patterns);
+    if (planned > need) need = planned;
+  }
+  return need;
 }
 
-int parse_set_prefill_schedule(int32_t schedule) {
-  if (schedule < 0 || schedule > 2) return PARSE_EINVAL;
-  set_prefill_schedule(schedule);
-  return PARSE_OK;
+size_t parse_lowrank_prefill_planned_workspace_bytes(const parse_layer *L, int32_t rows, int32_t P, int32_t k,
+                                                     int32_t n_patterns) {
+  if (!L || rows <= 0 || k <= 0 || P <= 0 || n_patterns <= 0 || L->G <= 0 || L->R <= 0) return 0;
+  return prefill_planned_z_bytes(prefill_plan_capacity(rows, P, n_patterns), k * (L->R / L->G));
+}
+
+int parse_lowrank_prefill_planned(const parse_layer *L, const parse_patterns *pt, const void *X, int32_t rows,
+                                  const int32_t *tok_offsets, const int32_t *pattern_id, int32_t P, const void *plan,
+                                  void *Y, void *workspace, size_t workspace_bytes, parse_stream stream) {
+  int st = check_layer(L);
+  if (st != PARSE_OK) return st;
+  if (!pt || !X || !Y || !plan || !tok_offsets || !pattern_id || !pt->Vt_S || !pt->Ut_S) return PARSE_EINVAL;
+  if (rows <= 0 || P <= 0 || pt->n_patterns <= 0 || pt->k <= 0) return PARSE_EINVAL;
+  if (L->dtype != PARSE_BF16 || L->layout != PARSE_MFMA16) return PARSE_ELAYOUT;
+  if (pt->n_shared != 0) return PARSE_ELAYOUT;
+  const int rS = pt->k * (L->R / L->G);
+  if (pt->k > L->G || P > rows || !prefill_plan_supported(P, pt->n_patterns) ||
+      !prefill_planned_supported(L->n, L->m, rS)) return PARSE_ESHAPE;
+  if (!aligned16(X) || !aligned16(Y) || !aligned16(plan) || !aligned16(pt->Vt_S) || !aligned16(pt->Ut_S)) return PARSE_EALIGN;
+  const int cap = prefill_plan_capacity(rows, P, pt->n_patterns);
+  if (!workspace || workspace_bytes < prefill_planned_z_bytes(cap, rS)) return PARSE_EWORKSPACE;
+  if (!aligned16(workspace)) return PARSE_EALIGN;
+  PfArgs a{(const uint16_t *)X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, (uint16_t *)Y, tok_offsets, pattern_id,
+           pt->n_patterns, rows, L->n, L->m, rS, P};
+  return forward_prefill_planned_bf16(a, (const int32_t *)plan, cap, (uint16_t *)workspace, rows / P, (hipStream_t)stream);
 }
 
 int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patterns *pt, const void *X, int32_t rows,
@@ -47,7 +90,7 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patter
   if (pt->k > L->G || P > rows) return PARSE_ESHAPE;
   if (!aligned16(X) || !aligned16(Y)) return PARSE_EALIGN;
   if (mode == PARSE_DECODE && (L->dtype != PARSE_BF16 || L->layout != PARSE_MFMA16)) return PARSE_ELAYOUT;
-  const size_t need = parse_lowrank_workspace_bytes(mode, L, rows, pt->k);
+  const size_t need = parse_lowrank_workspace_bytes(mode, L, rows, pt->k, 0, 0);   // the smallest workspace any schedule takes
   // bf16 prefill may run without a workspace (fused kernel only); every other mode needs the queried size
   const bool optional_ws = mode == PARSE_PREFILL && L->dtype == PARSE_BF16 && workspace == nullptr;
   if (!optional_ws && need > 0 && (!workspace || workspace_bytes < need)) return PARSE_EWORKSPACE;

@@ -355,8 +355,16 @@ size_t prefill_split_workspace_bytes(int rows, int rS);
 bool prefill_split_supported(int n, int rS);
 int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s);
 
-static int g_prefill_schedule = 0;   // 0 = choose by size, 1 = fused kernel, 2 = two launches
-void set_prefill_schedule(int v) { g_prefill_schedule = v; }
+// planned form (plan.hip, prefill_lds_bf16.hip)
+size_t prefill_plan_bytes(int rows, int P, int n_patterns);
+int prefill_plan_capacity(int rows, int P, int n_patterns);
+bool prefill_plan_supported(int P, int n_patterns);
+int build_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, int P, int rows, int n_patterns,
+                       int32_t *plan, hipStream_t s);
+size_t prefill_planned_z_bytes(int cap_tiles, int rS);
+bool prefill_planned_supported(int n, int m, int rS);
+int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, uint16_t *Z, int avg_prompt_rows,
+                                 hipStream_t s);
 
 int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *X, int rows,
                          const int32_t *tok_offsets, const int32_t *pattern_id, int P, uint16_t *Y, void *workspace,
@@ -364,18 +372,33 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
   const int gs = L->R / L->G, rS = pt->k * gs;
   PfArgs a{X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, Y, tok_offsets, pattern_id,
            pt->n_patterns, rows, L->n, L->m, rS, P};
-  if (pt->n_shared > 0) {   // shared head: operands from two blocks, built into the two-launch kernels only
+  if (pt->n_shared > 0) {   // shared head: operands from two blocks, built into the two-launch tile kernels only
     a.Vt_sh = (const uint16_t *)pt->Vt_shared;
     a.Ut_sh = (const uint16_t *)pt->Ut_shared;
     a.sh_ranks = pt->n_shared * gs;
   }
-  // The two-launch form is the faster one whenever its workspace is there: at small batches the fused kernel
-  // (rows/64 workgroups) cannot fill the chip, at large ones the two-launch tiles move fewer bytes per flop.
+  const int schedule = pt->schedule;
+  if (schedule < PARSE_SCHED_AUTO || schedule > PARSE_SCHED_PLANNED) return PARSE_EINVAL;
+  // planned: plan + two launches of the LDS-staged tile kernel; workspace = intermediate of the padded rows, then the plan
+  const bool planned_shapes = a.sh_ranks == 0 && prefill_plan_supported(P, pt->n_patterns) &&
+                              prefill_planned_supported(L->n, L->m, rS);
+  const int cap = planned_shapes ? prefill_plan_capacity(rows, P, pt->n_patterns) : 0;
+  const size_t zb = planned_shapes ? prefill_planned_z_bytes(cap, rS) : 0;
+  const bool can_plan = planned_shapes && workspace != nullptr &&
+                        workspace_bytes >= zb + prefill_plan_bytes(rows, P, pt->n_patterns);
+  if (schedule == PARSE_SCHED_PLANNED && !can_plan) return planned_shapes ? PARSE_EWORKSPACE : PARSE_ESHAPE;
+  if (can_plan && (schedule == PARSE_SCHED_PLANNED || schedule == PARSE_SCHED_AUTO)) {
+    int32_t *plan = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(workspace) + zb);
+    int st = build_prefill_plan(tok_offsets, pattern_id, P, rows, pt->n_patterns, plan, s);
+    if (st != PARSE_OK) return st;
+    return forward_prefill_planned_bf16(a, plan, cap, (uint16_t *)workspace, rows / (P > 0 ? P : 1), s);
+  }
+  // two launches of the register-operand tile kernel
   const bool can_split = workspace != nullptr && workspace_bytes >= prefill_split_workspace_bytes(rows, rS) &&
                          prefill_split_supported(L->n, rS);
   bool split = can_split;
-  if (g_prefill_schedule == 1) split = false;
-  if (g_prefill_schedule == 2 || a.sh_ranks > 0) {
+  if (schedule == PARSE_SCHED_FUSED) split = false;
+  if (schedule == PARSE_SCHED_TILES || a.sh_ranks > 0) {
     if (!can_split) return prefill_split_supported(L->n, rS) ? PARSE_EWORKSPACE : PARSE_ESHAPE;
     split = true;
   }

@@ -1,0 +1,314 @@
+// a6, planned form of the bf16 prefill product (Sec. 4.4, Eq. 10):  launch 1  Z = X Vt_S^T,  launch 2  Y = Z Ut_S,
+// both with ONE tile kernel, `gemm_lds`, over the virtual rows of a prefill plan (plan.hip): a tile of token rows
+// belongs to one pattern, so a workgroup runs one reduction with one factor block, whatever the prompt lengths.
+//
+// Data path.  Both operands of a tile are staged in LDS by loads that write LDS directly (no register round trip,
+// 1 KiB per wavefront instruction), STAGES reduction slices of BK deep; the matrix-core operands are then 16-byte
+// LDS reads.  Factor operands are stored in operand order in memory (PARSE_MFMA16), so a 1 KiB load lands as one
+// ready operand and is read back linearly (conflict-free).  The intermediate Z is written by launch 1 in the same
+// operand order (token block x reduction block), so launch 2 stages it exactly like a factor.  Only X is row-major:
+// its rows are loaded 16 bytes per lane, whole cache lines per row, and the 16-byte chunks of a row are XOR-swizzled
+// on the way in (the swizzle is applied to the global address, the LDS write is linear) so that the operand reads --
+// 32 rows x one chunk -- spread over all banks.
+// Pipeline per reduction slice: ... [LDS reads of step s+1 | matrix instructions of step s] ...; in the last step of
+// a slice the wavefront waits for its own loads of the next slice, meets the others at a barrier (so everybody's loads
+// have landed and everybody is done reading the current slice), requests the slice STAGES ahead into the buffer just
+// freed and reads the next slice's first operands -- all of that while its matrix instructions of the last step are
+// still to be issued, so the matrix pipe does not drain at the barrier.
+// Output: the accumulator of the 32x32x16 instruction gives a lane 4 consecutive factor rows (output columns) of one
+// token in each of four 8-row bands; one 32-lane swap pairs the bands up to 8 consecutive columns = 16 bytes, which is
+// one piece of a Z operand (launch 1: stored linearly, 1 KiB per instruction) or a 16-byte store into the token's
+// row of Y (launch 2).
+#include "prefill_common.hpp"
+
+namespace parse {
+
+#define PARSE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define PARSE_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+
+template <int N> __device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit count");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// barrier without the fences of __syncthreads(): those would wait for ALL outstanding loads, also the slices
+// requested ahead.  The explicit vmcnt wait before it covers exactly the slice that is about to be read.
+__device__ __forceinline__ void wg_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+struct LgArgs {
+  const uint16_t *Tk;      // MODE 0: X row-major [rows][K];  MODE 1: Z in operand order [(virtual rows)/32][K/16][1 KiB]
+  const uint16_t *F;       // factor operands of all patterns
+  uint16_t *O;             // MODE 0: Z (operand order);  MODE 1: Y row-major [rows][M]
+  size_t pattern_stride;   // elements of F per pattern
+  int K, M;                // reduction length, factor rows (= output columns)
+  const int32_t *plan;     // header | tile patterns | row map (plan.hip)
+  int cap;                 // plan capacity in 256-row tiles (fixes where the row map starts)
+  int ntn, gm, ngroups;    // column tiles, token tiles per locality group, groups
+};
+
+// FORD: factor order, 0 = right factor (operand (rb, kb) at rb*(K/16)+kb), 1 = left factor (operand (kb, cb) at kb*(M/32)+cb).
+// TROW: token operand 1 = row-major rows looked up through the plan's row map (X, or a row-major intermediate),
+//       0 = operand order over the plan's virtual rows.   OROW: output 1 = row-major through the row map, 0 = operand order.
+// First product: <FORD 0, TROW 1, OROW 0>; second product: <FORD 1, TROW 0, OROW 1>, or <1, 1, 1> on a row-major Z.
+template <int BM, int BN, int WM, int WN, int BK, int STAGES, int FORD, int TROW, int OROW>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
+  constexpr int NW = WM * WN;
+  constexpr int KK = BK / 16;                 // matrix-instruction steps per staged slice
+  constexpr int TB = BM / WM / 32, FB = BN / WN / 32;
+  constexpr int F_BYTES = BN * BK * 2, T_BYTES = BM * BK * 2, STAGE_BYTES = F_BYTES + T_BYTES;
+  constexpr int NI_F = F_BYTES / 1024, NI_T = T_BYTES / 1024;   // 1 KiB load instructions per slice
+  static_assert(NI_F % NW == 0 && NI_T % NW == 0, "the loads of a slice divide evenly over the wavefronts");
+  static_assert(KK == 2 || KK == 4, "register double-buffering assumes an even number of steps");
+  static_assert(256 % BM == 0, "token tiles subdivide the plan's 256-row tiles");
+  constexpr int LF = NI_F / NW, LT = NI_T / NW, L = LF + LT;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int j = lane & 31, q = lane >> 5;
+
+  // tile of this workgroup: consecutive ids share a die (and its L2); within a locality group the token tile runs fastest
+  // The grid is sized for the plan's capacity; the real tile count comes from the plan.  Workgroups past it leave at
+  // once, the others are renumbered over the REAL count so that every die gets its share.
+  const int per = a.gm * a.ntn;
+  const int vrows = a.plan[1];
+  const int n_real = ((vrows + BM - 1) / BM + a.gm - 1) / a.gm * per;
+  if ((int)blockIdx.x >= n_real) return;
+  const int tile = xcd_tile(blockIdx.x, n_real);
+  const int g = tile / per, r = tile % per;
+  const int tm = g * a.gm + r % a.gm, tn = r / a.gm;
+  const int K = a.K, M = a.M;
+  const int nk = K / BK;
+  if (tm * BM >= vrows) return;                // the last locality group may be partial
+  const int32_t *tile_pat = a.plan + 16;
+  const int32_t *rowmap = a.plan + 16 + (a.cap + 15) / 16 * 16;
+  const int pat = tile_pat[tm * BM / 256];
+  if (pat < 0) {
+    // prompts without a valid pattern: the first product has nothing to do, the second one writes zero rows
+    if (OROW == 1 && FORD == 1) {
+      for (int rr = wave; rr < BM; rr += NW) {
+        const int orow = rowmap[tm * BM + rr];
+        if (orow < 0) continue;
+        for (int c = lane * 8; c < BN; c += 512) {
+          const int col = tn * BN + c;
+          if (col < M) *reinterpret_cast<u32x4 *>(a.O + (size_t)orow * M + col) = u32x4{0, 0, 0, 0};
+        }
+      }
+    }
+    return;
+  }
+  const uint16_t *Fp = a.F + (size_t)pat * a.pattern_stride;
+
+  // ---- per-lane global sources of this wavefront's load instructions; they advance by a constant per slice ----
+  const char *fsrc[LF];
+  int fdst[LF];
+#pragma unroll
+  for (int i = 0; i < LF; ++i) {
+    const int ins = wave + i * NW;             // instruction id within the factor part, LDS order [fb][kk]
+    const int fb = ins / KK, kk = ins % KK;
+    const int gb = min(tn * (BN / 32) + fb, M / 32 - 1);   // blocks past the end re-read the last one (never stored)
+    if (FORD == 0) fsrc[i] = (const char *)Fp + ((size_t)gb * (K / 16) + kk) * 1024 + lane * 16;
+    else fsrc[i] = (const char *)Fp + ((size_t)kk * (M / 32) + gb) * 1024 + lane * 16;
+    fdst[i] = ins * 1024;
+  }
+  const size_t fstep = FORD == 0 ? (size_t)KK * 1024 : (size_t)KK * (M / 32) * 1024;
+  const char *tsrc[LT];
+  int tdst[LT];
+  constexpr int CPR = BK * 2 / 16;             // 16-byte chunks per staged X row
+#pragma unroll
+  for (int i = 0; i < LT; ++i) {
+    const int ins = wave + i * NW;
+    if (TROW == 0) {
+      const int tb = ins / KK, kk = ins % KK;
+      tsrc[i] = (const char *)a.Tk + ((size_t)(tm * (BM / 32) + tb) * (K / 16) + kk) * 1024 + lane * 16;
+    } else {
+      constexpr int RPI = 1024 / (BK * 2);     // rows per instruction
+      const int rr = ins * RPI + lane / CPR, cp = lane % CPR;   // LDS position (row, chunk slot)
+      const int sw = CPR == 4 ? ((rr >> 2) & 3) : ((rr >> 1) & 7);
+      const int c = cp ^ sw;                                    // chunk of the row that is stored in that slot
+      int row = rowmap[tm * BM + rr];
+      row = row < 0 ? 0 : row;                 // padding rows read row 0; their results are never stored to Y
+      tsrc[i] = (const char *)a.Tk + (size_t)row * K * 2 + c * 16;
+    }
+    tdst[i] = F_BYTES + ins * 1024;
+  }
+  const size_t tstep = TROW == 0 ? (size_t)KK * 1024 : (size_t)BK * 2;
+
+  auto issue = [&](int stage_buf) {
+    char *base = smem + stage_buf * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < LF; ++i) {
+      __builtin_amdgcn_global_load_lds(PARSE_GLB_PTR(fsrc[i]), PARSE_LDS_PTR(base + fdst[i]), 16, 0, 0);
+      fsrc[i] += fstep;
+    }
+#pragma unroll
+    for (int i = 0; i < LT; ++i) {
+      __builtin_amdgcn_global_load_lds(PARSE_GLB_PTR(tsrc[i]), PARSE_LDS_PTR(base + tdst[i]), 16, 0, 0);
+      tsrc[i] += tstep;
+    }
+  };
+
+  // ---- LDS operand addresses (relative to the slice's buffer) ----
+  int foff[FB], toff[TB];
+#pragma unroll
+  for (int i = 0; i < FB; ++i) foff[i] = ((wn * FB + i) * KK) * 1024 + lane * 16;
+#pragma unroll
+  for (int t = 0; t < TB; ++t) {
+    if (TROW == 0) toff[t] = F_BYTES + ((wm * TB + t) * KK) * 1024 + lane * 16;
+    else toff[t] = F_BYTES + (wm * TB * 32 + t * 32 + j) * (BK * 2);
+  }
+  auto tchunk = [&](int t, int kk) -> int {    // byte offset of this lane's 16 bytes of token operand (t, kk)
+    if (TROW == 0) return toff[t] + kk * 1024;
+    const int rr = wm * TB * 32 + t * 32 + j;
+    const int sw = CPR == 4 ? ((rr >> 2) & 3) : ((rr >> 1) & 7);
+    return toff[t] + (((kk * 2 + q) ^ sw) * 16);
+  };
+
+  f32x16 acc[TB][FB];
+#pragma unroll
+  for (int t = 0; t < TB; ++t)
+#pragma unroll
+    for (int i = 0; i < FB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
+
+  u32x4 fr[2][FB], tr[2][TB];
+  auto read_ops = [&](int buf, int stage_buf, int kk) {
+    const char *base = smem + stage_buf * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < FB; ++i) fr[buf][i] = *reinterpret_cast<const u32x4 *>(base + foff[i] + kk * 1024);
+#pragma unroll
+    for (int t = 0; t < TB; ++t) tr[buf][t] = *reinterpret_cast<const u32x4 *>(base + tchunk(t, kk));
+  };
+
+  // prologue: STAGES-1 slices requested, the first one awaited, one more requested
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < nk) issue(s);
+  if (nk >= STAGES - 1) wait_vm<(STAGES - 2) * L>(); else wait_vm<0>();
+  wg_barrier();
+  if (STAGES - 1 < nk) issue((STAGES - 1) % STAGES);
+  read_ops(0, 0, 0);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int sb = kt % STAGES;
+#pragma unroll
+    for (int s = 0; s < KK; ++s) {
+      const int cur = s & 1;
+      if (s < KK - 1) {
+        read_ops(cur ^ 1, sb, s + 1);
+      } else if (kt + 1 < nk) {
+        // hand-over: slice kt+1 must have landed for every wavefront; slice kt's buffer is free after the barrier
+        const int later = min(kt + STAGES - 1, nk - 1) - (kt + 1);   // slices requested after kt+1
+        if (later >= STAGES - 2) wait_vm<(STAGES - 2) * L>();
+        else if (STAGES > 3 && later == 1) wait_vm<L>();
+        else wait_vm<0>();
+        wg_barrier();
+        if (kt + STAGES < nk) issue(sb);
+        read_ops(cur ^ 1, (kt + 1) % STAGES, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < FB; ++i)
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+          acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fr[cur][i]), as_bf16x8(tr[cur][t]), acc[t][i], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // ---- output: lane (j, q) of acc[t][i] holds token t*32+j, factor rows i*32 + 8*band + 4*q + (0..3) ----
+#pragma unroll
+  for (int t = 0; t < TB; ++t) {
+    const int vrow = tm * BM + (wm * TB + t) * 32 + j;
+    int orow = -1;
+    if (OROW == 1) orow = rowmap[vrow];
+#pragma unroll
+    for (int i = 0; i < FB; ++i) {
+      const int gb = tn * (BN / 32) + wn * FB + i;     // 32-row factor block of the whole matrix
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const uint32_t p0x = cvt_pk_bf16(acc[t][i][(2 * h) * 4 + 0], acc[t][i][(2 * h) * 4 + 1]);
+        const uint32_t p0y = cvt_pk_bf16(acc[t][i][(2 * h) * 4 + 2], acc[t][i][(2 * h) * 4 + 3]);
+        const uint32_t p1x = cvt_pk_bf16(acc[t][i][(2 * h + 1) * 4 + 0], acc[t][i][(2 * h + 1) * 4 + 1]);
+        const uint32_t p1y = cvt_pk_bf16(acc[t][i][(2 * h + 1) * 4 + 2], acc[t][i][(2 * h + 1) * 4 + 3]);
+        // the upper 32 lanes of band 2h are exchanged with the lower 32 lanes of band 2h+1: afterwards lane (j, q)
+        // holds the 8 consecutive factor rows gb*32 + 16h + 8q + (0..7) of its token
+        const u32x2 sx = __builtin_amdgcn_permlane32_swap(p0x, p1x, false, false);
+        const u32x2 sy = __builtin_amdgcn_permlane32_swap(p0y, p1y, false, false);
+        const u32x4 w = {sx[0], sy[0], sx[1], sy[1]};
+        if (gb < M / 32) {
+          if (OROW == 0) {   // Z operand (token block, reduction block gb*2 + h), lane's piece at lane*16
+            const int tbg = tm * (BM / 32) + wm * TB + t;
+            *reinterpret_cast<u32x4 *>((char *)a.O + ((size_t)tbg * (M / 16) + gb * 2 + h) * 1024 + lane * 16) = w;
+          } else if (orow >= 0) {
+            *reinterpret_cast<u32x4 *>(a.O + (size_t)orow * M + gb * 32 + h * 16 + q * 8) = w;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int STAGES, int FORD, int TROW, int OROW>
+static int launch_gemm_lds(LgArgs a, int avg_tiles_per_pattern, hipStream_t s) {
+  constexpr int smem = STAGES * (BM + BN) * BK * 2;
+  auto kern = gemm_lds<BM, BN, WM, WN, BK, STAGES, FORD, TROW, OROW>;
+  static bool attr_done[64] = {false};
+  int dev = 0;
+  PARSE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return PARSE_EINVAL;
+  if (!attr_done[dev]) {
+    PARSE_HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+    attr_done[dev] = true;
+  }
+  const int ntm = a.cap * (256 / BM);          // token tiles the plan can hold (the kernel exits past the real count)
+  a.ntn = (a.M + BN - 1) / BN;
+  int gm = avg_tiles_per_pattern * (256 / BM);
+  a.gm = gm < 1 ? 1 : (gm > 8 ? 8 : gm);
+  a.ngroups = (ntm + a.gm - 1) / a.gm;
+  hipLaunchKernelGGL(kern, dim3(a.ngroups * a.gm * a.ntn), dim3(WM * WN * 64), smem, s, a);
+  PARSE_LAUNCH_CHECK();
+  return PARSE_OK;
+}
+
+// Z workspace of the planned form: the plan's capacity in virtual rows x rS bf16 (operand order)
+bool prefill_split_supported(int n, int rS);
+size_t prefill_planned_z_bytes(int cap_tiles, int rS) { return round_up((size_t)cap_tiles * 256 * rS * sizeof(uint16_t), 256); }
+
+bool prefill_planned_supported(int n, int m, int rS) { return n % 64 == 0 && rS % 32 == 0 && m % 32 == 0 && n >= 64 && rS >= 32; }
+
+int forward_prefill_split_first_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s);
+
+// X [rows][n] row-major, plan built for (tok_offsets, pattern ids of these patterns), Z workspace, Y [rows][m].
+// Short batches (too few 256-row tiles of the first product to occupy the chip) run the first product with the
+// register-operand tile kernel on 64-token tiles, which leaves Z row-major; the second product then looks its token
+// rows up through the plan's row map like the first product does with X.
+int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, uint16_t *Z, int avg_prompt_rows,
+                                 hipStream_t s) {
+  LgArgs g1{p.X, p.Vt_S, Z, (size_t)p.rS * p.n, p.n, p.rS, plan, cap, 0, 0, 0};
+  LgArgs g2{Z, p.Ut_S, p.Y, (size_t)p.rS * p.m, p.rS, p.m, plan, cap, 0, 0, 0};
+  const long long tiles256 = (long long)((p.rows + 255) / 256);
+  const int per_pattern = avg_prompt_rows / 256;
+  // 256 x 256 tiles halve the bytes a compute unit has to take in per flop; they are used when they still give the
+  // chip enough workgroups
+  const bool big1 = tiles256 * ((p.rS + 255) / 256) >= 192;
+  const bool big2 = tiles256 * ((p.m + 255) / 256) >= 192;
+  const bool rowmajor_z = !big1 && p.tok_offsets != nullptr && p.pattern_id != nullptr && prefill_split_supported(p.n, p.rS);
+  int st;
+  if (big1) st = launch_gemm_lds<256, 256, 2, 2, 32, 4, 0, 1, 0>(g1, per_pattern, s);
+  else if (rowmajor_z) st = forward_prefill_split_first_bf16(p, Z, avg_prompt_rows, s);
+  else st = launch_gemm_lds<128, 128, 2, 2, 64, 4, 0, 1, 0>(g1, per_pattern, s);
+  if (st != PARSE_OK) return st;
+  if (rowmajor_z) {
+    if (big2) return launch_gemm_lds<256, 256, 2, 4, 32, 4, 1, 1, 1>(g2, per_pattern, s);
+    return launch_gemm_lds<128, 128, 2, 2, 32, 4, 1, 1, 1>(g2, per_pattern, s);
+  }
+  if (big2) return launch_gemm_lds<256, 256, 2, 4, 32, 4, 1, 0, 1>(g2, per_pattern, s);
+  return launch_gemm_lds<128, 128, 2, 2, 32, 4, 1, 0, 1>(g2, per_pattern, s);
+}
+
+}  // namespace parse

@@ -125,7 +125,7 @@ def test_forward_rejects_bad_arguments():
     Lb = _layer(n=64, m=64, R=64, G=2, dtype=1, layout=1)
     assert call(mode=1, layer=Lb, rows=40, P=40) == -2                  # more than 32 sequences
     assert call(mode=1, layer=Lb, rows=8, P=4) == -2                    # decode: one row per sequence
-    assert lib.parse_lowrank_workspace_bytes(0, C.byref(L), 8, 1) >= 8 * 16 * 4
+    assert lib.parse_lowrank_workspace_bytes(0, C.byref(L), 8, 1, 0, 0) >= 8 * 16 * 4
 
 
 def test_decode_multi_rejects_bad_arguments():
@@ -148,7 +148,7 @@ def test_decode_multi_rejects_bad_arguments():
     assert call([La, La], [pt, pt], 2, ys=[FAKE.value, None]) == -1
     assert call([La, La], [pt, pt], 2, wsb=64) == -5
     larr = (B._Layer * 2)(La, La)
-    assert lib.parse_lowrank_decode_multi_workspace_bytes(larr, 2) == 2 * lib.parse_lowrank_workspace_bytes(1, C.byref(La), 8, 1)
+    assert lib.parse_lowrank_decode_multi_workspace_bytes(larr, 2) == 2 * lib.parse_lowrank_workspace_bytes(1, C.byref(La), 8, 1, 0, 0)
 
 
 def test_prefill_multi_rejects_bad_arguments():

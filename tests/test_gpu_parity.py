@@ -314,13 +314,9 @@ def _run_prefill(lay, lengths, subsets_per_prompt, seed, dtype, schedule=0):
     sd = i32(subs)
     pid, perm, boff, npat, rep = pa.bucket_patterns(sd, k)
     Vs, Us = pa.pack_patterns(dl, sd, k, k, rep, npat, len(lengths))
-    pa.set_prefill_schedule(schedule)
-    try:
-        Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, len(lengths), Vs, Us), upload_tokens(X, dtype),
-                               i32(off), pid, no_workspace=(schedule == 1))
-        torch.cuda.synchronize()
-    finally:
-        pa.set_prefill_schedule(0)
+    Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, len(lengths), Vs, Us, schedule=schedule),
+                           upload_tokens(X, dtype), i32(off), pid, no_workspace=(schedule == 1))
+    torch.cuda.synchronize()
     Yg = Y.float().cpu().numpy().astype(np.float64)
     return Yg, Yref, off
 
@@ -352,7 +348,13 @@ def test_prefill_config0_fp32():
     (512, 512, 2560, 20, 10, [40, 100], 1),               # r_S = 1280: 32-token workgroups
     (512, 800, 2560, 20, 10, [40, 300], 2),               # two launches, output blocks not a multiple of a chunk
     (1024, 4096, 1024, 8, 4, [512, 512, 37], 0),          # default choice at a size with whole 128-row tiles
-    (256, 256, 1024, 8, 8, [9000, 7400], 0),              # many token tiles: 128-token tiles in both launches
+    (256, 256, 1024, 8, 8, [9000, 7400], 2),              # many token tiles: 128-token tiles in both launches
+    (512, 768, 256, 8, 4, [70, 1, 33, 129, 64], 3),       # planned schedule: every prompt its own pattern, ragged
+    (1024, 1024, 512, 4, 3, [64, 200], 3),                # planned, r_S = 384: a partial column tile in the first product
+    (512, 800, 2560, 20, 10, [40, 300], 3),               # planned, r_S = 1280, 25 output blocks (partial tile)
+    (256, 1024, 1024, 8, 8, [9000, 7400], 3),             # planned, 256-row tiles in both launches, short reduction
+    (256, 1024, 1024, 8, 8, [9000, 7400], 0),             # the default choice at that size
+    (64, 64, 64, 2, 1, [300], 3),                         # planned, the smallest shapes: one reduction slice
 ])
 def test_prefill_bf16_small(n, m, R, G, k, lengths, schedule):
     say(f"prefill bf16 n={n} m={m} R={R} G={G} k={k} lengths={lengths} schedule={schedule}")
@@ -371,6 +373,54 @@ def test_prefill_bf16_small(n, m, R, G, k, lengths, schedule):
     Yg, Yref, off = _run_prefill(lay, lengths, subs, 504, "bf16", schedule)
     for p in range(len(lengths)):
         assert_close(Yg[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"prompt {p}")
+
+
+def test_prefill_plan_matches_the_row_grouping_and_serves_shared_patterns():
+    """The prefill plan against the oracle's row grouping (bit-exact), then the planned product with prompts that share
+    patterns in interleaved arrival order, one prompt with an invalid pattern id (zero rows), and guard rows around Y."""
+    say("prefill plan: row map, tile patterns; planned product with shared patterns and an invalid id")
+    n, m, R, G, k = 512, 640, 256, 8, 3
+    lay = si.small_layer(521, n, m, R, G, "bf16")
+    lengths = [300, 17, 256, 90, 1, 513, 64, 40]
+    pid_h = np.array([2, 0, 2, 5, 0, 1, 9, 1], np.int32)          # 9 is out of range for 6 slots
+    n_slots = 6
+    rng = np.random.default_rng(522)
+    slot_subs = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(n_slots)]).astype(np.int32)
+    off = si.offsets_from_lengths(lengths)
+    rows = int(off[-1])
+    X = si.make_tokens(rng, rows, n, "bf16")
+    Xv = si.bf16_bits_to_f32(X).astype(np.float64)
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    Vs, Us = pa.pack_patterns(dl, i32(slot_subs), k, k, None, None, n_slots)
+    offd, pidd, Xd = i32(off), i32(pid_h), upload_tokens(X, "bf16")
+    plan = pa.prefill_plan(offd, pidd, rows, n_slots)
+    torch.cuda.synchronize()
+    words = plan.view(torch.int32).cpu().numpy()
+    rowmap_ref, tpat_ref = po.plan_rows(off, pid_h, n_slots, 256)
+    nt, cap = int(words[0]), int(words[3])
+    assert nt == len(tpat_ref) and int(words[1]) == nt * 256 and int(words[2]) == 256
+    assert np.array_equal(words[16:16 + nt], tpat_ref)
+    rm0 = 16 + (cap + 15) // 16 * 16
+    assert np.array_equal(words[rm0:rm0 + nt * 256], rowmap_ref)
+    # planned product, output between guard rows
+    guard = 4
+    Ybuf = torch.full((rows + 2 * guard, m), 7.0, dtype=torch.bfloat16, device=DEV)
+    Y = Ybuf[guard:guard + rows]
+    pt = pa.Patterns(k, n_slots, Vs, Us)
+    pa.lowrank_prefill_planned(dl, pt, Xd, offd, pidd, plan, Y=Y)
+    Y2 = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt.with_schedule(pa.PARSE_SCHED_PLANNED), Xd, offd, pidd)
+    torch.cuda.synchronize()
+    assert torch.all(Ybuf[:guard] == 7.0) and torch.all(Ybuf[guard + rows:] == 7.0), "stores outside Y"
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "ready plan vs plan built inside the call"
+    U0, sg, V = oracle_factors(lay)
+    Yn = Y.float().cpu().numpy().astype(np.float64)
+    for p, L_ in enumerate(lengths):
+        a, b = off[p], off[p + 1]
+        if pid_h[p] >= n_slots:
+            assert np.all(Yn[a:b] == 0), "prompt with an invalid pattern id must give zero rows"
+            continue
+        Yref = po.forward(U0, sg, V, lay.gs, Xv[a:b], [0, b - a], slot_subs[pid_h[p]][None, :])
+        assert_close(Yn[a:b], Yref, TOL_BF16, f"prompt {p} (pattern {pid_h[p]})")
 
 
 def test_prefill_invalid_pattern_gives_zero_rows_and_is_repeatable():
@@ -401,13 +451,9 @@ def test_prefill_config1_full_size_sampled():
     pid, perm, boff, npat, rep = pa.bucket_patterns(sub_d, w.k)
     Vs, Us = pa.pack_patterns(dl, sub_d, w.k, w.k, rep, npat, w.P)
     Ys = {}
-    for schedule in (1, 2):
-        pa.set_prefill_schedule(schedule)
-        try:
-            Ys[schedule] = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us), Xd, offd, pid)
-            torch.cuda.synchronize()
-        finally:
-            pa.set_prefill_schedule(0)
+    for schedule in (1, 2, 3):
+        Ys[schedule] = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us, schedule=schedule), Xd, offd, pid)
+        torch.cuda.synchronize()
     assert np.all(margin > 1e-4) and np.array_equal(sub_d.cpu().numpy(), subs)
     U0, sg, V = oracle_factors(lay)
     rng = np.random.default_rng(7)
@@ -546,17 +592,13 @@ def test_prefill_multi_matches_oracle_and_single_calls(shapes, n, lengths):
         patterns.append(pa.Patterns(k, P, Vs, Us))
     ys = pa.lowrank_prefill_multi(layers, patterns, Xd, offd, pid)
     torch.cuda.synchronize()
-    pa.set_prefill_schedule(2)
-    try:
-        for li in range(len(shapes)):
-            yn = ys[li].float().cpu().numpy().astype(np.float64)
-            for p in range(P):
-                assert_close(yn[off[p]:off[p + 1]], refs[li][off[p]:off[p + 1]], TOL_BF16, f"layer {li} prompt {p}")
-            single = pa.lowrank_forward(pa.PARSE_PREFILL, layers[li], patterns[li], Xd, offd, pid)
-            torch.cuda.synchronize()
-            assert torch.equal(single.view(torch.int16), ys[li].view(torch.int16)), f"layer {li}: fused vs separate call"
-    finally:
-        pa.set_prefill_schedule(0)
+    for li in range(len(shapes)):
+        yn = ys[li].float().cpu().numpy().astype(np.float64)
+        for p in range(P):
+            assert_close(yn[off[p]:off[p + 1]], refs[li][off[p]:off[p + 1]], TOL_BF16, f"layer {li} prompt {p}")
+        single = pa.lowrank_forward(pa.PARSE_PREFILL, layers[li], patterns[li].with_schedule(pa.PARSE_SCHED_TILES), Xd, offd, pid)
+        torch.cuda.synchronize()
+        assert torch.equal(single.view(torch.int16), ys[li].view(torch.int16)), f"layer {li}: fused vs separate call"
 
 
 def test_shared_head_route_cache_pack_and_prefill():
@@ -607,14 +649,10 @@ def test_shared_head_route_cache_pack_and_prefill():
         assert torch.equal(Vw[p, ns * gs:].view(torch.int16), Vp[p].view(torch.int16))
         assert torch.equal(Uw[p, ns * gs:].view(torch.int16), Up[p].view(torch.int16))
     pid = i32(np.arange(P, dtype=np.int32))
-    pa.set_prefill_schedule(2)
-    try:
-        y_sh = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns),
-                                  Xd, offd, pid)
-        y_whole = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw), Xd, offd, pid)
-        torch.cuda.synchronize()
-    finally:
-        pa.set_prefill_schedule(0)
+    y_sh = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns,
+                                                                 schedule=pa.PARSE_SCHED_TILES), Xd, offd, pid)
+    y_whole = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw, schedule=pa.PARSE_SCHED_TILES), Xd, offd, pid)
+    torch.cuda.synchronize()
     assert torch.equal(y_sh.view(torch.int16), y_whole.view(torch.int16))
     U0, sg, V = oracle_factors(lay)
     Yref = po.forward(U0, sg, V, lay.gs, Xv, off, subs_ref)
@@ -676,14 +714,10 @@ def test_rank_granular_route_pack_and_prefill():
     pid = i32(np.arange(P, dtype=np.int32))
     U0, sgm, V = oracle_factors(lay)
     Yref = po.forward(U0, sgm, V, 1, Xv, off, sg)
-    for schedule in (1, 2):
-        pa.set_prefill_schedule(schedule)
-        try:
-            y = pa.lowrank_forward(pa.PARSE_PREFILL, desc, pa.Patterns(K // 32, P, Vs, Us), Xd, offd, pid,
-                                   no_workspace=(schedule == 1))
-            torch.cuda.synchronize()
-        finally:
-            pa.set_prefill_schedule(0)
+    for schedule in (1, 2, 3):
+        y = pa.lowrank_forward(pa.PARSE_PREFILL, desc, pa.Patterns(K // 32, P, Vs, Us, schedule=schedule), Xd, offd, pid,
+                               no_workspace=(schedule == 1))
+        torch.cuda.synchronize()
         yn = y.float().cpu().numpy().astype(np.float64)
         for p in range(P):
             assert_close(yn[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"schedule {schedule} prompt {p}")

@@ -523,3 +523,32 @@ def test_soft_mask_values_fixed_by_the_formula():
     assert sharp[0] > 0.6 and sharp[2] < 1e-4 and np.all(np.abs(flat - 1.0 / 3.0) < 0.02)
     # the largest score always gets the largest mask entry; the entries sum to K when eps = 0
     assert np.argmax(sharp) == 0 and abs(po.soft_mask(s3, 2, 0.5, 0.0).sum() - 2.0) < 1e-15
+
+
+def test_plan_rows_hand_case_and_properties():
+    """Row-level grouping: a hand case (tile of 4 rows), then properties on random input: every real row appears exactly
+    once, rows of a tile share the tile's pattern, prompts of a pattern keep arrival order, padding only at the end of a
+    pattern's run and shorter than a tile."""
+    off = np.array([0, 3, 5, 6, 11], np.int32)          # lengths 3, 2, 1, 5
+    pid = np.array([2, 0, 7, 2], np.int32)               # 7 is out of range for n_patterns = 3
+    rowmap, tpat = po.plan_rows(off, pid, 3, tile=4)
+    assert rowmap.tolist() == [3, 4, -1, -1,   0, 1, 2, 6, 7, 8, 9, 10,   5, -1, -1, -1]
+    assert tpat.tolist() == [0, 2, 2, -1]
+    rng = np.random.default_rng(77)
+    lengths = rng.integers(1, 40, size=23)
+    off = si.offsets_from_lengths(lengths)
+    pid = rng.integers(-1, 6, size=23).astype(np.int32)  # -1 and 5 are invalid for n_patterns = 5
+    rowmap, tpat = po.plan_rows(off, pid, 5, tile=16)
+    real = rowmap[rowmap >= 0]
+    assert sorted(real.tolist()) == list(range(int(off[-1])))
+    prompt_of = np.searchsorted(off, np.arange(off[-1]), side="right") - 1
+    for t, b in enumerate(tpat):
+        rows = rowmap[t * 16:(t + 1) * 16]
+        for r in rows[rows >= 0]:
+            q = pid[prompt_of[r]]
+            assert (q if 0 <= q < 5 else -1) == b
+    for b in set(tpat.tolist()):
+        run = rowmap[np.repeat(tpat == b, 16)]
+        n_real = int((run >= 0).sum())
+        assert np.all(run[:n_real] >= 0) and np.all(run[n_real:] == -1) and len(run) - n_real < 16
+        assert np.all(np.diff(run[:n_real]) > 0)          # arrival order = ascending rows within a pattern
