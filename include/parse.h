@@ -348,21 +348,42 @@ int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *
                                const void *X, int32_t rows, const int32_t *pattern_id, void *const *Y,
                                void *workspace, size_t workspace_bytes, parse_stream stream);
 
+/* ---- decode plan (Sec. 4.3, rank reuse: the subsets are fixed after prefill) -------------------------------------
+ * Everything the decode kernels derive from the subsets -- per layer the sequence mask of every group, the ascending
+ * list of groups that at least one sequence selected, their count -- computed ONCE per batch instead of in every step.
+ *   layers, patterns  host arrays [n_layers] (1..4 layers that share their input; patterns[l].subsets is used)
+ *   pattern_id        device int32 [rows], a sequence's pattern (cache entry); rows <= 32
+ *   plan              device, >= parse_decode_plan_bytes(n_layers) bytes, 16-byte aligned, caller-owned
+ * parse_lowrank_decode_planned is the decode step of those layers over a ready plan: TWO launches (the intermediate of
+ * every used rank block is reduced completely inside one workgroup, then the output columns), nothing derived from
+ * the subsets at run time.  Results are bit-identical to parse_lowrank_forward(PARSE_DECODE) / parse_lowrank_decode_multi,
+ * which build the same plan inside the call (one more small launch).
+ *   X device [rows][n] bf16;  Y host array [n_layers] of device pointers [rows][layers[l].m] bf16
+ *   workspace device, >= parse_lowrank_decode_planned_workspace_bytes(layers, n_layers) (the intermediates) */
+size_t parse_decode_plan_bytes(int32_t n_layers);
+int parse_decode_plan(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
+                      const int32_t *pattern_id, int32_t rows, void *plan, size_t plan_bytes, parse_stream stream);
+size_t parse_lowrank_decode_planned_workspace_bytes(const parse_layer *layers, int32_t n_layers);
+int parse_lowrank_decode_planned(const parse_layer *layers, int32_t n_layers, const void *X, int32_t rows,
+                                 const void *plan, void *const *Y, void *workspace, size_t workspace_bytes,
+                                 parse_stream stream);
+
 /* ---- decode without allocation ---------------------------------------------------------------------------
  * For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  The same step as parse_lowrank_forward(PARSE_DECODE, ...) -- same kernels, same bits --
- * but the memory the kernels need beyond inputs and outputs (slice partials of the intermediate, its rounded
- * copy, the list of used groups) is a fixed array of PARSE_DECODE_STATIC_SCRATCH_BYTES inside the library's
+ * but the memory the kernels need beyond inputs and outputs (the rounded intermediate in operand order and the decode
+ * plan: group masks, list of used groups) is a fixed array of PARSE_DECODE_STATIC_SCRATCH_BYTES inside the library's
  * device image instead of a caller's workspace.  The call allocates and frees nothing, on any call, and calls no
  * allocating routine; every GPU the library runs on holds its own copy of the array until the process ends.
  *   layer, patterns, X, rows, pattern_id, Y   as for PARSE_DECODE (device pointers, rows <= 32, bf16 PARSE_MFMA16)
- * PARSE_EWORKSPACE when the layer needs more than the array holds (the need grows with the stored rank R:
- * parse_lowrank_workspace_bytes(PARSE_DECODE, layer, rows, k) tells; R <= 2560 fits); other errors as
+ * PARSE_EWORKSPACE when the layer needs more than the array holds (64 bytes per stored rank plus 768 for the plan, so
+ * layers up to a stored rank of 8160 fit; parse_lowrank_workspace_bytes(PARSE_DECODE, layer, rows, k, 0, 0) tells);
+ * other errors as
  * parse_lowrank_forward.  Nothing is launched on error.
  * All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two threads) race;
  * issue them on one stream or order them.  The array keeps the last call's contents; the kernels read only what
  * the same call wrote, so nothing needs clearing between calls. */
-#define PARSE_DECODE_STATIC_SCRATCH_BYTES (24u << 20)
+#define PARSE_DECODE_STATIC_SCRATCH_BYTES (512u << 10)
 size_t parse_lowrank_decode_static_capacity(void);
 int parse_lowrank_decode_static(const parse_layer *layer, const parse_patterns *patterns, const void *X,
                                 int32_t rows, const int32_t *pattern_id, void *Y, parse_stream stream);

@@ -114,6 +114,13 @@ def lib():
     L.parse_lowrank_forward.restype = C.c_int
     L.parse_lowrank_forward.argtypes = [i32, C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, i32, vp, vp,
                                         sz, vp]
+    L.parse_decode_plan_bytes.restype = sz; L.parse_decode_plan_bytes.argtypes = [i32]
+    L.parse_decode_plan.restype = C.c_int
+    L.parse_decode_plan.argtypes = [C.POINTER(_Layer), C.POINTER(_Patterns), i32, vp, i32, vp, sz, vp]
+    L.parse_lowrank_decode_planned_workspace_bytes.restype = sz
+    L.parse_lowrank_decode_planned_workspace_bytes.argtypes = [C.POINTER(_Layer), i32]
+    L.parse_lowrank_decode_planned.restype = C.c_int
+    L.parse_lowrank_decode_planned.argtypes = [C.POINTER(_Layer), i32, vp, i32, vp, C.POINTER(C.c_void_p), vp, sz, vp]
     L.parse_lowrank_decode_static_capacity.restype = sz; L.parse_lowrank_decode_static_capacity.argtypes = []
     L.parse_lowrank_decode_static.restype = C.c_int
     L.parse_lowrank_decode_static.argtypes = [C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, vp]
@@ -420,6 +427,37 @@ def lowrank_decode_static(layer: Layer, patterns: Patterns, X, pattern_id, Y):
     _check(lib().parse_lowrank_decode_static(C.byref(cl), C.byref(cp), _ptr(X), X.shape[0], _ptr(pattern_id), _ptr(Y),
                                              _stream()), "parse_lowrank_decode_static")
     return Y
+
+
+def decode_plan(layers, patterns, pattern_id, plan=None):
+    """parse_decode_plan -> the plan buffer (uint8 device tensor) for these layers and this batch."""
+    nl = len(layers)
+    if plan is None:
+        plan = torch.empty(int(lib().parse_decode_plan_bytes(nl)), dtype=torch.uint8, device=pattern_id.device)
+    larr = (_Layer * nl)(*[l.c() for l in layers])
+    parr = (_Patterns * nl)(*[p.c() for p in patterns])
+    _check(lib().parse_decode_plan(larr, parr, nl, _ptr(pattern_id), pattern_id.numel(), _ptr(plan), plan.numel(),
+                                   _stream()), "parse_decode_plan")
+    return plan
+
+
+def lowrank_decode_planned_workspace_bytes(layers) -> int:
+    arr = (_Layer * len(layers))(*[l.c() for l in layers])
+    return int(lib().parse_lowrank_decode_planned_workspace_bytes(arr, len(layers)))
+
+
+def lowrank_decode_planned(layers, X, plan, Ys=None, workspace=None):
+    """parse_lowrank_decode_planned: one decode step of several layers that share X over a ready plan."""
+    rows, nl = X.shape[0], len(layers)
+    if Ys is None:
+        Ys = [torch.empty((rows, l.m), dtype=X.dtype, device=X.device) for l in layers]
+    if workspace is None:
+        workspace = torch.empty(max(lowrank_decode_planned_workspace_bytes(layers), 256), dtype=torch.uint8, device=X.device)
+    larr = (_Layer * nl)(*[l.c() for l in layers])
+    yarr = (C.c_void_p * nl)(*[y.data_ptr() for y in Ys])
+    _check(lib().parse_lowrank_decode_planned(larr, nl, _ptr(X), rows, _ptr(plan), yarr, _ptr(workspace),
+                                              workspace.numel(), _stream()), "parse_lowrank_decode_planned")
+    return Ys
 
 
 def lowrank_decode_multi_workspace_bytes(layers) -> int:

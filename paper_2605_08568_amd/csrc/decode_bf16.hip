@@ -1,252 +1,218 @@
 // a7: decode step for bf16 PARSE_MFMA16 layers (Sec. 4.3, "Rank Reuse for Decoding"): every sequence keeps the
-// rank subset chosen at prefill; one token per sequence.  Bandwidth-bound: the kernels stream each rank group
-// that ANY sequence of the batch selected exactly once, straight from the layer's factor store in operand
-// order (1 KiB coalesced per wavefront instruction, no LDS hop, no packed copies), and apply it to all
-// sequences at once on the matrix cores (32 sequences = the N side of a 32x32x16 instruction).  A sequence
-// whose pattern does not hold a group gets a zero in that group's part of z, so it contributes nothing.
-// Three launches: decode_z (Vt stream -> fp32 partials of z per slice of n), decode_zfin (tiny: adds the slices
-// up in slice order, masks, rounds, operand order), decode_y (Ut stream -> y).  A compute unit sustains only
-// about 50 GB/s of cache-line fills, so both streams are cut into about as many workgroups as there are units,
-// and the small operands (x, z) are shared inside a workgroup instead of being re-fetched per factor operand.
-// The streaming loops are branch-free: operand lists are walked in chunks with fetches past the end clamped
-// to the last valid operand and their contribution switched off by zeroing the small operand.
-// Horizontal fusion (Sec. 4.4, Eq. 11-12): up to DEC_MAX_LAYERS layers that read the SAME x (Q/K/V, gate/up)
-// go through the same three launches together -- each launch's grid is the concatenation of the layers' task
-// lists, so the per-launch floor is paid once and x is staged once per task whichever layer the task belongs to.
-#include "common.hpp"
+// rank subset chosen at prefill; one token per sequence.  Bandwidth-bound: the kernels stream each rank group that
+// ANY sequence of the batch selected exactly once, straight from the layer's factor store in operand order
+// (1 KiB coalesced per wavefront instruction, no packed copies), and apply it to all sequences at once on the
+// matrix cores (32 sequences = the N side of a 32x32x16 instruction).  A sequence whose pattern does not hold a
+// group gets a zero in that group's part of z, so it contributes nothing.
+//
+// Decode plan (Sec. 4.3: the subsets are fixed after prefill, so everything derived from them is computed once per
+// batch, not once per step): per layer the sequence mask of every group, the ascending list of groups selected by at
+// least one sequence and their count.  decode_plan_build writes it; both kernels below only read it.
+//
+// Two launches per step:
+//   decode_zf  one workgroup per 32-rank block of a used group; the workgroup owns the WHOLE reduction over n, so z
+//              needs no partial sums in memory and no second pass: the token rows x and the block's Vt operands are
+//              staged through LDS in chunks of 256 columns (loads that write LDS directly, four chunks in rotation,
+//              three in flight), each of the eight wavefronts takes an eighth of every chunk's reduction steps, the
+//              eight partial accumulators are added in wavefront order through LDS, masked, rounded to bf16 and
+//              stored as operands of the second product.
+//   decode_y   NC (1..4) 32-column output blocks per workgroup; the eight wavefronts split the used reduction blocks,
+//              all Ut operands requested up front; LDS reduction in wavefront order.
+// Horizontal fusion (Sec. 4.4, Eq. 11-12): up to DEC_MAX_LAYERS layers that read the SAME x (Q/K/V, gate/up) go
+// through the same two launches together -- each launch's grid is the concatenation of the layers' task lists.
+// No floating-point atomics; the summation order is fixed: same inputs, same bits.
+#include "prefill_common.hpp"
 
 namespace parse {
 
 constexpr int DZ_WAVES = 8, DZ_THREADS = DZ_WAVES * 64;
 constexpr int DY_WAVES = 8, DY_THREADS = DY_WAVES * 64;
-constexpr int DEC_CHUNK = 4;       // operands fetched per chunk; four chunks in flight per wavefront
 constexpr int DEC_MAXG = 64;
-constexpr int DZ_MAXSLICE = 64;    // reduction steps (of 16 columns) of x staged per decode_z task
-constexpr int DZ_XLD = DZ_MAXSLICE * 16 + 8;
-constexpr int DEC_MAX_SLICES = 64; // slices of n the workspace is sized for
-constexpr int DY_CHUNK = 4;        // decode_y: operands per chunk after the first block
-constexpr int DY_MAXKB = 1024;     // selected reduction blocks a decode_y workgroup can list
-
+constexpr int DZ_CH = 256;                 // columns of x staged per chunk
+constexpr int DZ_CH_KB = DZ_CH / 16;       // reduction steps per chunk (16)
+constexpr int DZ_WKB = DZ_CH_KB / DZ_WAVES;   // reduction steps per wavefront per chunk (2)
+constexpr int DZ_XBYTES = 32 * DZ_CH * 2;  // x part of a staged chunk: 32 rows x 512 bytes
+constexpr int DZ_BUF = DZ_XBYTES + DZ_CH_KB * 1024;   // + the chunk's 16 Vt operands = 32 KiB
+constexpr int DZ_NBUF = 4;
+constexpr int DY_CHUNK = 4;                // decode_y: operands per chunk after the first block
+constexpr int DY_MAXKB = 1024;             // selected reduction blocks a decode_y workgroup can list
 constexpr int DEC_MAX_LAYERS = 4;
+constexpr int DEC_PLAN_WORDS = 192;        // per layer: [0] count, [1..64] used group ids, [65..128] sequence masks
+
+#define PARSE_DEC_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define PARSE_DEC_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
 struct DecLayer {
   const uint16_t *Vt, *Ut;
   uint16_t *y;
-  const int32_t *subsets;      // this layer's patterns
-  int stride, k, n_patterns;
-  float *zp;                   // workspace parts of this layer
-  uint16_t *zf;
-  int32_t *used;
+  uint16_t *zf;                // workspace: z of this layer in operand order
+  const int32_t *plan;         // this layer's DEC_PLAN_WORDS of the decode plan
   int R, G, gs, m;
-  int z_first, f_first, y_first;   // first workgroup of this layer in decode_z / decode_zfin / decode_y
+  int z_first, y_first;        // first workgroup of this layer in decode_zf / decode_y
 };
 struct DecArgs {
   DecLayer L[DEC_MAX_LAYERS];
   int n_layers;
   const uint16_t *x;
+  int B, n;
+};
+
+struct DecPlanArgs {
+  const int32_t *subsets[DEC_MAX_LAYERS];
+  int stride[DEC_MAX_LAYERS], k[DEC_MAX_LAYERS], n_patterns[DEC_MAX_LAYERS], G[DEC_MAX_LAYERS];
   const int32_t *pattern_id;
-  int B, n, S;                 // sequences, input width, slices of n (the same for every layer)
+  int B;
+  int32_t *plan;
 };
 
 __device__ __forceinline__ bf16x8 dec_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// Per-group sequence masks built by the whole workgroup with two dependent loads per lane: lane t looks at entry
-// i = t / 32 (+ blockDim/32 ...) of sequence b = t % 32's pattern and ORs bit b into gmask[that group].
-// gmask (LDS, DEC_MAXG words) must be zeroed by the caller before; ends with a barrier.
-__device__ __forceinline__ void build_group_masks(const int32_t *__restrict__ subsets, int stride, int k,
-                                                  int n_patterns, const int32_t *__restrict__ pattern_id, int B, int G,
-                                                  uint32_t *gmask) {
-  const int b = threadIdx.x & 31;
-  int pid = -1;
-  if (b < B) pid = pattern_id[b];
-  const bool ok = pid >= 0 && pid < n_patterns;
-  for (int i = threadIdx.x >> 5; i < k; i += blockDim.x >> 5) {
-    if (ok) {
-      const int g = subsets[(size_t)pid * stride + i];
-      if (g >= 0 && g < G) atomicOr(&gmask[g], 1u << b);
+// grid = layers, one wavefront each: lane b < B looks at its sequence's k group ids and ORs its bit into the groups'
+// masks (LDS, integer OR: order-free); then the used groups are listed in ascending order by a vote.
+__global__ __launch_bounds__(64) void decode_plan_build(DecPlanArgs a) {
+  __shared__ uint32_t gmask[DEC_MAXG];
+  const int l = blockIdx.x, lane = threadIdx.x;
+  int32_t *out = a.plan + (size_t)l * DEC_PLAN_WORDS;
+  gmask[lane] = 0u;
+  __syncthreads();
+  const int G = a.G[l];
+  if (lane < a.B && lane < 32) {
+    const int pid = a.pattern_id[lane];
+    if (pid >= 0 && pid < a.n_patterns[l]) {
+      for (int i = 0; i < a.k[l]; ++i) {
+        const int g = a.subsets[l][(size_t)pid * a.stride[l] + i];
+        if (g >= 0 && g < G) atomicOr(&gmask[g], 1u << lane);
+      }
     }
   }
   __syncthreads();
+  __shared__ int32_t used_l[DEC_MAXG];
+  const bool u = lane < G && gmask[lane] != 0u;
+  const unsigned long long votes = __ballot(u);
+  used_l[lane] = -1;
+  __syncthreads();
+  if (u) used_l[__popcll(votes & ((1ull << lane) - 1ull))] = lane;
+  __syncthreads();
+  out[1 + lane] = used_l[lane];
+  out[65 + lane] = (int32_t)gmask[lane];
+  if (lane == 0) out[0] = __popcll(votes);
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// decode_z: z partials.  grid = nquads * S tasks; task = (four consecutive 32-rank blocks, slice s of n).
-// The slice of the token rows x is staged in LDS once (coalesced row reads; the matrix-core operand read
-// pattern is only ever applied to LDS) and shared by the four rank blocks; wavefront w owns rank block w % 4
-// and half w / 4 of the slice; its Vt operands come straight from the store, four chunks in flight; the two
-// halves add up through LDS; fp32 partials go to the workspace as zp[quad][slice][piece][8], a piece being the
-// 8 ranks x 1 sequence that one lane of the next product holds, so that both this kernel's stores and
-// decode_zfin's loads are contiguous per wavefront.  Rank blocks of groups nobody selected are skipped (nothing
-// of them is read or written).  Workgroup 0 also lists the groups selected by at least one sequence
-// (ascending) for decode_y.
-__global__ __launch_bounds__(DZ_THREADS) void decode_z(DecArgs a) {
+// decode_zf.  grid = sum over layers of R/32; workgroup = (layer, 32-rank block rb).
+// Everything the loop reads from memory goes straight into LDS (loads that write LDS directly), DZ_NBUF chunks in
+// rotation, so the only waits in the loop are the explicit ones below: per chunk of 256 columns the 32 x rows
+// (512 bytes each, their 16-byte pieces XOR-swizzled by the row so that an operand read -- 32 rows x the same piece --
+// spreads over the banks) and the 16 Vt operands of the rank block (two per wavefront, which that wavefront alone
+// reads back).  The LDS is reused for the wavefronts' partial sums at the end.
+__global__ __launch_bounds__(DZ_THREADS) void decode_zf(DecArgs a) {
   int li = 0;
 #pragma unroll
   for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].z_first) ? 1 : 0;
   const DecLayer &ly = a.L[li];
-  const uint16_t *__restrict__ Vt = ly.Vt;
-  const uint16_t *__restrict__ x = a.x;
-  const int32_t *__restrict__ subsets = ly.subsets;
-  const int32_t *__restrict__ pattern_id = a.pattern_id;
-  float *__restrict__ zp = ly.zp;
-  int32_t *__restrict__ used_out = ly.used;   // [0] = count, [1..] = ids
-  const int B = a.B, n = a.n, R = ly.R, G = ly.G, gs = ly.gs, stride = ly.stride, k = ly.k, n_patterns = ly.n_patterns;
-  const int S = a.S;
-  const int bid = blockIdx.x - ly.z_first;    // task within the layer
-  __shared__ __attribute__((aligned(16))) uint16_t xs[32 * DZ_XLD];  // 66 KiB; reused for the halves' sum
-  __shared__ uint32_t gmask[DEC_MAXG];
-  float(*red)[16][64] = reinterpret_cast<float(*)[16][64]>(xs);       // [4][16][64] floats = 16 KiB
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l32 = lane & 31, q = lane >> 5;
-  const int nkb = n / 16, nrb = R / 32;
-  const int quad = bid / S, sl = bid - quad * S;
-  const int w0 = (int)(((long long)nkb * sl) / S), w1 = (int)(((long long)nkb * (sl + 1)) / S);
-  const int len = w1 - w0;                                           // <= DZ_MAXSLICE (host)
-  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  const int rbl = wave_s & 3, half = wave_s >> 2;
-  const int rb = quad * 4 + rbl;
-  const int h0 = (len * half) / 2, h1 = (len * (half + 1)) / 2;      // this wavefront's steps of the slice
-  const int cnt_all = rb < nrb ? h1 - h0 : 0;
-  const char *vblock = reinterpret_cast<const char *>(Vt) + ((size_t)min(rb, nrb - 1) * nkb + w0 + h0) * 1024;
-  const uint32_t lane_off = lane * 16;
-  u32x4 V0[DEC_CHUNK], V1[DEC_CHUNK], V2[DEC_CHUNK], V3[DEC_CHUNK];
-  auto load_v = [&](u32x4 *V, int base, int cnt) {
+  const int rb = blockIdx.x - ly.z_first;
+  const int n = a.n, B = a.B, gs = ly.gs;
+  const uint32_t mask = (uint32_t)ly.plan[65 + (rb * 32) / gs];     // sequences whose pattern holds this block's group
+  if (mask == 0u) return;                                            // nobody selected it: nothing is read or written
+  __shared__ __attribute__((aligned(1024))) char xs[DZ_NBUF * DZ_BUF];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int j = lane & 31, q = lane >> 5;
+  const int nkb = n / 16;
+  const int nch = (nkb + DZ_CH_KB - 1) / DZ_CH_KB;
+  // x: 16 instructions of 1 KiB (two rows of 512 bytes each) per chunk, two per wavefront.  Lane l writes slot l % 32
+  // of row 2*ins + l / 32 and fetches the piece (slot ^ (row & 15)) of that row's chunk; pieces past the end of the row
+  // re-read its last one (their products are switched off below).
+  const char *xrow[2];
+  int xslot[2];
 #pragma unroll
-    for (int i = 0; i < DEC_CHUNK; ++i)
-      V[i] = *reinterpret_cast<const u32x4 *>(vblock + (size_t)max(min(base + i, cnt - 1), 0) * 1024 + lane_off);
-  };
-  // x slice: rows of len*32 bytes in 16-byte pieces; all of a lane's pieces (at most 8) are requested together
-  const int ppr = len * 2;
-  u32x4 xp[8];
+  for (int i = 0; i < 2; ++i) {
+    const int r = (wave * 2 + i) * 2 + (lane >> 5);
+    xrow[i] = (const char *)a.x + (size_t)min(r, B - 1) * n * 2;
+    xslot[i] = (lane & 31) ^ (r & 15);
+  }
+  const int last_piece = n / 8 - 1;
+  // Vt: operands (rb, kb) are contiguous in kb; this wavefront owns steps wave*2 + (0, 1) of every chunk
+  const char *vbase = (const char *)ly.Vt + ((size_t)rb * nkb) * 1024 + lane * 16;
+  auto issue = [&](int c) {
+    char *buf = xs + (c % DZ_NBUF) * DZ_BUF;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int piece = min(i * DZ_THREADS + (int)threadIdx.x, 32 * ppr - 1);
-    const int r = piece / ppr, c = (piece - r * ppr) * 8;
-    xp[i] = *reinterpret_cast<const u32x4 *>(x + (size_t)min(r, B - 1) * n + (size_t)w0 * 16 + c);
-  }
-  if (threadIdx.x < DEC_MAXG) gmask[threadIdx.x] = 0;
-  __syncthreads();
-  build_group_masks(subsets, stride, k, n_patterns, pattern_id, B, G, gmask);
-  if (bid == 0 && threadIdx.x < 64) {
-    const bool u = lane < G && gmask[lane] != 0u;
-    const unsigned long long mask = __ballot(u);
-    if (u) used_out[1 + __popcll(mask & ((1ull << lane) - 1ull))] = lane;
-    if (lane == 0) used_out[0] = __popcll(mask);
-  }
-  bool any = false;
-  for (int i = 0; i < 4; ++i) {
-    const int r = quad * 4 + i;
-    any = any || (r < nrb && gmask[r * 32 / gs] != 0u);
-  }
-  if (!any) return;   // uniform: nobody selected any of these rank blocks
-  const bool live = rb < nrb && gmask[min(rb, nrb - 1) * 32 / gs] != 0u;   // uniform per wavefront
-  const int cnt = live ? cnt_all : 0;
-  load_v(V0, 0, cnt);
-  load_v(V1, DEC_CHUNK, cnt);
-  load_v(V2, 2 * DEC_CHUNK, cnt);
-  load_v(V3, 3 * DEC_CHUNK, cnt);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int piece = i * DZ_THREADS + threadIdx.x;
-    if (piece < 32 * ppr) {
-      const int r = piece / ppr, c = (piece - r * ppr) * 8;
-      *reinterpret_cast<u32x4 *>(xs + r * DZ_XLD + c) = r < B ? xp[i] : u32x4{0, 0, 0, 0};
+    for (int i = 0; i < 2; ++i) {
+      const int piece = min(c * (DZ_CH / 8) + xslot[i], last_piece);
+      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(xrow[i] + (size_t)piece * 16),
+                                       PARSE_DEC_LDS_PTR(buf + (wave * 2 + i) * 1024), 16, 0, 0);
     }
-  }
-  __syncthreads();      // x slice staged
+#pragma unroll
+    for (int i = 0; i < DZ_WKB; ++i) {
+      const int kb = min(c * DZ_CH_KB + wave * DZ_WKB + i, nkb - 1);
+      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(vbase + (size_t)kb * 1024),
+                                       PARSE_DEC_LDS_PTR(buf + DZ_XBYTES + (wave * DZ_WKB + i) * 1024), 16, 0, 0);
+    }
+  };
   f32x16 acc;
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-  const uint16_t *xb_base = xs + l32 * DZ_XLD + h0 * 16 + q * 8;
   const u32x4 zero = {0, 0, 0, 0};
-  auto compute = [&](const u32x4 *V, int base) {
+  constexpr int LPC = 2 + DZ_WKB;          // loads per chunk per wavefront
 #pragma unroll
-    for (int i = 0; i < DEC_CHUNK; ++i) {
-      const int st = min(base + i, max(cnt - 1, 0));
-      const u32x4 xv = *reinterpret_cast<const u32x4 *>(xb_base + st * 16);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(V[i]), dec_bf16x8(base + i < cnt ? xv : zero), acc, 0, 0, 0);
+  for (int c = 0; c < DZ_NBUF - 1; ++c)
+    if (c < nch) issue(c);
+  for (int c = 0; c < nch; ++c) {
+    // chunk c has landed when only the chunks requested after it are outstanding
+    const int later = min(c + DZ_NBUF - 2, nch - 1) - c;
+    if (later >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPC) : "memory");
+    else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPC) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();          // everybody's x rows of chunk c are in LDS; everybody is done with chunk c-1
+    asm volatile("" ::: "memory");
+    if (c + DZ_NBUF - 1 < nch) issue(c + DZ_NBUF - 1);
+    const char *buf = xs + (c % DZ_NBUF) * DZ_BUF;
+#pragma unroll
+    for (int i = 0; i < DZ_WKB; ++i) {
+      const int kl = wave * DZ_WKB + i;                       // reduction step within the chunk
+      const u32x4 xv = *reinterpret_cast<const u32x4 *>(buf + j * (DZ_CH * 2) + (((kl * 2 + q) ^ (j & 15)) * 16));
+      const u32x4 vv = *reinterpret_cast<const u32x4 *>(buf + DZ_XBYTES + kl * 1024 + lane * 16);
+      const bool live = c * DZ_CH_KB + kl < nkb;              // steps past the end of n contribute nothing
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(vv), dec_bf16x8(live ? xv : zero), acc, 0, 0, 0);
     }
-  };
-  for (int c0 = 0; c0 < cnt; c0 += 4 * DEC_CHUNK) {
-    compute(V0, c0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_v(V0, c0 + 4 * DEC_CHUNK, cnt);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(V1, c0 + DEC_CHUNK);
-    __builtin_amdgcn_sched_barrier(0);
-    load_v(V1, c0 + 5 * DEC_CHUNK, cnt);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(V2, c0 + 2 * DEC_CHUNK);
-    __builtin_amdgcn_sched_barrier(0);
-    load_v(V2, c0 + 6 * DEC_CHUNK, cnt);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(V3, c0 + 3 * DEC_CHUNK);
-    __builtin_amdgcn_sched_barrier(0);
-    load_v(V3, c0 + 7 * DEC_CHUNK, cnt);
-    __builtin_amdgcn_sched_barrier(0);
   }
-  __syncthreads();      // every wavefront is done with the x slice; its LDS now holds the halves' sum
-  if (half == 1) {
+  __syncthreads();        // the staged chunks are dead: their LDS now takes the wavefronts' partial sums
+  float(*red)[16][64] = reinterpret_cast<float(*)[16][64]>(xs);     // [8][16][64] floats = 32 KiB
 #pragma unroll
-    for (int e = 0; e < 16; ++e) red[rbl][e][lane] = acc[e];
-  }
+  for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[e];
   __syncthreads();
-  float *zq = zp + (size_t)quad * S * 4096;   // this quad's partials: [S][512 pieces][8]
-  if (half == 0 && live) {
+  if (wave == 0) {
+    float s[16];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] += red[rbl][e][lane];
-    // entries of sequences whose pattern does not hold the rank's group are zero in z
+    for (int e = 0; e < 16; ++e) {
+      float v = red[0][e][lane];
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk) {
-      const bool member = (gmask[(rb * 32 + 8 * blk + 4 * q) / gs] >> l32) & 1u;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[blk * 4 + j] = member ? acc[blk * 4 + j] : 0.f;
+      for (int w = 1; w < DZ_WAVES; ++w) v += red[w][e][lane];
+      s[e] = v;
     }
-    // lane: sequence l32, local ranks rbl*32 + 8*blk + 4*q + (0..3) = piece (rbl*4 + blk)*32 + l32, floats 4q..4q+3
-    float *dst = zq + (size_t)sl * 4096 + ((rbl * 4) * 32 + l32) * 8 + q * 4;
+    // lane (j, q): sequence j, ranks rb*32 + 8*band + 4*q + (0..3); a sequence outside the group's mask gets zeros
+    const bool member = (mask >> j) & 1u;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk)
-      *reinterpret_cast<float4 *>(dst + blk * 256) = float4{acc[blk * 4], acc[blk * 4 + 1], acc[blk * 4 + 2], acc[blk * 4 + 3]};
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t p0x = member ? cvt_pk_bf16(s[(2 * h) * 4 + 0], s[(2 * h) * 4 + 1]) : 0u;
+      const uint32_t p0y = member ? cvt_pk_bf16(s[(2 * h) * 4 + 2], s[(2 * h) * 4 + 3]) : 0u;
+      const uint32_t p1x = member ? cvt_pk_bf16(s[(2 * h + 1) * 4 + 0], s[(2 * h + 1) * 4 + 1]) : 0u;
+      const uint32_t p1y = member ? cvt_pk_bf16(s[(2 * h + 1) * 4 + 2], s[(2 * h + 1) * 4 + 3]) : 0u;
+      // after the swap lane (j, q) holds the 8 consecutive ranks rb*32 + 16h + 8q + (0..7) of sequence j:
+      // the lane's piece of z operand (reduction block rb*2 + h)
+      const u32x2 sx = __builtin_amdgcn_permlane32_swap(p0x, p1x, false, false);
+      const u32x2 sy = __builtin_amdgcn_permlane32_swap(p0y, p1y, false, false);
+      *reinterpret_cast<u32x4 *>((char *)ly.zf + (size_t)(rb * 2 + h) * 1024 + lane * 16) = u32x4{sx[0], sy[0], sx[1], sy[1]};
+    }
   }
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// decode_zfin: z = sum of the S slices (in slice order), rounded to bf16, stored in operand order: piece
-// o = (kb*2 + q)*32 + b holds z[b][16kb + 8q + (0..7)] (the partials use the same piece numbering and are
-// already masked).  One wavefront per workgroup, one piece per lane, the loads of eight slices in flight at
-// once.  Pieces of rank blocks nobody selected hold whatever the workspace held; decode_y never reads them.
-__global__ __launch_bounds__(64) void decode_zfin(DecArgs a) {
-  int li = 0;
-#pragma unroll
-  for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].f_first) ? 1 : 0;
-  const DecLayer &ly = a.L[li];
-  const float *__restrict__ zp = ly.zp;
-  uint16_t *__restrict__ zf = ly.zf;
-  const int S = a.S, R = ly.R;
-  const int o = ((int)blockIdx.x - ly.f_first) * 64 + threadIdx.x;   // piece
-  const int quad = o >> 9, t = o & 511;
-  if ((o >> 5) * 8 >= R) return;
-  float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  const float *src = zp + ((size_t)quad * S * 512 + t) * 8;
-#pragma unroll 8
-  for (int s2 = 0; s2 < S; ++s2) {
-    const float4 f0 = *reinterpret_cast<const float4 *>(src + (size_t)s2 * 4096);
-    const float4 f1 = *reinterpret_cast<const float4 *>(src + (size_t)s2 * 4096 + 4);
-    v[0] += f0.x; v[1] += f0.y; v[2] += f0.z; v[3] += f0.w;
-    v[4] += f1.x; v[5] += f1.y; v[6] += f1.z; v[7] += f1.w;
-  }
-  u32x4 w;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
-  *reinterpret_cast<u32x4 *>(zf + (size_t)o * 8) = w;
-}
-
-// ---------------------------------------------------------------------------------------------------------
-// decode_y: y.  grid = ceil(ncb / NC) workgroups, each owns NC (1 or 2) consecutive 32-column output blocks;
-// wavefront w owns an eighth of the selected reduction blocks for all NC column blocks, so one z operand
-// (cache-resident) feeds NC products; the Ut operands of its first MAXK reduction blocks are requested at
-// once (MAXK sized so that everything stays in registers), the rest is streamed in chunks; the eight wavefronts
-// add up through LDS.
+// decode_y: y.  grid = ceil(ncb / NC) workgroups per layer, each owns NC consecutive 32-column output blocks;
+// wavefront w owns an eighth of the used reduction blocks for all NC column blocks, so one z operand (cache-resident)
+// feeds NC products; the Ut operands of its first MAXK reduction blocks are requested at once (MAXK sized so that
+// everything stays in registers), the rest is streamed in chunks; the eight wavefronts add up through LDS.
 template <int NC>
 __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
   int li = 0;
@@ -255,7 +221,7 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
   const DecLayer &ly = a.L[li];
   const uint16_t *__restrict__ Ut = ly.Ut;
   const uint16_t *__restrict__ zf = ly.zf;
-  const int32_t *__restrict__ used_in = ly.used;
+  const int32_t *__restrict__ plan = ly.plan;
   uint16_t *__restrict__ y = ly.y;
   const int B = a.B, m = ly.m, G = ly.G, gs = ly.gs;
   const int bid = blockIdx.x - ly.y_first;
@@ -267,14 +233,14 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
   const int ncb = m / 32;
   const int c0 = bid * NC;
   const int nc = min(NC, ncb - c0);
-  // count and ids are fetched together (ids past the count are whatever the list held; they are not used)
-  const int n_used_raw = used_in[0];
-  if (threadIdx.x < DEC_MAXG) used[threadIdx.x] = used_in[1 + threadIdx.x];
+  // count and ids come from the plan in one round trip (ids past the count are -1 and not used)
+  const int n_used_raw = plan[0];
+  if (threadIdx.x < DEC_MAXG) used[threadIdx.x] = plan[1 + threadIdx.x];
   const int n_used = max(0, min(n_used_raw, G));
   __syncthreads();
   const int kpg = gs / 16;                 // reduction blocks per group
   const int total_kb = n_used * kpg;       // selected reduction blocks
-  for (int i = threadIdx.x; i < total_kb; i += DY_THREADS) kb_list[i] = used[i / kpg] * kpg + i % kpg;
+  for (int i = threadIdx.x; i < total_kb; i += DY_THREADS) kb_list[i] = max(used[i / kpg], 0) * kpg + i % kpg;
   __syncthreads();
   const int k0 = (total_kb * wave) / DY_WAVES, k1 = (total_kb * (wave + 1)) / DY_WAVES;
   const int cnt = k1 - k0;
@@ -357,50 +323,34 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
   }
 }
 
-// Slices of n: at most one task per compute unit over the rank quads (of all layers of the call) that can be
-// selected at all (the host knows k and the number of patterns, not the subsets), a slice no longer than
-// DZ_MAXSLICE steps, at most DEC_MAX_SLICES slices.
-static int live_quads_bound(const parse_layer *L, const parse_patterns *pt) {
-  const int gs = L->R / L->G, nquads = (L->R / 32 + 3) / 4;
-  long long groups = (long long)pt->k * pt->n_patterns;
-  if (groups > L->G) groups = L->G;
-  long long live = (groups * gs + 127) / 128;
-  if (live > nquads) live = nquads;
-  return live < 1 ? 1 : (int)live;
-}
-
-static int decode_slices(int n, int live, int n_cu) {
-  const int nkb = n / 16;
-  int S = n_cu / live;   // rounded down: a unit that gets two tasks runs both at half the rate
-  const int s_min = (nkb + DZ_MAXSLICE - 1) / DZ_MAXSLICE;
-  if (S < s_min) S = s_min;
-  if (S > DEC_MAX_SLICES) S = DEC_MAX_SLICES;   // decode_supported() keeps the slice within DZ_MAXSLICE
-  if (S > nkb) S = nkb;
-  if (S < 1) S = 1;
-  return S;
-}
-
-static size_t dec_zp_bytes(const parse_layer *L) {
-  const int nquads = (L->R / 32 + 3) / 4;
-  return round_up((size_t)DEC_MAX_SLICES * nquads * 4096 * sizeof(float), 256);
-}
-static size_t dec_zf_bytes(const parse_layer *L) {
-  const int nquads = (L->R / 32 + 3) / 4;
-  return round_up((size_t)nquads * 4096 * sizeof(uint16_t), 256);
-}
-
-size_t decode_workspace_bytes(const parse_layer *L) {
-  return dec_zp_bytes(L) + dec_zf_bytes(L) + round_up((DEC_MAXG + 1) * sizeof(int32_t), 256);
-}
+// workspace of one layer: z in operand order (R/16 operands of 1 KiB)
+static size_t dec_zf_bytes(const parse_layer *L) { return round_up((size_t)(L->R / 16) * 1024, 256); }
+size_t decode_plan_bytes(int n_layers) { return round_up((size_t)n_layers * DEC_PLAN_WORDS * sizeof(int32_t), 256); }
+// z of the layer, then room for a one-layer plan (used when the caller brings no plan)
+size_t decode_workspace_bytes(const parse_layer *L) { return dec_zf_bytes(L) + decode_plan_bytes(1); }
 
 bool decode_supported(const parse_layer *L) {
-  const int s_min = (L->n / 16 + DZ_MAXSLICE - 1) / DZ_MAXSLICE;
-  return s_min <= DEC_MAX_SLICES && L->R / 16 <= DY_MAXKB && L->G <= DEC_MAXG;
+  return L->R / 16 <= DY_MAXKB && L->G <= DEC_MAXG && L->n % 16 == 0 && L->n >= 16;
 }
 
-// n_layers layers that share x (same n); Y[l] and the workspace part of layer l follow the order of `layers`.
-int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *pts, int n_layers, const uint16_t *x,
-                              int B, const int32_t *pattern_id, uint16_t *const *Y, void *workspace, hipStream_t s) {
+int build_decode_plan(const parse_layer *layers, const parse_patterns *pts, int n_layers, const int32_t *pattern_id,
+                      int B, int32_t *plan, hipStream_t s) {
+  if (n_layers < 1 || n_layers > DEC_MAX_LAYERS) return PARSE_ESHAPE;
+  DecPlanArgs pa{};
+  for (int l = 0; l < n_layers; ++l) {
+    pa.subsets[l] = pts[l].subsets; pa.stride[l] = pts[l].subset_stride; pa.k[l] = pts[l].k;
+    pa.n_patterns[l] = pts[l].n_patterns; pa.G[l] = layers[l].G;
+  }
+  pa.pattern_id = pattern_id; pa.B = B; pa.plan = plan;
+  hipLaunchKernelGGL(decode_plan_build, dim3(n_layers), dim3(64), 0, s, pa);
+  PARSE_LAUNCH_CHECK();
+  return PARSE_OK;
+}
+
+// n_layers layers that share x (same n); plan = n_layers consecutive layer plans; Y[l] and the z part of layer l in the
+// workspace follow the order of `layers`.
+int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const uint16_t *x, int B, const int32_t *plan,
+                                uint16_t *const *Y, void *workspace, hipStream_t s) {
   if (n_layers < 1 || n_layers > DEC_MAX_LAYERS) return PARSE_ESHAPE;
   static int n_cu_of[64] = {0};
   int dev = 0;
@@ -415,18 +365,14 @@ int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *p
   DecArgs a{};
   a.n_layers = n_layers;
   a.x = x;
-  a.pattern_id = pattern_id;
   a.B = B;
   a.n = layers[0].n;
-  int live = 0;
   for (int l = 0; l < n_layers; ++l) {
     if (!decode_supported(&layers[l])) return PARSE_ESHAPE;
     if (layers[l].n != a.n) return PARSE_ESHAPE;
-    live += live_quads_bound(&layers[l], &pts[l]);
   }
-  a.S = decode_slices(a.n, live, n_cu);
   // column blocks per workgroup (one z operand feeds NC products): the smallest count that puts at most one
-  // workgroup on a compute unit -- a unit with two streams at half the rate and sets the kernel's time
+  // workgroup on a compute unit -- a unit with two streams runs both at half the rate and sets the kernel's time
   int NC = 1;
   for (; NC < 4; ++NC) {
     int wgs = 0;
@@ -434,30 +380,21 @@ int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *p
     if (wgs <= n_cu) break;
   }
   char *ws = reinterpret_cast<char *>(workspace);
-  int zb = 0, fb = 0, yb = 0;
+  int zb = 0, yb = 0;
   for (int l = 0; l < n_layers; ++l) {
     const parse_layer *L = &layers[l];
     DecLayer &d = a.L[l];
     d.Vt = (const uint16_t *)L->Vt;
     d.Ut = (const uint16_t *)L->Ut;
     d.y = Y[l];
-    d.subsets = pts[l].subsets;
-    d.stride = pts[l].subset_stride;
-    d.k = pts[l].k;
-    d.n_patterns = pts[l].n_patterns;
-    d.zp = reinterpret_cast<float *>(ws);
-    d.zf = reinterpret_cast<uint16_t *>(ws + dec_zp_bytes(L));
-    d.used = reinterpret_cast<int32_t *>(ws + dec_zp_bytes(L) + dec_zf_bytes(L));
-    ws += decode_workspace_bytes(L);
+    d.zf = reinterpret_cast<uint16_t *>(ws);
+    ws += dec_zf_bytes(L);
+    d.plan = plan + (size_t)l * DEC_PLAN_WORDS;
     d.R = L->R; d.G = L->G; d.gs = L->R / L->G; d.m = L->m;
-    const int nquads = (L->R / 32 + 3) / 4, ncb = L->m / 32;
-    d.z_first = zb; zb += nquads * a.S;
-    d.f_first = fb; fb += nquads * 8;
-    d.y_first = yb; yb += (ncb + NC - 1) / NC;
+    d.z_first = zb; zb += L->R / 32;
+    d.y_first = yb; yb += (L->m / 32 + NC - 1) / NC;
   }
-  hipLaunchKernelGGL(decode_z, dim3(zb), dim3(DZ_THREADS), 0, s, a);
-  PARSE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(decode_zfin, dim3(fb), dim3(64), 0, s, a);
+  hipLaunchKernelGGL(decode_zf, dim3(zb), dim3(DZ_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   if (NC == 1) hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   else if (NC == 2) hipLaunchKernelGGL(decode_y<2>, dim3(yb), dim3(DY_THREADS), 0, s, a);
@@ -465,6 +402,23 @@ int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *p
   else hipLaunchKernelGGL(decode_y<4>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
+}
+
+// z workspace of several layers laid end to end (what forward_decode_planned_bf16 walks)
+size_t decode_z_bytes(const parse_layer *layers, int n_layers) {
+  size_t t = 0;
+  for (int l = 0; l < n_layers; ++l) t += dec_zf_bytes(&layers[l]);
+  return t;
+}
+
+// Without a caller's plan: the plan is built into the workspace (after the z parts), one more small launch.
+int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *pts, int n_layers, const uint16_t *x,
+                              int B, const int32_t *pattern_id, uint16_t *const *Y, void *workspace, hipStream_t s) {
+  if (n_layers < 1 || n_layers > DEC_MAX_LAYERS) return PARSE_ESHAPE;
+  int32_t *plan = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(workspace) + decode_z_bytes(layers, n_layers));
+  int st = build_decode_plan(layers, pts, n_layers, pattern_id, B, plan, s);
+  if (st != PARSE_OK) return st;
+  return forward_decode_planned_bf16(layers, n_layers, x, B, plan, Y, workspace, s);
 }
 
 int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *x, int B,

@@ -21,6 +21,13 @@ int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, 
                                  hipStream_t s);
 size_t prefill_lds_bytes(int BM, int rS);
 size_t decode_workspace_bytes(const parse_layer *L);
+size_t decode_plan_bytes(int n_layers);
+size_t decode_z_bytes(const parse_layer *layers, int n_layers);
+bool decode_supported(const parse_layer *L);
+int build_decode_plan(const parse_layer *layers, const parse_patterns *pts, int n_layers, const int32_t *pattern_id,
+                      int B, int32_t *plan, hipStream_t s);
+int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const uint16_t *x, int B, const int32_t *plan,
+                                uint16_t *const *Y, void *workspace, hipStream_t s);
 int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *pts, int n_layers, const uint16_t *x,
                               int B, const int32_t *pattern_id, uint16_t *const *Y, void *workspace, hipStream_t s);
 int forward_decode_bf16(const parse_layer *L, const parse_patterns *pt, const uint16_t *x, int B,
@@ -157,6 +164,66 @@ int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *
   if (!aligned16(workspace)) return PARSE_EALIGN;
   return forward_decode_multi_bf16(layers, patterns, n_layers, (const uint16_t *)X, rows, pattern_id,
                                    (uint16_t *const *)Y, workspace, (hipStream_t)stream);
+}
+
+// checks shared by the decode entry points that take several layers
+static int check_decode_layers(const parse_layer *layers, int32_t n_layers) {
+  if (!layers || n_layers < 1) return PARSE_EINVAL;
+  if (n_layers > 4) return PARSE_ESHAPE;
+  for (int l = 0; l < n_layers; ++l) {
+    int st = check_layer(&layers[l]);
+    if (st != PARSE_OK) return st;
+    if (layers[l].dtype != PARSE_BF16 || layers[l].layout != PARSE_MFMA16) return PARSE_ELAYOUT;
+    if (layers[l].G > 64 || layers[l].n != layers[0].n || !decode_supported(&layers[l])) return PARSE_ESHAPE;
+  }
+  return PARSE_OK;
+}
+
+size_t parse_decode_plan_bytes(int32_t n_layers) {
+  if (n_layers < 1 || n_layers > 4) return 0;
+  return decode_plan_bytes(n_layers);
+}
+
+int parse_decode_plan(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
+                      const int32_t *pattern_id, int32_t rows, void *plan, size_t plan_bytes, parse_stream stream) {
+  if (!patterns || !pattern_id || !plan) return PARSE_EINVAL;
+  int st = check_decode_layers(layers, n_layers);
+  if (st != PARSE_OK) return st;
+  if (rows <= 0) return PARSE_EINVAL;
+  if (rows > 32) return PARSE_ESHAPE;
+  for (int l = 0; l < n_layers; ++l) {
+    if (!patterns[l].subsets || patterns[l].n_patterns <= 0 || patterns[l].k <= 0) return PARSE_EINVAL;
+    if (patterns[l].k > layers[l].G || patterns[l].subset_stride < patterns[l].k) return PARSE_ESHAPE;
+  }
+  if (!aligned16(plan)) return PARSE_EALIGN;
+  if (plan_bytes < decode_plan_bytes(n_layers)) return PARSE_EWORKSPACE;
+  return build_decode_plan(layers, patterns, n_layers, pattern_id, rows, (int32_t *)plan, (hipStream_t)stream);
+}
+
+size_t parse_lowrank_decode_planned_workspace_bytes(const parse_layer *layers, int32_t n_layers) {
+  if (!layers || n_layers < 1 || n_layers > 4) return 0;
+  for (int l = 0; l < n_layers; ++l)
+    if (layers[l].G <= 0 || layers[l].R <= 0) return 0;
+  return decode_z_bytes(layers, n_layers);
+}
+
+int parse_lowrank_decode_planned(const parse_layer *layers, int32_t n_layers, const void *X, int32_t rows,
+                                 const void *plan, void *const *Y, void *workspace, size_t workspace_bytes,
+                                 parse_stream stream) {
+  if (!X || !plan || !Y) return PARSE_EINVAL;
+  int st = check_decode_layers(layers, n_layers);
+  if (st != PARSE_OK) return st;
+  if (rows <= 0) return PARSE_EINVAL;
+  if (rows > 32) return PARSE_ESHAPE;
+  if (!aligned16(X) || !aligned16(plan)) return PARSE_EALIGN;
+  for (int l = 0; l < n_layers; ++l) {
+    if (!Y[l]) return PARSE_EINVAL;
+    if (!aligned16(Y[l])) return PARSE_EALIGN;
+  }
+  if (!workspace || workspace_bytes < decode_z_bytes(layers, n_layers)) return PARSE_EWORKSPACE;
+  if (!aligned16(workspace)) return PARSE_EALIGN;
+  return forward_decode_planned_bf16(layers, n_layers, (const uint16_t *)X, rows, (const int32_t *)plan,
+                                     (uint16_t *const *)Y, workspace, (hipStream_t)stream);
 }
 
 size_t parse_lowrank_prefill_multi_workspace_bytes(const parse_layer *layers, const parse_patterns *patterns,

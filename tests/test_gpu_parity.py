@@ -482,6 +482,63 @@ def test_decode_matches_oracle_and_prefill(n, m, R, G, k, B, npat, schedule):
     _decode_case(n, m, R, G, k, B, npat)
 
 
+def test_decode_plan_contents_and_planned_step():
+    """The decode plan (group masks, ascending list of used groups) against a plain restatement from the subsets, and the
+    planned two-launch step: bit-identical to the ordinary calls (which build the same plan inside), on two layers that
+    share x, with guard bytes around the outputs and the intermediate workspace."""
+    say("decode plan: masks / used list; planned step = ordinary step bit for bit")
+    n, B, npat = 1024, 29, 5
+    shapes = [(1536, 640, 20, 10), (512, 256, 8, 3)]
+    rng = np.random.default_rng(611)
+    seq_pat = rng.integers(0, npat, size=B).astype(np.int32)
+    seq_pat[3] = 77                                            # an invalid pattern id: that sequence gets zeros
+    x = si.make_tokens(rng, B, n, "bf16")
+    xd, pid = upload_tokens(x, "bf16"), i32(seq_pat)
+    layers, pats, subs_h = [], [], []
+    for i, (m, R, G, k) in enumerate(shapes):
+        lay = si.make_layer(np.random.default_rng(612 + i), n, m, R, G, "bf16")
+        sub = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(npat)]).astype(np.int32)
+        layers.append(pa.layer_to_mfma16(upload_layer(lay))); subs_h.append((lay, sub, G, k))
+        pats.append(pa.Patterns(k, npat, subsets=i32(sub)))
+    plan = pa.decode_plan(layers, pats, pid)
+    torch.cuda.synchronize()
+    words = plan.view(torch.int32).cpu().numpy()
+    for li, (lay, sub, G, k) in enumerate(subs_h):
+        w = words[li * 192:(li + 1) * 192]
+        masks = np.zeros(64, np.uint32)
+        for b in range(B):
+            if 0 <= seq_pat[b] < npat:
+                for g in sub[seq_pat[b]]:
+                    masks[g] |= np.uint32(1 << b)
+        used = [g for g in range(G) if masks[g]]
+        assert int(w[0]) == len(used) and w[1:1 + len(used)].tolist() == used and np.all(w[1 + len(used):65] == -1)
+        assert np.array_equal(w[65:129].view(np.uint32), masks)
+    # planned step between guards
+    def guarded(rows, cols):
+        buf = torch.full((rows + 2, cols), 5.0, dtype=torch.bfloat16, device=DEV)
+        return buf, buf[1:1 + rows]
+    bufs = [guarded(B, m) for (m, R, G, k) in shapes]
+    need = pa.lowrank_decode_planned_workspace_bytes(layers)
+    wsbuf = torch.full((need + 512,), 0x5A, dtype=torch.uint8, device=DEV)
+    pa.lowrank_decode_planned(layers, xd, plan, [v for _, v in bufs], wsbuf[256:256 + need])
+    ys_multi = pa.lowrank_decode_multi(layers, pats, xd, pid)
+    torch.cuda.synchronize()
+    assert torch.all(wsbuf[:256] == 0x5A) and torch.all(wsbuf[256 + need:] == 0x5A), "stores outside the workspace"
+    for li, (lay, sub, G, k) in enumerate(subs_h):
+        buf, view = bufs[li]
+        assert torch.all(buf[0] == 5.0) and torch.all(buf[-1] == 5.0), "stores outside Y"
+        y_single = pa.lowrank_forward(pa.PARSE_DECODE, layers[li], pats[li], xd, None, pid)
+        torch.cuda.synchronize()
+        assert torch.equal(view.view(torch.int16), ys_multi[li].view(torch.int16))
+        assert torch.equal(view.view(torch.int16), y_single.view(torch.int16))
+        U0, sg, V = oracle_factors(lay)
+        ok = np.flatnonzero((seq_pat >= 0) & (seq_pat < npat))
+        Yo = po.decode_step(U0, sg, V, lay.gs, si.bf16_bits_to_f32(x[ok]).astype(np.float64), sub[seq_pat[ok]])
+        yn = view.float().cpu().numpy().astype(np.float64)
+        assert_close(yn[ok], Yo, TOL_BF16, f"layer {li}")
+        assert np.all(yn[3] == 0), "a sequence with an invalid pattern id must get zeros"
+
+
 def _decode_case(n, m, R, G, k, B, npat):
     lay = si.make_layer(np.random.default_rng(601), n, m, R, G, "bf16", fast=(R > 1024))
     rng = np.random.default_rng(602)
