@@ -28,12 +28,12 @@ namespace parse {
 constexpr int DZ_WAVES = 8, DZ_THREADS = DZ_WAVES * 64;
 constexpr int DY_WAVES = 8, DY_THREADS = DY_WAVES * 64;
 constexpr int DEC_MAXG = 64;
-constexpr int DZ_CH = 256;                 // columns of x staged per chunk
-constexpr int DZ_CH_KB = DZ_CH / 16;       // reduction steps per chunk (16)
-constexpr int DZ_WKB = DZ_CH_KB / DZ_WAVES;   // reduction steps per wavefront per chunk (2)
-constexpr int DZ_XBYTES = 32 * DZ_CH * 2;  // x part of a staged chunk: 32 rows x 512 bytes
-constexpr int DZ_BUF = DZ_XBYTES + DZ_CH_KB * 1024;   // + the chunk's 16 Vt operands = 32 KiB
-constexpr int DZ_NBUF = 4;
+constexpr int DZ_CH = 256;                 // columns staged per chunk: 32 per wavefront (one 16x16x32 or two 32x32x16 steps)
+constexpr int DZ32_CH_KB = DZ_CH / 16;     // 32-rank form: reduction steps per chunk (16)
+constexpr int DZ32_WKB = DZ32_CH_KB / DZ_WAVES;   // per wavefront (2)
+constexpr int DZ32_XBYTES = 32 * DZ_CH * 2;       // x part of a staged chunk: 32 rows x 512 bytes
+constexpr int DZ32_BUF = DZ32_XBYTES + DZ32_CH_KB * 1024;   // + the chunk's 16 Vt operands = 32 KiB
+constexpr int DZ32_NBUF = 4;
 constexpr int DY_CHUNK = 4;                // decode_y: operands per chunk after the first block
 constexpr int DY_MAXKB = 1024;             // selected reduction blocks a decode_y workgroup can list
 constexpr int DEC_MAX_LAYERS = 4;
@@ -99,13 +99,14 @@ __global__ __launch_bounds__(64) void decode_plan_build(DecPlanArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// decode_zf.  grid = sum over layers of R/32; workgroup = (layer, 32-rank block rb).
-// Everything the loop reads from memory goes straight into LDS (loads that write LDS directly), DZ_NBUF chunks in
+// decode_zf32.  grid = sum over layers of R/32; workgroup = (layer, 32-rank block rb): the form for calls with many
+// rank blocks (the x rows are re-read once per workgroup, so wider blocks mean less traffic).
+// Everything the loop reads from memory goes straight into LDS (loads that write LDS directly), DZ32_NBUF chunks in
 // rotation, so the only waits in the loop are the explicit ones below: per chunk of 256 columns the 32 x rows
 // (512 bytes each, their 16-byte pieces XOR-swizzled by the row so that an operand read -- 32 rows x the same piece --
 // spreads over the banks) and the 16 Vt operands of the rank block (two per wavefront, which that wavefront alone
 // reads back).  The LDS is reused for the wavefronts' partial sums at the end.
-__global__ __launch_bounds__(DZ_THREADS) void decode_zf(DecArgs a) {
+__global__ __launch_bounds__(DZ_THREADS) void decode_zf32(DecArgs a) {
   int li = 0;
 #pragma unroll
   for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].z_first) ? 1 : 0;
@@ -114,12 +115,12 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_zf(DecArgs a) {
   const int n = a.n, B = a.B, gs = ly.gs;
   const uint32_t mask = (uint32_t)ly.plan[65 + (rb * 32) / gs];     // sequences whose pattern holds this block's group
   if (mask == 0u) return;                                            // nobody selected it: nothing is read or written
-  __shared__ __attribute__((aligned(1024))) char xs[DZ_NBUF * DZ_BUF];
+  __shared__ __attribute__((aligned(1024))) char xs[DZ32_NBUF * DZ32_BUF];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int j = lane & 31, q = lane >> 5;
   const int nkb = n / 16;
-  const int nch = (nkb + DZ_CH_KB - 1) / DZ_CH_KB;
+  const int nch = (nkb + DZ32_CH_KB - 1) / DZ32_CH_KB;
   // x: 16 instructions of 1 KiB (two rows of 512 bytes each) per chunk, two per wavefront.  Lane l writes slot l % 32
   // of row 2*ins + l / 32 and fetches the piece (slot ^ (row & 15)) of that row's chunk; pieces past the end of the row
   // re-read its last one (their products are switched off below).
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_zf(DecArgs a) {
   // Vt: operands (rb, kb) are contiguous in kb; this wavefront owns steps wave*2 + (0, 1) of every chunk
   const char *vbase = (const char *)ly.Vt + ((size_t)rb * nkb) * 1024 + lane * 16;
   auto issue = [&](int c) {
-    char *buf = xs + (c % DZ_NBUF) * DZ_BUF;
+    char *buf = xs + (c % DZ32_NBUF) * DZ32_BUF;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int piece = min(c * (DZ_CH / 8) + xslot[i], last_piece);
@@ -143,37 +144,37 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_zf(DecArgs a) {
                                        PARSE_DEC_LDS_PTR(buf + (wave * 2 + i) * 1024), 16, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < DZ_WKB; ++i) {
-      const int kb = min(c * DZ_CH_KB + wave * DZ_WKB + i, nkb - 1);
+    for (int i = 0; i < DZ32_WKB; ++i) {
+      const int kb = min(c * DZ32_CH_KB + wave * DZ32_WKB + i, nkb - 1);
       __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(vbase + (size_t)kb * 1024),
-                                       PARSE_DEC_LDS_PTR(buf + DZ_XBYTES + (wave * DZ_WKB + i) * 1024), 16, 0, 0);
+                                       PARSE_DEC_LDS_PTR(buf + DZ32_XBYTES + (wave * DZ32_WKB + i) * 1024), 16, 0, 0);
     }
   };
   f32x16 acc;
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   const u32x4 zero = {0, 0, 0, 0};
-  constexpr int LPC = 2 + DZ_WKB;          // loads per chunk per wavefront
+  constexpr int LPC = 2 + DZ32_WKB;          // loads per chunk per wavefront
 #pragma unroll
-  for (int c = 0; c < DZ_NBUF - 1; ++c)
+  for (int c = 0; c < DZ32_NBUF - 1; ++c)
     if (c < nch) issue(c);
   for (int c = 0; c < nch; ++c) {
     // chunk c has landed when only the chunks requested after it are outstanding
-    const int later = min(c + DZ_NBUF - 2, nch - 1) - c;
+    const int later = min(c + DZ32_NBUF - 2, nch - 1) - c;
     if (later >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPC) : "memory");
     else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPC) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();          // everybody's x rows of chunk c are in LDS; everybody is done with chunk c-1
     asm volatile("" ::: "memory");
-    if (c + DZ_NBUF - 1 < nch) issue(c + DZ_NBUF - 1);
-    const char *buf = xs + (c % DZ_NBUF) * DZ_BUF;
+    if (c + DZ32_NBUF - 1 < nch) issue(c + DZ32_NBUF - 1);
+    const char *buf = xs + (c % DZ32_NBUF) * DZ32_BUF;
 #pragma unroll
-    for (int i = 0; i < DZ_WKB; ++i) {
-      const int kl = wave * DZ_WKB + i;                       // reduction step within the chunk
+    for (int i = 0; i < DZ32_WKB; ++i) {
+      const int kl = wave * DZ32_WKB + i;                       // reduction step within the chunk
       const u32x4 xv = *reinterpret_cast<const u32x4 *>(buf + j * (DZ_CH * 2) + (((kl * 2 + q) ^ (j & 15)) * 16));
-      const u32x4 vv = *reinterpret_cast<const u32x4 *>(buf + DZ_XBYTES + kl * 1024 + lane * 16);
-      const bool live = c * DZ_CH_KB + kl < nkb;              // steps past the end of n contribute nothing
+      const u32x4 vv = *reinterpret_cast<const u32x4 *>(buf + DZ32_XBYTES + kl * 1024 + lane * 16);
+      const bool live = c * DZ32_CH_KB + kl < nkb;              // steps past the end of n contribute nothing
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(vv), dec_bf16x8(live ? xv : zero), acc, 0, 0, 0);
     }
   }
@@ -205,6 +206,180 @@ __global__ __launch_bounds__(DZ_THREADS) void decode_zf(DecArgs a) {
       const u32x2 sy = __builtin_amdgcn_permlane32_swap(p0y, p1y, false, false);
       *reinterpret_cast<u32x4 *>((char *)ly.zf + (size_t)(rb * 2 + h) * 1024 + lane * 16) = u32x4{sx[0], sy[0], sx[1], sy[1]};
     }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// decode_zf<NSB>.  Workgroup = (layer, 16-rank block, NSB 16-sequence blocks): NSB = 2 takes all 32 sequences, NSB = 1
+// half of them (twice the workgroups; used for long reductions, where the rank blocks alone are too few to keep the
+// chip's memory pipes full).  16 ranks x 16 sequences is one 16x16x32 matrix instruction per 32 columns.
+// Everything the loop reads from memory goes straight into LDS (loads that write LDS directly), NBUF chunks of 256
+// columns in rotation, NBUF-1 in flight, so the only waits in the loop are the explicit ones: per chunk the x rows
+// (512 bytes each, their 16-byte pieces XOR-swizzled by the row so that an operand read -- 16 rows x the same piece --
+// spreads over the banks) and the block's Vt operands, 1 KiB per wavefront, which that wavefront alone reads back.
+// A 16-rank half of a 32-rank operand block of the store is the lanes' 16-byte pieces (q*32 + 16*half + row): lane
+// (row, kg) of the 16x16x32 instruction takes piece ((kg & 1)*32 + 16*half + row) of operand kb0 + (kg >> 1).
+// The LDS is reused for the wavefronts' partial sums at the end.
+template <int NSB>
+__global__ __launch_bounds__(DZ_THREADS) void decode_zf(DecArgs a) {
+  constexpr int SPLIT = 2 / NSB;                       // workgroups per rank block
+  constexpr int XB = NSB * 16 * DZ_CH * 2;             // x part of a chunk
+  constexpr int BUF = XB + DZ_WAVES * 1024;            // + one Vt operand per wavefront
+  constexpr int NBUF = NSB == 2 ? 6 : 8;               // 144 KiB / 128 KiB
+  constexpr int LPC = NSB + 1;                         // loads per chunk per wavefront
+  int li = 0;
+#pragma unroll
+  for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].z_first) ? 1 : 0;
+  const DecLayer &ly = a.L[li];
+  const int bid = blockIdx.x - ly.z_first;
+  const int rb16 = bid / SPLIT, sh = bid % SPLIT;      // 16-rank block, sequence half (NSB == 1)
+  const int n = a.n, B = a.B, gs = ly.gs;
+  const uint32_t mask = (uint32_t)ly.plan[65 + (rb16 * 16) / gs];   // sequences whose pattern holds this block's group
+  const uint32_t mine = NSB == 2 ? 0xFFFFFFFFu : (0xFFFFu << (16 * sh));
+  if ((mask & mine) == 0u) {
+    // none of this workgroup's sequences selected the group.  If other sequences did, decode_y will read the whole
+    // operand: this half of it must be zeros (the workspace may hold anything).
+    if (mask != 0u && threadIdx.x < 32) {
+      const int q = threadIdx.x >> 4, jj = threadIdx.x & 15;
+      *reinterpret_cast<u32x4 *>((char *)ly.zf + (size_t)rb16 * 1024 + (q * 32 + sh * 16 + jj) * 16) = u32x4{0, 0, 0, 0};
+    }
+    return;
+  }
+  __shared__ __attribute__((aligned(1024))) char xs[NBUF * BUF];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int r16 = lane & 15, kg = lane >> 4;
+  const int nkb = n / 16;                              // 16-column operands per rank block in the store
+  const int nch = (n + DZ_CH - 1) / DZ_CH;
+  // x: NSB*8 instructions of 1 KiB (two rows of 512 bytes) per chunk, NSB per wavefront.  Lane l writes slot l % 32 of
+  // local row 2*ins + l / 32 and fetches the piece (slot ^ (row & 15)) of that row's chunk; pieces past the end of the
+  // row re-read its last one (their products are switched off below).
+  const char *xrow[NSB];
+  int xslot[NSB];
+#pragma unroll
+  for (int i = 0; i < NSB; ++i) {
+    const int lr = (wave + i * DZ_WAVES) * 2 + (lane >> 5);          // local row 0 .. NSB*16-1
+    const int r = sh * 16 + lr;                                      // sequence
+    xrow[i] = (const char *)a.x + (size_t)min(r, B - 1) * n * 2;
+    xslot[i] = (lane & 31) ^ (lr & 15);
+  }
+  const int last_piece = n / 8 - 1;
+  // Vt: this wavefront owns the 32 columns [c*256 + wave*32, +32) of every chunk = operands kb0, kb0+1 of the 32-rank block
+  const char *vbase = (const char *)ly.Vt + ((size_t)(rb16 >> 1) * nkb) * 1024 + ((kg & 1) * 32 + (rb16 & 1) * 16 + r16) * 16;
+  // general form (any chunk; clamps at the end of the rows) and running-pointer form (whole chunks in sequence)
+  auto issue_at = [&](int c, char *buf) {
+#pragma unroll
+    for (int i = 0; i < NSB; ++i) {
+      const int piece = min(c * (DZ_CH / 8) + xslot[i], last_piece);
+      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(xrow[i] + (size_t)piece * 16),
+                                       PARSE_DEC_LDS_PTR(buf + (wave + i * DZ_WAVES) * 1024), 16, 0, 0);
+    }
+    const int kb = min(c * (DZ_CH / 16) + wave * 2 + (kg >> 1), nkb - 1);
+    __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(vbase + (size_t)kb * 1024), PARSE_DEC_LDS_PTR(buf + XB + wave * 1024), 16, 0, 0);
+  };
+  const char *xp[NSB], *vp;
+  auto seek = [&](int c) {                 // running pointers at chunk c
+#pragma unroll
+    for (int i = 0; i < NSB; ++i) xp[i] = xrow[i] + ((size_t)c * (DZ_CH / 8) + xslot[i]) * 16;
+    vp = vbase + ((size_t)c * (DZ_CH / 16) + wave * 2 + (kg >> 1)) * 1024;
+  };
+  auto issue_next = [&](char *buf) {       // the chunk at the running pointers (must be a whole chunk), then advance
+#pragma unroll
+    for (int i = 0; i < NSB; ++i) {
+      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(xp[i]), PARSE_DEC_LDS_PTR(buf + (wave + i * DZ_WAVES) * 1024), 16, 0, 0);
+      xp[i] += DZ_CH * 2;
+    }
+    __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(vp), PARSE_DEC_LDS_PTR(buf + XB + wave * 1024), 16, 0, 0);
+    vp += (DZ_CH / 16) * 1024;
+  };
+  f32x4 acc[NSB];
+#pragma unroll
+  for (int i = 0; i < NSB; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const u32x4 zero = {0, 0, 0, 0};
+  // this lane's LDS read offsets within a chunk buffer
+  int xoff[NSB];
+#pragma unroll
+  for (int i = 0; i < NSB; ++i) {
+    const int lr = i * 16 + r16;
+    xoff[i] = lr * (DZ_CH * 2) + (((wave * 4 + kg) ^ (lr & 15)) * 16);
+  }
+  const int voff = XB + wave * 1024 + lane * 16;
+  auto compute = [&](const char *buf, bool live) {
+    const u32x4 vv = *reinterpret_cast<const u32x4 *>(buf + voff);
+#pragma unroll
+    for (int i = 0; i < NSB; ++i) {
+      const u32x4 xv = *reinterpret_cast<const u32x4 *>(buf + xoff[i]);
+      acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dec_bf16x8(vv), dec_bf16x8(live ? xv : zero), acc[i], 0, 0, 0);
+    }
+  };
+  auto barrier = [&]() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();          // everybody's x rows of the chunk are in LDS; everybody is done with the previous one
+    asm volatile("" ::: "memory");
+  };
+  const int nfull = n / DZ_CH;             // whole chunks; a last partial one goes through the general form
+  // prologue: NBUF-1 chunks requested
+#pragma unroll
+  for (int c = 0; c < NBUF - 1; ++c)
+    if (c < nch) issue_at(c, xs + c * BUF);
+  int c = 0;
+  seek(NBUF - 1);
+  // steady state, unrolled over the buffers: chunk c is awaited with exactly NBUF-2 later chunks outstanding, and the
+  // chunk NBUF-1 ahead (a whole one) is requested into the buffer that the barrier has just freed
+  while (c + NBUF - 1 + NBUF <= nfull) {
+#pragma unroll
+    for (int u = 0; u < NBUF; ++u) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NBUF - 2) * LPC) : "memory");
+      barrier();
+      issue_next(xs + ((u + NBUF - 1) % NBUF) * BUF);
+      compute(xs + u * BUF, true);
+    }
+    c += NBUF;
+  }
+  // the rest (at most 2*NBUF-2 chunks): general form
+  for (; c < nch; ++c) {
+    const int later = min(c + NBUF - 2, nch - 1) - c;
+    switch (later) {
+      case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+      case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(1 * LPC) : "memory"); break;
+      case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPC) : "memory"); break;
+      case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LPC) : "memory"); break;
+      case 4: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * LPC) : "memory"); break;
+      case 5: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(5 * LPC) : "memory"); break;
+      default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(6 * LPC) : "memory"); break;
+    }
+    barrier();
+    if (c + NBUF - 1 < nch) issue_at(c + NBUF - 1, xs + ((c + NBUF - 1) % NBUF) * BUF);
+    compute(xs + (c % NBUF) * BUF, c * DZ_CH + wave * 32 + kg * 8 < n);
+  }
+  __syncthreads();        // the staged chunks are dead: their LDS now takes the wavefronts' partial sums
+  float(*red)[NSB][4][64] = reinterpret_cast<float(*)[NSB][4][64]>(xs);     // [8][NSB][4][64] floats
+#pragma unroll
+  for (int i = 0; i < NSB; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[wave][i][e][lane] = acc[i][e];
+  __syncthreads();
+  // accumulator lane (col = l % 16, g = l / 16) holds ranks 4g + (0..3) of sequence col.  Thread (q, jj) gathers the 8
+  // consecutive ranks 8q + (0..7) of its sequence, each summed over the wavefronts in wavefront order: one 16-byte
+  // piece of z operand rb16 (its reduction block in the second product).
+  if (threadIdx.x < NSB * 32) {
+    const int q = threadIdx.x / (NSB * 16), jj = threadIdx.x % (NSB * 16);
+    const int sb = jj >> 4, col = jj & 15;
+    const int seq = sh * 16 + jj;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int g = 2 * q + (e >> 2), ln = g * 16 + col;
+      float sum = red[0][sb][e & 3][ln];
+#pragma unroll
+      for (int w = 1; w < DZ_WAVES; ++w) sum += red[w][sb][e & 3][ln];
+      v[e] = sum;
+    }
+    const bool member = (mask >> seq) & 1u;       // a sequence outside the group's mask gets zeros
+    u32x4 w4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w4[e] = member ? cvt_pk_bf16(v[2 * e], v[2 * e + 1]) : 0u;
+    *reinterpret_cast<u32x4 *>((char *)ly.zf + (size_t)rb16 * 1024 + (q * 32 + seq) * 16) = w4;
   }
 }
 
@@ -379,6 +554,11 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
     for (int l = 0; l < n_layers; ++l) wgs += (layers[l].m / 32 + NC - 1) / NC;
     if (wgs <= n_cu) break;
   }
+  // 32-rank workgroups when they alone give the chip enough streams (each workgroup re-reads the x rows, so wider blocks
+  // mean less traffic); 16-rank workgroups otherwise (twice as many, each with half the factor stream)
+  int blocks32 = 0;
+  for (int l = 0; l < n_layers; ++l) blocks32 += layers[l].R / 32;
+  const bool wide = 2 * blocks32 >= n_cu;
   char *ws = reinterpret_cast<char *>(workspace);
   int zb = 0, yb = 0;
   for (int l = 0; l < n_layers; ++l) {
@@ -391,10 +571,11 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
     ws += dec_zf_bytes(L);
     d.plan = plan + (size_t)l * DEC_PLAN_WORDS;
     d.R = L->R; d.G = L->G; d.gs = L->R / L->G; d.m = L->m;
-    d.z_first = zb; zb += L->R / 32;
+    d.z_first = zb; zb += wide ? L->R / 32 : L->R / 16;
     d.y_first = yb; yb += (L->m / 32 + NC - 1) / NC;
   }
-  hipLaunchKernelGGL(decode_zf, dim3(zb), dim3(DZ_THREADS), 0, s, a);
+  if (wide) hipLaunchKernelGGL(decode_zf32, dim3(zb), dim3(DZ_THREADS), 0, s, a);
+  else hipLaunchKernelGGL(decode_zf<2>, dim3(zb), dim3(DZ_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   if (NC == 1) hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   else if (NC == 2) hipLaunchKernelGGL(decode_y<2>, dim3(yb), dim3(DY_THREADS), 0, s, a);
