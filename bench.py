@@ -48,6 +48,9 @@ def parse_args():
     ap.add_argument("--stack", action="store_true",
                     help="also time the full 32-layer x 7-projection stack (prefill 1 x 2048 tokens, then decode steps)")
     ap.add_argument("--stack-decode-steps", type=int, default=64)
+    ap.add_argument("--stress", action="store_true",
+                    help="also run the pattern-cache / grouped-execution stress (256 ragged prompts, MLP-shaped layers)")
+    ap.add_argument("--only-stress", action="store_true")
     ap.add_argument("--no-decode-separate", action="store_true",
                     help="skip the comparison run that calls gate and up separately (counter runs use this)")
     return ap.parse_args()
@@ -457,6 +460,105 @@ def bench_stack(args, torch, pa, si):
             "launches_per_decode_step": NL * 4 * 3}
 
 
+def bench_stress(args, torch, pa, si):
+    """Pattern-cache and grouped-execution stress: 256 prompts whose embeddings come from 16 Gaussian clusters (4096-d,
+    spread 0.1), lengths uniform in 32..2048 tokens, MLP-shaped layers (gate, up: 4096->11008, down: 11008->4096, R=2560
+    in 20 groups, top-10), cosine threshold 0.9.  One pass = cache probe with route-on-miss for the three routed matrices
+    -> bucket -> aggregation of the new cache entries (per layer) -> prefill plan (rows grouped by pattern) -> planned
+    prefill of gate, up and down, all prompts of a pattern in the same tiles.  Factors are Gaussian bf16 generated on the
+    device (timing; parity at this size is covered by the tests); tokens are N(0,1)."""
+    import numpy as np
+    from oracle import parse_oracle as po
+    dev = "cuda"
+    E, cid, off_h, Wr_h = si.config4_embeddings()
+    P, d, G, k, R, hidden, inter, L = E.shape[0], E.shape[1], 20, 10, 2560, 4096, 11008, 3
+    gs, rS = R // G, k * (R // G)
+    rows = int(off_h[-1])
+    shapes = [("gate", hidden, inter), ("up", hidden, inter), ("down", inter, hidden)]
+    n_slots = 32
+    layers_rm, layers = [], []
+    for nm, n, m in shapes:
+        Vt = (torch.randn((R, n), device=dev) * 0.02).to(torch.bfloat16)
+        Ut = (torch.randn((R, m), device=dev) * 0.02).to(torch.bfloat16)
+        rm = pa.Layer(Vt, Ut, n, m, R, G, pa.PARSE_ROWMAJOR)
+        layers_rm.append(rm); layers.append(pa.layer_to_mfma16(rm))
+    Xh = torch.randn((rows, hidden), device=dev).to(torch.bfloat16)
+    Xi = torch.randn((rows, inter), device=dev).to(torch.bfloat16)
+    Ys = [torch.empty((rows, m), dtype=torch.bfloat16, device=dev) for _, _, m in shapes]
+    Ed, off, Wr = torch.from_numpy(E).to(dev), torch.from_numpy(off_h).to(dev), torch.from_numpy(Wr_h).to(dev)
+    cache = pa.Cache(n_slots, d, L, k, P)
+    entry = torch.empty(P, dtype=torch.int32, device=dev); hit = torch.empty(P, dtype=torch.uint8, device=dev)
+    sim = torch.empty(P, dtype=torch.float32, device=dev); subs = torch.empty((P, L, k), dtype=torch.int32, device=dev)
+    bucket_out = (torch.empty(P, dtype=torch.int32, device=dev), torch.empty(P, dtype=torch.int32, device=dev),
+                  torch.empty(P + 1, dtype=torch.int32, device=dev), torch.empty(1, dtype=torch.int32, device=dev),
+                  torch.empty(P, dtype=torch.int32, device=dev))
+    packed = [(torch.empty((n_slots, rS, n), dtype=torch.bfloat16, device=dev),
+               torch.empty((n_slots, rS, m), dtype=torch.bfloat16, device=dev)) for _, n, m in shapes]
+    pts = [pa.Patterns(k, n_slots, Vs, Us) for Vs, Us in packed]
+    plan = torch.empty(pa.prefill_plan_bytes(rows, P, n_slots), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(pa.lowrank_prefill_planned_workspace_bytes(l, rows, P, k, n_slots) for l in layers),
+                     dtype=torch.uint8, device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+
+    def one_pass():
+        ev[0].record()
+        cache.lookup_or_route(Ed, 0.9, Wr, entry, hit, sim, subs)
+        pa.bucket_patterns(subs.view(P, L * k), L * k, L * k, bucket_out)
+        ev[1].record()
+        for l in range(L):   # aggregation once per new cache entry and layer (slot = cache entry)
+            pa.pack_new_entries(layers[l], subs.view(P, L * k)[:, l * k:], L * k, k, entry, hit, packed[l][0], packed[l][1])
+        ev[2].record()
+        pa.prefill_plan(off, entry, rows, n_slots, plan)
+        ev[3].record()
+        pa.lowrank_prefill_planned(layers[0], pts[0], Xh, off, entry, plan, Ys[0], ws)   # gate and up read the same rows
+        pa.lowrank_prefill_planned(layers[1], pts[1], Xh, off, entry, plan, Ys[1], ws)
+        ev[4].record()
+        pa.lowrank_prefill_planned(layers[2], pts[2], Xi, off, entry, plan, Ys[2], ws)
+        ev[5].record()
+        torch.cuda.synchronize()
+        return [ev[i].elapsed_time(ev[i + 1]) for i in range(5)]
+
+    cold = one_pass()                                      # empty cache: one miss per cluster, 16 x 3 aggregations
+    hits_cold, entries = int(hit.sum().item()), cache.count()
+    assert torch.equal(subs.cpu(), torch.from_numpy(po.PatternCache(n_slots, d, L, k).lookup_or_route(E, 0.9, Wr_h)[2]))
+    warm = [one_pass() for _ in range(3)][-1]              # every prompt hits: nothing is routed or aggregated
+    hits_warm = int(hit.sum().item())
+    words = plan.view(torch.int32)[:4].cpu().numpy()
+    vrows = int(words[1])
+    flops = sum(2.0 * rows * rS * (n + m) for _, n, m in shapes)
+    fwd_ms = warm[3] + warm[4]
+    # the oracle on 4 prompts per layer (dense reconstruction and apply in float64), extrapolated by flop count
+    t0 = time.perf_counter(); done_flops = 0.0
+    sub_h = subs.cpu().numpy()
+    for l, (nm, n, m) in enumerate(shapes):
+        Vt = layers_rm[l].Vt.float().cpu().numpy().astype(np.float64); Ut = layers_rm[l].Ut.float().cpu().numpy().astype(np.float64)
+        Xsrc = Xh if n == hidden else Xi
+        for p in (0, 1, 2, 3):
+            a, b = int(off_h[p]), int(off_h[p + 1])
+            po.forward(Ut.T, np.ones(R), Vt, gs, Xsrc[a:b].float().cpu().numpy().astype(np.float64), [0, b - a], sub_h[p:p + 1, l])
+            done_flops += 2.0 * (b - a) * rS * (n + m)
+    dt = time.perf_counter() - t0
+    cache.close()
+    return {"workload": "config4: 256 prompts, 16 clusters (spread 0.1), lengths U{32..2048}, gate/up 4096->11008 and down "
+                        "11008->4096, R=2560 in 20 groups, top-10, tau=0.9; one pass = probe, bucket, aggregation, plan, "
+                        "planned prefill of the three layers",
+            "prompts": P, "tokens": rows, "cache_entries": entries, "hits_first_pass": hits_cold,
+            "hit_rate_first_pass": round(hits_cold / P, 4), "expected_hit_rate": round((P - 16) / P, 4),
+            "hits_warm_pass": hits_warm, "patterns": int(bucket_out[3].item()),
+            "launches_per_layer_forward": 2, "tokens_per_launch": rows,
+            "virtual_rows": vrows, "tile_padding_overhead": round(vrows / rows - 1.0, 4),
+            "first_pass_ms": {"probe+bucket": round(cold[0], 3), "aggregate_16x3": round(cold[1], 3), "plan": round(cold[2], 3),
+                              "gate+up": round(cold[3], 3), "down": round(cold[4], 3)},
+            "warm_pass_ms": {"probe+bucket": round(warm[0], 3), "aggregate": round(warm[1], 3), "plan": round(warm[2], 3),
+                             "gate+up": round(warm[3], 3), "down": round(warm[4], 3)},
+            "forward_TFLOPs": round(flops / (fwd_ms * 1e-3) / 1e12, 1),
+            "forward_frac_of_mfma_peak": round(flops / (fwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "pass_TFLOPs": round(flops / (sum(warm) * 1e-3) / 1e12, 1),
+            "cpu_baseline": {"value": round(done_flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": len(os.sched_getaffinity(0)),
+                             "kind": "oracle", "sample": f"4 prompts per layer, {dt:.1f} s; extrapolated to the whole pass: "
+                                                         f"{flops / (done_flops / dt):.0f} s"}}
+
+
 def cpu_baseline(w, flops):
     """The CPU oracle as it stands, timed on the host cores on the same workload (bounded sample)."""
     import numpy as np
@@ -504,6 +606,9 @@ def main():
     if args.only_decode:
         print(json.dumps({"decode": bench_decode(args, torch, pa, si)}))
         return
+    if args.only_stress:
+        print(json.dumps({"stress": bench_stress(args, torch, pa, si)}))
+        return
     pre = bench_prefill(args, torch, pa, si)
     w = pre.pop("workload")
     if not args.no_decode:
@@ -532,6 +637,8 @@ def main():
     }
     if stack is not None:
         line["stack"] = stack
+    if args.stress:
+        line["stress"] = bench_stress(args, torch, pa, si)
     print(json.dumps(line))
 
 

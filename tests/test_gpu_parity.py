@@ -155,6 +155,71 @@ def test_cache_clustered_workload_hit_rate():
     cache.close()
 
 
+def test_config4_grouped_execution_full_size_sampled():
+    """The pattern-cache / grouped-execution workload at full size: 256 prompts from 16 clusters, lengths 32..2048
+    (about 270 K tokens), gate / up / down at the MLP shapes, cache probe -> aggregation of the 16 new entries per layer
+    -> prefill plan -> planned prefill.  Indexing against the oracle bit for bit; outputs of 8 sampled prompts (the
+    shortest, the longest, the first, the last and four more, several of them sharing a pattern) against the oracle's
+    forward on sampled rows."""
+    say("config 4 at full size: cache -> pack -> plan -> planned prefill of gate/up/down, 8 sampled prompts vs the oracle")
+    E, cid, off_h, Wr_h = si.config4_embeddings()
+    P, d, G, k, R, hidden, inter, L = E.shape[0], E.shape[1], 20, 10, 2560, 4096, 11008, 3
+    gs, rS, rows, n_slots = R // G, k * (R // G), int(off_h[-1]), 32
+    shapes = [("gate", hidden, inter), ("up", hidden, inter), ("down", inter, hidden)]
+    gen = torch.Generator(device=DEV); gen.manual_seed(85684)
+    layers_rm, layers = [], []
+    for nm, n, m in shapes:
+        Vt = (torch.randn((R, n), device=DEV, generator=gen) * 0.02).to(torch.bfloat16)
+        Ut = (torch.randn((R, m), device=DEV, generator=gen) * 0.02).to(torch.bfloat16)
+        rm = pa.Layer(Vt, Ut, n, m, R, G, pa.PARSE_ROWMAJOR)
+        layers_rm.append(rm); layers.append(pa.layer_to_mfma16(rm))
+    Xh = torch.randn((rows, hidden), device=DEV, generator=gen).to(torch.bfloat16)
+    Xi = torch.randn((rows, inter), device=DEV, generator=gen).to(torch.bfloat16)
+    Ed, off, Wr = torch.from_numpy(E).to(DEV), i32(off_h), torch.from_numpy(Wr_h).to(DEV)
+    cache = pa.Cache(n_slots, d, L, k, P)
+    entry, hit, sim, subs = cache.lookup_or_route(Ed, 0.9, Wr)
+    oc = po.PatternCache(n_slots, d, L, k)
+    e_ref, h_ref, s_ref = oc.lookup_or_route(E, 0.9, Wr_h)
+    torch.cuda.synchronize()
+    assert np.array_equal(entry.cpu().numpy(), e_ref) and np.array_equal(hit.cpu().numpy(), h_ref)
+    assert np.array_equal(subs.cpu().numpy(), s_ref) and int(h_ref.sum()) == 240 and cache.count() == 16
+    plan = pa.prefill_plan(off, entry, rows, n_slots)
+    words = plan.view(torch.int32).cpu().numpy()
+    rowmap_ref, tpat_ref = po.plan_rows(off_h, e_ref, n_slots, 256)
+    cap = int(words[3]); rm0 = 16 + (cap + 15) // 16 * 16
+    assert int(words[0]) == len(tpat_ref) and np.array_equal(words[16:16 + len(tpat_ref)], tpat_ref)
+    assert np.array_equal(words[rm0:rm0 + len(rowmap_ref)], rowmap_ref)
+    lens = np.diff(off_h)
+    sample = sorted({int(np.argmin(lens)), int(np.argmax(lens)), 0, P - 1, 7, 100, 101, 200})
+    rng = np.random.default_rng(9)
+    ws = None
+    for l, (nm, n, m) in enumerate(shapes):
+        Vs = torch.empty((n_slots, rS, n), dtype=torch.bfloat16, device=DEV)
+        Us = torch.empty((n_slots, rS, m), dtype=torch.bfloat16, device=DEV)
+        pa.pack_new_entries(layers[l], subs.view(P, L * k)[:, l * k:], L * k, k, entry, hit, Vs, Us)
+        X = Xh if n == hidden else Xi
+        Y = pa.lowrank_prefill_planned(layers[l], pa.Patterns(k, n_slots, Vs, Us), X, off, entry, plan)
+        torch.cuda.synchronize()
+        Vt64 = layers_rm[l].Vt.float().cpu().numpy().astype(np.float64)
+        U64 = layers_rm[l].Ut.float().cpu().numpy().astype(np.float64).T.copy()
+        Wcache = {}
+        for p in sample:
+            a, b = int(off_h[p]), int(off_h[p + 1])
+            ts = np.unique(np.concatenate([[a, b - 1], rng.integers(a, b, size=6)]))
+            key = tuple(s_ref[p, l].tolist())
+            if key not in Wcache:
+                Wcache[key] = po.reconstruct(U64, np.ones(R), Vt64, s_ref[p, l], gs)
+            tsd = torch.from_numpy(ts).to(DEV)
+            Yref = X[tsd].float().cpu().numpy().astype(np.float64) @ Wcache[key].T
+            # the oracle's forward is this same product with the reconstruction done inside; checked equal on one prompt
+            if p == sample[0]:
+                Yf = po.forward(U64, np.ones(R), Vt64, gs, X[tsd].float().cpu().numpy().astype(np.float64), [0, len(ts)], s_ref[p:p + 1, l])
+                assert np.allclose(Yf, Yref, rtol=0, atol=1e-12)
+            assert_close(Y[tsd].float().cpu().numpy(), Yref, TOL_BF16, f"{nm} prompt {p} ({b - a} tokens, entry {e_ref[p]})")
+        del Vs, Us, Y
+    cache.close()
+
+
 # ------------------------------------------------------------------ a5 bucket
 @pytest.mark.parametrize("P,k,npat,stride", [(32, 10, 4, 10), (256, 10, 16, 30), (1, 3, 1, 3), (1024, 2, 700, 2)])
 def test_bucket_matches_oracle(P, k, npat, stride):
