@@ -51,6 +51,8 @@ def parse_args():
     ap.add_argument("--stress", action="store_true",
                     help="also run the pattern-cache / grouped-execution stress (256 ragged prompts, MLP-shaped layers)")
     ap.add_argument("--only-stress", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the achievable-peak probes")
+    ap.add_argument("--only-peaks", action="store_true")
     ap.add_argument("--no-decode-separate", action="store_true",
                     help="skip the comparison run that calls gate and up separately (counter runs use this)")
     return ap.parse_args()
@@ -460,6 +462,49 @@ def bench_stack(args, torch, pa, si):
             "launches_per_decode_step": NL * 4 * 3}
 
 
+def bench_peaks(torch, pa):
+    """Achievable peaks on this machine, measured with the library's probe kernels (HIP events around 5 launches, best
+    of 3): the bf16 matrix-instruction loop on constant and on random operands, and read-only / copy streams at the
+    sizes the workloads move (a decode call's factors, a decode step, a large stream)."""
+    dev = "cuda"
+    out = {}
+    def timed(fn, reps=5):
+        best = 1e30
+        for _ in range(3):
+            fn(); torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) / reps)
+        return best * 1e-3
+    wgs, iters = 1024, 2048
+    sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
+    flop = wgs * 4 * iters * 8 * 32768.0
+    for nm, data in (("constant_operands", torch.full((24 * 1024 // 2,), 1.0, dtype=torch.bfloat16, device=dev)),
+                     ("random_operands", torch.randn(24 * 1024 // 2, device=dev).to(torch.bfloat16))):
+        t = timed(lambda: pa.probe_mfma_bf16(data, wgs, iters, sink))
+        out["mfma_bf16_TFLOPs_" + nm] = round(flop / t / 1e12, 1)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev); src.random_(0, 255)
+    dst = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    s32 = torch.zeros(1, dtype=torch.int32, device=dev)
+    reads = {}
+    for mb in (16, 64, 128, 224, 1024):
+        nbytes = mb << 20
+        for nwg in (128, 256):
+            if nbytes % (nwg * 65536):
+                continue
+            t = timed(lambda: pa.probe_read(src, nbytes, nwg, s32))
+            reads[f"{mb}MiB_{nwg}wg"] = round(nbytes / t / 1e9, 1)
+    out["read_stream_GBps"] = reads
+    out["copy_GBps"] = {f"{mb}MiB": round(2.0 * (mb << 20) / timed(lambda: pa.probe_copy(src, dst, mb << 20)) / 1e9, 1)
+                        for mb in (64, 256)}
+    out["note"] = ("read streams smaller than the 256 MiB last-level cache are re-read from it on the repeated launches; "
+                   "the 1 GiB stream comes from HBM.  copy counts bytes read plus bytes written.")
+    return out
+
+
 def bench_stress(args, torch, pa, si):
     """Pattern-cache and grouped-execution stress: 256 prompts whose embeddings come from 16 Gaussian clusters (4096-d,
     spread 0.1), lengths uniform in 32..2048 tokens, MLP-shaped layers (gate, up: 4096->11008, down: 11008->4096, R=2560
@@ -609,6 +654,9 @@ def main():
     if args.only_stress:
         print(json.dumps({"stress": bench_stress(args, torch, pa, si)}))
         return
+    if args.only_peaks:
+        print(json.dumps({"achievable": bench_peaks(torch, pa)}))
+        return
     pre = bench_prefill(args, torch, pa, si)
     w = pre.pop("workload")
     if not args.no_decode:
@@ -635,6 +683,8 @@ def main():
         "two_batches_in_flight": pre["two_batches_in_flight"],
         "decode": dec,
     }
+    if not args.no_peaks:
+        line["achievable"] = bench_peaks(torch, pa)
     if stack is not None:
         line["stack"] = stack
     if args.stress:

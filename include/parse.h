@@ -404,6 +404,19 @@ int parse_lowrank_prefill_multi(const parse_layer *layers, const parse_patterns 
                                 const int32_t *pattern_id, int32_t P, void *const *Y, void *workspace,
                                 size_t workspace_bytes, parse_stream stream);
 
+/* ---- achievable-peak probes (measurement only) ---------------------------------------------------------------
+ * Kernels with nothing but the resource a roofline prices: the caller times them with HIP events on its stream and
+ * reports the rates beside the nominal peaks (MI355X: 2.5 PFLOP/s dense bf16, 8 TB/s HBM).  They only enqueue.
+ * parse_probe_mfma_bf16  register-resident loop of 32x32x16 bf16 matrix instructions: `workgroups` x 4 wavefronts x
+ *                        `iters` x 8 instructions of 32768 flop each, operands taken once from `data` (device, >= 24 KiB,
+ *                        the caller chooses the values: the rate depends on them); out: device float [workgroups*256].
+ * parse_probe_read       read-only stream of `bytes` from src (device) by `workgroups` workgroups, contiguous shares;
+ *                        bytes must be a multiple of workgroups * 64 KiB; sink: device uint32 [1] or NULL.
+ * parse_probe_copy       dst[i] = src[i], 16 bytes per lane; bytes % 16 == 0. */
+int parse_probe_mfma_bf16(const void *data, int32_t workgroups, int32_t iters, float *out, parse_stream stream);
+int parse_probe_read(const void *src, size_t bytes, int32_t workgroups, void *sink, parse_stream stream);
+int parse_probe_copy(const void *src, void *dst, size_t bytes, parse_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

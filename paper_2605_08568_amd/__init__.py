@@ -11,5 +11,6 @@ from .binding import (  # noqa: F401
     pack_experts, pack_new_entries, pack_patterns, pack_ranks, rankmajor_left_factor, route, route_ranks, router_grad, route_workspace_bytes, status_string, version,
     PARSE_SCHED_AUTO, PARSE_SCHED_FUSED, PARSE_SCHED_TILES, PARSE_SCHED_PLANNED, prefill_plan, prefill_plan_bytes,
     lowrank_prefill_planned, lowrank_prefill_planned_workspace_bytes,
+    probe_mfma_bf16, probe_read, probe_copy,
     decode_plan, lowrank_decode_planned, lowrank_decode_planned_workspace_bytes,
 )

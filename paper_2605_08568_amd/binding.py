@@ -114,6 +114,9 @@ def lib():
     L.parse_lowrank_forward.restype = C.c_int
     L.parse_lowrank_forward.argtypes = [i32, C.POINTER(_Layer), C.POINTER(_Patterns), vp, i32, vp, vp, i32, vp, vp,
                                         sz, vp]
+    L.parse_probe_mfma_bf16.restype = C.c_int; L.parse_probe_mfma_bf16.argtypes = [vp, i32, i32, vp, vp]
+    L.parse_probe_read.restype = C.c_int; L.parse_probe_read.argtypes = [vp, sz, i32, vp, vp]
+    L.parse_probe_copy.restype = C.c_int; L.parse_probe_copy.argtypes = [vp, vp, sz, vp]
     L.parse_decode_plan_bytes.restype = sz; L.parse_decode_plan_bytes.argtypes = [i32]
     L.parse_decode_plan.restype = C.c_int
     L.parse_decode_plan.argtypes = [C.POINTER(_Layer), C.POINTER(_Patterns), i32, vp, i32, vp, sz, vp]
@@ -427,6 +430,18 @@ def lowrank_decode_static(layer: Layer, patterns: Patterns, X, pattern_id, Y):
     _check(lib().parse_lowrank_decode_static(C.byref(cl), C.byref(cp), _ptr(X), X.shape[0], _ptr(pattern_id), _ptr(Y),
                                              _stream()), "parse_lowrank_decode_static")
     return Y
+
+
+def probe_mfma_bf16(data, workgroups: int, iters: int, out):
+    _check(lib().parse_probe_mfma_bf16(_ptr(data), workgroups, iters, _ptr(out), _stream()), "parse_probe_mfma_bf16")
+
+
+def probe_read(src, nbytes: int, workgroups: int, sink=None):
+    _check(lib().parse_probe_read(_ptr(src), nbytes, workgroups, _ptr(sink), _stream()), "parse_probe_read")
+
+
+def probe_copy(src, dst, nbytes: int):
+    _check(lib().parse_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream()), "parse_probe_copy")
 
 
 def decode_plan(layers, patterns, pattern_id, plan=None):

@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libparse.so")
 SOURCES = ["api.hip", "route.hip", "cache.hip", "pack.hip", "bucket.hip", "forward_f32.hip",
-           "prefill_bf16.hip", "prefill_split_bf16.hip", "prefill_lds_bf16.hip", "plan.hip", "decode_bf16.hip", "decode_static.hip", "forward.hip", "ranks.hip", "train.hip"]
+           "prefill_bf16.hip", "prefill_split_bf16.hip", "prefill_lds_bf16.hip", "plan.hip", "decode_bf16.hip", "decode_static.hip", "forward.hip", "ranks.hip", "train.hip", "peaks.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + INCLUDE, "-I" + CSRC,
          # packed-fp32 instruction selection is switched off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
