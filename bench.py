@@ -412,13 +412,22 @@ def bench_stack(args, torch, pa, si):
     yh1 = [torch.empty((1, hidden), dtype=torch.bfloat16, device=dev) for _ in range(3)]
     yi1 = [torch.empty((1, inter), dtype=torch.bfloat16, device=dev) for _ in range(2)]
 
+    # decode plans, once per batch (the subsets are fixed after prefill): one per horizontally fused call of every layer
+    dplans = []
+    for l in range(NL):
+        Ly, Pt = layers[l], pats[l]
+        dplans.append({"qkv": pa.decode_plan([Ly["q"], Ly["k"], Ly["v"]], [Pt["q"], Pt["k"], Pt["v"]], pid),
+                       "o": pa.decode_plan([Ly["o"]], [Pt["o"]], pid),
+                       "gu": pa.decode_plan([Ly["gate"], Ly["up"]], [Pt["gate"], Pt["up"]], pid),
+                       "down": pa.decode_plan([Ly["down"]], [Pt["down"]], pid)})
+
     def decode_step():
         for l in range(NL):
-            Ly, Pt = layers[l], pats[l]
-            pa.lowrank_decode_multi([Ly["q"], Ly["k"], Ly["v"]], [Pt["q"], Pt["k"], Pt["v"]], xh1, pid, yh1, wsd)
-            pa.lowrank_forward(pa.PARSE_DECODE, Ly["o"], Pt["o"], xh1, None, pid, yh1[0], wsd)
-            pa.lowrank_decode_multi([Ly["gate"], Ly["up"]], [Pt["gate"], Pt["up"]], xh1, pid, yi1, wsd)
-            pa.lowrank_forward(pa.PARSE_DECODE, Ly["down"], Pt["down"], xi1, None, pid, yh1[0], wsd)
+            Ly, D = layers[l], dplans[l]
+            pa.lowrank_decode_planned([Ly["q"], Ly["k"], Ly["v"]], xh1, D["qkv"], yh1, wsd)
+            pa.lowrank_decode_planned([Ly["o"]], xh1, D["o"], yh1[:1], wsd)
+            pa.lowrank_decode_planned([Ly["gate"], Ly["up"]], xh1, D["gu"], yi1, wsd)
+            pa.lowrank_decode_planned([Ly["down"]], xi1, D["down"], yh1[:1], wsd)
 
     def wall(fn, reps):
         fn(); torch.cuda.synchronize()
@@ -455,11 +464,47 @@ def bench_stack(args, torch, pa, si):
                         "prefill 1 x 2048 tokens, decode 1 sequence",
             "stored_factor_GB": round(stored / 1e9, 2), "aggregation_ms_all_224_patterns": round(pack_ms, 2),
             "prefill_ms": round(t_pre * 1e3, 3), "prefill_TFLOPs": round(flops / t_pre / 1e12, 1),
+            "prefill_frac_of_mfma_peak": round(flops / t_pre / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "decode_frac_of_hbm_peak": round(dbytes / t_dec / 1e9 / HBM_PEAK_GBS, 4),
             "prefill_tokens_per_s": round(T / t_pre, 1),
             "decode_ms_per_step": round(t_dec * 1e3, 3), "decode_GBps": round(dbytes / t_dec / 1e9, 1),
             "decode_ms_per_step_graph": round(t_graph * 1e3, 3) if isinstance(t_graph, float) else t_graph,
             "decode_GBps_graph": round(dbytes / t_graph / 1e9, 1) if isinstance(t_graph, float) else None,
-            "launches_per_decode_step": NL * 4 * 3}
+            "launches_per_decode_step": NL * 4 * 2,
+            "cpu_baseline": stack_cpu_baseline(layers[0], pats[0], real, shapes, T, k, G, Xh, Xi, flops, dbytes)}
+
+
+def stack_cpu_baseline(L0, P0, real, shapes, T, k, G, Xh, Xi, flops_total, dbytes_total):
+    """The oracle on a sample of the full-stack workload: layer 0's seven projections, prefill rows 0..127 and two decode
+    steps of one sequence (dense reconstruction and apply in float64), extrapolated by flop / byte count."""
+    import numpy as np
+    from oracle import parse_oracle as po
+    pre_flops = dec_bytes = t_pre = t_dec = 0.0
+    for nm, n, m in shapes:
+        lay = L0[nm]
+        # stored (operand-order) factors back to row-major through the documented index map
+        R = lay.R
+        Vt = lay.Vt.view(R // 32, n // 16, 2, 32, 8).permute(0, 3, 1, 2, 4).reshape(R, n).float().cpu().numpy().astype(np.float64)
+        Ut = lay.Ut.view(R // 16, m // 32, 2, 32, 8).permute(0, 2, 4, 1, 3).reshape(R, m).float().cpu().numpy().astype(np.float64)
+        gp = R // G
+        sub = P0[nm].subsets.cpu().numpy()
+        X = (Xh if n == Xh.shape[1] else Xi)[:128].float().cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        po.forward(Ut.T, np.ones(R), Vt, gp, X, [0, 128], sub)
+        t_pre += time.perf_counter() - t0
+        pre_flops += 2.0 * 128 * k * real[nm][0] * (n + m)
+        t0 = time.perf_counter()
+        for _ in range(2):
+            po.decode_step(Ut.T, np.ones(R), Vt, gp, X[:1], sub)
+            dec_bytes += k * real[nm][0] * (n + m) * 2
+        t_dec += time.perf_counter() - t0
+    return {"kind": "oracle", "cores": len(os.sched_getaffinity(0)), "seconds": round(t_pre + t_dec, 2),
+            "sample": "layer 0's seven projections: prefill rows 0..127 and two decode steps of one sequence",
+            "prefill_TFLOPs_sample": round(pre_flops / t_pre / 1e12, 5),
+            "extrapolated_prefill_s": round(t_pre * flops_total / pre_flops, 1),
+            "decode_GBps_sample": round(dec_bytes / t_dec / 1e9, 3),
+            "extrapolated_decode_s_per_step": round(t_dec * dbytes_total / dec_bytes, 1),
+            "note": "extrapolated linearly by flop / byte count; the dense reconstruction of W_S dominates both samples"}
 
 
 def bench_peaks(torch, pa):
