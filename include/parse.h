@@ -135,7 +135,8 @@ int parse_route_shared(const void *X, int32_t xdtype, int32_t rows, const int32_
  * the nearest key by cosine similarity (smallest entry index on equal similarity); it is a hit
  * when the similarity is >= tau.  Calls on one cache must be issued on one stream (or be ordered
  * by the caller); calls that overlap on one cache race.
- * create/destroy/count/insert/clear synchronise; lookup and lookup_or_route only enqueue. */
+ * create, destroy and count synchronise (count copies to the host); everything else only enqueues, so a whole batch
+ * -- explicit inserts included -- can be recorded into a HIP graph. */
 typedef struct parse_cache parse_cache;
 int parse_cache_create(parse_cache **cache, int32_t capacity, int32_t d, int32_t L, int32_t k,
                        int32_t max_batch);
@@ -144,9 +145,11 @@ int parse_cache_clear(parse_cache *cache, parse_stream stream);
 /* Routing on a miss (parse_cache_lookup_or_route) keeps groups 0..n_shared-1 in every subset, as
  * parse_route_shared does.  Host-side setting, 0 by default; 0 <= n_shared <= k. */
 int parse_cache_set_shared(parse_cache *cache, int32_t n_shared);
-/* count_out: host int32. */
-int parse_cache_count(parse_cache *cache, int32_t *count_out, parse_stream stream);
-/* Appends one entry.  emb device float [d]; subsets device int32 [L][k].  PARSE_ECAPACITY when full. */
+/* count_out: host int32, the number of entries.  dropped_out: host int32 or NULL, the number of parse_cache_insert
+ * calls since create / clear whose entry was dropped because the cache was full. */
+int parse_cache_count(parse_cache *cache, int32_t *count_out, int32_t *dropped_out, parse_stream stream);
+/* Appends one entry (only enqueues).  emb device float [d]; subsets device int32 [L][k].  The capacity check happens on the
+ * device: an entry that finds the cache full is dropped and counted; parse_cache_count reports how many were. */
 int parse_cache_insert(parse_cache *cache, const float *emb, const int32_t *subsets,
                        parse_stream stream);
 /* Pure lookup for P <= max_batch embeddings (device float [P][d]).

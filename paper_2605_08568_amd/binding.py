@@ -78,7 +78,7 @@ def lib():
     L.parse_cache_create.argtypes = [C.POINTER(vp), i32, i32, i32, i32, i32]
     L.parse_cache_destroy.restype = C.c_int; L.parse_cache_destroy.argtypes = [vp]
     L.parse_cache_clear.restype = C.c_int; L.parse_cache_clear.argtypes = [vp, vp]
-    L.parse_cache_count.restype = C.c_int; L.parse_cache_count.argtypes = [vp, C.POINTER(i32), vp]
+    L.parse_cache_count.restype = C.c_int; L.parse_cache_count.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), vp]
     L.parse_cache_insert.restype = C.c_int; L.parse_cache_insert.argtypes = [vp, vp, vp, vp]
     L.parse_cache_lookup.restype = C.c_int
     L.parse_cache_lookup.argtypes = [vp, vp, i32, f32, vp, vp, vp, vp]
@@ -282,9 +282,15 @@ class Cache:
         _check(lib().parse_cache_set_shared(self._h, n_shared), "parse_cache_set_shared")
 
     def count(self) -> int:
-        n = C.c_int32(0)
-        _check(lib().parse_cache_count(self._h, C.byref(n), _stream()), "parse_cache_count")
+        n, dropped = C.c_int32(0), C.c_int32(0)
+        _check(lib().parse_cache_count(self._h, C.byref(n), C.byref(dropped), _stream()), "parse_cache_count")
         return n.value
+
+    def dropped(self) -> int:
+        """Explicit inserts dropped (cache full) since create / clear."""
+        n, dropped = C.c_int32(0), C.c_int32(0)
+        _check(lib().parse_cache_count(self._h, C.byref(n), C.byref(dropped), _stream()), "parse_cache_count")
+        return dropped.value
 
     def insert(self, emb, subsets):
         _check(lib().parse_cache_insert(self._h, _ptr(emb), _ptr(subsets), _stream()), "parse_cache_insert")

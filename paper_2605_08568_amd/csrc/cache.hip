@@ -22,7 +22,8 @@ struct parse_cache {
   int32_t capacity, d, L, k, max_batch;
   float *keys;      // [capacity][d]
   int32_t *values;  // [capacity][L][k]
-  int32_t *count;   // [2]: the live counter is count[cur]; a fused probe reads it and writes the other one
+  int32_t *count;   // [3]: the live counter is count[cur] (cur = 0/1; a fused probe reads it and writes the other one);
+                    //      count[2] = explicit inserts dropped because the cache was full
   int32_t cur;
   // scratch of one batch
   float *sims;      // [max_batch][capacity + max_batch]
@@ -30,7 +31,7 @@ struct parse_cache {
   int32_t *entry;   // [max_batch] (used when the caller passes no entry_out)
   uint8_t *hit;     // [max_batch]
   int32_t n_shared; // leading groups every routed subset holds (route-on-miss uses it)
-  int32_t count_ub; // host-side upper bound of *count (exact after count/insert/clear); sizes the probe grid
+  int32_t count_ub; // host-side upper bound of *count (exact after count and clear); sizes the probe grid
 };
 
 namespace parse {
@@ -290,10 +291,13 @@ __global__ __launch_bounds__(256) void resolve_route_or_gather(
 }
 
 __global__ void append_entry(const float *__restrict__ emb, const int32_t *__restrict__ subsets, int d, int Lk,
-                             int32_t *__restrict__ count, int capacity, float *__restrict__ keys,
-                             int32_t *__restrict__ values) {
+                             int32_t *__restrict__ count, int32_t *__restrict__ dropped, int capacity,
+                             float *__restrict__ keys, int32_t *__restrict__ values) {
   const int ent = *count;
-  if (ent >= capacity) return;
+  if (ent >= capacity) {               // full: the entry is dropped and counted (one workgroup: no race)
+    if (threadIdx.x == 0) *dropped += 1;
+    return;
+  }
   for (int c = threadIdx.x; c < d; c += blockDim.x) keys[(size_t)ent * d + c] = emb[c];
   for (int i = threadIdx.x; i < Lk; i += blockDim.x) values[(size_t)ent * Lk + i] = subsets[i];
   __syncthreads();   // one workgroup: every lane has read *count before it changes
@@ -335,12 +339,12 @@ int parse_cache_create(parse_cache **out, int32_t capacity, int32_t d, int32_t L
   };
   alloc((void **)&c->keys, (size_t)capacity * d * sizeof(float));
   alloc((void **)&c->values, (size_t)capacity * L * k * sizeof(int32_t));
-  alloc((void **)&c->count, 2 * sizeof(int32_t));
+  alloc((void **)&c->count, 4 * sizeof(int32_t));
   alloc((void **)&c->sims, (size_t)max_batch * ld * sizeof(float));
   alloc((void **)&c->src, (size_t)max_batch * sizeof(int32_t));
   alloc((void **)&c->entry, (size_t)max_batch * sizeof(int32_t));
   alloc((void **)&c->hit, (size_t)max_batch);
-  if (e == hipSuccess) e = hipMemset(c->count, 0, 2 * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMemset(c->count, 0, 4 * sizeof(int32_t));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     set_hip_error(e, "parse_cache_create");
@@ -373,32 +377,32 @@ int parse_cache_clear(parse_cache *c, parse_stream stream) {
   hipStream_t s = (hipStream_t)stream;
   hipLaunchKernelGGL(set_i32, dim3(1), dim3(1), 0, s, c->count + c->cur, 0);
   PARSE_LAUNCH_CHECK();
-  PARSE_HIP_TRY(hipStreamSynchronize(s));
-  c->count_ub = 0;
+  hipLaunchKernelGGL(set_i32, dim3(1), dim3(1), 0, s, c->count + 2, 0);
+  PARSE_LAUNCH_CHECK();
+  c->count_ub = 0;     // exact again: every later call on the cache is ordered after the two stores
   return PARSE_OK;
 }
 
-int parse_cache_count(parse_cache *c, int32_t *count_out, parse_stream stream) {
+int parse_cache_count(parse_cache *c, int32_t *count_out, int32_t *dropped_out, parse_stream stream) {
   if (!c || !count_out) return PARSE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
-  PARSE_HIP_TRY(hipMemcpyAsync(count_out, c->count + c->cur, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  int32_t both[2] = {0, 0};
+  PARSE_HIP_TRY(hipMemcpyAsync(&both[0], c->count + c->cur, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  PARSE_HIP_TRY(hipMemcpyAsync(&both[1], c->count + 2, sizeof(int32_t), hipMemcpyDeviceToHost, s));
   PARSE_HIP_TRY(hipStreamSynchronize(s));
-  c->count_ub = *count_out;
+  *count_out = both[0];
+  if (dropped_out) *dropped_out = both[1];
+  c->count_ub = both[0];
   return PARSE_OK;
 }
 
 int parse_cache_insert(parse_cache *c, const float *emb, const int32_t *subsets, parse_stream stream) {
   if (!c || !emb || !subsets) return PARSE_EINVAL;
-  int32_t n = 0;
-  int st = parse_cache_count(c, &n, stream);
-  if (st != PARSE_OK) return st;
-  if (n >= c->capacity) return PARSE_ECAPACITY;
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(append_entry, dim3(1), dim3(256), 0, s, emb, subsets, c->d, c->L * c->k, c->count + c->cur, c->capacity,
-                     c->keys, c->values);
+  hipLaunchKernelGGL(append_entry, dim3(1), dim3(256), 0, s, emb, subsets, c->d, c->L * c->k, c->count + c->cur, c->count + 2,
+                     c->capacity, c->keys, c->values);
   PARSE_LAUNCH_CHECK();
-  PARSE_HIP_TRY(hipStreamSynchronize(s));
-  c->count_ub = n + 1;
+  c->count_ub = c->count_ub + 1 < c->capacity ? c->count_ub + 1 : c->capacity;
   return PARSE_OK;
 }
 
@@ -449,6 +453,7 @@ int parse_cache_lookup_or_route(parse_cache *c, const float *emb, int32_t P, flo
   if (P <= kSmallBatch) {
     // small batch: every (layer, prompt) workgroup works out the batch's decisions itself, then does its own part;
     // the new entry count goes to the other counter slot, which becomes the live one
+    PARSE_ALLOW_LDS(resolve_route_or_gather, (size_t)(c->d + 128) * sizeof(float));
     hipLaunchKernelGGL(resolve_route_or_gather, dim3(c->L, P), dim3(256), (size_t)(c->d + 128) * sizeof(float), s, c->sims,
                        ld, c->capacity, P, tau, c->count + c->cur, c->count + (c->cur ^ 1), emb, c->d, Wr, G, c->L, c->k,
                        entry, hit, sim_out, c->keys, c->values, subset_out, c->n_shared);
@@ -459,6 +464,7 @@ int parse_cache_lookup_or_route(parse_cache *c, const float *emb, int32_t P, flo
   hipLaunchKernelGGL(resolve, dim3(1), dim3(1024), (size_t)P * 12, s, c->sims, ld, c->capacity, P, tau, 1, c->count + c->cur,
                      entry, hit, sim_out, c->src);
   PARSE_LAUNCH_CHECK();
+  PARSE_ALLOW_LDS(route_or_gather, (size_t)(c->d + 128) * sizeof(float));
   hipLaunchKernelGGL(route_or_gather, dim3(c->L, P), dim3(256), (size_t)(c->d + 128) * sizeof(float), s, emb, c->d, Wr,
                      G, c->L, c->k, c->capacity, 1, entry, hit, c->src, c->keys, c->values, subset_out, c->n_shared);
   PARSE_LAUNCH_CHECK();

@@ -45,6 +45,14 @@ void set_hip_error(hipError_t e, const char *where);
     }                                               \
   } while (0)
 
+// A launch with more than 64 KiB of dynamic LDS needs the kernel's limit raised first (gfx950 has 160 KiB per CU).
+// Only the rare large shapes take this path, so the attribute is simply set again on each such call.
+#define PARSE_ALLOW_LDS(kernel, bytes)                                                                            \
+  do {                                                                                                            \
+    if ((size_t)(bytes) > (size_t)65536)                                                                          \
+      PARSE_HIP_TRY(hipFuncSetAttribute((const void *)(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(bytes))); \
+  } while (0)
+
 #define PARSE_LAUNCH_CHECK()                        \
   do {                                              \
     hipError_t _e = hipGetLastError();              \

@@ -177,6 +177,7 @@ int parse_route_shared(const void *X, int32_t xdtype, int32_t rows, const int32_
   const int st = launch_pool_partials(X, xdtype, rows, tok_offsets, P, d, partial, &Q, s);
   if (st != PARSE_OK) return st;
   const size_t lds = (size_t)(d + 64) * sizeof(float);
+  PARSE_ALLOW_LDS(route_finish, lds);
   hipLaunchKernelGGL(route_finish, dim3(P), dim3(kFinishThreads), lds, s, partial, Q, rows, d, tok_offsets, Wr, G, k,
                      subset_out, subset_stride, scores_out, emb_out, n_shared);
   PARSE_LAUNCH_CHECK();

@@ -33,6 +33,7 @@ def assert_close(Y, Yref, tol, what):
     ("bf16", [1, 7, 300, 33, 2], 512, 16, 8),
     ("f32", [1] * 9, 264, 20, 10),
     ("bf16", [513, 40], 4096, 64, 1),
+    ("f32", [5, 90, 2], 16384, 12, 4),          # the largest model width the router accepts (more than 64 KiB of LDS)
 ])
 def test_route_matches_oracle(dtype, lengths, d, G, k):
     say(f"route dtype={dtype} lengths={lengths} d={d} G={G} k={k}")
@@ -120,6 +121,18 @@ def test_cache_sequential_batches_match_oracle():
     cache.close()
 
 
+def test_cache_at_the_largest_model_width():
+    say("cache lookup_or_route at d=16384: small-batch (one launch) and large-batch (two launches) paths")
+    d, L, G, k = 16384, 2, 8, 3
+    for P, seed in ((6, 211), (70, 212)):        # 70 > the small-batch limit of 64
+        E, cid, Wr = _cache_inputs(2 * P, d, L, G, 9, seed)
+        cache = pa.Cache(16, d, L, k, P)
+        oc = po.PatternCache(16, d, L, k)
+        for b in range(2):
+            _check_cache_batch(cache, oc, E[b * P:(b + 1) * P], 0.9, Wr)
+        cache.close()
+
+
 def test_cache_empty_full_and_insert():
     say("cache: empty lookup, explicit insert, capacity overflow")
     d, L, G, k = 256, 2, 8, 3
@@ -135,11 +148,15 @@ def test_cache_empty_full_and_insert():
     assert cache.count() == 1
     _check_cache_batch(cache, oc, E, 0.9, Wr)
     assert cache.count() == 4
-    with pytest.raises(pa.ParseError) as ei:
-        cache.insert(torch.from_numpy(E[5]).to(DEV), i32(s0))
-    assert ei.value.status == -4
+    # a full cache drops an explicit insert on the device and counts it; the host call only enqueues
+    for extra in (5, 6):
+        cache.insert(torch.from_numpy(E[extra]).to(DEV), i32(s0))
+    assert cache.count() == 4 and cache.dropped() == 2
+    _check_cache_batch(cache, oc, E[:4], 0.9, Wr)          # the four entries are untouched: same hits as the oracle's
     cache.clear()
-    assert cache.count() == 0
+    assert cache.count() == 0 and cache.dropped() == 0
+    cache.insert(torch.from_numpy(E[0]).to(DEV), i32(s0))
+    assert cache.count() == 1 and cache.dropped() == 0
     cache.close()
 
 
