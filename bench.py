@@ -53,6 +53,7 @@ def parse_args():
     ap.add_argument("--only-stress", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the achievable-peak probes")
     ap.add_argument("--only-peaks", action="store_true")
+    ap.add_argument("--no-decode-graph", action="store_true", help="skip the HIP-graph replay of the decode steps")
     ap.add_argument("--no-decode-separate", action="store_true",
                     help="skip the comparison run that calls gate and up separately (counter runs use this)")
     return ap.parse_args()
@@ -344,10 +345,45 @@ def bench_decode(args, torch, pa, si):
     out["separate_calls"] = {"gate,up_us": round(us_sep[0], 2), "down_us": round(us_sep[1], 2),
                              "ms_per_step": round(wall_sep / steps * 1e3, 4)}
     tot_bytes, tot_us = b_gu + b_dn, us[0] + us[1]
-    ach = tot_bytes / tot_us / 1e3
-    out["roofline"] = {"bound": "hbm", "kernel": "decode_zf + decode_y over a decode plan (two calls per step: gate+up fused, down; four launches)",
+    out["eager"] = {"us_per_step": round(tot_us, 2), "GBps": round(tot_bytes / tot_us / 1e3, 1),
+                    "end_to_end_GBps": round(tot_bytes * steps / wall / 1e9, 1)}
+    # The same steps replayed from a HIP graph (one graph = `copies` consecutive steps = 4 * copies kernel nodes, no
+    # memset nodes): what a serving loop runs.  Every replay is checked against the eager result of the same steps.
+    graph_us = None
+    if not args.no_decode_graph:
+        for s in range(copies):
+            step(s)
+        torch.cuda.synchronize()
+        ref = [ys[inter].clone(), ys2.clone(), ys[hidden].clone()]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for s in range(copies):
+                step(s)
+        reps = max(2, steps // copies)
+        same = True
+        g.replay()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        for a_, b_ in zip(ref, [ys[inter], ys2, ys[hidden]]):
+            same = same and bool(torch.equal(a_.view(torch.int16), b_.view(torch.int16)))
+        graph_us = e0.elapsed_time(e1) * 1e3 / (reps * copies)
+        out["graph_replay"] = {"us_per_step": round(graph_us, 2), "GBps": round(tot_bytes / graph_us / 1e3, 1),
+                               "steps_per_graph": copies, "replays": reps, "matches_eager_bitwise": same}
+        if not same:
+            graph_us = None
+    best_us = graph_us if graph_us is not None else tot_us
+    ach = tot_bytes / best_us / 1e3
+    out["roofline"] = {"bound": "hbm",
+                       "kernel": "decode_zr + decode_y over a decode plan (two calls per step: gate+up fused, down; four launches)"
+                                 + (", steps replayed from a HIP graph" if graph_us is not None else ", eager launches"),
                        "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                       "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic_from_profiles("decode_config2")}
+                       "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic_from_profiles("decode_config2"),
+                       "us_per_step": round(best_us, 2)}
     out["end_to_end_GBps"] = round(tot_bytes * steps / wall / 1e9, 1)
     return out
 

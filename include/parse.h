@@ -358,35 +358,42 @@ int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *
  *   pattern_id        device int32 [rows], a sequence's pattern (cache entry); rows <= 32
  *   plan              device, >= parse_decode_plan_bytes(n_layers) bytes, 16-byte aligned, caller-owned
  * parse_lowrank_decode_planned is the decode step of those layers over a ready plan: TWO launches (the intermediate of
- * every used rank block is reduced completely inside one workgroup, then the output columns), nothing derived from
- * the subsets at run time.  Results are bit-identical to parse_lowrank_forward(PARSE_DECODE) / parse_lowrank_decode_multi,
- * which build the same plan inside the call (one more small launch).
+ * every used rank block, then the output columns), nothing derived from the subsets at run time.  Results are
+ * bit-identical to parse_lowrank_forward(PARSE_DECODE) / parse_lowrank_decode_multi, which build the same plan inside
+ * the call (one more small launch), and the same from run to run (no floating-point atomics: partial sums are added in
+ * a fixed order).
+ * The plan also holds the arrival counters with which the workgroups that share a rank block's reduction find out
+ * which of them finishes it (zero after parse_decode_plan and again after every call): the decode call WRITES the
+ * plan, so a plan serves one decode call at a time -- calls that share a plan go on one stream or are ordered by the
+ * caller; concurrent calls need a plan each.
  *   X device [rows][n] bf16;  Y host array [n_layers] of device pointers [rows][layers[l].m] bf16
- *   workspace device, >= parse_lowrank_decode_planned_workspace_bytes(layers, n_layers) (the intermediates) */
+ *   workspace device, >= parse_lowrank_decode_planned_workspace_bytes(layers, n_layers) (the intermediates and the
+ *             partial sums of the split reduction; contents irrelevant before, undefined after) */
 size_t parse_decode_plan_bytes(int32_t n_layers);
 int parse_decode_plan(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
                       const int32_t *pattern_id, int32_t rows, void *plan, size_t plan_bytes, parse_stream stream);
 size_t parse_lowrank_decode_planned_workspace_bytes(const parse_layer *layers, int32_t n_layers);
 int parse_lowrank_decode_planned(const parse_layer *layers, int32_t n_layers, const void *X, int32_t rows,
-                                 const void *plan, void *const *Y, void *workspace, size_t workspace_bytes,
+                                 void *plan, void *const *Y, void *workspace, size_t workspace_bytes,
                                  parse_stream stream);
 
 /* ---- decode without allocation ---------------------------------------------------------------------------
  * For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  The same step as parse_lowrank_forward(PARSE_DECODE, ...) -- same kernels, same bits --
- * but the memory the kernels need beyond inputs and outputs (the rounded intermediate in operand order and the decode
- * plan: group masks, list of used groups) is a fixed array of PARSE_DECODE_STATIC_SCRATCH_BYTES inside the library's
+ * but the memory the kernels need beyond inputs and outputs (the rounded intermediate in operand order, the partial
+ * sums of its split reduction and the decode plan: group masks, list of used groups, arrival counters) is a fixed
+ * array of PARSE_DECODE_STATIC_SCRATCH_BYTES inside the library's
  * device image instead of a caller's workspace.  The call allocates and frees nothing, on any call, and calls no
  * allocating routine; every GPU the library runs on holds its own copy of the array until the process ends.
  *   layer, patterns, X, rows, pattern_id, Y   as for PARSE_DECODE (device pointers, rows <= 32, bf16 PARSE_MFMA16)
- * PARSE_EWORKSPACE when the layer needs more than the array holds (64 bytes per stored rank plus 768 for the plan, so
- * layers up to a stored rank of 8160 fit; parse_lowrank_workspace_bytes(PARSE_DECODE, layer, rows, k, 0, 0) tells);
- * other errors as
+ * PARSE_EWORKSPACE when the layer needs more than the array holds: parse_lowrank_workspace_bytes(PARSE_DECODE, layer,
+ * rows, k, 0, 0) is what it needs (64 bytes per stored rank, 128 more per stored rank and slice when the reduction
+ * over n is split in slices, about 2 KiB of plan: 2.1 MiB for R = 2560, n = 11008); other errors as
  * parse_lowrank_forward.  Nothing is launched on error.
  * All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two threads) race;
  * issue them on one stream or order them.  The array keeps the last call's contents; the kernels read only what
  * the same call wrote, so nothing needs clearing between calls. */
-#define PARSE_DECODE_STATIC_SCRATCH_BYTES (512u << 10)
+#define PARSE_DECODE_STATIC_SCRATCH_BYTES (4u << 20)
 size_t parse_lowrank_decode_static_capacity(void);
 int parse_lowrank_decode_static(const parse_layer *layer, const parse_patterns *patterns, const void *X,
                                 int32_t rows, const int32_t *pattern_id, void *Y, parse_stream stream);

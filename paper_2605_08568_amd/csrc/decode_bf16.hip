@@ -29,15 +29,12 @@ constexpr int DZ_WAVES = 8, DZ_THREADS = DZ_WAVES * 64;
 constexpr int DY_WAVES = 8, DY_THREADS = DY_WAVES * 64;
 constexpr int DEC_MAXG = 64;
 constexpr int DZ_CH = 256;                 // columns staged per chunk: 32 per wavefront (one 16x16x32 or two 32x32x16 steps)
-constexpr int DZ32_CH_KB = DZ_CH / 16;     // 32-rank form: reduction steps per chunk (16)
-constexpr int DZ32_WKB = DZ32_CH_KB / DZ_WAVES;   // per wavefront (2)
-constexpr int DZ32_XBYTES = 32 * DZ_CH * 2;       // x part of a staged chunk: 32 rows x 512 bytes
-constexpr int DZ32_BUF = DZ32_XBYTES + DZ32_CH_KB * 1024;   // + the chunk's 16 Vt operands = 32 KiB
-constexpr int DZ32_NBUF = 4;
 constexpr int DY_CHUNK = 4;                // decode_y: operands per chunk after the first block
 constexpr int DY_MAXKB = 1024;             // selected reduction blocks a decode_y workgroup can list
 constexpr int DEC_MAX_LAYERS = 4;
-constexpr int DEC_PLAN_WORDS = 192;        // per layer: [0] count, [1..64] used group ids, [65..128] sequence masks
+constexpr int DEC_TICKETS = 256;           // pairs of 32-rank blocks of the largest layer (R = 16384)
+constexpr int DEC_PLAN_WORDS = 192 + DEC_TICKETS;   // per layer: [0] count, [1..64] used group ids, [65..128] sequence masks,
+                                                    // [192..) arrival counters of the split reduction (zero between calls)
 
 #define PARSE_DEC_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define PARSE_DEC_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -47,6 +44,8 @@ struct DecLayer {
   uint16_t *y;
   uint16_t *zf;                // workspace: z of this layer in operand order
   const int32_t *plan;         // this layer's DEC_PLAN_WORDS of the decode plan
+  float *zpart;                // workspace: partial sums of z, [R/32][KS][16][64] floats (KS > 1)
+  int32_t *ticket;             // [DEC_TICKETS] arrival counters in the plan, one per pair of 32-rank blocks
   int R, G, gs, m;
   int z_first, y_first;        // first workgroup of this layer in decode_zf / decode_y
 };
@@ -55,6 +54,7 @@ struct DecArgs {
   int n_layers;
   const uint16_t *x;
   int B, n;
+  int KS;                      // decode_zr: slices of the reduction range
 };
 
 struct DecPlanArgs {
@@ -96,116 +96,183 @@ __global__ __launch_bounds__(64) void decode_plan_build(DecPlanArgs a) {
   out[1 + lane] = used_l[lane];
   out[65 + lane] = (int32_t)gmask[lane];
   if (lane == 0) out[0] = __popcll(votes);
+  for (int i = lane; i < DEC_TICKETS; i += 64) out[192 + i] = 0;
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// decode_zf32.  grid = sum over layers of R/32; workgroup = (layer, 32-rank block rb): the form for calls with many
-// rank blocks (the x rows are re-read once per workgroup, so wider blocks mean less traffic).
-// Everything the loop reads from memory goes straight into LDS (loads that write LDS directly), DZ32_NBUF chunks in
-// rotation, so the only waits in the loop are the explicit ones below: per chunk of 256 columns the 32 x rows
-// (512 bytes each, their 16-byte pieces XOR-swizzled by the row so that an operand read -- 32 rows x the same piece --
-// spreads over the banks) and the 16 Vt operands of the rank block (two per wavefront, which that wavefront alone
-// reads back).  The LDS is reused for the wavefronts' partial sums at the end.
-__global__ __launch_bounds__(DZ_THREADS) void decode_zf32(DecArgs a) {
+// decode_zr.  Workgroup = (layer, pair of 32-rank blocks, slice s of KS of the reduction range).  The form for layers
+// whose groups are multiples of 32 ranks.  A slice is at most 128 reduction steps (2048 columns): wavefront
+// (block, quarter) owns a quarter of the slice for one of the two rank blocks and requests ALL its Vt operands at once,
+// straight into registers (1 KiB coalesced per instruction, up to 32 of them): the registers of the eight wavefronts are
+// the staging buffer -- up to 256 KiB of factor stream in flight per compute unit, several times what LDS staging can
+// hold, which is what a stream from HBM needs.  The slice of the x rows is staged once per workgroup in LDS (loads that
+// write LDS directly; 512-byte row segments, 16-byte pieces XOR-swizzled by the row so that an operand read -- 32 rows x
+// the same piece -- spreads over the banks) and feeds both rank blocks.  After one wait and one barrier the products run
+// from registers and LDS; the four quarter sums of a block are added in quarter order through LDS.
+// KS == 1: the block's z is masked, rounded to bf16 and stored as operands of the second product.
+// KS  > 1: the workgroup stores its partial sum (fp32) and takes a ticket of its pair; the workgroup that draws the last
+// ticket adds the KS partial sums in slice order (not in arrival order: same inputs, same bits) and stores the operands.
+// Nobody waits for anybody: a workgroup that is not the last simply ends.  The tickets live in the decode plan (zeroed
+// when the plan is built, reset by the last workgroup), so a plan serves one decode call at a time.
+constexpr int DR_WAVES = 8, DR_THREADS = DR_WAVES * 64;
+constexpr int DR_MAXK = 32;                  // Vt operands a wavefront requests (its quarter of the slice)
+constexpr int DR_SEG_KB = 16;                // reduction steps per staged x segment (256 columns, 512 bytes per row)
+constexpr int DR_SEG_BYTES = 32 * 512;       // 16 KiB
+constexpr int DR_MAXSEG = 4 * DR_MAXK / DR_SEG_KB;   // 8 segments = 128 KiB
+constexpr int DR_MAX_KS = 16;
+constexpr int DR_TARGET_WGS = 240;           // workgroups wanted per launch: a little under one per compute unit
+
+// lane (j, q) holds s[e] = ranks 8*(e/4) + 4*q + e%4 of sequence j of a 32-rank block: mask, round, pair the bands into
+// 8 consecutive ranks and store the two z operands (reduction blocks rb*2, rb*2+1 of the second product)
+__device__ __forceinline__ void dec_store_z_operands(const float (&s)[16], uint32_t mask, int lane, uint16_t *zf, int rb) {
+  const bool member = (mask >> (lane & 31)) & 1u;     // a sequence outside the group's mask gets zeros
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint32_t p0x = member ? cvt_pk_bf16(s[(2 * h) * 4 + 0], s[(2 * h) * 4 + 1]) : 0u;
+    const uint32_t p0y = member ? cvt_pk_bf16(s[(2 * h) * 4 + 2], s[(2 * h) * 4 + 3]) : 0u;
+    const uint32_t p1x = member ? cvt_pk_bf16(s[(2 * h + 1) * 4 + 0], s[(2 * h + 1) * 4 + 1]) : 0u;
+    const uint32_t p1y = member ? cvt_pk_bf16(s[(2 * h + 1) * 4 + 2], s[(2 * h + 1) * 4 + 3]) : 0u;
+    // after the swap lane (j, q) holds the 8 consecutive ranks rb*32 + 16h + 8q + (0..7) of sequence j
+    const u32x2 sx = __builtin_amdgcn_permlane32_swap(p0x, p1x, false, false);
+    const u32x2 sy = __builtin_amdgcn_permlane32_swap(p0y, p1y, false, false);
+    *reinterpret_cast<u32x4 *>((char *)zf + (size_t)(rb * 2 + h) * 1024 + lane * 16) = u32x4{sx[0], sy[0], sx[1], sy[1]};
+  }
+}
+
+__global__ __launch_bounds__(DR_THREADS) void decode_zr(DecArgs a) {
   int li = 0;
 #pragma unroll
   for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].z_first) ? 1 : 0;
   const DecLayer &ly = a.L[li];
-  const int rb = blockIdx.x - ly.z_first;
+  const int KS = a.KS;
+  const int bid = blockIdx.x - ly.z_first;
+  const int pair = bid / KS, sl = bid % KS;
   const int n = a.n, B = a.B, gs = ly.gs;
-  const uint32_t mask = (uint32_t)ly.plan[65 + (rb * 32) / gs];     // sequences whose pattern holds this block's group
-  if (mask == 0u) return;                                            // nobody selected it: nothing is read or written
-  __shared__ __attribute__((aligned(1024))) char xs[DZ32_NBUF * DZ32_BUF];
+  const int nb32 = ly.R / 32;
+  const int rb0 = pair * 2;
+  // sequences whose pattern holds each block's group; a block nobody selected is neither read nor written
+  const uint32_t mask0 = (uint32_t)ly.plan[65 + (rb0 * 32) / gs];
+  const uint32_t mask1 = rb0 + 1 < nb32 ? (uint32_t)ly.plan[65 + ((rb0 + 1) * 32) / gs] : 0u;
+  if ((mask0 | mask1) == 0u) return;
+  __shared__ __attribute__((aligned(1024))) char xs[DR_MAXSEG * DR_SEG_BYTES];
+  __shared__ int32_t am_last;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int j = lane & 31, q = lane >> 5;
+  const int blk = wave >> 2, kq = wave & 3;
+  const uint32_t my_mask = blk == 0 ? mask0 : mask1;
   const int nkb = n / 16;
-  const int nch = (nkb + DZ32_CH_KB - 1) / DZ32_CH_KB;
-  // x: 16 instructions of 1 KiB (two rows of 512 bytes each) per chunk, two per wavefront.  Lane l writes slot l % 32
-  // of row 2*ins + l / 32 and fetches the piece (slot ^ (row & 15)) of that row's chunk; pieces past the end of the row
-  // re-read its last one (their products are switched off below).
-  const char *xrow[2];
-  int xslot[2];
+  const int ks0 = (int)(((long long)nkb * sl) / KS), ks1 = (int)(((long long)nkb * (sl + 1)) / KS);
+  const int cnt_wg = ks1 - ks0;                         // <= 4 * DR_MAXK (the host picks KS so)
+  const int k0w = (cnt_wg * kq) / 4, k1w = (cnt_wg * (kq + 1)) / 4;
+  const int cnt_w = my_mask != 0u ? k1w - k0w : 0;      // this wavefront's reduction steps (<= DR_MAXK)
+  // ---- all Vt operands of this wavefront, requested at once (steps past the count re-read the last one) ----
+  u32x4 vr[DR_MAXK];
+  {
+    const char *vbase = (const char *)ly.Vt + ((size_t)(rb0 + blk) * nkb + ks0 + k0w) * 1024 + lane * 16;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int r = (wave * 2 + i) * 2 + (lane >> 5);
-    xrow[i] = (const char *)a.x + (size_t)min(r, B - 1) * n * 2;
-    xslot[i] = (lane & 31) ^ (r & 15);
+    for (int g = 0; g < DR_MAXK / 4; ++g) {
+      if (g * 4 < cnt_w) {                               // uniform
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii)
+          vr[g * 4 + ii] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)min(g * 4 + ii, cnt_w - 1) * 1024);
+      } else {
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) vr[g * 4 + ii] = u32x4{0, 0, 0, 0};
+      }
+    }
   }
+  // ---- the slice of the x rows into LDS: segment = 16 instructions of 1 KiB (two rows of 512 bytes each).  Lane l writes
+  // slot l % 32 of row 2*ins + l / 32 and fetches the piece (slot ^ (row & 15)) of that row's segment; pieces past the end
+  // of the row re-read its last one (their products are switched off below) ----
+  const int nseg = (cnt_wg + DR_SEG_KB - 1) / DR_SEG_KB;
   const int last_piece = n / 8 - 1;
-  // Vt: operands (rb, kb) are contiguous in kb; this wavefront owns steps wave*2 + (0, 1) of every chunk
-  const char *vbase = (const char *)ly.Vt + ((size_t)rb * nkb) * 1024 + lane * 16;
-  auto issue = [&](int c) {
-    char *buf = xs + (c % DZ32_NBUF) * DZ32_BUF;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int piece = min(c * (DZ_CH / 8) + xslot[i], last_piece);
-      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(xrow[i] + (size_t)piece * 16),
-                                       PARSE_DEC_LDS_PTR(buf + (wave * 2 + i) * 1024), 16, 0, 0);
+  for (int u = 0; u < DR_MAXSEG * 16 / DR_WAVES; ++u) {
+    const int t = wave + u * DR_WAVES;                   // instruction id: segment t / 16, row pair t % 16
+    if (t < nseg * 16) {                                 // uniform
+      const int seg = t >> 4, ins = t & 15;
+      const int r = ins * 2 + (lane >> 5);
+      const int piece = min(ks0 * 2 + seg * 32 + ((lane & 31) ^ (r & 15)), last_piece);
+      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR((const char *)a.x + (size_t)min(r, B - 1) * n * 2 + (size_t)piece * 16),
+                                       PARSE_DEC_LDS_PTR(xs + seg * DR_SEG_BYTES + ins * 1024), 16, 0, 0);
     }
-#pragma unroll
-    for (int i = 0; i < DZ32_WKB; ++i) {
-      const int kb = min(c * DZ32_CH_KB + wave * DZ32_WKB + i, nkb - 1);
-      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(vbase + (size_t)kb * 1024),
-                                       PARSE_DEC_LDS_PTR(buf + DZ32_XBYTES + (wave * DZ32_WKB + i) * 1024), 16, 0, 0);
-    }
-  };
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();                                       // everybody's x rows are in LDS
   f32x16 acc;
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   const u32x4 zero = {0, 0, 0, 0};
-  constexpr int LPC = 2 + DZ32_WKB;          // loads per chunk per wavefront
 #pragma unroll
-  for (int c = 0; c < DZ32_NBUF - 1; ++c)
-    if (c < nch) issue(c);
-  for (int c = 0; c < nch; ++c) {
-    // chunk c has landed when only the chunks requested after it are outstanding
-    const int later = min(c + DZ32_NBUF - 2, nch - 1) - c;
-    if (later >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPC) : "memory");
-    else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPC) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();          // everybody's x rows of chunk c are in LDS; everybody is done with chunk c-1
-    asm volatile("" ::: "memory");
-    if (c + DZ32_NBUF - 1 < nch) issue(c + DZ32_NBUF - 1);
-    const char *buf = xs + (c % DZ32_NBUF) * DZ32_BUF;
+  for (int g = 0; g < DR_MAXK / 4; ++g) {
+    if (g * 4 < cnt_w) {                                 // uniform
 #pragma unroll
-    for (int i = 0; i < DZ32_WKB; ++i) {
-      const int kl = wave * DZ32_WKB + i;                       // reduction step within the chunk
-      const u32x4 xv = *reinterpret_cast<const u32x4 *>(buf + j * (DZ_CH * 2) + (((kl * 2 + q) ^ (j & 15)) * 16));
-      const u32x4 vv = *reinterpret_cast<const u32x4 *>(buf + DZ32_XBYTES + kl * 1024 + lane * 16);
-      const bool live = c * DZ32_CH_KB + kl < nkb;              // steps past the end of n contribute nothing
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(vv), dec_bf16x8(live ? xv : zero), acc, 0, 0, 0);
+      for (int ii = 0; ii < 4; ++ii) {
+        const int i = g * 4 + ii;
+        const int kl = min(k0w + i, cnt_wg - 1);         // step within the slice
+        const u32x4 xv = *reinterpret_cast<const u32x4 *>(xs + (kl >> 4) * DR_SEG_BYTES + j * 512 +
+                                                          ((((kl & 15) * 2 + q) ^ (j & 15)) * 16));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(vr[i]), dec_bf16x8(i < cnt_w ? xv : zero), acc, 0, 0, 0);
+      }
     }
   }
-  __syncthreads();        // the staged chunks are dead: their LDS now takes the wavefronts' partial sums
-  float(*red)[16][64] = reinterpret_cast<float(*)[16][64]>(xs);     // [8][16][64] floats = 32 KiB
+  __syncthreads();        // the staged rows are dead: their LDS now takes the wavefronts' sums
+  float(*red)[16][64] = reinterpret_cast<float(*)[16][64]>(xs);               // [8][16][64] floats = 32 KiB
+  float(*sums)[16][64] = reinterpret_cast<float(*)[16][64]>(xs + 32768);      // [2][16][64]
 #pragma unroll
   for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[e];
   __syncthreads();
-  if (wave == 0) {
+  // the four quarter sums of each block, in quarter order; value v = (block, e, lane)
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int v = (int)threadIdx.x + u * DR_THREADS;
+    const int b2 = v >> 10, rem = v & 1023;
+    const float *r0 = &red[b2 * 4][0][0] + rem;
+    const float sum = ((r0[0] + r0[1024]) + r0[2048]) + r0[3072];
+    if (KS == 1) sums[b2][0][rem] = sum;
+    else if (rb0 + b2 < nb32)     // device-scope store: written through to memory, past this die's (non-coherent) L2
+      __hip_atomic_store(&ly.zpart[((size_t)(rb0 + b2) * KS + sl) * 1024 + rem], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (KS == 1) {
+    __syncthreads();
+    if (kq == 0 && my_mask != 0u) {
+      float s[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = sums[blk][e][lane];
+      dec_store_z_operands(s, my_mask, lane, ly.zf, rb0 + blk);
+    }
+    return;
+  }
+  // ---- ticket.  The partial sums and the ticket are device-scope accesses (they go past the die's L2, which is not
+  // coherent with the other dies'), so no cache has to be written back or invalidated as a device-scope fence would do
+  // (that would also throw away the x rows and factor lines the other workgroups of the die are using): every thread
+  // waits until its own stores are acknowledged, the barrier collects all of them, then thread 0 draws ----
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int t = __hip_atomic_fetch_add(&ly.ticket[pair], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = t == KS - 1 ? 1 : 0;
+    if (last) __hip_atomic_store(&ly.ticket[pair], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+    am_last = last;
+  }
+  __syncthreads();
+  if (!am_last) return;
+  // the last workgroup of the pair: all KS partial sums are in memory; read them past the L2 as well, add in slice order
+  if (kq == 0 && my_mask != 0u) {
     float s[16];
+    const float *zp = ly.zpart + (size_t)(rb0 + blk) * KS * 1024 + lane;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      float v = red[0][e][lane];
+    for (int e = 0; e < 16; ++e) s[e] = __hip_atomic_load(zp + e * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int o = 1; o < KS; ++o) {
+      float t[16];
 #pragma unroll
-      for (int w = 1; w < DZ_WAVES; ++w) v += red[w][e][lane];
-      s[e] = v;
+      for (int e = 0; e < 16; ++e) t[e] = __hip_atomic_load(zp + (size_t)o * 1024 + e * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] += t[e];
     }
-    // lane (j, q): sequence j, ranks rb*32 + 8*band + 4*q + (0..3); a sequence outside the group's mask gets zeros
-    const bool member = (mask >> j) & 1u;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t p0x = member ? cvt_pk_bf16(s[(2 * h) * 4 + 0], s[(2 * h) * 4 + 1]) : 0u;
-      const uint32_t p0y = member ? cvt_pk_bf16(s[(2 * h) * 4 + 2], s[(2 * h) * 4 + 3]) : 0u;
-      const uint32_t p1x = member ? cvt_pk_bf16(s[(2 * h + 1) * 4 + 0], s[(2 * h + 1) * 4 + 1]) : 0u;
-      const uint32_t p1y = member ? cvt_pk_bf16(s[(2 * h + 1) * 4 + 2], s[(2 * h + 1) * 4 + 3]) : 0u;
-      // after the swap lane (j, q) holds the 8 consecutive ranks rb*32 + 16h + 8q + (0..7) of sequence j:
-      // the lane's piece of z operand (reduction block rb*2 + h)
-      const u32x2 sx = __builtin_amdgcn_permlane32_swap(p0x, p1x, false, false);
-      const u32x2 sy = __builtin_amdgcn_permlane32_swap(p0y, p1y, false, false);
-      *reinterpret_cast<u32x4 *>((char *)ly.zf + (size_t)(rb * 2 + h) * 1024 + lane * 16) = u32x4{sx[0], sy[0], sx[1], sy[1]};
-    }
+    dec_store_z_operands(s, my_mask, lane, ly.zf, rb0 + blk);
   }
 }
 
@@ -498,11 +565,43 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
   }
 }
 
-// workspace of one layer: z in operand order (R/16 operands of 1 KiB)
+// workspace of one layer: z in operand order (R/16 operands of 1 KiB), then the partial sums of decode_zr
 static size_t dec_zf_bytes(const parse_layer *L) { return round_up((size_t)(L->R / 16) * 1024, 256); }
+// decode_zr serves layers whose groups are whole 32-rank blocks and whose reduction fits DR_MAX_KS slices
+static bool dec_zr_ok(const parse_layer *layers, int n_layers) {
+  for (int l = 0; l < n_layers; ++l) {
+    const parse_layer *L = &layers[l];
+    if (L->G <= 0 || L->R % L->G != 0 || (L->R / L->G) % 32 != 0) return false;
+    if ((L->R / 32 + 1) / 2 > DEC_TICKETS) return false;
+  }
+  const int nkb = layers[0].n / 16;
+  return (nkb + 4 * DR_MAXK - 1) / (4 * DR_MAXK) <= DR_MAX_KS;
+}
+// slices of the reduction range: enough that a slice fits a workgroup (4 * DR_MAXK steps), and enough workgroups to give
+// every compute unit one
+static int dec_zr_slices(const parse_layer *layers, int n_layers) {
+  const int nkb = layers[0].n / 16;
+  int pairs = 0;
+  for (int l = 0; l < n_layers; ++l) pairs += (layers[l].R / 32 + 1) / 2;
+  int ks = (nkb + 4 * DR_MAXK - 1) / (4 * DR_MAXK);
+  const int fill = pairs > 0 ? DR_TARGET_WGS / pairs : 1;
+  if (fill > ks) ks = fill;
+  if (ks > nkb / 4) ks = nkb / 4;          // at least one step per wavefront
+  if (ks < (nkb + 4 * DR_MAXK - 1) / (4 * DR_MAXK)) ks = (nkb + 4 * DR_MAXK - 1) / (4 * DR_MAXK);
+  if (ks > DR_MAX_KS) ks = DR_MAX_KS;
+  return ks < 1 ? 1 : ks;
+}
+static size_t dec_zpart_bytes(const parse_layer *L, int ks) { return ks > 1 ? (size_t)(L->R / 32) * ks * 4096 : 0; }
 size_t decode_plan_bytes(int n_layers) { return round_up((size_t)n_layers * DEC_PLAN_WORDS * sizeof(int32_t), 256); }
-// z of the layer, then room for a one-layer plan (used when the caller brings no plan)
-size_t decode_workspace_bytes(const parse_layer *L) { return dec_zf_bytes(L) + decode_plan_bytes(1); }
+// z workspace of several layers that go through one call: per layer z, then its partial sums
+size_t decode_z_bytes(const parse_layer *layers, int n_layers) {
+  const int ks = dec_zr_ok(layers, n_layers) ? dec_zr_slices(layers, n_layers) : 1;
+  size_t t = 0;
+  for (int l = 0; l < n_layers; ++l) t += dec_zf_bytes(&layers[l]) + dec_zpart_bytes(&layers[l], ks);
+  return t;
+}
+// one layer's intermediates, then room for a one-layer plan (used when the caller brings no plan)
+size_t decode_workspace_bytes(const parse_layer *L) { return decode_z_bytes(L, 1) + decode_plan_bytes(1); }
 
 bool decode_supported(const parse_layer *L) {
   return L->R / 16 <= DY_MAXKB && L->G <= DEC_MAXG && L->n % 16 == 0 && L->n >= 16;
@@ -524,7 +623,7 @@ int build_decode_plan(const parse_layer *layers, const parse_patterns *pts, int 
 
 // n_layers layers that share x (same n); plan = n_layers consecutive layer plans; Y[l] and the z part of layer l in the
 // workspace follow the order of `layers`.
-int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const uint16_t *x, int B, const int32_t *plan,
+int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const uint16_t *x, int B, int32_t *plan,
                                 uint16_t *const *Y, void *workspace, hipStream_t s) {
   if (n_layers < 1 || n_layers > DEC_MAX_LAYERS) return PARSE_ESHAPE;
   static int n_cu_of[64] = {0};
@@ -554,11 +653,10 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
     for (int l = 0; l < n_layers; ++l) wgs += (layers[l].m / 32 + NC - 1) / NC;
     if (wgs <= n_cu) break;
   }
-  // 32-rank workgroups when they alone give the chip enough streams (each workgroup re-reads the x rows, so wider blocks
-  // mean less traffic); 16-rank workgroups otherwise (twice as many, each with half the factor stream)
-  int blocks32 = 0;
-  for (int l = 0; l < n_layers; ++l) blocks32 += layers[l].R / 32;
-  const bool wide = 2 * blocks32 >= n_cu;
+  // decode_zr when every layer's groups are whole 32-rank blocks; else 16-rank workgroups with LDS staging
+  const bool zr = dec_zr_ok(layers, n_layers);
+  const int KS = zr ? dec_zr_slices(layers, n_layers) : 1;
+  a.KS = KS;
   char *ws = reinterpret_cast<char *>(workspace);
   int zb = 0, yb = 0;
   for (int l = 0; l < n_layers; ++l) {
@@ -569,12 +667,15 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
     d.y = Y[l];
     d.zf = reinterpret_cast<uint16_t *>(ws);
     ws += dec_zf_bytes(L);
+    d.zpart = reinterpret_cast<float *>(ws);
+    ws += dec_zpart_bytes(L, KS);
     d.plan = plan + (size_t)l * DEC_PLAN_WORDS;
+    d.ticket = plan + (size_t)l * DEC_PLAN_WORDS + 192;
     d.R = L->R; d.G = L->G; d.gs = L->R / L->G; d.m = L->m;
-    d.z_first = zb; zb += wide ? L->R / 32 : L->R / 16;
+    d.z_first = zb; zb += zr ? ((L->R / 32 + 1) / 2) * KS : L->R / 16;
     d.y_first = yb; yb += (L->m / 32 + NC - 1) / NC;
   }
-  if (wide) hipLaunchKernelGGL(decode_zf32, dim3(zb), dim3(DZ_THREADS), 0, s, a);
+  if (zr) hipLaunchKernelGGL(decode_zr, dim3(zb), dim3(DR_THREADS), 0, s, a);
   else hipLaunchKernelGGL(decode_zf<2>, dim3(zb), dim3(DZ_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   if (NC == 1) hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
@@ -583,13 +684,6 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
   else hipLaunchKernelGGL(decode_y<4>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
-}
-
-// z workspace of several layers laid end to end (what forward_decode_planned_bf16 walks)
-size_t decode_z_bytes(const parse_layer *layers, int n_layers) {
-  size_t t = 0;
-  for (int l = 0; l < n_layers; ++l) t += dec_zf_bytes(&layers[l]);
-  return t;
 }
 
 // Without a caller's plan: the plan is built into the workspace (after the z parts), one more small launch.

@@ -56,8 +56,9 @@ int parse_lowrank_decode_static(const parse_layer *L, const parse_patterns *pt, 
   void *ws = nullptr;
   st = scratch_address(&ws);
   if (st != PARSE_OK) return st;
-  // Nothing in the array has to start at zero: every partial and every list entry the kernels read in a call was
-  // written earlier in that same call (the previous call's contents are overwritten or never looked at).
+  // What has to start at zero -- the arrival counters of the split reduction -- is part of the decode plan, which the
+  // call builds into the array first (a small kernel, no memset); every partial sum and every list entry the kernels
+  // read in a call was written earlier in that same call (the previous call's contents are overwritten or never looked at).
   return forward_decode_bf16(L, pt, (const uint16_t *)X, rows, pattern_id, (uint16_t *)Y, ws, (hipStream_t)stream);
 }
 

@@ -26,7 +26,7 @@ size_t decode_z_bytes(const parse_layer *layers, int n_layers);
 bool decode_supported(const parse_layer *L);
 int build_decode_plan(const parse_layer *layers, const parse_patterns *pts, int n_layers, const int32_t *pattern_id,
                       int B, int32_t *plan, hipStream_t s);
-int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const uint16_t *x, int B, const int32_t *plan,
+int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const uint16_t *x, int B, int32_t *plan,
                                 uint16_t *const *Y, void *workspace, hipStream_t s);
 int forward_decode_multi_bf16(const parse_layer *layers, const parse_patterns *pts, int n_layers, const uint16_t *x,
                               int B, const int32_t *pattern_id, uint16_t *const *Y, void *workspace, hipStream_t s);
@@ -133,12 +133,9 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patter
 
 size_t parse_lowrank_decode_multi_workspace_bytes(const parse_layer *layers, int32_t n_layers) {
   if (!layers || n_layers < 1 || n_layers > 4) return 0;
-  size_t total = 0;
-  for (int l = 0; l < n_layers; ++l) {
+  for (int l = 0; l < n_layers; ++l)
     if (layers[l].G <= 0 || layers[l].R <= 0) return 0;
-    total += decode_workspace_bytes(&layers[l]);
-  }
-  return total;
+  return decode_z_bytes(layers, n_layers) + decode_plan_bytes(n_layers);   // the call builds its plan behind the intermediates
 }
 
 int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
@@ -208,7 +205,7 @@ size_t parse_lowrank_decode_planned_workspace_bytes(const parse_layer *layers, i
 }
 
 int parse_lowrank_decode_planned(const parse_layer *layers, int32_t n_layers, const void *X, int32_t rows,
-                                 const void *plan, void *const *Y, void *workspace, size_t workspace_bytes,
+                                 void *plan, void *const *Y, void *workspace, size_t workspace_bytes,
                                  parse_stream stream) {
   if (!X || !plan || !Y) return PARSE_EINVAL;
   int st = check_decode_layers(layers, n_layers);
@@ -222,7 +219,7 @@ int parse_lowrank_decode_planned(const parse_layer *layers, int32_t n_layers, co
   }
   if (!workspace || workspace_bytes < decode_z_bytes(layers, n_layers)) return PARSE_EWORKSPACE;
   if (!aligned16(workspace)) return PARSE_EALIGN;
-  return forward_decode_planned_bf16(layers, n_layers, (const uint16_t *)X, rows, (const int32_t *)plan,
+  return forward_decode_planned_bf16(layers, n_layers, (const uint16_t *)X, rows, (int32_t *)plan,
                                      (uint16_t *const *)Y, workspace, (hipStream_t)stream);
 }
 

@@ -584,9 +584,12 @@ def test_decode_plan_contents_and_planned_step():
         pats.append(pa.Patterns(k, npat, subsets=i32(sub)))
     plan = pa.decode_plan(layers, pats, pid)
     torch.cuda.synchronize()
+    PLAN_WORDS = 448      # per layer: count, 64 used ids, 64 masks, padding to 192, then 256 arrival counters
+    assert plan.numel() >= len(shapes) * PLAN_WORDS * 4
     words = plan.view(torch.int32).cpu().numpy()
     for li, (lay, sub, G, k) in enumerate(subs_h):
-        w = words[li * 192:(li + 1) * 192]
+        w = words[li * PLAN_WORDS:(li + 1) * PLAN_WORDS]
+        assert np.all(w[192:] == 0), "arrival counters start at zero"
         masks = np.zeros(64, np.uint32)
         for b in range(B):
             if 0 <= seq_pat[b] < npat:
@@ -606,6 +609,8 @@ def test_decode_plan_contents_and_planned_step():
     ys_multi = pa.lowrank_decode_multi(layers, pats, xd, pid)
     torch.cuda.synchronize()
     assert torch.all(wsbuf[:256] == 0x5A) and torch.all(wsbuf[256 + need:] == 0x5A), "stores outside the workspace"
+    after = plan.view(torch.int32).cpu().numpy()
+    assert np.array_equal(after, words), "a decode call leaves the plan as it found it (arrival counters back at zero)"
     for li, (lay, sub, G, k) in enumerate(subs_h):
         buf, view = bufs[li]
         assert torch.all(buf[0] == 5.0) and torch.all(buf[-1] == 5.0), "stores outside Y"

@@ -52,13 +52,15 @@ def test_decode_static_matches_decode_with_workspace_twice_in_a_row():
 
 def test_decode_static_rejects_a_layer_beyond_its_capacity():
     cap = int(pa.lib().parse_lowrank_decode_static_capacity())
-    assert cap == 512 << 10
-    R, G = 8192, 64        # 64 bytes of scratch per stored rank + the plan: just beyond the fixed array
-    Vt = torch.zeros((R, 256), dtype=torch.bfloat16, device=DEV); Ut = torch.zeros((R, 256), dtype=torch.bfloat16, device=DEV)
-    big = pa.Layer(Vt, Ut, 256, 256, R, G, pa.PARSE_MFMA16)
+    assert cap == 4 << 20
+    # 64 bytes of scratch per stored rank, 128 more per stored rank and slice of the reduction (two slices at n = 4096),
+    # and the plan: 5 MiB, beyond the fixed array
+    R, G, n = 16384, 64, 4096
+    Vt = torch.zeros((R, n), dtype=torch.bfloat16, device=DEV); Ut = torch.zeros((R, 256), dtype=torch.bfloat16, device=DEV)
+    big = pa.Layer(Vt, Ut, n, 256, R, G, pa.PARSE_MFMA16)
     assert pa.lowrank_workspace_bytes(pa.PARSE_DECODE, big, 4, 2) > cap
     pt = pa.Patterns(2, 1, subsets=i32(np.array([[0, 1]], np.int32)))
-    x = torch.zeros((4, 256), dtype=torch.bfloat16, device=DEV); y = torch.full((4, 256), 3.0, dtype=torch.bfloat16, device=DEV)
+    x = torch.zeros((4, n), dtype=torch.bfloat16, device=DEV); y = torch.full((4, 256), 3.0, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(pa.ParseError) as ei:
         pa.lowrank_decode_static(big, pt, x, i32(np.zeros(4, np.int32)), y)
     assert ei.value.status == -5
