@@ -32,7 +32,7 @@ constexpr int DZ_CH = 256;                 // columns staged per chunk: 32 per w
 constexpr int DY_CHUNK = 4;                // decode_y: operands per chunk after the first block
 constexpr int DY_MAXKB = 1024;             // selected reduction blocks a decode_y workgroup can list
 constexpr int DEC_MAX_LAYERS = 4;
-constexpr int DEC_TICKETS = 256;           // pairs of 32-rank blocks of the largest layer (R = 16384)
+constexpr int DEC_TICKETS = 512;           // 32-rank blocks of the largest layer (R = 16384)
 constexpr int DEC_PLAN_WORDS = 192 + DEC_TICKETS;   // per layer: [0] count, [1..64] used group ids, [65..128] sequence masks,
                                                     // [192..) arrival counters of the split reduction (zero between calls)
 
@@ -45,7 +45,7 @@ struct DecLayer {
   uint16_t *zf;                // workspace: z of this layer in operand order
   const int32_t *plan;         // this layer's DEC_PLAN_WORDS of the decode plan
   float *zpart;                // workspace: partial sums of z, [R/32][KS][16][64] floats (KS > 1)
-  int32_t *ticket;             // [DEC_TICKETS] arrival counters in the plan, one per pair of 32-rank blocks
+  int32_t *ticket;             // [DEC_TICKETS] arrival counters in the plan, one per 32-rank block
   int R, G, gs, m;
   int z_first, y_first;        // first workgroup of this layer in decode_zf / decode_y
 };
@@ -100,25 +100,29 @@ __global__ __launch_bounds__(64) void decode_plan_build(DecPlanArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// decode_zr.  Workgroup = (layer, pair of 32-rank blocks, slice s of KS of the reduction range).  The form for layers
-// whose groups are multiples of 32 ranks.  A slice is at most 128 reduction steps (2048 columns): wavefront
-// (block, quarter) owns a quarter of the slice for one of the two rank blocks and requests ALL its Vt operands at once,
-// straight into registers (1 KiB coalesced per instruction, up to 32 of them): the registers of the eight wavefronts are
-// the staging buffer -- up to 256 KiB of factor stream in flight per compute unit, several times what LDS staging can
-// hold, which is what a stream from HBM needs.  The slice of the x rows is staged once per workgroup in LDS (loads that
-// write LDS directly; 512-byte row segments, 16-byte pieces XOR-swizzled by the row so that an operand read -- 32 rows x
-// the same piece -- spreads over the banks) and feeds both rank blocks.  After one wait and one barrier the products run
-// from registers and LDS; the four quarter sums of a block are added in quarter order through LDS.
+// decode_zr.  Workgroup = (layer, 32-rank block, slice s of KS of the reduction range).  The form for layers whose
+// groups are multiples of 32 ranks.  A slice is at most 256 reduction steps (4096 columns): each of the eight wavefronts
+// owns an eighth of it and requests ALL its Vt operands at once, straight into registers (1 KiB coalesced per
+// instruction, up to 32 of them): the registers of the eight wavefronts are the staging buffer -- 256 KiB of factor
+// stream in flight per compute unit, several times what LDS staging can hold, which is what a stream from HBM needs.
+// The x rows of the slice are staged in LDS (loads that write LDS directly; 512-byte row segments, 16-byte pieces
+// XOR-swizzled by the row so that an operand read -- 32 rows x the same piece -- spreads over the banks), at most 128
+// steps at a time.  TWO == false (slices of up to 128 steps): one wait, one barrier, then the products run from registers
+// and LDS.  TWO == true: the slice is staged in two halves; a wavefront's operands are ordered first half, second half,
+// so the products of the first half run while the second half of the factor stream is still arriving, and the second
+// half of x -- requested as soon as the first is consumed, long before the stream ends -- is there when it does.
+// The eight wavefronts' sums are added in wavefront order through LDS.
 // KS == 1: the block's z is masked, rounded to bf16 and stored as operands of the second product.
-// KS  > 1: the workgroup stores its partial sum (fp32) and takes a ticket of its pair; the workgroup that draws the last
-// ticket adds the KS partial sums in slice order (not in arrival order: same inputs, same bits) and stores the operands.
-// Nobody waits for anybody: a workgroup that is not the last simply ends.  The tickets live in the decode plan (zeroed
-// when the plan is built, reset by the last workgroup), so a plan serves one decode call at a time.
+// KS  > 1: the workgroup stores its partial sum (fp32) and takes a ticket of its rank block; the workgroup that draws
+// the last ticket adds the KS partial sums in slice order (not in arrival order: same inputs, same bits) and stores the
+// operands.  Nobody waits for anybody: a workgroup that is not the last simply ends.  The tickets live in the decode plan
+// (zeroed when the plan is built, reset by the last workgroup), so a plan serves one decode call at a time.
 constexpr int DR_WAVES = 8, DR_THREADS = DR_WAVES * 64;
-constexpr int DR_MAXK = 32;                  // Vt operands a wavefront requests (its quarter of the slice)
+constexpr int DR_MAXK = 32;                  // Vt operands a wavefront requests (its eighth of the slice)
 constexpr int DR_SEG_KB = 16;                // reduction steps per staged x segment (256 columns, 512 bytes per row)
 constexpr int DR_SEG_BYTES = 32 * 512;       // 16 KiB
-constexpr int DR_MAXSEG = 4 * DR_MAXK / DR_SEG_KB;   // 8 segments = 128 KiB
+constexpr int DR_MAXSEG = 8;                 // segments staged at a time: 128 steps, 128 KiB
+constexpr int DR_HALF_KB = DR_MAXSEG * DR_SEG_KB;    // 128
 constexpr int DR_MAX_KS = 16;
 constexpr int DR_TARGET_WGS = 240;           // workgroups wanted per launch: a little under one per compute unit
 
@@ -139,108 +143,177 @@ __device__ __forceinline__ void dec_store_z_operands(const float (&s)[16], uint3
   }
 }
 
+template <bool TWO>
 __global__ __launch_bounds__(DR_THREADS) void decode_zr(DecArgs a) {
+  constexpr int HK = DR_MAXK / 2;            // TWO: operands per half and wavefront
   int li = 0;
 #pragma unroll
   for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].z_first) ? 1 : 0;
   const DecLayer &ly = a.L[li];
   const int KS = a.KS;
   const int bid = blockIdx.x - ly.z_first;
-  const int pair = bid / KS, sl = bid % KS;
+  const int rb = bid / KS, sl = bid % KS;
   const int n = a.n, B = a.B, gs = ly.gs;
-  const int nb32 = ly.R / 32;
-  const int rb0 = pair * 2;
-  // sequences whose pattern holds each block's group; a block nobody selected is neither read nor written
-  const uint32_t mask0 = (uint32_t)ly.plan[65 + (rb0 * 32) / gs];
-  const uint32_t mask1 = rb0 + 1 < nb32 ? (uint32_t)ly.plan[65 + ((rb0 + 1) * 32) / gs] : 0u;
-  if ((mask0 | mask1) == 0u) return;
+  // sequences whose pattern holds this block's group; a block nobody selected is neither read nor written
+  const uint32_t mask = (uint32_t)ly.plan[65 + (rb * 32) / gs];
+  if (mask == 0u) return;
   __shared__ __attribute__((aligned(1024))) char xs[DR_MAXSEG * DR_SEG_BYTES];
   __shared__ int32_t am_last;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int j = lane & 31, q = lane >> 5;
-  const int blk = wave >> 2, kq = wave & 3;
-  const uint32_t my_mask = blk == 0 ? mask0 : mask1;
   const int nkb = n / 16;
   const int ks0 = (int)(((long long)nkb * sl) / KS), ks1 = (int)(((long long)nkb * (sl + 1)) / KS);
-  const int cnt_wg = ks1 - ks0;                         // <= 4 * DR_MAXK (the host picks KS so)
-  const int k0w = (cnt_wg * kq) / 4, k1w = (cnt_wg * (kq + 1)) / 4;
-  const int cnt_w = my_mask != 0u ? k1w - k0w : 0;      // this wavefront's reduction steps (<= DR_MAXK)
-  // ---- all Vt operands of this wavefront, requested at once (steps past the count re-read the last one) ----
-  u32x4 vr[DR_MAXK];
-  {
-    const char *vbase = (const char *)ly.Vt + ((size_t)(rb0 + blk) * nkb + ks0 + k0w) * 1024 + lane * 16;
+  const int cnt_wg = ks1 - ks0;                         // <= 8 * DR_MAXK, and <= DR_HALF_KB unless TWO (the host picks KS so)
+  // the slice in one part (A) or two (A, B); x segments are counted from the start of the slice
+  const int nseg = (cnt_wg + DR_SEG_KB - 1) / DR_SEG_KB;
+  const int nsegA = TWO ? (nseg + 1) / 2 : nseg;        // <= DR_MAXSEG
+  const int cntA = min(cnt_wg, nsegA * DR_SEG_KB), cntB = cnt_wg - cntA;
+  const int a0 = (cntA * wave) / DR_WAVES, cntAw = (cntA * (wave + 1)) / DR_WAVES - a0;   // this wavefront's steps of part A
+  const int b0 = (cntB * wave) / DR_WAVES, cntBw = (cntB * (wave + 1)) / DR_WAVES - b0;   // ... of part B (<= HK each if TWO)
+  const int last_piece = n / 8 - 1;
+  // x segments [s0, s0 + ns) of the slice into LDS slots 0..ns-1: a segment is 16 instructions of 1 KiB (two rows of 512
+  // bytes each).  Lane l writes slot l % 32 of row 2*ins + l / 32 and fetches the piece (slot ^ (row & 15)) of that row's
+  // segment; pieces past the end of the row re-read its last one (their products are switched off below)
+  auto stage_x = [&](int s0, int ns) {
 #pragma unroll
-    for (int g = 0; g < DR_MAXK / 4; ++g) {
-      if (g * 4 < cnt_w) {                               // uniform
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii)
-          vr[g * 4 + ii] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)min(g * 4 + ii, cnt_w - 1) * 1024);
-      } else {
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii) vr[g * 4 + ii] = u32x4{0, 0, 0, 0};
+    for (int u = 0; u < DR_MAXSEG * 16 / DR_WAVES; ++u) {
+      const int t = wave + u * DR_WAVES;                 // instruction id: segment t / 16, row pair t % 16
+      if (t < ns * 16) {                                 // uniform
+        const int seg = t >> 4, ins = t & 15;
+        const int r = ins * 2 + (lane >> 5);
+        const int piece = min(ks0 * 2 + (s0 + seg) * 32 + ((lane & 31) ^ (r & 15)), last_piece);
+        __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR((const char *)a.x + (size_t)min(r, B - 1) * n * 2 + (size_t)piece * 16),
+                                         PARSE_DEC_LDS_PTR(xs + seg * DR_SEG_BYTES + ins * 1024), 16, 0, 0);
       }
     }
-  }
-  // ---- the slice of the x rows into LDS: segment = 16 instructions of 1 KiB (two rows of 512 bytes each).  Lane l writes
-  // slot l % 32 of row 2*ins + l / 32 and fetches the piece (slot ^ (row & 15)) of that row's segment; pieces past the end
-  // of the row re-read its last one (their products are switched off below) ----
-  const int nseg = (cnt_wg + DR_SEG_KB - 1) / DR_SEG_KB;
-  const int last_piece = n / 8 - 1;
-#pragma unroll
-  for (int u = 0; u < DR_MAXSEG * 16 / DR_WAVES; ++u) {
-    const int t = wave + u * DR_WAVES;                   // instruction id: segment t / 16, row pair t % 16
-    if (t < nseg * 16) {                                 // uniform
-      const int seg = t >> 4, ins = t & 15;
-      const int r = ins * 2 + (lane >> 5);
-      const int piece = min(ks0 * 2 + seg * 32 + ((lane & 31) ^ (r & 15)), last_piece);
-      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR((const char *)a.x + (size_t)min(r, B - 1) * n * 2 + (size_t)piece * 16),
-                                       PARSE_DEC_LDS_PTR(xs + seg * DR_SEG_BYTES + ins * 1024), 16, 0, 0);
-    }
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();                                       // everybody's x rows are in LDS
+  };
+  // lane's x operand of step kl (counted from the first staged segment)
+  auto x_operand = [&](int kl) -> u32x4 {
+    return *reinterpret_cast<const u32x4 *>(xs + (kl >> 4) * DR_SEG_BYTES + j * 512 + ((((kl & 15) * 2 + q) ^ (j & 15)) * 16));
+  };
   f32x16 acc;
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   const u32x4 zero = {0, 0, 0, 0};
+  const char *vrow = (const char *)ly.Vt + ((size_t)rb * nkb + ks0) * 1024;   // uniform; operand k of the slice at + k KiB
+  const int vlane = lane * 16;
+  u32x4 vr[DR_MAXK];
+  if (!TWO) {
+    // ---- all Vt operands of this wavefront, requested at once (steps past the count re-read the last one) ----
 #pragma unroll
-  for (int g = 0; g < DR_MAXK / 4; ++g) {
-    if (g * 4 < cnt_w) {                                 // uniform
+    for (int g = 0; g < HK / 4; ++g) {                   // a slice of up to 128 steps: up to HK per wavefront
+      if (g * 4 < cntAw) {                               // uniform
 #pragma unroll
-      for (int ii = 0; ii < 4; ++ii) {
-        const int i = g * 4 + ii;
-        const int kl = min(k0w + i, cnt_wg - 1);         // step within the slice
-        const u32x4 xv = *reinterpret_cast<const u32x4 *>(xs + (kl >> 4) * DR_SEG_BYTES + j * 512 +
-                                                          ((((kl & 15) * 2 + q) ^ (j & 15)) * 16));
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(vr[i]), dec_bf16x8(i < cnt_w ? xv : zero), acc, 0, 0, 0);
+        for (int ii = 0; ii < 4; ++ii)
+          vr[g * 4 + ii] = *reinterpret_cast<const u32x4 *>(vrow + (size_t)(a0 + min(g * 4 + ii, cntAw - 1)) * 1024 + vlane);
+      } else {
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) vr[g * 4 + ii] = zero;
       }
+    }
+    stage_x(0, nsegA);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                                     // everybody's x rows are in LDS
+#pragma unroll
+    for (int g = 0; g < HK / 4; ++g) {
+      if (g * 4 < cntAw) {                               // uniform
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+          const int i = g * 4 + ii;
+          const u32x4 xv = x_operand(min(a0 + i, cntA - 1));
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(vr[i]), dec_bf16x8(i < cntAw ? xv : zero), acc, 0, 0, 0);
+        }
+      }
+    }
+  } else {
+    // ---- Two stagings.  Here the x rows go through registers (16 loads of 1 KiB per wavefront and half, then 16 LDS
+    // writes): with plain loads the compiler counts every outstanding load exactly, so the products of part A start while
+    // the operands of part B are still in flight (it does not do that across loads that write LDS directly).  Every
+    // wavefront issues the same number of loads whatever the counts are -- instructions past the end repeat the last
+    // one (same data to the same place) -- first half of x, operands of part A, operands of part B ----
+    constexpr int XI = DR_MAXSEG * 16 / DR_WAVES;        // x instructions per wavefront and half
+    auto x_src = [&](int s0, int ns, int u) -> const char * {
+      const int t = min(wave + u * DR_WAVES, ns * 16 - 1);
+      const int seg = t >> 4, ins = t & 15;
+      const int r = ins * 2 + (lane >> 5);
+      const int piece = min(ks0 * 2 + (s0 + seg) * 32 + ((lane & 31) ^ (r & 15)), last_piece);
+      return (const char *)a.x + (size_t)min(r, B - 1) * n * 2 + (size_t)piece * 16;
+    };
+    auto x_dst = [&](int ns, int u) -> char * {          // wave-uniform slot + the lane's 16 bytes
+      const int t = min(wave + u * DR_WAVES, ns * 16 - 1);
+      return xs + (t >> 4) * DR_SEG_BYTES + (t & 15) * 1024 + lane * 16;
+    };
+    auto bare_barrier = [&]() {     // the usual barrier comes with a fence that waits for every outstanding load
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    };
+    u32x4 xr[XI];
+#pragma unroll
+    for (int u = 0; u < XI; ++u) xr[u] = *reinterpret_cast<const u32x4 *>(x_src(0, nsegA, u));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < HK; ++i)
+      vr[i] = *reinterpret_cast<const u32x4 *>(vrow + (size_t)(a0 + min(i, max(cntAw - 1, 0))) * 1024 + vlane);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < HK; ++i)
+      vr[HK + i] = *reinterpret_cast<const u32x4 *>(vrow + (size_t)min(cntA + b0 + min(i, max(cntBw - 1, 0)), cnt_wg - 1) * 1024 + vlane);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < XI; ++u) *reinterpret_cast<u32x4 *>(x_dst(nsegA, u)) = xr[u];
+    bare_barrier();                                      // everybody's share of the first half of x is in LDS
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < HK; ++i) {
+      const u32x4 xv = x_operand(min(a0 + i, cntA - 1));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(vr[i]), dec_bf16x8(i < cntAw ? xv : zero), acc, 0, 0, 0);
+      if (i % 4 == 3) __builtin_amdgcn_sched_barrier(0);     // a few x operands in registers at a time, not all sixteen
+    }
+    bare_barrier();                                      // everybody is done with the first half of x
+    __builtin_amdgcn_sched_barrier(0);
+    const int nsegB = max(nseg - nsegA, 1);
+#pragma unroll
+    for (int u = 0; u < XI; ++u) xr[u] = *reinterpret_cast<const u32x4 *>(x_src(min(nsegA, nseg - 1), nsegB, u));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < XI; ++u) *reinterpret_cast<u32x4 *>(x_dst(nsegB, u)) = xr[u];
+    bare_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    const int offB = cntA - nsegA * DR_SEG_KB;           // first step of part B counted from the first segment staged now (0)
+#pragma unroll
+    for (int i = 0; i < HK; ++i) {
+      const u32x4 xv = x_operand(max(0, min(offB + b0 + i, offB + cntB - 1)));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dec_bf16x8(vr[HK + i]), dec_bf16x8(i < cntBw ? xv : zero), acc, 0, 0, 0);
+      if (i % 4 == 3) __builtin_amdgcn_sched_barrier(0);
     }
   }
   __syncthreads();        // the staged rows are dead: their LDS now takes the wavefronts' sums
   float(*red)[16][64] = reinterpret_cast<float(*)[16][64]>(xs);               // [8][16][64] floats = 32 KiB
-  float(*sums)[16][64] = reinterpret_cast<float(*)[16][64]>(xs + 32768);      // [2][16][64]
+  float *sums = reinterpret_cast<float *>(xs + 32768);                        // [16][64]
 #pragma unroll
   for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[e];
   __syncthreads();
-  // the four quarter sums of each block, in quarter order; value v = (block, e, lane)
+  // the eight sums of each value, in wavefront order; value v = (e, lane)
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
+  for (int u = 0; u < 2; ++u) {
     const int v = (int)threadIdx.x + u * DR_THREADS;
-    const int b2 = v >> 10, rem = v & 1023;
-    const float *r0 = &red[b2 * 4][0][0] + rem;
-    const float sum = ((r0[0] + r0[1024]) + r0[2048]) + r0[3072];
-    if (KS == 1) sums[b2][0][rem] = sum;
-    else if (rb0 + b2 < nb32)     // device-scope store: written through to memory, past this die's (non-coherent) L2
-      __hip_atomic_store(&ly.zpart[((size_t)(rb0 + b2) * KS + sl) * 1024 + rem], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const float *r0 = &red[0][0][0] + v;
+    float sum = r0[0];
+#pragma unroll
+    for (int w = 1; w < DR_WAVES; ++w) sum += r0[w * 1024];
+    if (KS == 1) sums[v] = sum;
+    else           // device-scope store: written through to memory, past this die's (non-coherent) L2
+      __hip_atomic_store(&ly.zpart[((size_t)rb * KS + sl) * 1024 + v], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   if (KS == 1) {
     __syncthreads();
-    if (kq == 0 && my_mask != 0u) {
+    if (wave == 0) {
       float s[16];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) s[e] = sums[blk][e][lane];
-      dec_store_z_operands(s, my_mask, lane, ly.zf, rb0 + blk);
+      for (int e = 0; e < 16; ++e) s[e] = sums[e * 64 + lane];
+      dec_store_z_operands(s, mask, lane, ly.zf, rb);
     }
     return;
   }
@@ -252,17 +325,17 @@ __global__ __launch_bounds__(DR_THREADS) void decode_zr(DecArgs a) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (threadIdx.x == 0) {
-    const int t = __hip_atomic_fetch_add(&ly.ticket[pair], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int t = __hip_atomic_fetch_add(&ly.ticket[rb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int last = t == KS - 1 ? 1 : 0;
-    if (last) __hip_atomic_store(&ly.ticket[pair], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+    if (last) __hip_atomic_store(&ly.ticket[rb], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
     am_last = last;
   }
   __syncthreads();
   if (!am_last) return;
-  // the last workgroup of the pair: all KS partial sums are in memory; read them past the L2 as well, add in slice order
-  if (kq == 0 && my_mask != 0u) {
+  // the last workgroup of the block: all KS partial sums are in memory; read them past the L2 as well, add in slice order
+  if (wave == 0) {
     float s[16];
-    const float *zp = ly.zpart + (size_t)(rb0 + blk) * KS * 1024 + lane;
+    const float *zp = ly.zpart + (size_t)rb * KS * 1024 + lane;
 #pragma unroll
     for (int e = 0; e < 16; ++e) s[e] = __hip_atomic_load(zp + e * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int o = 1; o < KS; ++o) {
@@ -272,7 +345,7 @@ __global__ __launch_bounds__(DR_THREADS) void decode_zr(DecArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[e] += t[e];
     }
-    dec_store_z_operands(s, my_mask, lane, ly.zf, rb0 + blk);
+    dec_store_z_operands(s, mask, lane, ly.zf, rb);
   }
 }
 
@@ -572,22 +645,21 @@ static bool dec_zr_ok(const parse_layer *layers, int n_layers) {
   for (int l = 0; l < n_layers; ++l) {
     const parse_layer *L = &layers[l];
     if (L->G <= 0 || L->R % L->G != 0 || (L->R / L->G) % 32 != 0) return false;
-    if ((L->R / 32 + 1) / 2 > DEC_TICKETS) return false;
+    if (L->R / 32 > DEC_TICKETS) return false;
   }
   const int nkb = layers[0].n / 16;
-  return (nkb + 4 * DR_MAXK - 1) / (4 * DR_MAXK) <= DR_MAX_KS;
+  return (nkb + 8 * DR_MAXK - 1) / (8 * DR_MAXK) <= DR_MAX_KS;
 }
-// slices of the reduction range: enough that a slice fits a workgroup (4 * DR_MAXK steps), and enough workgroups to give
+// slices of the reduction range: enough that a slice fits a workgroup (8 * DR_MAXK steps), and enough workgroups to give
 // every compute unit one
 static int dec_zr_slices(const parse_layer *layers, int n_layers) {
   const int nkb = layers[0].n / 16;
-  int pairs = 0;
-  for (int l = 0; l < n_layers; ++l) pairs += (layers[l].R / 32 + 1) / 2;
-  int ks = (nkb + 4 * DR_MAXK - 1) / (4 * DR_MAXK);
-  const int fill = pairs > 0 ? DR_TARGET_WGS / pairs : 1;
-  if (fill > ks) ks = fill;
-  if (ks > nkb / 4) ks = nkb / 4;          // at least one step per wavefront
-  if (ks < (nkb + 4 * DR_MAXK - 1) / (4 * DR_MAXK)) ks = (nkb + 4 * DR_MAXK - 1) / (4 * DR_MAXK);
+  int blocks = 0;
+  for (int l = 0; l < n_layers; ++l) blocks += layers[l].R / 32;
+  const int need = (nkb + 8 * DR_MAXK - 1) / (8 * DR_MAXK);
+  int ks = blocks > 0 ? DR_TARGET_WGS / blocks : 1;
+  if (ks > nkb / 8) ks = nkb / 8;          // at least one step per wavefront
+  if (ks < need) ks = need;
   if (ks > DR_MAX_KS) ks = DR_MAX_KS;
   return ks < 1 ? 1 : ks;
 }
@@ -672,10 +744,13 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
     d.plan = plan + (size_t)l * DEC_PLAN_WORDS;
     d.ticket = plan + (size_t)l * DEC_PLAN_WORDS + 192;
     d.R = L->R; d.G = L->G; d.gs = L->R / L->G; d.m = L->m;
-    d.z_first = zb; zb += zr ? ((L->R / 32 + 1) / 2) * KS : L->R / 16;
+    d.z_first = zb; zb += zr ? (L->R / 32) * KS : L->R / 16;
     d.y_first = yb; yb += (L->m / 32 + NC - 1) / NC;
   }
-  if (zr) hipLaunchKernelGGL(decode_zr, dim3(zb), dim3(DR_THREADS), 0, s, a);
+  const int nkb = a.n / 16;
+  const bool two = (nkb + KS - 1) / KS > DR_HALF_KB;     // the longest slice needs two stagings of x
+  if (zr && two) hipLaunchKernelGGL(decode_zr<true>, dim3(zb), dim3(DR_THREADS), 0, s, a);
+  else if (zr) hipLaunchKernelGGL(decode_zr<false>, dim3(zb), dim3(DR_THREADS), 0, s, a);
   else hipLaunchKernelGGL(decode_zf<2>, dim3(zb), dim3(DZ_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   if (NC == 1) hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);

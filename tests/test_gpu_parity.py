@@ -584,7 +584,7 @@ def test_decode_plan_contents_and_planned_step():
         pats.append(pa.Patterns(k, npat, subsets=i32(sub)))
     plan = pa.decode_plan(layers, pats, pid)
     torch.cuda.synchronize()
-    PLAN_WORDS = 448      # per layer: count, 64 used ids, 64 masks, padding to 192, then 256 arrival counters
+    PLAN_WORDS = 704      # per layer: count, 64 used ids, 64 masks, padding to 192, then 512 arrival counters
     assert plan.numel() >= len(shapes) * PLAN_WORDS * 4
     words = plan.view(torch.int32).cpu().numpy()
     for li, (lay, sub, G, k) in enumerate(subs_h):

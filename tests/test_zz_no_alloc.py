@@ -53,9 +53,9 @@ def test_decode_static_matches_decode_with_workspace_twice_in_a_row():
 def test_decode_static_rejects_a_layer_beyond_its_capacity():
     cap = int(pa.lib().parse_lowrank_decode_static_capacity())
     assert cap == 4 << 20
-    # 64 bytes of scratch per stored rank, 128 more per stored rank and slice of the reduction (two slices at n = 4096),
+    # 64 bytes of scratch per stored rank, 128 more per stored rank and slice of the reduction (two slices at n = 8192),
     # and the plan: 5 MiB, beyond the fixed array
-    R, G, n = 16384, 64, 4096
+    R, G, n = 16384, 64, 8192
     Vt = torch.zeros((R, n), dtype=torch.bfloat16, device=DEV); Ut = torch.zeros((R, 256), dtype=torch.bfloat16, device=DEV)
     big = pa.Layer(Vt, Ut, n, 256, R, G, pa.PARSE_MFMA16)
     assert pa.lowrank_workspace_bytes(pa.PARSE_DECODE, big, 4, 2) > cap
