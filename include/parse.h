@@ -212,8 +212,10 @@ int parse_pack_new_entries(const parse_layer *layer, const int32_t *subset, int3
  * groups 0..n_shared-1; they are stored ONCE (Vt_shared, Ut_shared = parse_pack_experts of the ids
  * 0..n_shared-1) and the per-pattern blocks hold only the other k - n_shared groups (parse_pack_patterns /
  * parse_pack_new_entries on `subset + n_shared` with k - n_shared ids and the full row stride), so a prompt
- * reads two contiguous blocks.  bf16 prefill in the two-launch schedule only (a workspace is then required);
- * decode reads the layer's own store by group id and ignores these three fields. */
+ * reads two contiguous blocks.  bf16 prefill in the planned and two-launch schedules (a workspace is then required;
+ * the head must be whole 32-rank blocks for the planned one; the fused kernel reads one block per pattern and
+ * answers PARSE_ELAYOUT); decode reads the layer's own store by group id and ignores these three fields -- there the
+ * shared groups are simply groups that every sequence selected: streamed once per step, applied to all. */
 typedef struct {
   const void *Vt_S;       /* device, packed [n_patterns][(k-n_shared)*gs][n] in the layer's layout; prefill only */
   const void *Ut_S;       /* device, packed [n_patterns][(k-n_shared)*gs][m];                       prefill only */
@@ -255,7 +257,9 @@ size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *layer, int
  *                  X device [rows][n], Y device [rows][m] (layer dtype), tok_offsets device int32 [P+1],
  *                  pattern_id device int32 [P].
  * PARSE_DECODE   one token per sequence (rows == P, tok_offsets ignored, may be NULL), bf16 PARSE_MFMA16
- *                layers only, rows <= 32 per call.  Streams every group that some sequence selected exactly
+ *                layers only.  Sequences are taken in panels of 32 (the N side of the matrix instruction): rows > 32
+ *                costs one pass over the selected groups per panel, and a group is streamed for a panel only if one
+ *                of that panel's sequences selected it.  Per panel: streams every group that some sequence selected exactly
  *                once from the layer's own store (layer->Vt / layer->Ut, not the packed copies) and applies
  *                it to the sequences whose pattern holds it (Sec. 4.3, rank reuse: pattern_id is fixed
  *                at prefill).  Bandwidth-bound.
@@ -282,7 +286,8 @@ size_t parse_prefill_plan_bytes(int32_t rows, int32_t P, int32_t n_patterns);
 int parse_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, int32_t P, int32_t rows,
                        int32_t n_patterns, void *plan, size_t plan_bytes, parse_stream stream);
 /* The bf16 prefill product (Eq. 10) of one layer over a ready plan: two launches, no prompt-dependent work on the
- * host.  layer bf16 PARSE_MFMA16 with n % 64 == 0; patterns as for PARSE_PREFILL (no shared head); the plan must
+ * host.  layer bf16 PARSE_MFMA16 with n % 64 == 0; patterns as for PARSE_PREFILL (a shared head must be whole 32-rank
+ * blocks); the plan must
  * have been built from the same tok_offsets, pattern_id, rows, P and patterns->n_patterns (short batches run their
  * first product on prompt-order tiles, which read the two arrays directly).
  *   workspace  device, >= parse_lowrank_prefill_planned_workspace_bytes(layer, rows, P, k, n_patterns): the
@@ -341,11 +346,12 @@ int parse_router_grad(const parse_layer *layer, const void *Ut_rankmajor, const 
  * (equal n; m, R, G and the patterns may differ per layer) take ONE decode step together: the result equals
  * n_layers separate PARSE_DECODE calls, at the launch count of one.
  *   layers, patterns  host arrays [n_layers]; layer l uses patterns[l] (its own subsets, k, n_patterns)
- *   X                 device [rows][n] bf16, rows <= 32, one token per sequence
+ *   X                 device [rows][n] bf16, one token per sequence (panels of 32 as for PARSE_DECODE)
  *   pattern_id        device int32 [rows], shared by all layers (a sequence's cache entry)
  *   Y                 host array [n_layers] of device pointers, Y[l] = [rows][layers[l].m] bf16
  *   workspace         device, >= parse_lowrank_decode_multi_workspace_bytes(layers, n_layers), caller-owned
- * Errors as parse_lowrank_forward; nothing is launched on error.  Same inputs, same bits. */
+ * Errors as parse_lowrank_forward; nothing is launched on error.  Same inputs, same bits.  (A result may differ in
+ * rounding from the single-layer call's: the reduction over n is cut into slices by the size of the whole call.) */
 size_t parse_lowrank_decode_multi_workspace_bytes(const parse_layer *layers, int32_t n_layers);
 int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
                                const void *X, int32_t rows, const int32_t *pattern_id, void *const *Y,

@@ -73,8 +73,13 @@ int parse_lowrank_prefill_planned(const parse_layer *L, const parse_patterns *pt
   if (!pt || !X || !Y || !plan || !tok_offsets || !pattern_id || !pt->Vt_S || !pt->Ut_S) return PARSE_EINVAL;
   if (rows <= 0 || P <= 0 || pt->n_patterns <= 0 || pt->k <= 0) return PARSE_EINVAL;
   if (L->dtype != PARSE_BF16 || L->layout != PARSE_MFMA16) return PARSE_ELAYOUT;
-  if (pt->n_shared != 0) return PARSE_ELAYOUT;
+  if (pt->n_shared < 0) return PARSE_EINVAL;
   const int rS = pt->k * (L->R / L->G);
+  if (pt->n_shared > 0) {   // shared head: whole 32-rank blocks, stored once
+    if (!pt->Vt_shared || !pt->Ut_shared) return PARSE_EINVAL;
+    if (pt->n_shared >= pt->k || (pt->n_shared * (L->R / L->G)) % 32 != 0) return PARSE_ESHAPE;
+    if (!aligned16(pt->Vt_shared) || !aligned16(pt->Ut_shared)) return PARSE_EALIGN;
+  }
   if (pt->k > L->G || P > rows || !prefill_plan_supported(P, pt->n_patterns) ||
       !prefill_planned_supported(L->n, L->m, rS)) return PARSE_ESHAPE;
   if (!aligned16(X) || !aligned16(Y) || !aligned16(plan) || !aligned16(pt->Vt_S) || !aligned16(pt->Ut_S)) return PARSE_EALIGN;
@@ -83,6 +88,11 @@ int parse_lowrank_prefill_planned(const parse_layer *L, const parse_patterns *pt
   if (!aligned16(workspace)) return PARSE_EALIGN;
   PfArgs a{(const uint16_t *)X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, (uint16_t *)Y, tok_offsets, pattern_id,
            pt->n_patterns, rows, L->n, L->m, rS, P};
+  if (pt->n_shared > 0) {
+    a.Vt_sh = (const uint16_t *)pt->Vt_shared;
+    a.Ut_sh = (const uint16_t *)pt->Ut_shared;
+    a.sh_ranks = pt->n_shared * (L->R / L->G);
+  }
   return forward_prefill_planned_bf16(a, (const int32_t *)plan, cap, (uint16_t *)workspace, rows / P, (hipStream_t)stream);
 }
 
@@ -107,8 +117,16 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *L, const parse_patter
 
   if (mode == PARSE_DECODE) {
     if (!pt->subsets) return PARSE_EINVAL;
-    if (rows != P || rows > 32 || L->G > 64 || pt->subset_stride < pt->k) return PARSE_ESHAPE;
-    return forward_decode_bf16(L, pt, (const uint16_t *)X, rows, pattern_id, (uint16_t *)Y, workspace, s);
+    if (rows != P || L->G > 64 || pt->subset_stride < pt->k) return PARSE_ESHAPE;
+    // panels of 32 sequences (the matrix instruction's N side); every panel has its own masks and streams the groups
+    // its own sequences selected
+    for (int r0 = 0; r0 < rows; r0 += 32) {
+      const int nb = rows - r0 < 32 ? rows - r0 : 32;
+      st = forward_decode_bf16(L, pt, (const uint16_t *)X + (size_t)r0 * L->n, nb, pattern_id + r0,
+                               (uint16_t *)Y + (size_t)r0 * L->m, workspace, s);
+      if (st != PARSE_OK) return st;
+    }
+    return PARSE_OK;
   }
 
   if (!tok_offsets || !pt->Vt_S || !pt->Ut_S) return PARSE_EINVAL;
@@ -143,7 +161,7 @@ int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *
                                void *workspace, size_t workspace_bytes, parse_stream stream) {
   if (!layers || !patterns || !X || !pattern_id || !Y) return PARSE_EINVAL;
   if (n_layers < 1 || rows <= 0) return PARSE_EINVAL;
-  if (n_layers > 4 || rows > 32) return PARSE_ESHAPE;
+  if (n_layers > 4) return PARSE_ESHAPE;
   if (!aligned16(X)) return PARSE_EALIGN;
   for (int l = 0; l < n_layers; ++l) {
     const parse_layer *L = &layers[l];
@@ -159,8 +177,16 @@ int parse_lowrank_decode_multi(const parse_layer *layers, const parse_patterns *
   const size_t need = parse_lowrank_decode_multi_workspace_bytes(layers, n_layers);
   if (!workspace || workspace_bytes < need) return PARSE_EWORKSPACE;
   if (!aligned16(workspace)) return PARSE_EALIGN;
-  return forward_decode_multi_bf16(layers, patterns, n_layers, (const uint16_t *)X, rows, pattern_id,
-                                   (uint16_t *const *)Y, workspace, (hipStream_t)stream);
+  // panels of 32 sequences, as in parse_lowrank_forward(PARSE_DECODE)
+  for (int r0 = 0; r0 < rows; r0 += 32) {
+    const int nb = rows - r0 < 32 ? rows - r0 : 32;
+    uint16_t *Yp[4] = {nullptr, nullptr, nullptr, nullptr};
+    for (int l = 0; l < n_layers; ++l) Yp[l] = (uint16_t *)Y[l] + (size_t)r0 * layers[l].m;
+    const int st = forward_decode_multi_bf16(layers, patterns, n_layers, (const uint16_t *)X + (size_t)r0 * layers[0].n, nb,
+                                             pattern_id + r0, Yp, workspace, (hipStream_t)stream);
+    if (st != PARSE_OK) return st;
+  }
+  return PARSE_OK;
 }
 
 // checks shared by the decode entry points that take several layers

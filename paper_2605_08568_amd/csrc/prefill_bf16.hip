@@ -372,7 +372,7 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
   const int gs = L->R / L->G, rS = pt->k * gs;
   PfArgs a{X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, Y, tok_offsets, pattern_id,
            pt->n_patterns, rows, L->n, L->m, rS, P};
-  if (pt->n_shared > 0) {   // shared head: operands from two blocks, built into the two-launch tile kernels only
+  if (pt->n_shared > 0) {   // shared head: operands from two blocks (planned and two-launch schedules; the fused kernel has none)
     a.Vt_sh = (const uint16_t *)pt->Vt_shared;
     a.Ut_sh = (const uint16_t *)pt->Ut_shared;
     a.sh_ranks = pt->n_shared * gs;
@@ -380,7 +380,7 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
   const int schedule = pt->schedule;
   if (schedule < PARSE_SCHED_AUTO || schedule > PARSE_SCHED_PLANNED) return PARSE_EINVAL;
   // planned: plan + two launches of the LDS-staged tile kernel; workspace = intermediate of the padded rows, then the plan
-  const bool planned_shapes = a.sh_ranks == 0 && prefill_plan_supported(P, pt->n_patterns) &&
+  const bool planned_shapes = a.sh_ranks % 32 == 0 && prefill_plan_supported(P, pt->n_patterns) &&
                               prefill_planned_supported(L->n, L->m, rS);
   const int cap = planned_shapes ? prefill_plan_capacity(rows, P, pt->n_patterns) : 0;
   const size_t zb = planned_shapes ? prefill_planned_z_bytes(cap, rS) : 0;
@@ -397,7 +397,10 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
   const bool can_split = workspace != nullptr && workspace_bytes >= prefill_split_workspace_bytes(rows, rS) &&
                          prefill_split_supported(L->n, rS);
   bool split = can_split;
-  if (schedule == PARSE_SCHED_FUSED) split = false;
+  if (schedule == PARSE_SCHED_FUSED) {
+    if (a.sh_ranks > 0) return PARSE_ELAYOUT;   // the fused kernel reads one block per pattern
+    split = false;
+  }
   if (schedule == PARSE_SCHED_TILES || a.sh_ranks > 0) {
     if (!can_split) return prefill_split_supported(L->n, rS) ? PARSE_EWORKSPACE : PARSE_ESHAPE;
     split = true;

@@ -47,6 +47,12 @@ struct LgArgs {
   const int32_t *plan;     // header | tile patterns | row map (plan.hip)
   int cap;                 // plan capacity in 256-row tiles (fixes where the row map starts)
   int ntn, gm, ngroups;    // column tiles, token tiles per locality group, groups
+  // shared head (Sec. 4.4: shared experts at the head of memory, stored once): the first sh_blocks 32-rank blocks of
+  // every pattern's selection come from Fsh (same operand order, as many rank rows as the head has), the per-pattern
+  // blocks in F hold the rest, renumbered from 0.  FORD 0: the leading factor-row blocks; FORD 1 (BK == 32 only): the
+  // leading reduction slices.  0 = everything per pattern.
+  const uint16_t *Fsh;
+  int sh_blocks;
 };
 
 // FORD: factor order, 0 = right factor (operand (rb, kb) at rb*(K/16)+kb), 1 = left factor (operand (kb, cb) at kb*(M/32)+cb).
@@ -104,17 +110,27 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
 
   // ---- per-lane global sources of this wavefront's load instructions; they advance by a constant per slice ----
   const char *fsrc[LF];
+  const char *fsrc_own[LF];                    // FORD 1 with a shared head: where the pattern's own slices start
   int fdst[LF];
+  const int shb = a.sh_blocks;
 #pragma unroll
   for (int i = 0; i < LF; ++i) {
     const int ins = wave + i * NW;             // instruction id within the factor part, LDS order [fb][kk]
     const int fb = ins / KK, kk = ins % KK;
     const int gb = min(tn * (BN / 32) + fb, M / 32 - 1);   // blocks past the end re-read the last one (never stored)
-    if (FORD == 0) fsrc[i] = (const char *)Fp + ((size_t)gb * (K / 16) + kk) * 1024 + lane * 16;
-    else fsrc[i] = (const char *)Fp + ((size_t)kk * (M / 32) + gb) * 1024 + lane * 16;
+    if (FORD == 0) {
+      const char *src = gb < shb ? (const char *)a.Fsh + (size_t)gb * (K / 16) * 1024
+                                 : (const char *)Fp + (size_t)(gb - shb) * (K / 16) * 1024;
+      fsrc[i] = src + (size_t)kk * 1024 + lane * 16;
+      fsrc_own[i] = fsrc[i];
+    } else {
+      fsrc_own[i] = (const char *)Fp + ((size_t)kk * (M / 32) + gb) * 1024 + lane * 16;
+      fsrc[i] = shb > 0 ? (const char *)a.Fsh + ((size_t)kk * (M / 32) + gb) * 1024 + lane * 16 : fsrc_own[i];
+    }
     fdst[i] = ins * 1024;
   }
   const size_t fstep = FORD == 0 ? (size_t)KK * 1024 : (size_t)KK * (M / 32) * 1024;
+  int issued = 0;                              // FORD 1: slices requested so far (a slice of BK = 32 is one 32-rank block)
   const char *tsrc[LT];
   int tdst[LT];
   constexpr int CPR = BK * 2 / 16;             // 16-byte chunks per staged X row
@@ -148,6 +164,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
     for (int i = 0; i < LT; ++i) {
       __builtin_amdgcn_global_load_lds(PARSE_GLB_PTR(tsrc[i]), PARSE_LDS_PTR(base + tdst[i]), 16, 0, 0);
       tsrc[i] += tstep;
+    }
+    if (FORD == 1 && BK == 32) {               // the reduction leaves the shared head: continue in the pattern's own block
+      if (++issued == shb) {
+#pragma unroll
+        for (int i = 0; i < LF; ++i) fsrc[i] = fsrc_own[i];
+      }
     }
   };
 
@@ -289,8 +311,10 @@ int forward_prefill_split_first_bf16(const PfArgs &p, uint16_t *Z, int avg_promp
 // rows up through the plan's row map like the first product does with X.
 int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, uint16_t *Z, int avg_prompt_rows,
                                  hipStream_t s) {
-  LgArgs g1{p.X, p.Vt_S, Z, (size_t)p.rS * p.n, p.n, p.rS, plan, cap, 0, 0, 0};
-  LgArgs g2{Z, p.Ut_S, p.Y, (size_t)p.rS * p.m, p.rS, p.m, plan, cap, 0, 0, 0};
+  if (p.sh_ranks % 32 != 0 || p.sh_ranks >= p.rS) return PARSE_ESHAPE;
+  const int own = p.rS - p.sh_ranks;           // ranks in a pattern's own block
+  LgArgs g1{p.X, p.Vt_S, Z, (size_t)own * p.n, p.n, p.rS, plan, cap, 0, 0, 0, p.Vt_sh, p.sh_ranks / 32};
+  LgArgs g2{Z, p.Ut_S, p.Y, (size_t)own * p.m, p.rS, p.m, plan, cap, 0, 0, 0, p.Ut_sh, p.sh_ranks / 32};
   const long long tiles256 = (long long)((p.rows + 255) / 256);
   const int per_pattern = avg_prompt_rows / 256;
   // 256 x 256 tiles halve the bytes a compute unit has to take in per flop; they are used when they still give the

@@ -382,9 +382,12 @@ int forward_prefill_split_first_bf16(const PfArgs &p, uint16_t *Z, int avg_promp
   GtArgs g1{};
   g1.n_layers = 1;
   g1.tok_offsets = p.tok_offsets; g1.pattern_id = p.pattern_id; g1.rows = p.rows; g1.P = p.P;
-  g1.L[0] = GtLayer{p.X, p.Vt_S, Z, (size_t)p.rS * p.n, p.n / 16, 1, p.n, p.rS, p.n_patterns, 0, nullptr, 0};
+  const int rp = p.rS - p.sh_ranks;            // ranks in the per-pattern blocks (the shared head is stored once)
+  g1.L[0] = GtLayer{p.X, p.Vt_S, Z, (size_t)rp * p.n, p.n / 16, 1, p.n, p.rS, p.n_patterns, 0, p.Vt_sh, p.sh_ranks / 32};
   int gt64 = avg_prompt_rows / 64;  gt64 = gt64 < 1 ? 1 : (gt64 > 8 ? 8 : gt64);
-  return (p.n % (PF_BK * 4) == 0) ? launch_gemm_tokens<64, 2, 8, 2, 0>(g1, gt64, s) : launch_gemm_tokens<64, 2, 8, 1, 0>(g1, gt64, s);
+  const bool halves = p.n % (PF_BK * 4) == 0;
+  if (p.sh_ranks > 0) return halves ? launch_gemm_tokens<64, 2, 8, 2, 1>(g1, gt64, s) : launch_gemm_tokens<64, 2, 8, 1, 1>(g1, gt64, s);
+  return halves ? launch_gemm_tokens<64, 2, 8, 2, 0>(g1, gt64, s) : launch_gemm_tokens<64, 2, 8, 1, 0>(g1, gt64, s);
 }
 
 int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s) {

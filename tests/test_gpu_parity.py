@@ -653,6 +653,92 @@ def _decode_case(n, m, R, G, k, B, npat):
     assert_close(y1n, yp.float().cpu().numpy(), TOL_BF16, "decode vs prefill kernel")
 
 
+def test_decode_more_than_32_sequences_in_panels():
+    """70 sequences = panels of 32, 32 and 6: every panel has its own masks; single-layer and fused calls, all rows
+    against the oracle."""
+    say("decode B=70 (three panels), single call and two layers in one call")
+    n, B, npat = 1024, 70, 5
+    shapes = [(768, 256, 8, 3), (512, 384, 12, 5)]
+    rng = np.random.default_rng(621)
+    seq_pat = rng.integers(0, npat, size=B).astype(np.int32)
+    x = si.make_tokens(rng, B, n, "bf16")
+    xd, pid = upload_tokens(x, "bf16"), i32(seq_pat)
+    layers, pats, host = [], [], []
+    for i, (m, R, G, k) in enumerate(shapes):
+        lay = si.make_layer(np.random.default_rng(622 + i), n, m, R, G, "bf16")
+        sub = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(npat)]).astype(np.int32)
+        layers.append(pa.layer_to_mfma16(upload_layer(lay))); host.append((lay, sub))
+        pats.append(pa.Patterns(k, npat, subsets=i32(sub)))
+    ys = pa.lowrank_decode_multi(layers, pats, xd, pid)
+    torch.cuda.synchronize()
+    xv = si.bf16_bits_to_f32(x).astype(np.float64)
+    for li, (lay, sub) in enumerate(host):
+        y1 = pa.lowrank_forward(pa.PARSE_DECODE, layers[li], pats[li], xd, None, pid)
+        torch.cuda.synchronize()
+        U0, sg, V = oracle_factors(lay)
+        Yo = po.decode_step(U0, sg, V, lay.gs, xv, sub[seq_pat])
+        for y in (y1, ys[li]):
+            assert y.shape == (B, lay.m)
+            yn = y.float().cpu().numpy().astype(np.float64)
+            for b in range(B):
+                assert_close(yn[b:b + 1], Yo[b:b + 1], TOL_BF16, f"layer {li} sequence {b}")
+
+
+def test_decode_with_a_shared_head_streams_it_once():
+    """Shared experts (Sec. 4.4): every pattern starts with the same two groups.  Decode reads the layer's own store by
+    group id, so the shared groups are simply groups that every sequence selected: streamed once, applied to all."""
+    say("decode: patterns with a shared head of two groups")
+    n, m, R, G, k, B, npat, ns = 1024, 768, 384, 12, 5, 19, 4, 2
+    lay = si.make_layer(np.random.default_rng(631), n, m, R, G, "bf16")
+    rng = np.random.default_rng(632)
+    shared = np.array([0, 1], np.int32)                        # the two largest-sigma groups
+    sub = np.stack([np.concatenate([shared, np.sort(rng.choice(np.arange(ns, G), size=k - ns, replace=False))])
+                    for _ in range(npat)]).astype(np.int32)
+    seq_pat = rng.integers(0, npat, size=B).astype(np.int32)
+    x = si.make_tokens(rng, B, n, "bf16")
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    pt = pa.Patterns(k, npat, subsets=i32(sub))
+    plan = pa.decode_plan([dl], [pt], i32(seq_pat))
+    y = pa.lowrank_forward(pa.PARSE_DECODE, dl, pt, upload_tokens(x, "bf16"), None, i32(seq_pat))
+    torch.cuda.synchronize()
+    words = plan.view(torch.int32).cpu().numpy()
+    present = np.uint32(0)
+    for b in range(B):
+        present |= np.uint32(1 << b)
+    assert np.uint32(words[65 + 0]) == present and np.uint32(words[65 + 1]) == present   # every sequence holds the shared groups
+    U0, sg, V = oracle_factors(lay)
+    Yo = po.decode_step(U0, sg, V, lay.gs, si.bf16_bits_to_f32(x).astype(np.float64), sub[seq_pat])
+    yn = y.float().cpu().numpy().astype(np.float64)
+    for b in range(B):
+        assert_close(yn[b:b + 1], Yo[b:b + 1], TOL_BF16, f"sequence {b}")
+
+
+def test_rank_granular_decode_over_packed_blocks():
+    """Rank-granular patterns (one expert per rank) have no groups to mask on: a decode step is the product over each
+    sequence's own aggregated block, one row per sequence -- the prefill kernels with unit-length prompts.  All three
+    schedules, every sequence against the oracle."""
+    say("rank-granular decode: one token per sequence over the aggregated rank blocks")
+    n, m, R, K, B = 512, 768, 512, 128, 11
+    lay = si.small_layer(911, n, m, R, R, "bf16")
+    rng = np.random.default_rng(912)
+    subs = np.stack([np.sort(rng.choice(R, size=K, replace=False)) for _ in range(B)]).astype(np.int32)
+    x = si.make_tokens(rng, B, n, "bf16")
+    dl = upload_layer(lay)
+    Vs, Us = pa.pack_ranks(dl, i32(subs), K, B)
+    desc = pa.Layer(dl.Vt, dl.Ut, n, m, R, R // 32, pa.PARSE_MFMA16)
+    off = np.arange(B + 1, dtype=np.int32)
+    U0, sg, V = oracle_factors(lay)
+    Yo = po.forward(U0, sg, V, 1, si.bf16_bits_to_f32(x).astype(np.float64), off, subs)
+    for schedule in (1, 2, 3):
+        y = pa.lowrank_forward(pa.PARSE_PREFILL, desc, pa.Patterns(K // 32, B, Vs, Us, schedule=schedule),
+                               upload_tokens(x, "bf16"), i32(off), i32(np.arange(B, dtype=np.int32)),
+                               no_workspace=(schedule == 1))
+        torch.cuda.synchronize()
+        yn = y.float().cpu().numpy().astype(np.float64)
+        for b in range(B):
+            assert_close(yn[b:b + 1], Yo[b:b + 1], TOL_BF16, f"schedule {schedule} sequence {b}")
+
+
 def test_decode_unselected_groups_are_not_needed():
     say("decode: factors of groups nobody selected may hold anything (they are never read into the result)")
     lay = si.small_layer(603, 512, 512, 256, 8, "bf16")
@@ -803,10 +889,57 @@ def test_shared_head_route_cache_pack_and_prefill():
     yn = y_sh.float().cpu().numpy().astype(np.float64)
     for p in range(P):
         assert_close(yn[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"prompt {p}")
-    # a shared head without the two-launch schedule's workspace is refused, not silently ignored
+    # the planned schedule reads the shared head the same way: bit-identical to the whole blocks under that schedule,
+    # through the all-in-one call (fixed and automatic choice) and through the call that takes a ready plan
+    pt_sh = pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns)
+    y_pw = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw, schedule=pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
+    y_ps = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh.with_schedule(pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
+    y_auto = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh, Xd, offd, pid)
+    plan = pa.prefill_plan(offd, pid, int(off[-1]), P)
+    y_plan = pa.lowrank_prefill_planned(dl, pt_sh, Xd, offd, pid, plan)
+    torch.cuda.synchronize()
+    for nm, y in (("planned", y_ps), ("auto", y_auto), ("ready plan", y_plan)):
+        assert torch.equal(y.view(torch.int16), y_pw.view(torch.int16)), nm
+    ypn = y_ps.float().cpu().numpy().astype(np.float64)
+    for p in range(P):
+        assert_close(ypn[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"planned, prompt {p}")
+    # the fused kernel reads one block per pattern: a shared head is refused there, not silently ignored
     with pytest.raises(pa.ParseError):
-        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns),
-                           Xd, offd, pid, no_workspace=True)
+        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh, Xd, offd, pid, no_workspace=True)
+    with pytest.raises(pa.ParseError):
+        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh.with_schedule(pa.PARSE_SCHED_FUSED), Xd, offd, pid)
+
+
+def test_shared_head_planned_on_the_large_tile_path():
+    """A batch long enough for the 256 x 256 tiles of both products (24576 rows), one shared group of 128 ranks at
+    the head of every pattern: bit-identical to the same subsets packed whole, sampled rows against the oracle."""
+    say("shared head, planned schedule, 6 x 4096 tokens (large tiles in both products)")
+    n, m, R, G, k, ns, P, T = 1024, 1024, 1024, 8, 4, 1, 6, 4096
+    lay = si.make_layer(np.random.default_rng(811), n, m, R, G, "bf16", fast=True)
+    rng = np.random.default_rng(812)
+    off = si.offsets_from_lengths([T] * P)
+    X = si.make_tokens(rng, P * T, n, "bf16")
+    subs = np.stack([np.concatenate([[0], np.sort(rng.choice(np.arange(1, G), size=k - 1, replace=False))])
+                     for _ in range(P)]).astype(np.int32)
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    sd = i32(subs)
+    Vsh, Ush = pa.pack_experts(dl, i32(np.arange(ns, dtype=np.int32)))
+    Vp, Up = pa.pack_patterns(dl, sd[:, ns:], k, k - ns, None, None, P)
+    Vw, Uw = pa.pack_patterns(dl, sd, k, k, None, None, P)
+    Xd, offd, pid = upload_tokens(X, "bf16"), i32(off), i32(np.arange(P, dtype=np.int32))
+    y_sh = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns,
+                                                                 schedule=pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
+    y_w = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw, schedule=pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
+    torch.cuda.synchronize()
+    assert torch.equal(y_sh.view(torch.int16), y_w.view(torch.int16))
+    U0, sg, V = oracle_factors(lay)
+    yn = y_sh.float().cpu().numpy().astype(np.float64)
+    for p in range(P):
+        rows = np.sort(rng.choice(T, size=6, replace=False)) + p * T
+        rows[0], rows[-1] = p * T, (p + 1) * T - 1              # first and last row of the prompt
+        Yo = po.forward(U0, sg, V, lay.gs, si.bf16_bits_to_f32(X[rows]).astype(np.float64),
+                        np.array([0, len(rows)], np.int32), subs[p:p + 1])
+        assert_close(yn[rows], Yo, TOL_BF16, f"prompt {p}")
 
 
 def test_rank_granular_route_pack_and_prefill():
