@@ -46,3 +46,73 @@ def oracle_factors(lay: si.Layer):
         Vt, Ut = lay.stored_values()
         return Ut.T.copy(), np.ones(lay.R), Vt
     return lay.U0, lay.sigma, lay.V
+
+
+# ---- guard bands: every output and workspace of a checked call sits between two canaries of 4 KiB -----------------
+CANARY = 4096
+_CANARY_BYTE = 0xA5
+
+
+def guarded_bytes(nbytes: int, device="cuda"):
+    """(whole buffer, the nbytes in the middle); both ends hold the canary byte."""
+    nbytes = max(int(nbytes), 256)
+    buf = torch.full((nbytes + 2 * CANARY,), _CANARY_BYTE, dtype=torch.uint8, device=device)
+    return buf, buf[CANARY:CANARY + nbytes]
+
+
+def guarded_like(rows: int, cols: int, dtype, device="cuda"):
+    """(whole buffer, a [rows][cols] tensor of `dtype` in its middle)."""
+    esz = torch.empty((), dtype=dtype).element_size()
+    buf, mid = guarded_bytes(rows * cols * esz, device)
+    return buf, mid[:rows * cols * esz].view(dtype).view(rows, cols)
+
+
+def check_guards(buf: torch.Tensor, what: str):
+    torch.cuda.synchronize()
+    n = buf.numel() - 2 * CANARY
+    assert bool(torch.all(buf[:CANARY] == _CANARY_BYTE)), f"{what}: stores below the buffer"
+    assert bool(torch.all(buf[CANARY + n:] == _CANARY_BYTE)), f"{what}: stores beyond the buffer"
+
+
+def forward_guarded(mode, layer, patterns, X, tok_offsets, pattern_id, Y=None, workspace=None, no_workspace=False):
+    """pa.lowrank_forward with Y and the workspace (exactly the queried size) between canaries, checked after the call."""
+    if Y is not None or workspace is not None:
+        return pa.lowrank_forward(mode, layer, patterns, X, tok_offsets, pattern_id, Y, workspace, no_workspace)
+    rows = X.shape[0]
+    ybuf, Yt = guarded_like(rows, layer.m, X.dtype, X.device)
+    wbuf, ws = None, None
+    if not no_workspace:
+        need = pa.lowrank_workspace_bytes(mode, layer, rows, patterns.k, pattern_id.numel(), patterns.n_patterns)
+        wbuf, ws = guarded_bytes(need, X.device)
+    pa.lowrank_forward(mode, layer, patterns, X, tok_offsets, pattern_id, Yt, ws, no_workspace)
+    check_guards(ybuf, "Y")
+    if wbuf is not None:
+        check_guards(wbuf, "workspace")
+    return Yt
+
+
+def decode_multi_guarded(layers, patterns, X, pattern_id):
+    rows = X.shape[0]
+    ys = [guarded_like(rows, l.m, X.dtype, X.device) for l in layers]
+    wbuf, ws = guarded_bytes(pa.lowrank_decode_multi_workspace_bytes(layers), X.device)
+    pa.lowrank_decode_multi(layers, patterns, X, pattern_id, [v for _, v in ys], ws)
+    for i, (b, _) in enumerate(ys):
+        check_guards(b, f"Y[{i}]")
+    check_guards(wbuf, "workspace")
+    return [v for _, v in ys]
+
+
+def prefill_multi_guarded(layers, patterns, X, tok_offsets, pattern_id):
+    rows = X.shape[0]
+    ys = [guarded_like(rows, l.m, X.dtype, X.device) for l in layers]
+    import ctypes as C
+    from paper_2605_08568_amd import binding as _b
+    nl = len(layers)
+    larr = (_b._Layer * nl)(*[l.c() for l in layers])
+    parr = (_b._Patterns * nl)(*[p.c() for p in patterns])
+    wbuf, ws = guarded_bytes(int(pa.lib().parse_lowrank_prefill_multi_workspace_bytes(larr, parr, nl, rows)), X.device)
+    pa.lowrank_prefill_multi(layers, patterns, X, tok_offsets, pattern_id, [v for _, v in ys], ws)
+    for i, (b, _) in enumerate(ys):
+        check_guards(b, f"Y[{i}]")
+    check_guards(wbuf, "workspace")
+    return [v for _, v in ys]

@@ -123,7 +123,7 @@ def test_forward_rejects_bad_arguments():
     assert call(layer=_layer(dtype=1, layout=0)) == -7                  # bf16 prefill needs operand order
     assert call(mode=1) == -7                                           # decode is bf16 operand-order only
     Lb = _layer(n=64, m=64, R=64, G=2, dtype=1, layout=1)
-    assert call(mode=1, layer=Lb, rows=40, P=40) == -2                  # more than 32 sequences
+    assert call(mode=1, layer=Lb, rows=40, P=20) == -2                  # decode: one token per sequence (rows == P)
     assert call(mode=1, layer=Lb, rows=8, P=4) == -2                    # decode: one row per sequence
     assert lib.parse_lowrank_workspace_bytes(0, C.byref(L), 8, 1, 0, 0) >= 8 * 16 * 4
 
@@ -142,7 +142,6 @@ def test_decode_multi_rejects_bad_arguments():
 
     assert call([La, La], [pt, pt], 0) == -1 and call([La, La], [pt, pt], 2, X=None) == -1
     assert call([La] * 5, [pt] * 5, 5) == -2                       # at most four layers
-    assert call([La, La], [pt, pt], 2, rows=33) == -2              # at most 32 sequences
     assert call([La, Lb], [pt, pt], 2) == -2                       # the layers must share the input width
     assert call([La, _layer(n=64, m=64, R=64, G=2, dtype=1, layout=0)], [pt, pt], 2) == -7
     assert call([La, La], [pt, pt], 2, ys=[FAKE.value, None]) == -1

@@ -11,7 +11,8 @@ from oracle import parse_oracle as po
 pytestmark = pytest.mark.gpu
 
 pa = pytest.importorskip("paper_2605_08568_amd")
-from helpers import i32, mfma16_u, mfma16_v, oracle_factors, upload_layer, upload_tokens  # noqa: E402
+from helpers import (decode_multi_guarded, forward_guarded, i32, mfma16_u, mfma16_v, oracle_factors,  # noqa: E402
+                     prefill_multi_guarded, upload_layer, upload_tokens)
 
 TOL_F32, TOL_BF16 = 1e-4, 1e-2
 DEV = "cuda"
@@ -396,7 +397,7 @@ def _run_prefill(lay, lengths, subsets_per_prompt, seed, dtype, schedule=0):
     sd = i32(subs)
     pid, perm, boff, npat, rep = pa.bucket_patterns(sd, k)
     Vs, Us = pa.pack_patterns(dl, sd, k, k, rep, npat, len(lengths))
-    Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, len(lengths), Vs, Us, schedule=schedule),
+    Y = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(k, len(lengths), Vs, Us, schedule=schedule),
                            upload_tokens(X, dtype), i32(off), pid, no_workspace=(schedule == 1))
     torch.cuda.synchronize()
     Yg = Y.float().cpu().numpy().astype(np.float64)
@@ -412,7 +413,7 @@ def test_prefill_config0_fp32():
     sd = i32(subs)
     pid, perm, boff, npat, rep = pa.bucket_patterns(sd, w.k)
     Vs, Us = pa.pack_patterns(dl, sd, w.k, w.k, rep, npat, w.P)
-    Y = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us), upload_tokens(w.X, "f32"),
+    Y = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us), upload_tokens(w.X, "f32"),
                            i32(w.tok_offsets), pid)
     torch.cuda.synchronize()
     Yref = po.forward(lay.U0, lay.sigma, lay.V, lay.gs, w.X_values(), w.tok_offsets, subs)
@@ -490,7 +491,7 @@ def test_prefill_plan_matches_the_row_grouping_and_serves_shared_patterns():
     Y = Ybuf[guard:guard + rows]
     pt = pa.Patterns(k, n_slots, Vs, Us)
     pa.lowrank_prefill_planned(dl, pt, Xd, offd, pidd, plan, Y=Y)
-    Y2 = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt.with_schedule(pa.PARSE_SCHED_PLANNED), Xd, offd, pidd)
+    Y2 = forward_guarded(pa.PARSE_PREFILL, dl, pt.with_schedule(pa.PARSE_SCHED_PLANNED), Xd, offd, pidd)
     torch.cuda.synchronize()
     assert torch.all(Ybuf[:guard] == 7.0) and torch.all(Ybuf[guard + rows:] == 7.0), "stores outside Y"
     assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)), "ready plan vs plan built inside the call"
@@ -514,8 +515,8 @@ def test_prefill_invalid_pattern_gives_zero_rows_and_is_repeatable():
     X = upload_tokens(si.make_tokens(np.random.default_rng(1), 100, 256, "bf16"), "bf16")
     off = i32([0, 30, 70, 100]); pid = i32([1, 5, 0])
     pt = pa.Patterns(2, 2, Vs, Us)
-    Y1 = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid)
-    Y2 = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt, X, off, pid)
+    Y1 = forward_guarded(pa.PARSE_PREFILL, dl, pt, X, off, pid)
+    Y2 = forward_guarded(pa.PARSE_PREFILL, dl, pt, X, off, pid)
     torch.cuda.synchronize()
     assert torch.equal(Y1.view(torch.int16), Y2.view(torch.int16))
     assert torch.all(Y1[30:70] == 0) and torch.any(Y1[:30] != 0) and torch.any(Y1[70:] != 0)
@@ -534,7 +535,7 @@ def test_prefill_config1_full_size_sampled():
     Vs, Us = pa.pack_patterns(dl, sub_d, w.k, w.k, rep, npat, w.P)
     Ys = {}
     for schedule in (1, 2, 3):
-        Ys[schedule] = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us, schedule=schedule), Xd, offd, pid)
+        Ys[schedule] = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us, schedule=schedule), Xd, offd, pid)
         torch.cuda.synchronize()
     assert np.all(margin > 1e-4) and np.array_equal(sub_d.cpu().numpy(), subs)
     U0, sg, V = oracle_factors(lay)
@@ -606,7 +607,7 @@ def test_decode_plan_contents_and_planned_step():
     need = pa.lowrank_decode_planned_workspace_bytes(layers)
     wsbuf = torch.full((need + 512,), 0x5A, dtype=torch.uint8, device=DEV)
     pa.lowrank_decode_planned(layers, xd, plan, [v for _, v in bufs], wsbuf[256:256 + need])
-    ys_multi = pa.lowrank_decode_multi(layers, pats, xd, pid)
+    ys_multi = decode_multi_guarded(layers, pats, xd, pid)
     torch.cuda.synchronize()
     assert torch.all(wsbuf[:256] == 0x5A) and torch.all(wsbuf[256 + need:] == 0x5A), "stores outside the workspace"
     after = plan.view(torch.int32).cpu().numpy()
@@ -614,7 +615,7 @@ def test_decode_plan_contents_and_planned_step():
     for li, (lay, sub, G, k) in enumerate(subs_h):
         buf, view = bufs[li]
         assert torch.all(buf[0] == 5.0) and torch.all(buf[-1] == 5.0), "stores outside Y"
-        y_single = pa.lowrank_forward(pa.PARSE_DECODE, layers[li], pats[li], xd, None, pid)
+        y_single = forward_guarded(pa.PARSE_DECODE, layers[li], pats[li], xd, None, pid)
         torch.cuda.synchronize()
         assert torch.equal(view.view(torch.int16), ys_multi[li].view(torch.int16))
         assert torch.equal(view.view(torch.int16), y_single.view(torch.int16))
@@ -639,8 +640,8 @@ def _decode_case(n, m, R, G, k, B, npat):
     dl = pa.layer_to_mfma16(upload_layer(lay))
     xd = upload_tokens(x, "bf16")
     pt = pa.Patterns(k, npat, subsets=i32(pats))
-    y1 = pa.lowrank_forward(pa.PARSE_DECODE, dl, pt, xd, None, i32(seq_pat))
-    y2 = pa.lowrank_forward(pa.PARSE_DECODE, dl, pt, xd, None, i32(seq_pat))
+    y1 = forward_guarded(pa.PARSE_DECODE, dl, pt, xd, None, i32(seq_pat))
+    y2 = forward_guarded(pa.PARSE_DECODE, dl, pt, xd, None, i32(seq_pat))
     torch.cuda.synchronize()
     assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
     y1n = y1.float().cpu().numpy()
@@ -648,7 +649,7 @@ def _decode_case(n, m, R, G, k, B, npat):
         assert_close(y1n[b:b + 1], Yref[i:i + 1], TOL_BF16, f"sequence {b}")
     # cross-kernel check: the prefill kernel on the same single rows and subsets
     Vs, Us = pa.pack_patterns(dl, i32(pats), k, k, None, None, npat)
-    yp = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, npat, Vs, Us), xd, i32(np.arange(B + 1)), i32(seq_pat))
+    yp = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(k, npat, Vs, Us), xd, i32(np.arange(B + 1)), i32(seq_pat))
     torch.cuda.synchronize()
     assert_close(y1n, yp.float().cpu().numpy(), TOL_BF16, "decode vs prefill kernel")
 
@@ -669,11 +670,11 @@ def test_decode_more_than_32_sequences_in_panels():
         sub = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(npat)]).astype(np.int32)
         layers.append(pa.layer_to_mfma16(upload_layer(lay))); host.append((lay, sub))
         pats.append(pa.Patterns(k, npat, subsets=i32(sub)))
-    ys = pa.lowrank_decode_multi(layers, pats, xd, pid)
+    ys = decode_multi_guarded(layers, pats, xd, pid)
     torch.cuda.synchronize()
     xv = si.bf16_bits_to_f32(x).astype(np.float64)
     for li, (lay, sub) in enumerate(host):
-        y1 = pa.lowrank_forward(pa.PARSE_DECODE, layers[li], pats[li], xd, None, pid)
+        y1 = forward_guarded(pa.PARSE_DECODE, layers[li], pats[li], xd, None, pid)
         torch.cuda.synchronize()
         U0, sg, V = oracle_factors(lay)
         Yo = po.decode_step(U0, sg, V, lay.gs, xv, sub[seq_pat])
@@ -699,7 +700,7 @@ def test_decode_with_a_shared_head_streams_it_once():
     dl = pa.layer_to_mfma16(upload_layer(lay))
     pt = pa.Patterns(k, npat, subsets=i32(sub))
     plan = pa.decode_plan([dl], [pt], i32(seq_pat))
-    y = pa.lowrank_forward(pa.PARSE_DECODE, dl, pt, upload_tokens(x, "bf16"), None, i32(seq_pat))
+    y = forward_guarded(pa.PARSE_DECODE, dl, pt, upload_tokens(x, "bf16"), None, i32(seq_pat))
     torch.cuda.synchronize()
     words = plan.view(torch.int32).cpu().numpy()
     present = np.uint32(0)
@@ -730,7 +731,7 @@ def test_rank_granular_decode_over_packed_blocks():
     U0, sg, V = oracle_factors(lay)
     Yo = po.forward(U0, sg, V, 1, si.bf16_bits_to_f32(x).astype(np.float64), off, subs)
     for schedule in (1, 2, 3):
-        y = pa.lowrank_forward(pa.PARSE_PREFILL, desc, pa.Patterns(K // 32, B, Vs, Us, schedule=schedule),
+        y = forward_guarded(pa.PARSE_PREFILL, desc, pa.Patterns(K // 32, B, Vs, Us, schedule=schedule),
                                upload_tokens(x, "bf16"), i32(off), i32(np.arange(B, dtype=np.int32)),
                                no_workspace=(schedule == 1))
         torch.cuda.synchronize()
@@ -752,7 +753,7 @@ def test_decode_unselected_groups_are_not_needed():
     outs = []
     for l in (lay, poisoned):
         dl = pa.layer_to_mfma16(upload_layer(l))
-        outs.append(pa.lowrank_forward(pa.PARSE_DECODE, dl, pa.Patterns(2, 2, subsets=i32(pats)),
+        outs.append(forward_guarded(pa.PARSE_DECODE, dl, pa.Patterns(2, 2, subsets=i32(pats)),
                                        upload_tokens(x, "bf16"), None, i32(seq_pat)))
     torch.cuda.synchronize()
     assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
@@ -783,15 +784,15 @@ def test_decode_multi_matches_oracle_and_single_calls(shapes, n, B):
         layers.append(pa.layer_to_mfma16(upload_layer(lay)))
         patterns.append(pa.Patterns(k, npat, subsets=i32(pats)))
     pid = i32(seq_pat)
-    ys = pa.lowrank_decode_multi(layers, patterns, xd, pid)
-    ys2 = pa.lowrank_decode_multi(layers, patterns, xd, pid)
+    ys = decode_multi_guarded(layers, patterns, xd, pid)
+    ys2 = decode_multi_guarded(layers, patterns, xd, pid)
     torch.cuda.synchronize()
     for li in range(len(shapes)):
         assert torch.equal(ys[li].view(torch.int16), ys2[li].view(torch.int16))
         yn = ys[li].float().cpu().numpy()
         for i, b in enumerate(rows_of[li]):
             assert_close(yn[b:b + 1], refs[li][i:i + 1], TOL_BF16, f"layer {li} sequence {b}")
-        single = pa.lowrank_forward(pa.PARSE_DECODE, layers[li], patterns[li], xd, None, pid)
+        single = forward_guarded(pa.PARSE_DECODE, layers[li], patterns[li], xd, None, pid)
         torch.cuda.synchronize()
         assert_close(yn, single.float().cpu().numpy(), TOL_BF16, f"layer {li}: fused vs separate call")
 
@@ -820,13 +821,13 @@ def test_prefill_multi_matches_oracle_and_single_calls(shapes, n, lengths):
         Vs, Us = pa.pack_patterns(dl, i32(subs), k, k, None, None, P)
         layers.append(dl)
         patterns.append(pa.Patterns(k, P, Vs, Us))
-    ys = pa.lowrank_prefill_multi(layers, patterns, Xd, offd, pid)
+    ys = prefill_multi_guarded(layers, patterns, Xd, offd, pid)
     torch.cuda.synchronize()
     for li in range(len(shapes)):
         yn = ys[li].float().cpu().numpy().astype(np.float64)
         for p in range(P):
             assert_close(yn[off[p]:off[p + 1]], refs[li][off[p]:off[p + 1]], TOL_BF16, f"layer {li} prompt {p}")
-        single = pa.lowrank_forward(pa.PARSE_PREFILL, layers[li], patterns[li].with_schedule(pa.PARSE_SCHED_TILES), Xd, offd, pid)
+        single = forward_guarded(pa.PARSE_PREFILL, layers[li], patterns[li].with_schedule(pa.PARSE_SCHED_TILES), Xd, offd, pid)
         torch.cuda.synchronize()
         assert torch.equal(single.view(torch.int16), ys[li].view(torch.int16)), f"layer {li}: fused vs separate call"
 
@@ -879,9 +880,9 @@ def test_shared_head_route_cache_pack_and_prefill():
         assert torch.equal(Vw[p, ns * gs:].view(torch.int16), Vp[p].view(torch.int16))
         assert torch.equal(Uw[p, ns * gs:].view(torch.int16), Up[p].view(torch.int16))
     pid = i32(np.arange(P, dtype=np.int32))
-    y_sh = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns,
+    y_sh = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns,
                                                                  schedule=pa.PARSE_SCHED_TILES), Xd, offd, pid)
-    y_whole = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw, schedule=pa.PARSE_SCHED_TILES), Xd, offd, pid)
+    y_whole = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw, schedule=pa.PARSE_SCHED_TILES), Xd, offd, pid)
     torch.cuda.synchronize()
     assert torch.equal(y_sh.view(torch.int16), y_whole.view(torch.int16))
     U0, sg, V = oracle_factors(lay)
@@ -892,9 +893,9 @@ def test_shared_head_route_cache_pack_and_prefill():
     # the planned schedule reads the shared head the same way: bit-identical to the whole blocks under that schedule,
     # through the all-in-one call (fixed and automatic choice) and through the call that takes a ready plan
     pt_sh = pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns)
-    y_pw = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw, schedule=pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
-    y_ps = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh.with_schedule(pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
-    y_auto = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh, Xd, offd, pid)
+    y_pw = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw, schedule=pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
+    y_ps = forward_guarded(pa.PARSE_PREFILL, dl, pt_sh.with_schedule(pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
+    y_auto = forward_guarded(pa.PARSE_PREFILL, dl, pt_sh, Xd, offd, pid)
     plan = pa.prefill_plan(offd, pid, int(off[-1]), P)
     y_plan = pa.lowrank_prefill_planned(dl, pt_sh, Xd, offd, pid, plan)
     torch.cuda.synchronize()
@@ -905,9 +906,9 @@ def test_shared_head_route_cache_pack_and_prefill():
         assert_close(ypn[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"planned, prompt {p}")
     # the fused kernel reads one block per pattern: a shared head is refused there, not silently ignored
     with pytest.raises(pa.ParseError):
-        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh, Xd, offd, pid, no_workspace=True)
+        forward_guarded(pa.PARSE_PREFILL, dl, pt_sh, Xd, offd, pid, no_workspace=True)
     with pytest.raises(pa.ParseError):
-        pa.lowrank_forward(pa.PARSE_PREFILL, dl, pt_sh.with_schedule(pa.PARSE_SCHED_FUSED), Xd, offd, pid)
+        forward_guarded(pa.PARSE_PREFILL, dl, pt_sh.with_schedule(pa.PARSE_SCHED_FUSED), Xd, offd, pid)
 
 
 def test_shared_head_planned_on_the_large_tile_path():
@@ -927,9 +928,9 @@ def test_shared_head_planned_on_the_large_tile_path():
     Vp, Up = pa.pack_patterns(dl, sd[:, ns:], k, k - ns, None, None, P)
     Vw, Uw = pa.pack_patterns(dl, sd, k, k, None, None, P)
     Xd, offd, pid = upload_tokens(X, "bf16"), i32(off), i32(np.arange(P, dtype=np.int32))
-    y_sh = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns,
+    y_sh = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vp, Up, Vt_shared=Vsh, Ut_shared=Ush, n_shared=ns,
                                                                  schedule=pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
-    y_w = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw, schedule=pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
+    y_w = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vw, Uw, schedule=pa.PARSE_SCHED_PLANNED), Xd, offd, pid)
     torch.cuda.synchronize()
     assert torch.equal(y_sh.view(torch.int16), y_w.view(torch.int16))
     U0, sg, V = oracle_factors(lay)
@@ -992,7 +993,7 @@ def test_rank_granular_route_pack_and_prefill():
     U0, sgm, V = oracle_factors(lay)
     Yref = po.forward(U0, sgm, V, 1, Xv, off, sg)
     for schedule in (1, 2, 3):
-        y = pa.lowrank_forward(pa.PARSE_PREFILL, desc, pa.Patterns(K // 32, P, Vs, Us, schedule=schedule), Xd, offd, pid,
+        y = forward_guarded(pa.PARSE_PREFILL, desc, pa.Patterns(K // 32, P, Vs, Us, schedule=schedule), Xd, offd, pid,
                                no_workspace=(schedule == 1))
         torch.cuda.synchronize()
         yn = y.float().cpu().numpy().astype(np.float64)
@@ -1032,21 +1033,21 @@ def test_config3_layer_projections_with_padded_groups():
     Xh = si.make_tokens(rng, T, hidden, "bf16"); Xi = si.make_tokens(rng, T, inter, "bf16")
     Xhd, Xid, offd = upload_tokens(Xh, "bf16"), upload_tokens(Xi, "bf16"), i32(off)
     for group, Xb, Xd in ((["q", "k", "v"], Xh, Xhd), (["gate", "up"], Xh, Xhd)):
-        ys = pa.lowrank_prefill_multi([dls[g] for g in group], [pats[g] for g in group], Xd, offd, pid)
+        ys = prefill_multi_guarded([dls[g] for g in group], [pats[g] for g in group], Xd, offd, pid)
         torch.cuda.synchronize()
         for g, y in zip(group, ys):
             check(g, y, Xb, sample, "prefill")
-    y = pa.lowrank_forward(pa.PARSE_PREFILL, dls["down"], pats["down"], Xid, offd, pid)
+    y = forward_guarded(pa.PARSE_PREFILL, dls["down"], pats["down"], Xid, offd, pid)
     torch.cuda.synchronize()
     check("down", y, Xi, sample, "prefill")
     # decode: one sequence, one token
     one = np.array([0])
     for group, Xb, Xd in ((["q", "k", "v"], Xh, Xhd), (["gate", "up"], Xh, Xhd)):
-        ys = pa.lowrank_decode_multi([dls[g] for g in group], [pats[g] for g in group], Xd[:1].contiguous(), pid)
+        ys = decode_multi_guarded([dls[g] for g in group], [pats[g] for g in group], Xd[:1].contiguous(), pid)
         torch.cuda.synchronize()
         for g, yv in zip(group, ys):
             check(g, yv, Xb, one, "decode")
-    yv = pa.lowrank_forward(pa.PARSE_DECODE, dls["down"], pats["down"], Xid[:1].contiguous(), None, pid)
+    yv = forward_guarded(pa.PARSE_DECODE, dls["down"], pats["down"], Xid[:1].contiguous(), None, pid)
     torch.cuda.synchronize()
     check("down", yv, Xi, one, "decode")
 
@@ -1077,7 +1078,7 @@ def test_router_training_step_matches_oracle():
     scores = torch.empty((P, G), dtype=torch.float32, device=DEV)
     subs = pa.route(Xd, offd, Wrd, k, scores_out=scores, emb_out=emb)
     Vs, Us = pa.pack_patterns(dl, subs, k, k, None, None, P)
-    yhat = pa.lowrank_forward(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vs, Us), Xd, offd, i32(np.arange(P, dtype=np.int32)))
+    yhat = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(k, P, Vs, Us), Xd, offd, i32(np.arange(P, dtype=np.int32)))
     ydd = upload_tokens(Yd_bits, "bf16")
     loss, grad = pa.router_grad(dl, pa.rankmajor_left_factor(dl_rm), Xd, offd, yhat, ydd, emb, scores, k, tau, eps)
     loss2, grad2 = pa.router_grad(dl, pa.rankmajor_left_factor(dl_rm), Xd, offd, yhat, ydd, emb, scores, k, tau, eps)
@@ -1110,7 +1111,7 @@ def test_multi_calls_with_four_layers_and_a_shared_head():
         refs.append(po.decode_step(U0, sg, V, lay.gs, si.bf16_bits_to_f32(x).astype(np.float64), sub[seq_pat]))
         layers.append(pa.layer_to_mfma16(upload_layer(lay)))
         pats.append(pa.Patterns(k, 3, subsets=i32(sub)))
-    ys = pa.lowrank_decode_multi(layers, pats, xd, i32(seq_pat))
+    ys = decode_multi_guarded(layers, pats, xd, i32(seq_pat))
     torch.cuda.synchronize()
     for li in range(4):
         assert_close(ys[li].float().cpu().numpy().astype(np.float64), refs[li], TOL_BF16, f"decode layer {li}")
@@ -1140,7 +1141,7 @@ def test_multi_calls_with_four_layers_and_a_shared_head():
             Vp, Up = pa.pack_patterns(dl, sd, k, k, None, None, P)
             pats.append(pa.Patterns(k, P, Vp, Up))
         layers.append(dl)
-    ys = pa.lowrank_prefill_multi(layers, pats, Xd, offd, i32(np.arange(P, dtype=np.int32)))
+    ys = prefill_multi_guarded(layers, pats, Xd, offd, i32(np.arange(P, dtype=np.int32)))
     torch.cuda.synchronize()
     for li in range(4):
         yn = ys[li].float().cpu().numpy().astype(np.float64)
