@@ -53,6 +53,7 @@ def parse_args():
     ap.add_argument("--only-stress", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the achievable-peak probes")
     ap.add_argument("--only-peaks", action="store_true")
+    ap.add_argument("--no-token-scaled", action="store_true", help="skip the 8 x 4096-token side record")
     ap.add_argument("--no-decode-graph", action="store_true", help="skip the HIP-graph replay of the decode steps")
     ap.add_argument("--no-prefill-graph", action="store_true",
                     help="time the prefill steps as eager launches only (the default also replays them from a HIP graph)")
@@ -772,6 +773,21 @@ def main():
         return
     pre = bench_prefill(args, torch, pa, si)
     w = pre.pop("workload")
+    scaled = None
+    if not args.no_token_scaled and args.tokens == 512 and not args.no_extras:
+        # side record: the same step on prompts of 4096 tokens (8 x 4096 rows, large tiles in both products); the forward
+        # figure is the one timed inside the full steps (HIP events around the call), not a back-to-back loop
+        a2 = argparse.Namespace(**{**vars(args), "tokens": 4096, "steps": 10, "warmup": 2, "no_extras": True,
+                                   "no_prefill_graph": True})
+        p2 = bench_prefill(a2, torch, pa, si)
+        p2.pop("workload")
+        scaled = {"workload": f"{args.prompts} prompts x 4096 tokens, otherwise as config1", "steps": 10,
+                  "ms_per_step_eager": round(p2["ms_per_step"], 4), "step_TFLOPs": round(p2["value"], 1),
+                  "rows_us": p2["rows_us"], "forward_in_step_us": p2["roofline"]["launch_us"],
+                  "forward_TFLOPs": p2["roofline"]["achieved"], "forward_frac_of_mfma_peak": p2["roofline"]["frac"],
+                  "kernel": "gemm_lds<256,256,2x2,BK32,S4> + gemm_lds<256,256,2x4,BK32,S4> (one planned forward call)"}
+        del p2
+        torch.cuda.empty_cache()
     if not args.no_decode:
         dec = bench_decode(args, torch, pa, si)
     stack = bench_stack(args, torch, pa, si) if args.stack else None
@@ -800,6 +816,7 @@ def main():
         "cold_step_ms": pre["cold_step_ms"],
         "rank_granular_us": pre["rank_granular_us"],
         "two_batches_in_flight": pre["two_batches_in_flight"],
+        "token_scaled_8x4096": scaled,
         "decode": dec,
     }
     if not args.no_peaks:
