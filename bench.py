@@ -467,6 +467,7 @@ def bench_stack(args, torch, pa, si):
     ws_gu = torch.empty(int(pa.lowrank_workspace_bytes(pa.PARSE_PREFILL, L0["gate"], T, k)) * 2, dtype=torch.uint8, device=dev)
     wsd = torch.empty(max(pa.lowrank_decode_multi_workspace_bytes([L0["q"], L0["k"], L0["v"]]),
                           pa.lowrank_decode_multi_workspace_bytes([L0["gate"], L0["up"]]),
+                          pa.lowrank_workspace_bytes(pa.PARSE_DECODE, L0["o"], 1, k),
                           pa.lowrank_workspace_bytes(pa.PARSE_DECODE, L0["down"], 1, k)), dtype=torch.uint8, device=dev)
 
     def prefill():
