@@ -7,15 +7,16 @@
 //
 // Decode plan (Sec. 4.3: the subsets are fixed after prefill, so everything derived from them is computed once per
 // batch, not once per step): per layer the sequence mask of every group, the ascending list of groups selected by at
-// least one sequence and their count.  decode_plan_build writes it; both kernels below only read it.
+// least one sequence and their count, plus the arrival counters of decode_zr's split reduction.  decode_plan_build
+// writes it; the kernels below read it (decode_zr also draws and resets its tickets there).
 //
 // Two launches per step:
-//   decode_zf  one workgroup per 32-rank block of a used group; the workgroup owns the WHOLE reduction over n, so z
-//              needs no partial sums in memory and no second pass: the token rows x and the block's Vt operands are
-//              staged through LDS in chunks of 256 columns (loads that write LDS directly, four chunks in rotation,
-//              three in flight), each of the eight wavefronts takes an eighth of every chunk's reduction steps, the
-//              eight partial accumulators are added in wavefront order through LDS, masked, rounded to bf16 and
-//              stored as operands of the second product.
+//   decode_zr  (layers whose groups are whole 32-rank blocks) one workgroup per 32-rank block of a used group and slice
+//              of the reduction range: the Vt operands go straight into registers, all of a wavefront's at once; the x
+//              rows of the slice are staged in LDS; long reductions are cut in slices whose partial sums the last
+//              workgroup of a ticket adds in slice order.  decode_zf<2> (16-rank blocks, everything staged through LDS,
+//              the whole reduction in one workgroup) serves the other layers.  Either way z ends up masked, rounded to
+//              bf16 and stored as operands of the second product.
 //   decode_y   NC (1..4) 32-column output blocks per workgroup; the eight wavefronts split the used reduction blocks,
 //              all Ut operands requested up front; LDS reduction in wavefront order.
 // Horizontal fusion (Sec. 4.4, Eq. 11-12): up to DEC_MAX_LAYERS layers that read the SAME x (Q/K/V, gate/up) go

@@ -39,9 +39,9 @@ __device__ __forceinline__ void wg_barrier() {
 }
 
 struct LgArgs {
-  const uint16_t *Tk;      // MODE 0: X row-major [rows][K];  MODE 1: Z in operand order [(virtual rows)/32][K/16][1 KiB]
+  const uint16_t *Tk;      // TROW 1: row-major [rows][K] (X, or a row-major Z);  TROW 0: Z in operand order [(virtual rows)/32][K/16][1 KiB]
   const uint16_t *F;       // factor operands of all patterns
-  uint16_t *O;             // MODE 0: Z (operand order);  MODE 1: Y row-major [rows][M]
+  uint16_t *O;             // OROW 0: Z (operand order);  OROW 1: Y row-major [rows][M]
   size_t pattern_stride;   // elements of F per pattern
   int K, M;                // reduction length, factor rows (= output columns)
   const int32_t *plan;     // header | tile patterns | row map (plan.hip)
