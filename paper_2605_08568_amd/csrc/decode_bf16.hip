@@ -11,12 +11,11 @@
 // writes it; the kernels below read it (decode_zr also draws and resets its tickets there).
 //
 // Two launches per step:
-//   decode_zr  (layers whose groups are whole 32-rank blocks) one workgroup per 32-rank block of a used group and slice
+//   decode_zr  one workgroup per 32-rank block of a used group (operand-order layers have groups of whole blocks) and slice
 //              of the reduction range: the Vt operands go straight into registers, all of a wavefront's at once; the x
 //              rows of the slice are staged in LDS; long reductions are cut in slices whose partial sums the last
-//              workgroup of a ticket adds in slice order.  decode_zf<2> (16-rank blocks, everything staged through LDS,
-//              the whole reduction in one workgroup) serves the other layers.  Either way z ends up masked, rounded to
-//              bf16 and stored as operands of the second product.
+//              workgroup of a ticket adds in slice order.  z ends up masked, rounded to bf16 and stored as operands of
+//              the second product.
 //   decode_y   NC (1..4) 32-column output blocks per workgroup; the eight wavefronts split the used reduction blocks,
 //              all Ut operands requested up front; LDS reduction in wavefront order.
 // Horizontal fusion (Sec. 4.4, Eq. 11-12): up to DEC_MAX_LAYERS layers that read the SAME x (Q/K/V, gate/up) go
@@ -26,10 +25,8 @@
 
 namespace parse {
 
-constexpr int DZ_WAVES = 8, DZ_THREADS = DZ_WAVES * 64;
 constexpr int DY_WAVES = 8, DY_THREADS = DY_WAVES * 64;
 constexpr int DEC_MAXG = 64;
-constexpr int DZ_CH = 256;                 // columns staged per chunk: 32 per wavefront (one 16x16x32 or two 32x32x16 steps)
 constexpr int DY_CHUNK = 4;                // decode_y: operands per chunk after the first block
 constexpr int DY_MAXKB = 1024;             // selected reduction blocks a decode_y workgroup can list
 constexpr int DEC_MAX_LAYERS = 4;
@@ -48,7 +45,7 @@ struct DecLayer {
   float *zpart;                // workspace: partial sums of z, [R/32][KS][16][64] floats (KS > 1)
   int32_t *ticket;             // [DEC_TICKETS] arrival counters in the plan, one per 32-rank block
   int R, G, gs, m;
-  int z_first, y_first;        // first workgroup of this layer in decode_zf / decode_y
+  int z_first, y_first;        // first workgroup of this layer in decode_zr / decode_y
 };
 struct DecArgs {
   DecLayer L[DEC_MAX_LAYERS];
@@ -101,8 +98,7 @@ __global__ __launch_bounds__(64) void decode_plan_build(DecPlanArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// decode_zr.  Workgroup = (layer, 32-rank block, slice s of KS of the reduction range).  The form for layers whose
-// groups are multiples of 32 ranks.  A slice is at most 256 reduction steps (4096 columns): each of the eight wavefronts
+// decode_zr.  Workgroup = (layer, 32-rank block, slice s of KS of the reduction range).  A slice is at most 256 reduction steps (4096 columns): each of the eight wavefronts
 // owns an eighth of it and requests ALL its Vt operands at once, straight into registers (1 KiB coalesced per
 // instruction, up to 32 of them): the registers of the eight wavefronts are the staging buffer -- 256 KiB of factor
 // stream in flight per compute unit, several times what LDS staging can hold, which is what a stream from HBM needs.
@@ -351,180 +347,6 @@ __global__ __launch_bounds__(DR_THREADS) void decode_zr(DecArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// decode_zf<NSB>.  Workgroup = (layer, 16-rank block, NSB 16-sequence blocks): NSB = 2 takes all 32 sequences, NSB = 1
-// half of them (twice the workgroups; used for long reductions, where the rank blocks alone are too few to keep the
-// chip's memory pipes full).  16 ranks x 16 sequences is one 16x16x32 matrix instruction per 32 columns.
-// Everything the loop reads from memory goes straight into LDS (loads that write LDS directly), NBUF chunks of 256
-// columns in rotation, NBUF-1 in flight, so the only waits in the loop are the explicit ones: per chunk the x rows
-// (512 bytes each, their 16-byte pieces XOR-swizzled by the row so that an operand read -- 16 rows x the same piece --
-// spreads over the banks) and the block's Vt operands, 1 KiB per wavefront, which that wavefront alone reads back.
-// A 16-rank half of a 32-rank operand block of the store is the lanes' 16-byte pieces (q*32 + 16*half + row): lane
-// (row, kg) of the 16x16x32 instruction takes piece ((kg & 1)*32 + 16*half + row) of operand kb0 + (kg >> 1).
-// The LDS is reused for the wavefronts' partial sums at the end.
-template <int NSB>
-__global__ __launch_bounds__(DZ_THREADS) void decode_zf(DecArgs a) {
-  constexpr int SPLIT = 2 / NSB;                       // workgroups per rank block
-  constexpr int XB = NSB * 16 * DZ_CH * 2;             // x part of a chunk
-  constexpr int BUF = XB + DZ_WAVES * 1024;            // + one Vt operand per wavefront
-  constexpr int NBUF = NSB == 2 ? 6 : 8;               // 144 KiB / 128 KiB
-  constexpr int LPC = NSB + 1;                         // loads per chunk per wavefront
-  int li = 0;
-#pragma unroll
-  for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].z_first) ? 1 : 0;
-  const DecLayer &ly = a.L[li];
-  const int bid = blockIdx.x - ly.z_first;
-  const int rb16 = bid / SPLIT, sh = bid % SPLIT;      // 16-rank block, sequence half (NSB == 1)
-  const int n = a.n, B = a.B, gs = ly.gs;
-  const uint32_t mask = (uint32_t)ly.plan[65 + (rb16 * 16) / gs];   // sequences whose pattern holds this block's group
-  const uint32_t mine = NSB == 2 ? 0xFFFFFFFFu : (0xFFFFu << (16 * sh));
-  if ((mask & mine) == 0u) {
-    // none of this workgroup's sequences selected the group.  If other sequences did, decode_y will read the whole
-    // operand: this half of it must be zeros (the workspace may hold anything).
-    if (mask != 0u && threadIdx.x < 32) {
-      const int q = threadIdx.x >> 4, jj = threadIdx.x & 15;
-      *reinterpret_cast<u32x4 *>((char *)ly.zf + (size_t)rb16 * 1024 + (q * 32 + sh * 16 + jj) * 16) = u32x4{0, 0, 0, 0};
-    }
-    return;
-  }
-  __shared__ __attribute__((aligned(1024))) char xs[NBUF * BUF];
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
-  const int r16 = lane & 15, kg = lane >> 4;
-  const int nkb = n / 16;                              // 16-column operands per rank block in the store
-  const int nch = (n + DZ_CH - 1) / DZ_CH;
-  // x: NSB*8 instructions of 1 KiB (two rows of 512 bytes) per chunk, NSB per wavefront.  Lane l writes slot l % 32 of
-  // local row 2*ins + l / 32 and fetches the piece (slot ^ (row & 15)) of that row's chunk; pieces past the end of the
-  // row re-read its last one (their products are switched off below).
-  const char *xrow[NSB];
-  int xslot[NSB];
-#pragma unroll
-  for (int i = 0; i < NSB; ++i) {
-    const int lr = (wave + i * DZ_WAVES) * 2 + (lane >> 5);          // local row 0 .. NSB*16-1
-    const int r = sh * 16 + lr;                                      // sequence
-    xrow[i] = (const char *)a.x + (size_t)min(r, B - 1) * n * 2;
-    xslot[i] = (lane & 31) ^ (lr & 15);
-  }
-  const int last_piece = n / 8 - 1;
-  // Vt: this wavefront owns the 32 columns [c*256 + wave*32, +32) of every chunk = operands kb0, kb0+1 of the 32-rank block
-  const char *vbase = (const char *)ly.Vt + ((size_t)(rb16 >> 1) * nkb) * 1024 + ((kg & 1) * 32 + (rb16 & 1) * 16 + r16) * 16;
-  // general form (any chunk; clamps at the end of the rows) and running-pointer form (whole chunks in sequence)
-  auto issue_at = [&](int c, char *buf) {
-#pragma unroll
-    for (int i = 0; i < NSB; ++i) {
-      const int piece = min(c * (DZ_CH / 8) + xslot[i], last_piece);
-      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(xrow[i] + (size_t)piece * 16),
-                                       PARSE_DEC_LDS_PTR(buf + (wave + i * DZ_WAVES) * 1024), 16, 0, 0);
-    }
-    const int kb = min(c * (DZ_CH / 16) + wave * 2 + (kg >> 1), nkb - 1);
-    __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(vbase + (size_t)kb * 1024), PARSE_DEC_LDS_PTR(buf + XB + wave * 1024), 16, 0, 0);
-  };
-  const char *xp[NSB], *vp;
-  auto seek = [&](int c) {                 // running pointers at chunk c
-#pragma unroll
-    for (int i = 0; i < NSB; ++i) xp[i] = xrow[i] + ((size_t)c * (DZ_CH / 8) + xslot[i]) * 16;
-    vp = vbase + ((size_t)c * (DZ_CH / 16) + wave * 2 + (kg >> 1)) * 1024;
-  };
-  auto issue_next = [&](char *buf) {       // the chunk at the running pointers (must be a whole chunk), then advance
-#pragma unroll
-    for (int i = 0; i < NSB; ++i) {
-      __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(xp[i]), PARSE_DEC_LDS_PTR(buf + (wave + i * DZ_WAVES) * 1024), 16, 0, 0);
-      xp[i] += DZ_CH * 2;
-    }
-    __builtin_amdgcn_global_load_lds(PARSE_DEC_GLB_PTR(vp), PARSE_DEC_LDS_PTR(buf + XB + wave * 1024), 16, 0, 0);
-    vp += (DZ_CH / 16) * 1024;
-  };
-  f32x4 acc[NSB];
-#pragma unroll
-  for (int i = 0; i < NSB; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const u32x4 zero = {0, 0, 0, 0};
-  // this lane's LDS read offsets within a chunk buffer
-  int xoff[NSB];
-#pragma unroll
-  for (int i = 0; i < NSB; ++i) {
-    const int lr = i * 16 + r16;
-    xoff[i] = lr * (DZ_CH * 2) + (((wave * 4 + kg) ^ (lr & 15)) * 16);
-  }
-  const int voff = XB + wave * 1024 + lane * 16;
-  auto compute = [&](const char *buf, bool live) {
-    const u32x4 vv = *reinterpret_cast<const u32x4 *>(buf + voff);
-#pragma unroll
-    for (int i = 0; i < NSB; ++i) {
-      const u32x4 xv = *reinterpret_cast<const u32x4 *>(buf + xoff[i]);
-      acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dec_bf16x8(vv), dec_bf16x8(live ? xv : zero), acc[i], 0, 0, 0);
-    }
-  };
-  auto barrier = [&]() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();          // everybody's x rows of the chunk are in LDS; everybody is done with the previous one
-    asm volatile("" ::: "memory");
-  };
-  const int nfull = n / DZ_CH;             // whole chunks; a last partial one goes through the general form
-  // prologue: NBUF-1 chunks requested
-#pragma unroll
-  for (int c = 0; c < NBUF - 1; ++c)
-    if (c < nch) issue_at(c, xs + c * BUF);
-  int c = 0;
-  seek(NBUF - 1);
-  // steady state, unrolled over the buffers: chunk c is awaited with exactly NBUF-2 later chunks outstanding, and the
-  // chunk NBUF-1 ahead (a whole one) is requested into the buffer that the barrier has just freed
-  while (c + NBUF - 1 + NBUF <= nfull) {
-#pragma unroll
-    for (int u = 0; u < NBUF; ++u) {
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NBUF - 2) * LPC) : "memory");
-      barrier();
-      issue_next(xs + ((u + NBUF - 1) % NBUF) * BUF);
-      compute(xs + u * BUF, true);
-    }
-    c += NBUF;
-  }
-  // the rest (at most 2*NBUF-2 chunks): general form
-  for (; c < nch; ++c) {
-    const int later = min(c + NBUF - 2, nch - 1) - c;
-    switch (later) {
-      case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-      case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(1 * LPC) : "memory"); break;
-      case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPC) : "memory"); break;
-      case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LPC) : "memory"); break;
-      case 4: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * LPC) : "memory"); break;
-      case 5: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(5 * LPC) : "memory"); break;
-      default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(6 * LPC) : "memory"); break;
-    }
-    barrier();
-    if (c + NBUF - 1 < nch) issue_at(c + NBUF - 1, xs + ((c + NBUF - 1) % NBUF) * BUF);
-    compute(xs + (c % NBUF) * BUF, c * DZ_CH + wave * 32 + kg * 8 < n);
-  }
-  __syncthreads();        // the staged chunks are dead: their LDS now takes the wavefronts' partial sums
-  float(*red)[NSB][4][64] = reinterpret_cast<float(*)[NSB][4][64]>(xs);     // [8][NSB][4][64] floats
-#pragma unroll
-  for (int i = 0; i < NSB; ++i)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) red[wave][i][e][lane] = acc[i][e];
-  __syncthreads();
-  // accumulator lane (col = l % 16, g = l / 16) holds ranks 4g + (0..3) of sequence col.  Thread (q, jj) gathers the 8
-  // consecutive ranks 8q + (0..7) of its sequence, each summed over the wavefronts in wavefront order: one 16-byte
-  // piece of z operand rb16 (its reduction block in the second product).
-  if (threadIdx.x < NSB * 32) {
-    const int q = threadIdx.x / (NSB * 16), jj = threadIdx.x % (NSB * 16);
-    const int sb = jj >> 4, col = jj & 15;
-    const int seq = sh * 16 + jj;
-    float v[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int g = 2 * q + (e >> 2), ln = g * 16 + col;
-      float sum = red[0][sb][e & 3][ln];
-#pragma unroll
-      for (int w = 1; w < DZ_WAVES; ++w) sum += red[w][sb][e & 3][ln];
-      v[e] = sum;
-    }
-    const bool member = (mask >> seq) & 1u;       // a sequence outside the group's mask gets zeros
-    u32x4 w4;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) w4[e] = member ? cvt_pk_bf16(v[2 * e], v[2 * e + 1]) : 0u;
-    *reinterpret_cast<u32x4 *>((char *)ly.zf + (size_t)rb16 * 1024 + (q * 32 + seq) * 16) = w4;
-  }
-}
-
-// ---------------------------------------------------------------------------------------------------------
 // decode_y: y.  grid = ceil(ncb / NC) workgroups per layer, each owns NC consecutive 32-column output blocks;
 // wavefront w owns an eighth of the used reduction blocks for all NC column blocks, so one z operand (cache-resident)
 // feeds NC products; the Ut operands of its first MAXK reduction blocks are requested at once (MAXK sized so that
@@ -641,14 +463,12 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
 
 // workspace of one layer: z in operand order (R/16 operands of 1 KiB), then the partial sums of decode_zr
 static size_t dec_zf_bytes(const parse_layer *L) { return round_up((size_t)(L->R / 16) * 1024, 256); }
-// decode_zr serves layers whose groups are whole 32-rank blocks and whose reduction fits DR_MAX_KS slices
-static bool dec_zr_ok(const parse_layer *layers, int n_layers) {
-  for (int l = 0; l < n_layers; ++l) {
-    const parse_layer *L = &layers[l];
-    if (L->G <= 0 || L->R % L->G != 0 || (L->R / L->G) % 32 != 0) return false;
-    if (L->R / 32 > DEC_TICKETS) return false;
-  }
-  const int nkb = layers[0].n / 16;
+// decode_zr takes reductions of up to DR_MAX_KS slices of 8 * DR_MAXK steps (n <= 65536) and layers of up to DEC_TICKETS
+// rank blocks whose groups are whole 32-rank blocks (which the operand-order layout requires anyway)
+static bool dec_zr_ok(const parse_layer *L) {
+  if (L->G <= 0 || L->R % L->G != 0 || (L->R / L->G) % 32 != 0) return false;
+  if (L->R / 32 > DEC_TICKETS) return false;
+  const int nkb = L->n / 16;
   return (nkb + 8 * DR_MAXK - 1) / (8 * DR_MAXK) <= DR_MAX_KS;
 }
 // slices of the reduction range: enough that a slice fits a workgroup (8 * DR_MAXK steps), and enough workgroups to give
@@ -668,7 +488,7 @@ static size_t dec_zpart_bytes(const parse_layer *L, int ks) { return ks > 1 ? (s
 size_t decode_plan_bytes(int n_layers) { return round_up((size_t)n_layers * DEC_PLAN_WORDS * sizeof(int32_t), 256); }
 // z workspace of several layers that go through one call: per layer z, then its partial sums
 size_t decode_z_bytes(const parse_layer *layers, int n_layers) {
-  const int ks = dec_zr_ok(layers, n_layers) ? dec_zr_slices(layers, n_layers) : 1;
+  const int ks = dec_zr_slices(layers, n_layers);
   size_t t = 0;
   for (int l = 0; l < n_layers; ++l) t += dec_zf_bytes(&layers[l]) + dec_zpart_bytes(&layers[l], ks);
   return t;
@@ -677,7 +497,7 @@ size_t decode_z_bytes(const parse_layer *layers, int n_layers) {
 size_t decode_workspace_bytes(const parse_layer *L) { return decode_z_bytes(L, 1) + decode_plan_bytes(1); }
 
 bool decode_supported(const parse_layer *L) {
-  return L->R / 16 <= DY_MAXKB && L->G <= DEC_MAXG && L->n % 16 == 0 && L->n >= 16;
+  return L->R / 16 <= DY_MAXKB && L->G <= DEC_MAXG && L->n % 16 == 0 && L->n >= 16 && dec_zr_ok(L);
 }
 
 int build_decode_plan(const parse_layer *layers, const parse_patterns *pts, int n_layers, const int32_t *pattern_id,
@@ -726,9 +546,7 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
     for (int l = 0; l < n_layers; ++l) wgs += (layers[l].m / 32 + NC - 1) / NC;
     if (wgs <= n_cu) break;
   }
-  // decode_zr when every layer's groups are whole 32-rank blocks; else 16-rank workgroups with LDS staging
-  const bool zr = dec_zr_ok(layers, n_layers);
-  const int KS = zr ? dec_zr_slices(layers, n_layers) : 1;
+  const int KS = dec_zr_slices(layers, n_layers);
   a.KS = KS;
   char *ws = reinterpret_cast<char *>(workspace);
   int zb = 0, yb = 0;
@@ -745,14 +563,13 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
     d.plan = plan + (size_t)l * DEC_PLAN_WORDS;
     d.ticket = plan + (size_t)l * DEC_PLAN_WORDS + 192;
     d.R = L->R; d.G = L->G; d.gs = L->R / L->G; d.m = L->m;
-    d.z_first = zb; zb += zr ? (L->R / 32) * KS : L->R / 16;
+    d.z_first = zb; zb += (L->R / 32) * KS;
     d.y_first = yb; yb += (L->m / 32 + NC - 1) / NC;
   }
   const int nkb = a.n / 16;
   const bool two = (nkb + KS - 1) / KS > DR_HALF_KB;     // the longest slice needs two stagings of x
-  if (zr && two) hipLaunchKernelGGL(decode_zr<true>, dim3(zb), dim3(DR_THREADS), 0, s, a);
-  else if (zr) hipLaunchKernelGGL(decode_zr<false>, dim3(zb), dim3(DR_THREADS), 0, s, a);
-  else hipLaunchKernelGGL(decode_zf<2>, dim3(zb), dim3(DZ_THREADS), 0, s, a);
+  if (two) hipLaunchKernelGGL(decode_zr<true>, dim3(zb), dim3(DR_THREADS), 0, s, a);
+  else hipLaunchKernelGGL(decode_zr<false>, dim3(zb), dim3(DR_THREADS), 0, s, a);
   PARSE_LAUNCH_CHECK();
   if (NC == 1) hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   else if (NC == 2) hipLaunchKernelGGL(decode_y<2>, dim3(yb), dim3(DY_THREADS), 0, s, a);

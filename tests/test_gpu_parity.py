@@ -559,6 +559,7 @@ def test_prefill_config1_full_size_sampled():
     (512, 16384, 96, 3, 2, 32, 3, 0),      # three rank blocks (a partial quad), many column blocks
     (512, 32768, 96, 3, 2, 9, 3, 0),       # four column blocks per workgroup
     (2048, 2048, 2048, 64, 20, 32, 4, 0),  # the most groups a layer may have (64 of 32 ranks): quads span four groups
+    (8192, 512, 256, 8, 3, 32, 4, 0),      # a long reduction over few rank blocks: 16 slices, two stagings of x each
 ])
 def test_decode_matches_oracle_and_prefill(n, m, R, G, k, B, npat, schedule):
     say(f"decode n={n} m={m} R={R} G={G} k={k} B={B} patterns={npat} schedule={schedule}")
