@@ -615,8 +615,27 @@ def bench_peaks(torch, pa):
     out["read_stream_GBps"] = reads
     out["copy_GBps"] = {f"{mb}MiB": round(2.0 * (mb << 20) / timed(lambda: pa.probe_copy(src, dst, mb << 20)) / 1e9, 1)
                         for mb in (64, 256)}
+    # The vendor's GEMM (hipBLASLt behind torch.matmul) on the two products of the prefill workloads with ONE shared
+    # factor pair for all rows -- no per-prompt patterns, so it reads 117 MB less than the routed call at 8 x 512 -- as
+    # a yardstick for what these shapes reach on this machine.  Measurement context only: nothing in the path uses it.
+    del src, dst
+    torch.cuda.empty_cache()
+    n = m = 4096; rS = 1024
+    Vd = (torch.randn((n, rS), device=dev) * 0.02).to(torch.bfloat16)
+    Ud = (torch.randn((rS, m), device=dev) * 0.02).to(torch.bfloat16)
+    vend = {}
+    for T in (4096, 32768):
+        Xd = torch.randn((T, n), device=dev).to(torch.bfloat16)
+        Zd = torch.empty((T, rS), dtype=torch.bfloat16, device=dev); Yd = torch.empty((T, m), dtype=torch.bfloat16, device=dev)
+        def pair():
+            torch.matmul(Xd, Vd, out=Zd); torch.matmul(Zd, Ud, out=Yd)
+        t = timed(pair, reps=10)
+        vend[f"{T}_rows"] = {"us": round(t * 1e6, 1), "TFLOPs": round(2.0 * T * rS * (n + m) / t / 1e12, 1)}
+        del Xd, Zd, Yd
+    out["vendor_gemm_pair_one_shared_factor"] = vend
     out["note"] = ("read streams smaller than the 256 MiB last-level cache are re-read from it on the repeated launches; "
-                   "the 1 GiB stream comes from HBM.  copy counts bytes read plus bytes written.")
+                   "the 1 GiB stream comes from HBM.  copy counts bytes read plus bytes written.  vendor_gemm_pair: "
+                   "torch.matmul (hipBLASLt) X[T,4096] @ V[4096,1024] then Z @ U[1024,4096], bf16, back to back.")
     return out
 
 

@@ -206,6 +206,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
     for (int t = 0; t < TB; ++t) tr[buf][t] = *reinterpret_cast<const u32x4 *>(base + tchunk(t, kk));
   };
 
+  // The compiler treats a load that writes LDS directly like a flat access that may complete out of order with LDS
+  // reads, so after one of them every wait it inserts for LDS data is a wait for ALL outstanding LDS reads.  Placed by
+  // the compiler that wait sits between the reads of the next step and the matrix instructions of this step and exposes
+  // the LDS latency once per slice.  Touching this step's operands BEFORE the next step's reads are issued moves the wait
+  // to where nothing is outstanding but reads that had a whole step to finish.
+  auto settle = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < FB; ++i) asm volatile("" ::"v"(fr[buf][i]));
+#pragma unroll
+    for (int t = 0; t < TB; ++t) asm volatile("" ::"v"(tr[buf][t]));
+  };
+
   // prologue: STAGES-1 slices requested, the first one awaited, one more requested
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
@@ -220,6 +232,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
 #pragma unroll
     for (int s = 0; s < KK; ++s) {
       const int cur = s & 1;
+      settle(cur);
+      __builtin_amdgcn_sched_barrier(0);
       if (s < KK - 1) {
         read_ops(cur ^ 1, sb, s + 1);
       } else if (kt + 1 < nk) {

@@ -538,6 +538,12 @@ def test_prefill_config1_full_size_sampled():
         Ys[schedule] = forward_guarded(pa.PARSE_PREFILL, dl, pa.Patterns(w.k, w.P, Vs, Us, schedule=schedule), Xd, offd, pid)
         torch.cuda.synchronize()
     assert np.all(margin > 1e-4) and np.array_equal(sub_d.cpu().numpy(), subs)
+    # the launch configuration the benchmark times: a ready plan, then the planned call
+    rows = int(w.tok_offsets[-1])
+    plan = pa.prefill_plan(offd, pid, rows, w.P)
+    Ys["ready plan"] = pa.lowrank_prefill_planned(dl, pa.Patterns(w.k, w.P, Vs, Us), Xd, offd, pid, plan)
+    torch.cuda.synchronize()
+    assert torch.equal(Ys["ready plan"].view(torch.int16), Ys[3].view(torch.int16))
     U0, sg, V = oracle_factors(lay)
     rng = np.random.default_rng(7)
     for p in range(w.P):
