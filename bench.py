@@ -284,9 +284,9 @@ def bench_prefill(args, torch, pa, si):
         "rows_us": {k_: round(v, 2) for k_, v in per.items()},
         "cache_hits": hits, "forward_us_by_schedule": sched_us, "cold_step_ms": round(cold_ms, 4),
         "rank_granular_us": rank_us, "two_batches_in_flight": pipelined,
-        # the forward of the timed steps is parse_lowrank_prefill_planned: first product on 64-token register-operand
-        # tiles (Z row-major), second product on 256 x 256 LDS-staged tiles over the plan
-        "roofline": {"bound": "mfma", "kernel": "gemm_tokens<64,2,8,2> + gemm_lds<256,256,2x4,BK32,S4> (one planned forward call)",
+        # the forward of the timed steps is parse_lowrank_prefill_planned: both products on LDS-staged tiles over the
+        # plan, 128 x 128 for the first (256 workgroups), 256 x 256 for the second
+        "roofline": {"bound": "mfma", "kernel": "gemm_lds<128,128,2x2,BK64,S4> + gemm_lds<256,256,2x4,BK32,S4> (one planned forward call)",
                      "achieved": round(achieved, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": traffic_from_profiles("prefill_config1"),

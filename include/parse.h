@@ -288,8 +288,8 @@ int parse_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, in
 /* The bf16 prefill product (Eq. 10) of one layer over a ready plan: two launches, no prompt-dependent work on the
  * host.  layer bf16 PARSE_MFMA16 with n % 64 == 0; patterns as for PARSE_PREFILL (a shared head must be whole 32-rank
  * blocks); the plan must
- * have been built from the same tok_offsets, pattern_id, rows, P and patterns->n_patterns (short batches run their
- * first product on prompt-order tiles, which read the two arrays directly).
+ * have been built from the same tok_offsets, pattern_id, rows, P and patterns->n_patterns (the two arrays are checked
+ * for presence only: everything the kernels need from them is in the plan).
  *   workspace  device, >= parse_lowrank_prefill_planned_workspace_bytes(layer, rows, P, k, n_patterns): the
  *              intermediate of the padded virtual rows, in operand order. */
 size_t parse_lowrank_prefill_planned_workspace_bytes(const parse_layer *layer, int32_t rows, int32_t P, int32_t k,

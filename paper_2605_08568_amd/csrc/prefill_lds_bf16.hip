@@ -58,7 +58,7 @@ struct LgArgs {
 // FORD: factor order, 0 = right factor (operand (rb, kb) at rb*(K/16)+kb), 1 = left factor (operand (kb, cb) at kb*(M/32)+cb).
 // TROW: token operand 1 = row-major rows looked up through the plan's row map (X, or a row-major intermediate),
 //       0 = operand order over the plan's virtual rows.   OROW: output 1 = row-major through the row map, 0 = operand order.
-// First product: <FORD 0, TROW 1, OROW 0>; second product: <FORD 1, TROW 0, OROW 1>, or <1, 1, 1> on a row-major Z.
+// First product: <FORD 0, TROW 1, OROW 0>; second product: <FORD 1, TROW 0, OROW 1>.
 template <int BM, int BN, int WM, int WN, int BK, int STAGES, int FORD, int TROW, int OROW>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
   constexpr int NW = WM * WN;
@@ -312,17 +312,12 @@ static int launch_gemm_lds(LgArgs a, int avg_tiles_per_pattern, hipStream_t s) {
 }
 
 // Z workspace of the planned form: the plan's capacity in virtual rows x rS bf16 (operand order)
-bool prefill_split_supported(int n, int rS);
 size_t prefill_planned_z_bytes(int cap_tiles, int rS) { return round_up((size_t)cap_tiles * 256 * rS * sizeof(uint16_t), 256); }
 
 bool prefill_planned_supported(int n, int m, int rS) { return n % 64 == 0 && rS % 32 == 0 && m % 32 == 0 && n >= 64 && rS >= 32; }
 
-int forward_prefill_split_first_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s);
-
-// X [rows][n] row-major, plan built for (tok_offsets, pattern ids of these patterns), Z workspace, Y [rows][m].
-// Short batches (too few 256-row tiles of the first product to occupy the chip) run the first product with the
-// register-operand tile kernel on 64-token tiles, which leaves Z row-major; the second product then looks its token
-// rows up through the plan's row map like the first product does with X.
+// X [rows][n] row-major, plan built for (tok_offsets, pattern ids of these patterns), Z workspace (operand order over the
+// plan's virtual rows), Y [rows][m].
 int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, uint16_t *Z, int avg_prompt_rows,
                                  hipStream_t s) {
   if (p.sh_ranks % 32 != 0 || p.sh_ranks >= p.rS) return PARSE_ESHAPE;
@@ -332,19 +327,13 @@ int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, 
   const long long tiles256 = (long long)((p.rows + 255) / 256);
   const int per_pattern = avg_prompt_rows / 256;
   // 256 x 256 tiles halve the bytes a compute unit has to take in per flop; they are used when they still give the
-  // chip enough workgroups
+  // chip enough workgroups, 128 x 128 tiles otherwise (config 1's first product: 64 large tiles or 256 small ones)
   const bool big1 = tiles256 * ((p.rS + 255) / 256) >= 192;
   const bool big2 = tiles256 * ((p.m + 255) / 256) >= 192;
-  const bool rowmajor_z = !big1 && p.tok_offsets != nullptr && p.pattern_id != nullptr && prefill_split_supported(p.n, p.rS);
   int st;
   if (big1) st = launch_gemm_lds<256, 256, 2, 2, 32, 4, 0, 1, 0>(g1, per_pattern, s);
-  else if (rowmajor_z) st = forward_prefill_split_first_bf16(p, Z, avg_prompt_rows, s);
   else st = launch_gemm_lds<128, 128, 2, 2, 64, 4, 0, 1, 0>(g1, per_pattern, s);
   if (st != PARSE_OK) return st;
-  if (rowmajor_z) {
-    if (big2) return launch_gemm_lds<256, 256, 2, 4, 32, 4, 1, 1, 1>(g2, per_pattern, s);
-    return launch_gemm_lds<128, 128, 2, 2, 32, 4, 1, 1, 1>(g2, per_pattern, s);
-  }
   if (big2) return launch_gemm_lds<256, 256, 2, 4, 32, 4, 1, 0, 1>(g2, per_pattern, s);
   return launch_gemm_lds<128, 128, 2, 2, 32, 4, 1, 0, 1>(g2, per_pattern, s);
 }

@@ -377,19 +377,6 @@ int tokens_times_factor_bf16(const uint16_t *Tk, const uint16_t *F, uint16_t *O,
   return (K % (PF_BK * 4) == 0) ? launch_gemm_tokens<64, 2, 8, 2, 0>(g, 8, s) : launch_gemm_tokens<64, 2, 8, 1, 0>(g, 8, s);
 }
 
-// Only the first product, Z [rows][rS] row-major, on 64-token tiles (the planned schedule's choice for short batches).
-int forward_prefill_split_first_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s) {
-  GtArgs g1{};
-  g1.n_layers = 1;
-  g1.tok_offsets = p.tok_offsets; g1.pattern_id = p.pattern_id; g1.rows = p.rows; g1.P = p.P;
-  const int rp = p.rS - p.sh_ranks;            // ranks in the per-pattern blocks (the shared head is stored once)
-  g1.L[0] = GtLayer{p.X, p.Vt_S, Z, (size_t)rp * p.n, p.n / 16, 1, p.n, p.rS, p.n_patterns, 0, p.Vt_sh, p.sh_ranks / 32};
-  int gt64 = avg_prompt_rows / 64;  gt64 = gt64 < 1 ? 1 : (gt64 > 8 ? 8 : gt64);
-  const bool halves = p.n % (PF_BK * 4) == 0;
-  if (p.sh_ranks > 0) return halves ? launch_gemm_tokens<64, 2, 8, 2, 1>(g1, gt64, s) : launch_gemm_tokens<64, 2, 8, 1, 1>(g1, gt64, s);
-  return halves ? launch_gemm_tokens<64, 2, 8, 2, 0>(g1, gt64, s) : launch_gemm_tokens<64, 2, 8, 1, 0>(g1, gt64, s);
-}
-
 int forward_prefill_split_bf16(const PfArgs &p, uint16_t *Z, int avg_prompt_rows, hipStream_t s) {
   uint16_t *Zs[1] = {Z};
   return forward_prefill_split_multi_bf16(&p, 1, Zs, avg_prompt_rows, s);
