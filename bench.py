@@ -463,8 +463,11 @@ def bench_stack(args, torch, pa, si):
     Yh = [torch.empty((T, hidden), dtype=torch.bfloat16, device=dev) for _ in range(3)]
     Yi = [torch.empty((T, inter), dtype=torch.bfloat16, device=dev) for _ in range(2)]
     L0 = layers[0]
-    ws_qkv = torch.empty(int(pa.lowrank_workspace_bytes(pa.PARSE_PREFILL, L0["q"], T, k)) * 3, dtype=torch.uint8, device=dev)
-    ws_gu = torch.empty(int(pa.lowrank_workspace_bytes(pa.PARSE_PREFILL, L0["gate"], T, k)) * 2, dtype=torch.uint8, device=dev)
+    P0 = pats[0]
+    ws_qkv = torch.empty(max(pa.lowrank_prefill_multi_workspace_bytes([L0["q"], L0["k"], L0["v"]], [P0["q"], P0["k"], P0["v"]], T),
+                             int(pa.lowrank_workspace_bytes(pa.PARSE_PREFILL, L0["o"], T, k, 1, 1))), dtype=torch.uint8, device=dev)
+    ws_gu = torch.empty(max(pa.lowrank_prefill_multi_workspace_bytes([L0["gate"], L0["up"]], [P0["gate"], P0["up"]], T),
+                            int(pa.lowrank_workspace_bytes(pa.PARSE_PREFILL, L0["down"], T, k, 1, 1))), dtype=torch.uint8, device=dev)
     wsd = torch.empty(max(pa.lowrank_decode_multi_workspace_bytes([L0["q"], L0["k"], L0["v"]]),
                           pa.lowrank_decode_multi_workspace_bytes([L0["gate"], L0["up"]]),
                           pa.lowrank_workspace_bytes(pa.PARSE_DECODE, L0["o"], 1, k),

@@ -502,6 +502,13 @@ def lowrank_decode_multi(layers, patterns, X, pattern_id, Ys=None, workspace=Non
     return Ys
 
 
+def lowrank_prefill_multi_workspace_bytes(layers, patterns, rows: int) -> int:
+    nl = len(layers)
+    larr = (_Layer * nl)(*[l.c() for l in layers])
+    parr = (_Patterns * nl)(*[p.c() for p in patterns])
+    return int(lib().parse_lowrank_prefill_multi_workspace_bytes(larr, parr, nl, rows))
+
+
 def lowrank_prefill_multi(layers, patterns, X, tok_offsets, pattern_id, Ys=None, workspace=None):
     """parse_lowrank_prefill_multi: prefill of several layers that share X in two launches.  Returns the list of Y."""
     rows, nl = X.shape[0], len(layers)

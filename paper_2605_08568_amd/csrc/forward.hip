@@ -17,6 +17,8 @@ int build_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, in
                        int32_t *plan, hipStream_t s);
 size_t prefill_planned_z_bytes(int cap_tiles, int rS);
 bool prefill_planned_supported(int n, int m, int rS);
+int forward_prefill_planned_multi_bf16(const PfArgs *p, int n_layers, const int32_t *plan, int cap, uint16_t *const *Z,
+                                       int avg_prompt_rows, hipStream_t s);
 int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, uint16_t *Z, int avg_prompt_rows,
                                  hipStream_t s);
 size_t prefill_lds_bytes(int BM, int rS);
@@ -249,6 +251,27 @@ int parse_lowrank_decode_planned(const parse_layer *layers, int32_t n_layers, co
                                      (uint16_t *const *)Y, workspace, (hipStream_t)stream);
 }
 
+// workspace of the planned schedule for several layers: every layer's padded intermediate, then the plan.  The plan's
+// capacity is bounded without knowing the number of prompts (at most n_patterns + 1 pattern buckets).
+static bool multi_planned_shapes(const parse_layer *layers, const parse_patterns *patterns, int n_layers) {
+  for (int l = 0; l < n_layers; ++l) {
+    const parse_layer *L = &layers[l];
+    const parse_patterns *pt = &patterns[l];
+    if (L->G <= 0 || L->R % L->G != 0) return false;
+    const int gs = L->R / L->G;
+    if (pt->n_patterns != patterns[0].n_patterns || pt->n_patterns > 2048) return false;
+    if (!prefill_planned_supported(L->n, L->m, pt->k * gs)) return false;
+    if (pt->n_shared < 0 || (pt->n_shared * gs) % 32 != 0) return false;
+  }
+  return true;
+}
+static size_t multi_planned_bytes(const parse_layer *layers, const parse_patterns *patterns, int n_layers, int rows, int P) {
+  const int cap = prefill_plan_capacity(rows, P, patterns[0].n_patterns);
+  size_t total = prefill_plan_bytes(rows, P, patterns[0].n_patterns);
+  for (int l = 0; l < n_layers; ++l) total += prefill_planned_z_bytes(cap, patterns[l].k * (layers[l].R / layers[l].G));
+  return total;
+}
+
 size_t parse_lowrank_prefill_multi_workspace_bytes(const parse_layer *layers, const parse_patterns *patterns,
                                                    int32_t n_layers, int32_t rows) {
   if (!layers || !patterns || n_layers < 1 || n_layers > 4 || rows <= 0) return 0;
@@ -256,6 +279,11 @@ size_t parse_lowrank_prefill_multi_workspace_bytes(const parse_layer *layers, co
   for (int l = 0; l < n_layers; ++l) {
     if (layers[l].G <= 0 || layers[l].R <= 0 || patterns[l].k <= 0) return 0;
     total += prefill_split_workspace_bytes(rows, patterns[l].k * (layers[l].R / layers[l].G));
+  }
+  if (multi_planned_shapes(layers, patterns, n_layers)) {
+    const int p_ub = rows < 2048 ? rows : 2048;          // the plan takes at most 2048 prompts
+    const size_t planned = multi_planned_bytes(layers, patterns, n_layers, rows, p_ub);
+    if (planned > total) total = planned;
   }
   return total;
 }
@@ -269,6 +297,7 @@ int parse_lowrank_prefill_multi(const parse_layer *layers, const parse_patterns 
   if (n_layers > 4 || P > rows) return PARSE_ESHAPE;
   if (!aligned16(X)) return PARSE_EALIGN;
   PfArgs args[4];
+  bool tiles_ok = true;
   for (int l = 0; l < n_layers; ++l) {
     const parse_layer *L = &layers[l];
     const parse_patterns *pt = &patterns[l];
@@ -278,7 +307,8 @@ int parse_lowrank_prefill_multi(const parse_layer *layers, const parse_patterns 
     if (!Y[l] || !pt->Vt_S || !pt->Ut_S) return PARSE_EINVAL;
     if (pt->n_patterns <= 0 || pt->k <= 0) return PARSE_EINVAL;
     const int rS = pt->k * (L->R / L->G);
-    if (pt->k > L->G || L->n != layers[0].n || !prefill_split_supported(L->n, rS)) return PARSE_ESHAPE;
+    if (pt->k > L->G || L->n != layers[0].n) return PARSE_ESHAPE;
+    tiles_ok = tiles_ok && prefill_split_supported(L->n, rS);
     if (!aligned16(Y[l]) || !aligned16(pt->Vt_S) || !aligned16(pt->Ut_S)) return PARSE_EALIGN;
     args[l] = PfArgs{(const uint16_t *)X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, (uint16_t *)Y[l],
                      tok_offsets, pattern_id, pt->n_patterns, rows, L->n, L->m, rS, P};
@@ -292,16 +322,39 @@ int parse_lowrank_prefill_multi(const parse_layer *layers, const parse_patterns 
       args[l].sh_ranks = pt->n_shared * (L->R / L->G);
     }
   }
-  const size_t need = parse_lowrank_prefill_multi_workspace_bytes(layers, patterns, n_layers, rows);
-  if (!workspace || workspace_bytes < need) return PARSE_EWORKSPACE;
-  if (!aligned16(workspace)) return PARSE_EALIGN;
-  uint16_t *Z[4];
+  if (workspace && !aligned16(workspace)) return PARSE_EALIGN;
+  // schedule: patterns[0].schedule decides for the call (the fused single-launch kernel takes one layer only)
+  const int schedule = patterns[0].schedule;
+  if (schedule < PARSE_SCHED_AUTO || schedule > PARSE_SCHED_PLANNED || schedule == PARSE_SCHED_FUSED) return PARSE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
   char *ws = reinterpret_cast<char *>(workspace);
+  const bool planned_shapes = multi_planned_shapes(layers, patterns, n_layers) && prefill_plan_supported(P, patterns[0].n_patterns);
+  const bool can_plan = planned_shapes && workspace != nullptr &&
+                        workspace_bytes >= multi_planned_bytes(layers, patterns, n_layers, rows, P);
+  if (schedule == PARSE_SCHED_PLANNED && !can_plan) return planned_shapes ? PARSE_EWORKSPACE : PARSE_ESHAPE;
+  if (can_plan && schedule != PARSE_SCHED_TILES) {
+    // planned: every layer's padded intermediate, then the plan; one plan launch, then two launches for all layers
+    const int cap = prefill_plan_capacity(rows, P, patterns[0].n_patterns);
+    uint16_t *Z[4];
+    for (int l = 0; l < n_layers; ++l) {
+      Z[l] = reinterpret_cast<uint16_t *>(ws);
+      ws += prefill_planned_z_bytes(cap, args[l].rS);
+    }
+    int32_t *plan = reinterpret_cast<int32_t *>(ws);
+    int st = build_prefill_plan(tok_offsets, pattern_id, P, rows, patterns[0].n_patterns, plan, s);
+    if (st != PARSE_OK) return st;
+    return forward_prefill_planned_multi_bf16(args, n_layers, plan, cap, Z, rows / P, s);
+  }
+  if (!tiles_ok) return PARSE_ESHAPE;
+  size_t need = 0;
+  for (int l = 0; l < n_layers; ++l) need += prefill_split_workspace_bytes(rows, args[l].rS);
+  if (!workspace || workspace_bytes < need) return PARSE_EWORKSPACE;
+  uint16_t *Z[4];
   for (int l = 0; l < n_layers; ++l) {
     Z[l] = reinterpret_cast<uint16_t *>(ws);
     ws += prefill_split_workspace_bytes(rows, args[l].rS);
   }
-  return forward_prefill_split_multi_bf16(args, n_layers, Z, rows / P, (hipStream_t)stream);
+  return forward_prefill_split_multi_bf16(args, n_layers, Z, rows / P, s);
 }
 
 }  // extern "C"

@@ -38,21 +38,31 @@ __device__ __forceinline__ void wg_barrier() {
   asm volatile("" ::: "memory");
 }
 
-struct LgArgs {
-  const uint16_t *Tk;      // TROW 1: row-major [rows][K] (X, or a row-major Z);  TROW 0: Z in operand order [(virtual rows)/32][K/16][1 KiB]
+constexpr int LG_MAX_LAYERS = 4;
+
+// One product of one layer.  A launch covers up to LG_MAX_LAYERS of them (layers that share their token rows and the
+// plan: the stacked first product and the batched second product of Sec. 4.4, Eq. 11-12): the column tiles of the
+// layers are numbered through, tn_first is a layer's first.
+struct LgLayer {
+  const uint16_t *Tk;      // TROW 1: row-major [rows][K] (X);  TROW 0: Z in operand order [(virtual rows)/32][K/16][1 KiB]
   const uint16_t *F;       // factor operands of all patterns
   uint16_t *O;             // OROW 0: Z (operand order);  OROW 1: Y row-major [rows][M]
   size_t pattern_stride;   // elements of F per pattern
   int K, M;                // reduction length, factor rows (= output columns)
-  const int32_t *plan;     // header | tile patterns | row map (plan.hip)
-  int cap;                 // plan capacity in 256-row tiles (fixes where the row map starts)
-  int ntn, gm, ngroups;    // column tiles, token tiles per locality group, groups
   // shared head (Sec. 4.4: shared experts at the head of memory, stored once): the first sh_blocks 32-rank blocks of
   // every pattern's selection come from Fsh (same operand order, as many rank rows as the head has), the per-pattern
   // blocks in F hold the rest, renumbered from 0.  FORD 0: the leading factor-row blocks; FORD 1 (BK == 32 only): the
   // leading reduction slices.  0 = everything per pattern.
   const uint16_t *Fsh;
   int sh_blocks;
+  int tn_first;            // first column tile of this layer in the launch
+};
+struct LgArgs {
+  LgLayer L[LG_MAX_LAYERS];
+  int n_layers;
+  const int32_t *plan;     // header | tile patterns | row map (plan.hip)
+  int cap;                 // plan capacity in 256-row tiles (fixes where the row map starts)
+  int ntn, gm, ngroups;    // column tiles (all layers), token tiles per locality group, groups
 };
 
 // FORD: factor order, 0 = right factor (operand (rb, kb) at rb*(K/16)+kb), 1 = left factor (operand (kb, cb) at kb*(M/32)+cb).
@@ -85,8 +95,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
   if ((int)blockIdx.x >= n_real) return;
   const int tile = xcd_tile(blockIdx.x, n_real);
   const int g = tile / per, r = tile % per;
-  const int tm = g * a.gm + r % a.gm, tn = r / a.gm;
-  const int K = a.K, M = a.M;
+  const int tm = g * a.gm + r % a.gm;
+  int tn = r / a.gm;                           // column tile over all layers of the launch
+  int li = 0;
+#pragma unroll
+  for (int i = 1; i < LG_MAX_LAYERS; ++i) li += (i < a.n_layers && tn >= a.L[i].tn_first) ? 1 : 0;
+  const LgLayer &ly = a.L[li];
+  tn -= ly.tn_first;
+  const int K = ly.K, M = ly.M;
   const int nk = K / BK;
   if (tm * BM >= vrows) return;                // the last locality group may be partial
   const int32_t *tile_pat = a.plan + 16;
@@ -100,32 +116,32 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
         if (orow < 0) continue;
         for (int c = lane * 8; c < BN; c += 512) {
           const int col = tn * BN + c;
-          if (col < M) *reinterpret_cast<u32x4 *>(a.O + (size_t)orow * M + col) = u32x4{0, 0, 0, 0};
+          if (col < M) *reinterpret_cast<u32x4 *>(ly.O + (size_t)orow * M + col) = u32x4{0, 0, 0, 0};
         }
       }
     }
     return;
   }
-  const uint16_t *Fp = a.F + (size_t)pat * a.pattern_stride;
+  const uint16_t *Fp = ly.F + (size_t)pat * ly.pattern_stride;
 
   // ---- per-lane global sources of this wavefront's load instructions; they advance by a constant per slice ----
   const char *fsrc[LF];
   const char *fsrc_own[LF];                    // FORD 1 with a shared head: where the pattern's own slices start
   int fdst[LF];
-  const int shb = a.sh_blocks;
+  const int shb = ly.sh_blocks;
 #pragma unroll
   for (int i = 0; i < LF; ++i) {
     const int ins = wave + i * NW;             // instruction id within the factor part, LDS order [fb][kk]
     const int fb = ins / KK, kk = ins % KK;
     const int gb = min(tn * (BN / 32) + fb, M / 32 - 1);   // blocks past the end re-read the last one (never stored)
     if (FORD == 0) {
-      const char *src = gb < shb ? (const char *)a.Fsh + (size_t)gb * (K / 16) * 1024
+      const char *src = gb < shb ? (const char *)ly.Fsh + (size_t)gb * (K / 16) * 1024
                                  : (const char *)Fp + (size_t)(gb - shb) * (K / 16) * 1024;
       fsrc[i] = src + (size_t)kk * 1024 + lane * 16;
       fsrc_own[i] = fsrc[i];
     } else {
       fsrc_own[i] = (const char *)Fp + ((size_t)kk * (M / 32) + gb) * 1024 + lane * 16;
-      fsrc[i] = shb > 0 ? (const char *)a.Fsh + ((size_t)kk * (M / 32) + gb) * 1024 + lane * 16 : fsrc_own[i];
+      fsrc[i] = shb > 0 ? (const char *)ly.Fsh + ((size_t)kk * (M / 32) + gb) * 1024 + lane * 16 : fsrc_own[i];
     }
     fdst[i] = ins * 1024;
   }
@@ -139,7 +155,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
     const int ins = wave + i * NW;
     if (TROW == 0) {
       const int tb = ins / KK, kk = ins % KK;
-      tsrc[i] = (const char *)a.Tk + ((size_t)(tm * (BM / 32) + tb) * (K / 16) + kk) * 1024 + lane * 16;
+      tsrc[i] = (const char *)ly.Tk + ((size_t)(tm * (BM / 32) + tb) * (K / 16) + kk) * 1024 + lane * 16;
     } else {
       constexpr int RPI = 1024 / (BK * 2);     // rows per instruction
       const int rr = ins * RPI + lane / CPR, cp = lane % CPR;   // LDS position (row, chunk slot)
@@ -147,7 +163,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
       const int c = cp ^ sw;                                    // chunk of the row that is stored in that slot
       int row = rowmap[tm * BM + rr];
       row = row < 0 ? 0 : row;                 // padding rows read row 0; their results are never stored to Y
-      tsrc[i] = (const char *)a.Tk + (size_t)row * K * 2 + c * 16;
+      tsrc[i] = (const char *)ly.Tk + (size_t)row * K * 2 + c * 16;
     }
     tdst[i] = F_BYTES + ins * 1024;
   }
@@ -279,9 +295,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
         if (gb < M / 32) {
           if (OROW == 0) {   // Z operand (token block, reduction block gb*2 + h), lane's piece at lane*16
             const int tbg = tm * (BM / 32) + wm * TB + t;
-            *reinterpret_cast<u32x4 *>((char *)a.O + ((size_t)tbg * (M / 16) + gb * 2 + h) * 1024 + lane * 16) = w;
+            *reinterpret_cast<u32x4 *>((char *)ly.O + ((size_t)tbg * (M / 16) + gb * 2 + h) * 1024 + lane * 16) = w;
           } else if (orow >= 0) {
-            *reinterpret_cast<u32x4 *>(a.O + (size_t)orow * M + gb * 32 + h * 16 + q * 8) = w;
+            *reinterpret_cast<u32x4 *>(ly.O + (size_t)orow * M + gb * 32 + h * 16 + q * 8) = w;
           }
         }
       }
@@ -302,7 +318,11 @@ static int launch_gemm_lds(LgArgs a, int avg_tiles_per_pattern, hipStream_t s) {
     attr_done[dev] = true;
   }
   const int ntm = a.cap * (256 / BM);          // token tiles the plan can hold (the kernel exits past the real count)
-  a.ntn = (a.M + BN - 1) / BN;
+  a.ntn = 0;
+  for (int l = 0; l < a.n_layers; ++l) {
+    a.L[l].tn_first = a.ntn;
+    a.ntn += (a.L[l].M + BN - 1) / BN;
+  }
   int gm = avg_tiles_per_pattern * (256 / BM);
   a.gm = gm < 1 ? 1 : (gm > 8 ? 8 : gm);
   a.ngroups = (ntm + a.gm - 1) / a.gm;
@@ -316,26 +336,43 @@ size_t prefill_planned_z_bytes(int cap_tiles, int rS) { return round_up((size_t)
 
 bool prefill_planned_supported(int n, int m, int rS) { return n % 64 == 0 && rS % 32 == 0 && m % 32 == 0 && n >= 64 && rS >= 32; }
 
-// X [rows][n] row-major, plan built for (tok_offsets, pattern ids of these patterns), Z workspace (operand order over the
-// plan's virtual rows), Y [rows][m].
-int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, uint16_t *Z, int avg_prompt_rows,
-                                 hipStream_t s) {
-  if (p.sh_ranks % 32 != 0 || p.sh_ranks >= p.rS) return PARSE_ESHAPE;
-  const int own = p.rS - p.sh_ranks;           // ranks in a pattern's own block
-  LgArgs g1{p.X, p.Vt_S, Z, (size_t)own * p.n, p.n, p.rS, plan, cap, 0, 0, 0, p.Vt_sh, p.sh_ranks / 32};
-  LgArgs g2{Z, p.Ut_S, p.Y, (size_t)own * p.m, p.rS, p.m, plan, cap, 0, 0, 0, p.Ut_sh, p.sh_ranks / 32};
-  const long long tiles256 = (long long)((p.rows + 255) / 256);
+// n_layers layers that share X [rows][n] (row-major) and the plan (built for the tok_offsets and pattern ids of these
+// patterns); Z[l] = layer l's intermediate (operand order over the plan's virtual rows); p[l].Y [rows][m_l].
+// Two launches for all layers together: the stacked first product, the batched second product (Sec. 4.4, Eq. 11-12).
+int forward_prefill_planned_multi_bf16(const PfArgs *p, int n_layers, const int32_t *plan, int cap, uint16_t *const *Z,
+                                       int avg_prompt_rows, hipStream_t s) {
+  if (n_layers < 1 || n_layers > LG_MAX_LAYERS) return PARSE_ESHAPE;
+  LgArgs g1{}, g2{};
+  g1.n_layers = g2.n_layers = n_layers;
+  g1.plan = g2.plan = plan;
+  g1.cap = g2.cap = cap;
+  long long ct1 = 0, ct2 = 0;                  // 256-wide column tiles of the two products, all layers
+  for (int l = 0; l < n_layers; ++l) {
+    if (p[l].sh_ranks % 32 != 0 || p[l].sh_ranks >= p[l].rS) return PARSE_ESHAPE;
+    const int own = p[l].rS - p[l].sh_ranks;   // ranks in a pattern's own block
+    g1.L[l] = LgLayer{p[l].X, p[l].Vt_S, Z[l], (size_t)own * p[l].n, p[l].n, p[l].rS, p[l].Vt_sh, p[l].sh_ranks / 32, 0};
+    g2.L[l] = LgLayer{Z[l], p[l].Ut_S, p[l].Y, (size_t)own * p[l].m, p[l].rS, p[l].m, p[l].Ut_sh, p[l].sh_ranks / 32, 0};
+    ct1 += (p[l].rS + 255) / 256;
+    ct2 += (p[l].m + 255) / 256;
+  }
+  const long long tiles256 = (long long)((p[0].rows + 255) / 256);
   const int per_pattern = avg_prompt_rows / 256;
   // 256 x 256 tiles halve the bytes a compute unit has to take in per flop; they are used when they still give the
   // chip enough workgroups, 128 x 128 tiles otherwise (config 1's first product: 64 large tiles or 256 small ones)
-  const bool big1 = tiles256 * ((p.rS + 255) / 256) >= 192;
-  const bool big2 = tiles256 * ((p.m + 255) / 256) >= 192;
+  const bool big1 = tiles256 * ct1 >= 192;
+  const bool big2 = tiles256 * ct2 >= 192;
   int st;
   if (big1) st = launch_gemm_lds<256, 256, 2, 2, 32, 4, 0, 1, 0>(g1, per_pattern, s);
   else st = launch_gemm_lds<128, 128, 2, 2, 64, 4, 0, 1, 0>(g1, per_pattern, s);
   if (st != PARSE_OK) return st;
   if (big2) return launch_gemm_lds<256, 256, 2, 4, 32, 4, 1, 0, 1>(g2, per_pattern, s);
   return launch_gemm_lds<128, 128, 2, 2, 32, 4, 1, 0, 1>(g2, per_pattern, s);
+}
+
+int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, uint16_t *Z, int avg_prompt_rows,
+                                 hipStream_t s) {
+  uint16_t *Zs[1] = {Z};
+  return forward_prefill_planned_multi_bf16(&p, 1, plan, cap, Zs, avg_prompt_rows, s);
 }
 
 }  // namespace parse

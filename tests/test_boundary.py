@@ -166,7 +166,10 @@ def test_prefill_multi_rejects_bad_arguments():
     assert call([La, La], [pt, pt], 0) == -1 and call([La, La], [pt, pt], 2, off=None) == -1
     assert call([La] * 5, [pt] * 5, 5) == -2 and call([La, La], [pt, pt], 2, P=9) == -2
     assert call([La, Lb], [pt, pt], 2) == -2                       # the layers must share the input width
-    assert call([La, Lc], [pt, pt], 2) == -2                       # selected ranks not a multiple of 128
+    pt_tiles = B._Patterns(FAKE.value, FAKE.value, None, 1, 2, 1, None, None, 0, 2)
+    assert call([La, Lc], [pt_tiles, pt_tiles], 2) == -2           # two-launch schedule: selected ranks not a multiple of 128
+    pt_fused = B._Patterns(FAKE.value, FAKE.value, None, 1, 2, 1, None, None, 0, 1)
+    assert call([La, La], [pt_fused, pt_fused], 2) == -1           # the single-launch kernel takes one layer only
     assert call([La, _layer(n=256, m=256, R=256, G=2, dtype=1, layout=0)], [pt, pt], 2) == -7
     assert call([La, La], [pt, pt], 2, ys=[FAKE.value, None]) == -1
     assert call([La, La], [pt, pt], 2, wsb=64) == -5 and call([La, La], [pt, pt], 2, ws=None) == -5

@@ -828,15 +828,20 @@ def test_prefill_multi_matches_oracle_and_single_calls(shapes, n, lengths):
         Vs, Us = pa.pack_patterns(dl, i32(subs), k, k, None, None, P)
         layers.append(dl)
         patterns.append(pa.Patterns(k, P, Vs, Us))
-    ys = prefill_multi_guarded(layers, patterns, Xd, offd, pid)
-    torch.cuda.synchronize()
-    for li in range(len(shapes)):
-        yn = ys[li].float().cpu().numpy().astype(np.float64)
-        for p in range(P):
-            assert_close(yn[off[p]:off[p + 1]], refs[li][off[p]:off[p + 1]], TOL_BF16, f"layer {li} prompt {p}")
-        single = forward_guarded(pa.PARSE_PREFILL, layers[li], patterns[li].with_schedule(pa.PARSE_SCHED_TILES), Xd, offd, pid)
+    # the fused call under each schedule it takes (default = planned when the queried workspace is given): against the
+    # oracle, and bit for bit against the separate calls under the same schedule
+    for schedule in (pa.PARSE_SCHED_AUTO, pa.PARSE_SCHED_PLANNED, pa.PARSE_SCHED_TILES):
+        pats = [pt.with_schedule(schedule) for pt in patterns]
+        ys = prefill_multi_guarded(layers, pats, Xd, offd, pid)
         torch.cuda.synchronize()
-        assert torch.equal(single.view(torch.int16), ys[li].view(torch.int16)), f"layer {li}: fused vs separate call"
+        same_as = pa.PARSE_SCHED_TILES if schedule == pa.PARSE_SCHED_TILES else pa.PARSE_SCHED_PLANNED
+        for li in range(len(shapes)):
+            yn = ys[li].float().cpu().numpy().astype(np.float64)
+            for p in range(P):
+                assert_close(yn[off[p]:off[p + 1]], refs[li][off[p]:off[p + 1]], TOL_BF16, f"schedule {schedule} layer {li} prompt {p}")
+            single = forward_guarded(pa.PARSE_PREFILL, layers[li], patterns[li].with_schedule(same_as), Xd, offd, pid)
+            torch.cuda.synchronize()
+            assert torch.equal(single.view(torch.int16), ys[li].view(torch.int16)), f"schedule {schedule} layer {li}: fused vs separate call"
 
 
 def test_shared_head_route_cache_pack_and_prefill():
@@ -1148,12 +1153,14 @@ def test_multi_calls_with_four_layers_and_a_shared_head():
             Vp, Up = pa.pack_patterns(dl, sd, k, k, None, None, P)
             pats.append(pa.Patterns(k, P, Vp, Up))
         layers.append(dl)
-    ys = prefill_multi_guarded(layers, pats, Xd, offd, i32(np.arange(P, dtype=np.int32)))
-    torch.cuda.synchronize()
-    for li in range(4):
-        yn = ys[li].float().cpu().numpy().astype(np.float64)
-        for p in range(P):
-            assert_close(yn[off[p]:off[p + 1]], refs[li][off[p]:off[p + 1]], TOL_BF16, f"prefill layer {li} prompt {p}")
+    for schedule in (pa.PARSE_SCHED_AUTO, pa.PARSE_SCHED_TILES):       # planned (the default here) and two-launch
+        ys = prefill_multi_guarded(layers, [pt.with_schedule(schedule) for pt in pats], Xd, offd, i32(np.arange(P, dtype=np.int32)))
+        torch.cuda.synchronize()
+        for li in range(4):
+            yn = ys[li].float().cpu().numpy().astype(np.float64)
+            for p in range(P):
+                assert_close(yn[off[p]:off[p + 1]], refs[li][off[p]:off[p + 1]], TOL_BF16,
+                             f"prefill schedule {schedule} layer {li} prompt {p}")
 
 
 def test_rank_router_at_its_limits():
