@@ -406,13 +406,20 @@ int parse_lowrank_decode_static(const parse_layer *layer, const parse_patterns *
 
 /* Horizontal fusion for prefill (Sec. 4.4, Eq. 11-12): n_layers (1..4) bf16 PARSE_MFMA16 layers that read the
  * SAME token rows X (equal n) in two launches for all of them -- one stacked first product over the selected
- * ranks of every layer, one batched second product.  The result equals n_layers separate PARSE_PREFILL calls
- * in their two-launch schedule, bit for bit.
- *   layers, patterns  host arrays [n_layers]; patterns[l] holds layer l's packed factors (Vt_S, Ut_S, k)
+ * ranks of every layer, one batched second product.  patterns[0].schedule chooses for the call:
+ *   PARSE_SCHED_AUTO / PARSE_SCHED_PLANNED  the planned tile kernels over one prefill plan built inside the call (one
+ *     more small launch; every layer needs the same n_patterns, n % 64 == 0, k*gs % 32 == 0, m % 32 == 0); AUTO falls
+ *     back to the two-launch schedule when the shapes or the workspace do not allow it;
+ *   PARSE_SCHED_TILES  the two-launch tile kernels on prompt-order tiles (n and k*gs multiples of 128);
+ *   PARSE_SCHED_FUSED  PARSE_EINVAL (the single-launch kernel takes one layer).
+ * The result equals n_layers separate PARSE_PREFILL calls under the same schedule, bit for bit.
+ *   layers, patterns  host arrays [n_layers]; patterns[l] holds layer l's packed factors (Vt_S, Ut_S, k; shared head
+ *                     allowed)
  *   X                 device [rows][n] bf16; tok_offsets device int32 [P+1]; pattern_id device int32 [P]
  *   Y                 host array [n_layers] of device pointers, Y[l] = [rows][layers[l].m] bf16
- *   workspace         device, >= parse_lowrank_prefill_multi_workspace_bytes(...) (the intermediates), required
- * PARSE_ESHAPE when n or k*gs of a layer is not a multiple of 128 (use separate calls then). */
+ *   workspace         device, >= parse_lowrank_prefill_multi_workspace_bytes(...) (the intermediates and, for the
+ *                     planned schedule, the plan: sized for any number of prompts up to 2048), required
+ * PARSE_ESHAPE when no schedule takes the shapes (use separate calls then). */
 size_t parse_lowrank_prefill_multi_workspace_bytes(const parse_layer *layers, const parse_patterns *patterns,
                                                    int32_t n_layers, int32_t rows);
 int parse_lowrank_prefill_multi(const parse_layer *layers, const parse_patterns *patterns, int32_t n_layers,
