@@ -47,7 +47,7 @@ def parse_args():
                          "head, rank-granular mode) so that a profile of the run holds the timed kernels alone")
     ap.add_argument("--stack", action="store_true",
                     help="also time the full 32-layer x 7-projection stack (prefill 1 x 2048 tokens, then decode steps)")
-    ap.add_argument("--stack-decode-steps", type=int, default=64)
+    ap.add_argument("--stack-decode-steps", type=int, default=256, help="decode steps timed after the prefill (the workload names 256)")
     ap.add_argument("--stress", action="store_true",
                     help="also run the pattern-cache / grouped-execution stress (256 ragged prompts, MLP-shaped layers)")
     ap.add_argument("--only-stress", action="store_true")
