@@ -209,3 +209,79 @@ def test_router_grad_rejects_bad_arguments():
     assert call(layer=_layer(n=256, m=128, R=64, G=2, dtype=1, layout=0)) == -7
     assert call(X=ODD) == -3 and call(ws=None) == -5 and call(wsb=64) == -5
     assert lib.parse_router_grad_workspace_bytes(C.byref(L), 16, 2) >= 16 * 128 * 2 + 2 * 16 * 64 * 2
+
+
+def test_plan_entry_points_reject_bad_arguments_and_size_their_buffers():
+    """Prefill plan, decode plan and the calls that run over them: sizes the host works out, and every rejection that
+    happens before a launch."""
+    lib = pa.lib()
+    lib.parse_prefill_plan_bytes.restype = C.c_size_t
+    lib.parse_decode_plan_bytes.restype = C.c_size_t
+    # prefill plan: 16 header words, the tile patterns (rounded up to 16), 256 row-map words per tile;
+    # capacity = ceil(rows / 256) + min(P, n_patterns + 1)
+    def plan_bytes(rows, P, npat):
+        cap = (rows + 255) // 256 + min(P, npat + 1)
+        words = 16 + (cap + 15) // 16 * 16 + cap * 256
+        return (words * 4 + 255) // 256 * 256
+    for rows, P, npat in ((4096, 8, 32), (300, 300, 4), (1, 1, 1), (272660, 256, 32)):
+        assert lib.parse_prefill_plan_bytes(rows, P, npat) == plan_bytes(rows, P, npat)
+    assert lib.parse_prefill_plan_bytes(0, 1, 1) == 0
+
+    def plan(off=FAKE, pid=FAKE, P=8, rows=4096, npat=32, buf=FAKE, nbytes=1 << 24):
+        return lib.parse_prefill_plan(off, pid, P, rows, npat, buf, nbytes, None)
+    assert plan(off=None) == -1 and plan(pid=None) == -1 and plan(buf=None) == -1 and plan(P=0) == -1
+    assert plan(P=5000, rows=4096) == -2                       # more prompts than rows
+    assert plan(P=3000, rows=4096) == -2 and plan(npat=3000) == -2   # the plan kernel's table sizes
+    assert plan(buf=ODD) == -3 and plan(nbytes=1024) == -5
+
+    # planned prefill of one layer
+    L = _layer(n=256, m=256, R=256, G=4, dtype=1, layout=1)           # gs = 64
+    pt = B._Patterns(FAKE.value, FAKE.value, None, 2, 4, 2)           # k = 2 -> r_S = 128
+    def planned(layer=L, pat=pt, X=FAKE, rows=512, off=FAKE, pid=FAKE, P=2, pl=FAKE, Y=FAKE, ws=FAKE, wsb=1 << 24):
+        return lib.parse_lowrank_prefill_planned(C.byref(layer), C.byref(pat), X, rows, off, pid, P, pl, Y, ws, wsb, None)
+    assert planned(pl=None) == -1 and planned(off=None) == -1 and planned(Y=None) == -1
+    assert planned(layer=_layer(n=256, m=256, R=256, G=4, dtype=1, layout=0)) == -7
+    assert planned(layer=_layer(n=256, m=256, R=256, G=4, dtype=0, layout=0)) == -7
+    assert planned(P=600) == -2 and planned(layer=_layer(n=80, m=256, R=64, G=2, dtype=1, layout=1)) == -2   # n % 64
+    head = B._Patterns(FAKE.value, FAKE.value, None, 2, 4, 2, FAKE.value, FAKE.value, 2, 0)
+    assert planned(pat=head) == -2                                    # the shared head must leave groups to the patterns
+    assert planned(pat=B._Patterns(FAKE.value, FAKE.value, None, 2, 4, 2, None, None, 1, 0)) == -1   # head without its store
+    assert planned(X=ODD) == -3 and planned(pl=ODD) == -3
+    assert planned(ws=None) == -5 and planned(wsb=4096) == -5
+    lib.parse_lowrank_prefill_planned_workspace_bytes.restype = C.c_size_t
+    cap = 2 + 2                                                        # 512 rows, two prompts, four patterns
+    assert lib.parse_lowrank_prefill_planned_workspace_bytes(C.byref(L), 512, 2, 2, 4) == cap * 256 * 128 * 2
+
+    # decode plan: 704 words per layer (count, 64 group ids, 64 masks, padding to 192, 512 arrival counters)
+    assert lib.parse_decode_plan_bytes(1) == 704 * 4 and lib.parse_decode_plan_bytes(3) == (3 * 704 * 4 + 255) // 256 * 256
+    assert lib.parse_decode_plan_bytes(0) == 0 and lib.parse_decode_plan_bytes(5) == 0
+    D = _layer(n=256, m=256, R=256, G=4, dtype=1, layout=1)
+    dp = B._Patterns(None, None, FAKE.value, 2, 4, 2)
+    def dplan(layers=(D,), pats=(dp,), nl=1, pid=FAKE, rows=8, buf=FAKE, nbytes=1 << 16):
+        larr = (B._Layer * len(layers))(*layers)
+        parr = (B._Patterns * len(pats))(*pats)
+        return lib.parse_decode_plan(larr, parr, nl, pid, rows, buf, nbytes, None)
+    assert dplan(pid=None) == -1 and dplan(buf=None) == -1 and dplan(rows=0) == -1 and dplan(nl=0) == -1
+    assert dplan(rows=33) == -2                                        # a plan covers one panel of 32 sequences
+    assert dplan(layers=(D,) * 5, pats=(dp,) * 5, nl=5) == -2
+    assert dplan(layers=(_layer(n=256, m=256, R=256, G=4, dtype=1, layout=0),)) == -7
+    assert dplan(pats=(B._Patterns(None, None, None, 2, 4, 2),)) == -1  # decode needs the subsets
+    assert dplan(buf=ODD) == -3 and dplan(nbytes=512) == -5
+
+    def dstep(layers=(D,), nl=1, X=FAKE, rows=8, pl=FAKE, ys=None, ws=FAKE, wsb=1 << 24):
+        larr = (B._Layer * len(layers))(*layers)
+        yarr = (C.c_void_p * len(layers))(*(ys if ys is not None else [FAKE.value] * len(layers)))
+        return lib.parse_lowrank_decode_planned(larr, nl, X, rows, pl, yarr, ws, wsb, None)
+    assert dstep(X=None) == -1 and dstep(pl=None) == -1 and dstep(rows=0) == -1 and dstep(ys=[None]) == -1
+    assert dstep(rows=33) == -2 and dstep(X=ODD) == -3 and dstep(pl=ODD) == -3
+    assert dstep(ws=None) == -5 and dstep(wsb=64) == -5
+    # workspace of a decode call: z as operands (64 bytes per stored rank); partial sums (128 bytes per stored rank and
+    # slice) only when the reduction over n is split -- not here (n = 256, few rank blocks -> up to 2 slices of >= 8 steps)
+    lib.parse_lowrank_decode_planned_workspace_bytes.restype = C.c_size_t
+    larr = (B._Layer * 1)(D)
+    need = lib.parse_lowrank_decode_planned_workspace_bytes(larr, 1)
+    assert need in (256 * 64, 256 * 64 + 256 * 128 * 2)
+    big = (B._Layer * 1)(_layer(n=11008, m=4096, R=2560, G=20, dtype=1, layout=1))
+    assert lib.parse_lowrank_decode_planned_workspace_bytes(big, 1) == 2560 * 64 + 2560 * 128 * 3   # three slices of 229-230 steps
+    lib.parse_lowrank_decode_static_capacity.restype = C.c_size_t
+    assert lib.parse_lowrank_decode_static_capacity() == 4 << 20
