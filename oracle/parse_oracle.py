@@ -22,6 +22,8 @@ What each function follows:
                           tile serves one pattern.
   decode                  Sec. 4.3 "Rank Reuse for Decoding": the prefill subset is fixed
                           for every later step; same product with one row per sequence.
+  decode_groups           what a decode step over a batch needs from the fixed subsets:
+                          which groups some sequence selected, and which sequences hold each.
   soft_mask / router_grad Sec. 4.2 Eq. 6-9: reconstruction loss against the dense output,
                           hard top-k mask forward, K-normalised sigmoid mask backward
                           (straight-through), gradient with respect to the router matrix.
@@ -299,6 +301,21 @@ def plan_rows(tok_offsets, pattern_id, n_patterns: int, tile: int = 256):
 
 
 # ------------------------------------------------------------------ error metric
+def decode_groups(subsets, seq_pattern, G: int):
+    """For a decode batch whose sequence b keeps subset subsets[seq_pattern[b]] (Sec. 4.3, rank reuse): the ascending
+    list of groups that at least one sequence selected, and for every group the set of sequences that hold it as a
+    bit mask (bit b = sequence b).  A sequence whose pattern id is out of range selects nothing."""
+    subsets = np.asarray(subsets)
+    masks = [0] * G
+    for b, p in enumerate(np.asarray(seq_pattern).tolist()):
+        if 0 <= p < len(subsets):
+            for g in subsets[p].tolist():
+                if 0 <= g < G:
+                    masks[g] |= 1 << b
+    used = [g for g in range(G) if masks[g]]
+    return used, masks
+
+
 def rel_errors(Y, Yref):
     """(Frobenius relative error, max-abs error over max-abs reference)."""
     Y = np.asarray(Y, F64); Yref = np.asarray(Yref, F64)

@@ -598,12 +598,9 @@ def test_decode_plan_contents_and_planned_step():
     for li, (lay, sub, G, k) in enumerate(subs_h):
         w = words[li * PLAN_WORDS:(li + 1) * PLAN_WORDS]
         assert np.all(w[192:] == 0), "arrival counters start at zero"
+        used, mlist = po.decode_groups(sub, seq_pat, G)
         masks = np.zeros(64, np.uint32)
-        for b in range(B):
-            if 0 <= seq_pat[b] < npat:
-                for g in sub[seq_pat[b]]:
-                    masks[g] |= np.uint32(1 << b)
-        used = [g for g in range(G) if masks[g]]
+        masks[:G] = np.array(mlist, dtype=np.uint64).astype(np.uint32)
         assert int(w[0]) == len(used) and w[1:1 + len(used)].tolist() == used and np.all(w[1 + len(used):65] == -1)
         assert np.array_equal(w[65:129].view(np.uint32), masks)
     # planned step between guards

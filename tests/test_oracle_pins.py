@@ -552,3 +552,30 @@ def test_plan_rows_hand_case_and_properties():
         n_real = int((run >= 0).sum())
         assert np.all(run[:n_real] >= 0) and np.all(run[n_real:] == -1) and len(run) - n_real < 16
         assert np.all(np.diff(run[:n_real]) > 0)          # arrival order = ascending rows within a pattern
+
+
+def test_decode_groups_hand_case_and_consistency_with_decode_step():
+    # hand case: 3 patterns over 6 groups, 5 sequences, one with an invalid pattern id
+    subsets = np.array([[0, 2], [2, 5], [1, 2]], np.int32)
+    used, masks = po.decode_groups(subsets, [0, 1, 1, 7, 2], 6)
+    assert used == [0, 1, 2, 5]
+    assert masks == [0b00001, 0b10000, 0b10111, 0, 0, 0b00110]
+    # a group outside the used list changes no sequence's decode output; a group inside changes exactly the sequences
+    # of its mask (left-out group contributes exactly zero: Sec. 4.1)
+    rng = np.random.default_rng(5)
+    n, m, R, G = 24, 20, 12, 6
+    gs = R // G
+    U0, _ = np.linalg.qr(rng.standard_normal((m, R)))
+    V = np.linalg.qr(rng.standard_normal((n, R)))[0].T
+    sigma = (np.arange(R) + 1.0) ** -0.5
+    seq_pat = np.array([0, 1, 1, 2])
+    x = rng.standard_normal((4, n))
+    y = po.decode_step(U0, sigma, V, gs, x, subsets[seq_pat])
+    used, masks = po.decode_groups(subsets, seq_pat, G)
+    for g in range(G):
+        s2 = sigma.copy()
+        s2[g * gs:(g + 1) * gs] *= 3.0                       # disturb one group
+        y2 = po.decode_step(U0, s2, V, gs, x, subsets[seq_pat])
+        changed = sum(1 << b for b in range(4) if not np.allclose(y[b], y2[b], rtol=0, atol=1e-12))
+        assert changed == masks[g], g
+        assert (g in used) == (masks[g] != 0)
