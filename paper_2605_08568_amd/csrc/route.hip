@@ -1,9 +1,10 @@
 // a1 + a2: prompt pooling and the linear router with top-k (Sec. 4.1, Eq. 5).
 //
 // Two launches, both deterministic:
-//   pool_partial  grid (column blocks of 64 lanes x 16 bytes, Q token slices, P prompts): the four wavefronts
-//                 of a workgroup take a quarter of the slice's rows each for the same columns and add up
-//                 through LDS in wavefront order; fp32 partial sums per slice, rows streamed once.
+//   pool_partial  grid (column blocks of 64 lanes x 16 bytes, Q row slices, P prompts): the rows of a prompt are
+//                 dealt round robin to the wavefronts of its Q workgroups, 16 rows in flight per wavefront; the
+//                 four wavefronts of a workgroup add up through LDS in wavefront order; fp32 partial sums per
+//                 slice, rows streamed once.
 //   route_finish  one block per prompt: adds the Q partials in slice order, divides by the length,
 //                 scores the G groups (one wavefront per group, butterfly reduction) and selects the
 //                 top k with a rank count inside one wavefront.
@@ -21,50 +22,56 @@ __global__ __launch_bounds__(kPoolThreads) void pool_partial(const void *__restr
                                                              const int32_t *__restrict__ tok_offsets,
                                                              int Q, float *__restrict__ partial) {
   constexpr int PER = BF16 ? 8 : 4;  // columns per lane = 16 bytes
-  __shared__ float red[kPoolWaves - 1][64][PER];
+  constexpr int U = 16;              // rows a wavefront has in flight
+  __shared__ float red[kPoolWaves - 1][PER][64];
   const int p = blockIdx.z, q = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int c0 = (blockIdx.x * 64 + lane) * PER;
   const bool in = c0 < d;
   const int a = clampi(tok_offsets[p], 0, rows);
   const int b = clampi(tok_offsets[p + 1], a, rows);
-  const long long len = b - a;
-  const int s0 = a + (int)((len * q) / Q), s1 = a + (int)((len * (q + 1)) / Q);
-  const long long sl = s1 - s0;
-  const int r0 = s0 + (int)((sl * wave) / kPoolWaves), r1 = s0 + (int)((sl * (wave + 1)) / kPoolWaves);
+  // the rows of a prompt are dealt round robin to the Q * kPoolWaves wavefronts that share a column block: at any
+  // moment they read a window of consecutive rows
+  const int r0 = a + q * kPoolWaves + wave, r1 = b, rstep = Q * kPoolWaves;
   float acc[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) acc[i] = 0.f;
-  if (in) {
-    if constexpr (BF16) {
-      const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
-#pragma unroll 8
-      for (int r = r0; r < r1; ++r) {
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)r * d + c0);
+  // U rows at a time: all of them are requested before the first is added (left to itself the compiler waits for every
+  // row before it asks for the next); rows past the end re-read the wavefront's last row and are not added; the adds
+  // run in row order.  Lanes past the last column re-read the last piece of the row; their sums are not stored.
+  const char *xb = reinterpret_cast<const char *>(X) + (size_t)min(c0, d - PER) * (BF16 ? 2 : 4);
+  const size_t row_bytes = (size_t)d * (BF16 ? 2 : 4);
+  for (int r = r0; r < r1; r += rstep * U) {
+    const int rlast = r + ((r1 - 1 - r) / rstep) * rstep;
+    u32x4 v[U];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc[2 * i] += __uint_as_float(v[i] << 16);
-          acc[2 * i + 1] += __uint_as_float(v[i] & 0xFFFF0000u);
+    for (int u = 0; u < U; ++u) v[u] = *reinterpret_cast<const u32x4 *>(xb + (size_t)min(r + u * rstep, rlast) * row_bytes);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (r + u * rstep < r1) {       // uniform
+        if constexpr (BF16) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += __uint_as_float(v[u][i] << 16);
+            acc[2 * i + 1] += __uint_as_float(v[u][i] & 0xFFFF0000u);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[i] += __uint_as_float(v[u][i]);
         }
-      }
-    } else {
-      const float *x = reinterpret_cast<const float *>(X);
-#pragma unroll 8
-      for (int r = r0; r < r1; ++r) {
-        const float4 v = *reinterpret_cast<const float4 *>(x + (size_t)r * d + c0);
-        acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
       }
     }
   }
   if (wave > 0) {
 #pragma unroll
-    for (int i = 0; i < PER; ++i) red[wave - 1][lane][i] = acc[i];
+    for (int i = 0; i < PER; ++i) red[wave - 1][i][lane] = acc[i];
   }
   __syncthreads();
   if (wave == 0 && in) {
     for (int w = 0; w < kPoolWaves - 1; ++w)
 #pragma unroll
-      for (int i = 0; i < PER; ++i) acc[i] += red[w][lane][i];
+      for (int i = 0; i < PER; ++i) acc[i] += red[w][i][lane];
     float *dst = partial + ((size_t)p * Q + q) * d + c0;
 #pragma unroll
     for (int i = 0; i < PER; i += 4) *reinterpret_cast<float4 *>(dst + i) = float4{acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
@@ -106,8 +113,8 @@ __global__ __launch_bounds__(kFinishThreads) void route_finish(const float *__re
   if (threadIdx.x < 64) wave_topk_ascending(s, G, k, subset_out + (size_t)p * subset_stride, n_shared);
 }
 
-// Slices per prompt: enough workgroups to keep every compute unit streaming (about two per unit), a slice of
-// at least 32 rows (8 per wavefront), at most 32 slices.
+// Slices per prompt: about two workgroups per compute unit, a slice of at least 32 rows (8 per wavefront), at most
+// 32 slices.
 static int pool_slices(int rows, int P, int d, bool bf16) {
   const int per_block = 64 * (bf16 ? 8 : 4);
   const int colblocks = (d + per_block - 1) / per_block;
