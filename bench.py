@@ -107,7 +107,7 @@ def bench_prefill(args, torch, pa, si):
     pt = pa.Patterns(k, n_slots, Vs, Us)
     plan = torch.empty(pa.prefill_plan_bytes(rows, P, n_slots), dtype=torch.uint8, device=dev)
     ws_plan = torch.empty(max(pa.lowrank_prefill_planned_workspace_bytes(dl, rows, P, k, n_slots), 256), dtype=torch.uint8, device=dev)
-    names = ["route", "cache", "bucket", "plan", "pack", "forward"]
+    names = ["route", "cache", "bucket+plan", "pack", "forward"]
 
     def step(ev=None):
         def mark(i):
@@ -118,14 +118,14 @@ def bench_prefill(args, torch, pa, si):
         mark(1)
         cache.lookup_or_route(emb, 0.9, Wr, entry, hit, sim, sub)
         mark(2)
-        pa.bucket_patterns(sub, k, k, bucket_out)          # buckets of equal subsets (execution grouping)
+        # buckets of equal subsets (execution grouping) and the plan (token rows grouped by pattern = cache entry; it
+        # serves every layer) come out of one launch
+        pa.bucket_and_plan(sub, k, k, off, entry, rows, n_slots, bucket_out, plan)
         mark(3)
-        pa.prefill_plan(off, entry, rows, n_slots, plan)    # token rows grouped by pattern (= cache entry); serves every layer
-        mark(4)
         pa.pack_new_entries(dl, sub, k, k, entry, hit, Vs, Us)   # aggregation happens once per new cache entry
-        mark(5)
+        mark(4)
         pa.lowrank_prefill_planned(dl, pt, X, off, entry, plan, Y, ws_plan)   # two launches over the plan
-        mark(6)
+        mark(5)
 
     # cold step: empty cache, every prompt misses, is routed, appended and aggregated
     step(); torch.cuda.synchronize()
@@ -137,7 +137,7 @@ def bench_prefill(args, torch, pa, si):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -244,8 +244,7 @@ def bench_prefill(args, torch, pa, si):
                         s_ctl.wait_event(b["done"])            # batch i-2 has finished reading this buffer set
                     pa.route(X, off, Wr[0], k, subset_out=b["sub_route"], emb_out=b["emb"], workspace=ws_route2)
                     cache.lookup_or_route(b["emb"], 0.9, Wr, b["entry"], b["hit"], b["sim"], b["sub"])
-                    pa.bucket_patterns(b["sub"], k, k, b["bucket"])
-                    pa.prefill_plan(off, b["entry"], rows, n_slots, b["plan"])
+                    pa.bucket_and_plan(b["sub"], k, k, off, b["entry"], rows, n_slots, b["bucket"], b["plan"])
                     pa.pack_new_entries(dl, b["sub"], k, k, b["entry"], b["hit"], Vs, Us)
                     b["ready"].record(s_ctl)
                 with torch.cuda.stream(s_fwd):
@@ -823,7 +822,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config1: q_proj-shaped prefill, bf16, {lay.m}x{lay.n}, R={lay.R} in {lay.G} groups of "
                                f"{lay.gs}, top-{w.k}, {w.P} prompts x {args.tokens} tokens, one routed subset per prompt",
-                   "step": "pool+route, cache probe (route-on-miss), bucket, plan, pack of new cache entries, forward; "
+                   "step": "pool+route, cache probe (route-on-miss), buckets + plan (one launch), pack of new cache entries, forward; "
                            "warm cache in the timed steps, cold_step_ms = the same step with an empty cache",
                    "launch_mode": pre["launch_mode"] + (": the K timed steps are K/2 replays of a HIP graph of two "
                                                         "consecutive steps, checked bitwise against the eager steps; "

@@ -285,6 +285,16 @@ int parse_lowrank_forward(int32_t mode, const parse_layer *layer, const parse_pa
 size_t parse_prefill_plan_bytes(int32_t rows, int32_t P, int32_t n_patterns);
 int parse_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, int32_t P, int32_t rows,
                        int32_t n_patterns, void *plan, size_t plan_bytes, parse_stream stream);
+/* parse_bucket_patterns and parse_prefill_plan of the same batch in ONE launch (Sec. 4.3: both group the prompts of a
+ * batch by pattern, from the same probe results, and neither needs the other's output).  The first nine arguments are
+ * parse_bucket_patterns' (pattern_id_out .. rep are its outputs), the rest parse_prefill_plan's (plan_pattern_id is the
+ * id the plan groups by, e.g. the cache entry of each prompt); every output equals the separate calls', and so do the
+ * limits and the errors.  P <= 256 takes one launch, a larger batch the two launches of the separate calls.  Only
+ * enqueues. */
+int parse_bucket_and_plan(const int32_t *subset, int32_t P, int32_t k, int32_t subset_stride, int32_t *pattern_id_out,
+                          int32_t *perm, int32_t *bucket_off, int32_t *n_patterns_out, int32_t *rep,
+                          const int32_t *tok_offsets, const int32_t *plan_pattern_id, int32_t rows, int32_t n_patterns,
+                          void *plan, size_t plan_bytes, parse_stream stream);
 /* The bf16 prefill product (Eq. 10) of one layer over a ready plan: two launches, no prompt-dependent work on the
  * host.  layer bf16 PARSE_MFMA16 with n % 64 == 0; patterns as for PARSE_PREFILL (a shared head must be whole 32-rank
  * blocks); the plan must

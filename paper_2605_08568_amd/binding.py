@@ -96,6 +96,8 @@ def lib():
     L.parse_lowrank_workspace_bytes.argtypes = [i32, C.POINTER(_Layer), i32, i32, i32, i32]
     L.parse_prefill_plan_bytes.restype = sz; L.parse_prefill_plan_bytes.argtypes = [i32, i32, i32]
     L.parse_prefill_plan.restype = C.c_int; L.parse_prefill_plan.argtypes = [vp, vp, i32, i32, i32, vp, sz, vp]
+    L.parse_bucket_and_plan.restype = C.c_int
+    L.parse_bucket_and_plan.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
     L.parse_lowrank_prefill_planned_workspace_bytes.restype = sz
     L.parse_lowrank_prefill_planned_workspace_bytes.argtypes = [C.POINTER(_Layer), i32, i32, i32, i32]
     L.parse_lowrank_prefill_planned.restype = C.c_int
@@ -389,6 +391,24 @@ def prefill_plan(tok_offsets, pattern_id, rows: int, n_patterns: int, plan=None)
     _check(lib().parse_prefill_plan(_ptr(tok_offsets), _ptr(pattern_id), P, rows, n_patterns, _ptr(plan), plan.numel(),
                                     _stream()), "parse_prefill_plan")
     return plan
+
+
+def bucket_and_plan(subset, k, subset_stride, tok_offsets, plan_pattern_id, rows: int, n_patterns: int, out=None, plan=None):
+    """parse_bucket_and_plan -> (bucket outputs as bucket_patterns, plan as prefill_plan)."""
+    P = plan_pattern_id.numel()
+    stride = (subset.numel() // P) if subset_stride is None else subset_stride
+    dev = subset.device
+    if out is None:
+        out = (torch.empty(P, dtype=torch.int32, device=dev), torch.empty(P, dtype=torch.int32, device=dev),
+               torch.empty(P + 1, dtype=torch.int32, device=dev), torch.empty(1, dtype=torch.int32, device=dev),
+               torch.empty(P, dtype=torch.int32, device=dev))
+    if plan is None:
+        plan = torch.empty(prefill_plan_bytes(rows, P, n_patterns), dtype=torch.uint8, device=dev)
+    pid, perm, off, npat, rep = out
+    _check(lib().parse_bucket_and_plan(_ptr(subset), P, k, stride, _ptr(pid), _ptr(perm), _ptr(off), _ptr(npat), _ptr(rep),
+                                       _ptr(tok_offsets), _ptr(plan_pattern_id), rows, n_patterns, _ptr(plan), plan.numel(),
+                                       _stream()), "parse_bucket_and_plan")
+    return out, plan
 
 
 def lowrank_prefill_planned_workspace_bytes(layer: Layer, rows: int, P: int, k: int, n_patterns: int) -> int:

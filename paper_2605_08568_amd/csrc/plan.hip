@@ -10,6 +10,7 @@
 //   [0] number of 256-row virtual tiles  [1] virtual rows (= 256 * [0])  [2] 256  [3] capacity in tiles  [4..15] 0
 //   [16 .. 16+cap)            pattern of each virtual tile (-1: prompts whose pattern id is out of range -> zero rows)
 //   [16+cap16 .. +256*cap)    rowmap: actual token row of each virtual row, -1 for padding     (cap16 = cap rounded up to 16)
+#include "bucket.hpp"
 #include "common.hpp"
 
 namespace parse {
@@ -28,9 +29,10 @@ static inline size_t plan_words(int cap) { return (size_t)PLAN_HDR + (size_t)((c
 
 // Every workgroup works out the (small) per-pattern and per-prompt tables in its own LDS -- integer work, the same in
 // every workgroup -- and then fills its share of the row map.
-__global__ __launch_bounds__(PLAN_THREADS) void plan_build(const int32_t *__restrict__ tok_offsets,
-                                                           const int32_t *__restrict__ pattern_id, int P, int rows,
-                                                           int NP, int cap, int32_t *__restrict__ plan) {
+// (block, nblocks) = this workgroup's place among the workgroups that build the plan.
+__device__ __forceinline__ void plan_body(const int32_t *__restrict__ tok_offsets, const int32_t *__restrict__ pattern_id,
+                                          int P, int rows, int NP, int cap, int32_t *__restrict__ plan, int block,
+                                          int nblocks) {
   __shared__ int32_t cnt[PLAN_MAX_PATTERNS + 1];     // rows of each pattern (index NP: invalid ids); later: running fill
   __shared__ int32_t base[PLAN_MAX_PATTERNS + 2];    // first virtual row of each pattern
   __shared__ int32_t vstart[PLAN_MAX_P];             // first virtual row of each prompt
@@ -96,13 +98,13 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_build(const int32_t *__rest
   }
   __syncthreads();
   const int total = min(base[NP + 1], max_v);
-  const int gid = blockIdx.x * PLAN_THREADS + tid, gstride = gridDim.x * PLAN_THREADS;
+  const int gid = block * PLAN_THREADS + tid, gstride = nblocks * PLAN_THREADS;
   if (gid == 0) {
     plan[0] = total / PLAN_VT; plan[1] = total; plan[2] = PLAN_VT; plan[3] = cap;
     for (int i = 4; i < PLAN_HDR; ++i) plan[i] = 0;
   }
   // pattern of each tile, and the padding rows at the end of each pattern
-  for (int i = blockIdx.x; i <= NP; i += gridDim.x) {
+  for (int i = block; i <= NP; i += nblocks) {
     const int b0 = base[i], b1 = base[i + 1];
     if (b1 == b0) continue;
     for (int t = b0 / PLAN_VT + tid; t < b1 / PLAN_VT; t += PLAN_THREADS)
@@ -125,17 +127,43 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_build(const int32_t *__rest
   }
 }
 
+__global__ __launch_bounds__(PLAN_THREADS) void plan_build(const int32_t *__restrict__ tok_offsets,
+                                                           const int32_t *__restrict__ pattern_id, int P, int rows,
+                                                           int NP, int cap, int32_t *__restrict__ plan) {
+  plan_body(tok_offsets, pattern_id, P, rows, NP, cap, plan, blockIdx.x, gridDim.x);
+}
+
+// The plan and the buckets of a batch in one launch (they depend on the same probe results and not on each other): the
+// last workgroup buckets the prompts, the others build the plan.  P <= PLAN_THREADS (one lane per prompt in the bucketing).
+struct BucketArgs {
+  const int32_t *subset;
+  int k, stride;
+  int32_t *pattern_id, *perm, *bucket_off, *n_patterns, *rep;
+};
+__global__ __launch_bounds__(PLAN_THREADS) void bucket_and_plan(BucketArgs b, const int32_t *__restrict__ tok_offsets,
+                                                                const int32_t *__restrict__ pattern_id, int P, int rows,
+                                                                int NP, int cap, int32_t *__restrict__ plan) {
+  if (blockIdx.x + 1 == gridDim.x)     // uniform
+    bucket_body(b.subset, P, b.k, b.stride, b.pattern_id, b.perm, b.bucket_off, b.n_patterns, b.rep);
+  else
+    plan_body(tok_offsets, pattern_id, P, rows, NP, cap, plan, blockIdx.x, gridDim.x - 1);
+}
+
 size_t prefill_plan_bytes(int rows, int P, int n_patterns) {
   return round_up(plan_words(plan_capacity_tiles(rows, P, n_patterns)) * sizeof(int32_t), 256);
 }
 int prefill_plan_capacity(int rows, int P, int n_patterns) { return plan_capacity_tiles(rows, P, n_patterns); }
 bool prefill_plan_supported(int P, int n_patterns) { return P <= PLAN_MAX_P && n_patterns <= PLAN_MAX_PATTERNS; }
 
+static int plan_grid(int rows) {
+  const int grid = (rows + 4 * PLAN_THREADS - 1) / (4 * PLAN_THREADS);   // about four rows per thread
+  return grid < 1 ? 1 : (grid > 128 ? 128 : grid);
+}
+
 int build_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, int P, int rows, int n_patterns,
                        int32_t *plan, hipStream_t s) {
   const int cap = plan_capacity_tiles(rows, P, n_patterns);
-  int grid = (rows + 4 * PLAN_THREADS - 1) / (4 * PLAN_THREADS);   // about four rows per thread
-  grid = grid < 1 ? 1 : (grid > 128 ? 128 : grid);
+  const int grid = plan_grid(rows);
   hipLaunchKernelGGL(plan_build, dim3(grid), dim3(PLAN_THREADS), 0, s, tok_offsets, pattern_id, P, rows, n_patterns, cap, plan);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
@@ -160,6 +188,30 @@ int parse_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, in
   if (!aligned16(plan)) return PARSE_EALIGN;
   if (plan_bytes < prefill_plan_bytes(rows, P, n_patterns)) return PARSE_EWORKSPACE;
   return build_prefill_plan(tok_offsets, pattern_id, P, rows, n_patterns, (int32_t *)plan, (hipStream_t)stream);
+}
+
+int parse_bucket_and_plan(const int32_t *subset, int32_t P, int32_t k, int32_t subset_stride, int32_t *pattern_id_out,
+                          int32_t *perm, int32_t *bucket_off, int32_t *n_patterns_out, int32_t *rep,
+                          const int32_t *tok_offsets, const int32_t *plan_pattern_id, int32_t rows, int32_t n_patterns,
+                          void *plan, size_t plan_bytes, parse_stream stream) {
+  if (!subset || !pattern_id_out || !perm || !bucket_off || !n_patterns_out || !rep) return PARSE_EINVAL;
+  if (!tok_offsets || !plan_pattern_id || !plan) return PARSE_EINVAL;
+  if (P <= 0 || k <= 0 || rows <= 0 || n_patterns <= 0) return PARSE_EINVAL;
+  if (P > kBucketMaxP || k > kBucketMaxK || subset_stride < k) return PARSE_ESHAPE;
+  if (P > rows || !prefill_plan_supported(P, n_patterns)) return PARSE_ESHAPE;
+  if (!aligned16(plan)) return PARSE_EALIGN;
+  if (plan_bytes < prefill_plan_bytes(rows, P, n_patterns)) return PARSE_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  if (P > PLAN_THREADS) {     // more prompts than lanes of a plan workgroup: the two launches of the separate calls
+    const int st = parse_bucket_patterns(subset, P, k, subset_stride, pattern_id_out, perm, bucket_off, n_patterns_out, rep, stream);
+    if (st != PARSE_OK) return st;
+    return build_prefill_plan(tok_offsets, plan_pattern_id, P, rows, n_patterns, (int32_t *)plan, s);
+  }
+  const BucketArgs b{subset, k, subset_stride, pattern_id_out, perm, bucket_off, n_patterns_out, rep};
+  hipLaunchKernelGGL(bucket_and_plan, dim3(plan_grid(rows) + 1), dim3(PLAN_THREADS), 0, s, b, tok_offsets, plan_pattern_id, P,
+                     rows, n_patterns, plan_capacity_tiles(rows, P, n_patterns), (int32_t *)plan);
+  PARSE_LAUNCH_CHECK();
+  return PARSE_OK;
 }
 
 }  // extern "C"

@@ -234,6 +234,17 @@ def test_plan_entry_points_reject_bad_arguments_and_size_their_buffers():
     assert plan(P=3000, rows=4096) == -2 and plan(npat=3000) == -2   # the plan kernel's table sizes
     assert plan(buf=ODD) == -3 and plan(nbytes=1024) == -5
 
+    # buckets and plan in one launch: the union of the two calls' checks
+    def both(sub=FAKE, P=8, k=4, stride=4, outs=(FAKE,) * 5, off=FAKE, pid=FAKE, rows=4096, npat=32, buf=FAKE, nbytes=1 << 24):
+        return lib.parse_bucket_and_plan(sub, P, k, stride, *outs, off, pid, rows, npat, buf, nbytes, None)
+    assert both(sub=None) == -1 and both(off=None) == -1 and both(pid=None) == -1 and both(buf=None) == -1
+    for i in range(5):
+        assert both(outs=tuple(None if j == i else FAKE for j in range(5))) == -1
+    assert both(P=0) == -1 and both(k=0) == -1 and both(rows=0) == -1 and both(npat=0) == -1
+    assert both(P=1025, rows=1 << 20) == -2 and both(k=65, stride=65) == -2 and both(stride=3) == -2
+    assert both(P=5000, rows=4096) == -2 and both(npat=3000) == -2
+    assert both(buf=ODD) == -3 and both(nbytes=1024) == -5
+
     # planned prefill of one layer
     L = _layer(n=256, m=256, R=256, G=4, dtype=1, layout=1)           # gs = 64
     pt = B._Patterns(FAKE.value, FAKE.value, None, 2, 4, 2)           # k = 2 -> r_S = 128

@@ -11,7 +11,7 @@ from oracle import parse_oracle as po
 pytestmark = pytest.mark.gpu
 
 pa = pytest.importorskip("paper_2605_08568_amd")
-from helpers import (decode_multi_guarded, forward_guarded, i32, mfma16_u, mfma16_v, oracle_factors,  # noqa: E402
+from helpers import (check_guards, decode_multi_guarded, forward_guarded, guarded_bytes, i32, mfma16_u, mfma16_v, oracle_factors,  # noqa: E402
                      prefill_multi_guarded, upload_layer, upload_tokens)
 
 TOL_F32, TOL_BF16 = 1e-4, 1e-2
@@ -254,6 +254,49 @@ def test_bucket_matches_oracle(P, k, npat, stride):
     assert np.array_equal(pid.cpu().numpy(), pid_r) and np.array_equal(perm.cpu().numpy(), perm_r)
     assert np.array_equal(off.cpu().numpy()[:n_r + 1], off_r) and np.all(off.cpu().numpy()[n_r + 1:] == P)
     assert np.array_equal(rep.cpu().numpy()[:n_r], rep_r) and np.all(rep.cpu().numpy()[n_r:] == -1)
+
+
+@pytest.mark.parametrize("P,k,npat,stride,n_slots", [(8, 8, 3, 8, 32), (37, 5, 6, 9, 4), (256, 10, 16, 30, 64), (300, 4, 20, 4, 16), (1, 3, 1, 3, 1)])
+def test_bucket_and_plan_in_one_launch_equal_the_separate_calls(P, k, npat, stride, n_slots):
+    """The launch that buckets the prompts and builds the prefill plan: every output against the oracle and, bit for
+    bit, against the two separate calls (P = 300 takes the two-launch path behind the same entry point); outputs sit
+    between guard bands."""
+    say(f"bucket + plan in one call P={P} k={k} patterns<={npat} stride={stride} slots={n_slots}")
+    rng = np.random.default_rng(311 + P)
+    pats = np.stack([np.sort(rng.choice(24, size=k, replace=False)) for _ in range(npat)]).astype(np.int32)
+    which = rng.integers(0, npat, size=P)
+    full = rng.integers(0, 24, size=(P, stride)).astype(np.int32)
+    full[:, :k] = pats[which]
+    lengths = rng.integers(0, 700, size=P)
+    lengths[rng.integers(0, P)] = 257
+    off = si.offsets_from_lengths([int(v) for v in lengths])
+    rows = int(off[-1])
+    entry = rng.integers(-1, n_slots + 1, size=P).astype(np.int32)        # some ids out of range: zero rows
+    subd, offd, entd = i32(full), i32(off), i32(entry)
+    ref_b = pa.bucket_patterns(subd, k, stride)
+    ref_plan = pa.prefill_plan(offd, entd, rows, n_slots)
+    bufs = []
+    for t in list(ref_b) + [ref_plan]:
+        nbytes = t.numel() * t.element_size()
+        whole, mid = guarded_bytes(nbytes)
+        bufs.append((whole, mid, mid[:nbytes].view(t.dtype), nbytes))
+    out, plan = pa.bucket_and_plan(subd, k, stride, offd, entd, rows, n_slots, out=tuple(b[2] for b in bufs[:5]), plan=bufs[5][2])
+    torch.cuda.synchronize()
+    for whole, mid, _, nbytes in bufs:
+        check_guards(whole, "bucket + plan")
+        assert bool(torch.all(mid[nbytes:] == 0xA5)), "bucket + plan: stores beyond an output"
+    pid_r, perm_r, off_r, n_r, rep_r = po.bucket(full[:, :k])
+    assert int(out[3].item()) == n_r
+    assert np.array_equal(out[0].cpu().numpy(), pid_r) and np.array_equal(out[1].cpu().numpy(), perm_r)
+    for a, b in zip(out, ref_b):
+        assert torch.equal(a, b)
+    words, ref_words = plan.view(torch.int32).cpu().numpy(), ref_plan.view(torch.int32).cpu().numpy()
+    rowmap_ref, tpat_ref = po.plan_rows(off, entry, n_slots, 256)
+    nt, cap = int(words[0]), int(words[3])
+    rm0 = 16 + (cap + 15) // 16 * 16
+    assert nt == len(tpat_ref) and np.array_equal(words[16:16 + nt], tpat_ref)
+    assert np.array_equal(words[rm0:rm0 + nt * 256], rowmap_ref)
+    assert np.array_equal(words[:16 + nt], ref_words[:16 + nt]) and np.array_equal(words[rm0:rm0 + nt * 256], ref_words[rm0:rm0 + nt * 256])
 
 
 # ------------------------------------------------------------------ a4 pack (+ offline reorder)
