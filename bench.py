@@ -107,14 +107,14 @@ def bench_prefill(args, torch, pa, si):
     pt = pa.Patterns(k, n_slots, Vs, Us)
     plan = torch.empty(pa.prefill_plan_bytes(rows, P, n_slots), dtype=torch.uint8, device=dev)
     ws_plan = torch.empty(max(pa.lowrank_prefill_planned_workspace_bytes(dl, rows, P, k, n_slots), 256), dtype=torch.uint8, device=dev)
-    names = ["route", "cache", "bucket+plan", "pack", "forward"]
+    names = ["pool", "cache", "bucket+plan", "pack", "forward"]
 
     def step(ev=None):
         def mark(i):
             if ev is not None:
                 ev[i].record()
         mark(0)
-        pa.route(X, off, Wr[0], k, subset_out=sub_route, emb_out=emb, workspace=ws_route)
+        pa.pool(X, off, emb, ws_route)                      # the prompt embeddings; the router runs inside the probe, on a miss
         mark(1)
         cache.lookup_or_route(emb, 0.9, Wr, entry, hit, sim, sub)
         mark(2)
@@ -242,7 +242,7 @@ def bench_prefill(args, torch, pa, si):
                 with torch.cuda.stream(s_ctl):
                     if i >= 2:
                         s_ctl.wait_event(b["done"])            # batch i-2 has finished reading this buffer set
-                    pa.route(X, off, Wr[0], k, subset_out=b["sub_route"], emb_out=b["emb"], workspace=ws_route2)
+                    pa.pool(X, off, b["emb"], ws_route2)
                     cache.lookup_or_route(b["emb"], 0.9, Wr, b["entry"], b["hit"], b["sim"], b["sub"])
                     pa.bucket_and_plan(b["sub"], k, k, off, b["entry"], rows, n_slots, b["bucket"], b["plan"])
                     pa.pack_new_entries(dl, b["sub"], k, k, b["entry"], b["hit"], Vs, Us)
@@ -267,6 +267,7 @@ def bench_prefill(args, torch, pa, si):
         Utr = pa.rankmajor_left_factor(dl_rm)
         ws_t = torch.empty(int(pa.lib().parse_router_grad_workspace_bytes(C.byref(dl.c()), rows, P)), dtype=torch.uint8, device=dev)
         sched_us["router_training_step"] = timed(lambda: pa.router_grad(dl, Utr, X, off, Y, Yd_t, emb, scores_t, k, 1.0, 1e-6, ws_t))
+    pa.route(X, off, Wr[0], k, subset_out=sub_route, workspace=ws_route); torch.cuda.synchronize()
     assert torch.equal(sub.view(P, k), sub_route), "cache answered with a subset that differs from the route"
     flops = 2.0 * rows * rS * (n + m)
     eager_ms = wall / args.steps * 1e3
@@ -822,7 +823,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config1: q_proj-shaped prefill, bf16, {lay.m}x{lay.n}, R={lay.R} in {lay.G} groups of "
                                f"{lay.gs}, top-{w.k}, {w.P} prompts x {args.tokens} tokens, one routed subset per prompt",
-                   "step": "pool+route, cache probe (route-on-miss), buckets + plan (one launch), pack of new cache entries, forward; "
+                   "step": "pool, cache probe (route-on-miss), buckets + plan (one launch), pack of new cache entries, forward; "
                            "warm cache in the timed steps, cold_step_ms = the same step with an empty cache",
                    "launch_mode": pre["launch_mode"] + (": the K timed steps are K/2 replays of a HIP graph of two "
                                                         "consecutive steps, checked bitwise against the eager steps; "

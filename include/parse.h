@@ -115,6 +115,11 @@ int parse_layer_to_mfma16(const parse_layer *src, void *Vt_out, void *Ut_out, pa
  *                emb_out device float [P][d] or NULL.
  *   workspace    device, at least parse_route_workspace_bytes(rows, P, d) bytes. */
 size_t parse_route_workspace_bytes(int32_t rows, int32_t P, int32_t d);
+/* The prompt embedding alone (end of Sec. 4.1), for callers that ask the pattern cache first and run the router only on
+ * a miss (Sec. 4.3; parse_cache_lookup_or_route does that): emb_out [P][d] equals parse_route's emb_out bit for bit.
+ * Arguments, limits, workspace and errors as for parse_route. */
+int parse_pool(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_offsets, int32_t P, int32_t d,
+               float *emb_out, void *workspace, size_t workspace_bytes, parse_stream stream);
 int parse_route(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_offsets, int32_t P,
                 int32_t d, const float *Wr, int32_t G, int32_t k, int32_t *subset_out,
                 int32_t subset_stride, float *scores_out, float *emb_out, void *workspace,

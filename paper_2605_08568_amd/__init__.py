@@ -8,7 +8,7 @@ from .binding import (  # noqa: F401
     check_offsets, check_subset, layer_to_mfma16, lib, lowrank_decode_multi, lowrank_decode_multi_workspace_bytes, lowrank_decode_static,
     lowrank_prefill_multi, lowrank_prefill_multi_workspace_bytes,
     lowrank_forward, lowrank_workspace_bytes,
-    pack_experts, pack_new_entries, pack_patterns, pack_ranks, rankmajor_left_factor, route, route_ranks, router_grad, route_workspace_bytes, status_string, version,
+    pack_experts, pack_new_entries, pack_patterns, pack_ranks, rankmajor_left_factor, pool, route, route_ranks, router_grad, route_workspace_bytes, status_string, version,
     PARSE_SCHED_AUTO, PARSE_SCHED_FUSED, PARSE_SCHED_TILES, PARSE_SCHED_PLANNED, prefill_plan, prefill_plan_bytes, bucket_and_plan,
     lowrank_prefill_planned, lowrank_prefill_planned_workspace_bytes,
     probe_mfma_bf16, probe_read, probe_copy,

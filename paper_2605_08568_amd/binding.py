@@ -58,6 +58,8 @@ def lib():
     L.parse_layer_to_mfma16.restype = C.c_int
     L.parse_layer_to_mfma16.argtypes = [C.POINTER(_Layer), vp, vp, vp]
     L.parse_route_workspace_bytes.restype = sz; L.parse_route_workspace_bytes.argtypes = [i32, i32, i32]
+    L.parse_pool.restype = C.c_int
+    L.parse_pool.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp, sz, vp]
     L.parse_route.restype = C.c_int
     L.parse_route.argtypes = [vp, i32, i32, vp, i32, i32, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
     L.parse_route_shared.restype = C.c_int
@@ -255,6 +257,19 @@ def route(X, tok_offsets, Wr, k, subset_out=None, subset_stride=None, scores_out
                                         _ptr(subset_out), stride, _ptr(scores_out), _ptr(emb_out), _ptr(workspace),
                                         workspace.numel(), _stream()), "parse_route_shared")
     return subset_out
+
+
+def pool(X, tok_offsets, emb_out=None, workspace=None):
+    """parse_pool: the prompt embeddings [P][d] (float32) alone."""
+    rows, d = X.shape
+    P = tok_offsets.numel() - 1
+    if emb_out is None:
+        emb_out = torch.empty((P, d), dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = torch.empty(max(route_workspace_bytes(rows, P, d), 256), dtype=torch.uint8, device=X.device)
+    _check(lib().parse_pool(_ptr(X), _dtype_code(X), rows, _ptr(tok_offsets), P, d, _ptr(emb_out), _ptr(workspace),
+                            workspace.numel(), _stream()), "parse_pool")
+    return emb_out
 
 
 class Cache:

@@ -41,6 +41,14 @@ __global__ __launch_bounds__(256) void pool_finish(const float *__restrict__ par
   *reinterpret_cast<float4 *>(emb + (size_t)p * d + c) = acc;
 }
 
+// Shared with the embedding-only entry point.
+int launch_pool_finish(const float *partial, int Q, int rows, int d, const int32_t *tok_offsets, int P, float *emb,
+                       hipStream_t s) {
+  hipLaunchKernelGGL(pool_finish, dim3((d + 1023) / 1024, P), dim3(256), 0, s, partial, Q, rows, d, tok_offsets, emb);
+  PARSE_LAUNCH_CHECK();
+  return PARSE_OK;
+}
+
 // scores[p][g] = <Wr[g], e_p>.  grid (ceil(G/8), ceil(P/8)), block 256: wavefront w owns rows 2w, 2w+1 of the
 // block for the 8 prompts of the block.  Pure streaming, no LDS and no barrier: a lane reads 16 bytes of each of
 // its two router rows and of the 8 embeddings (cache-resident, 16 KB each) per 256-column step, four steps in
@@ -235,8 +243,8 @@ int parse_route_ranks(const void *X, int32_t xdtype, int32_t rows, const int32_t
   int Q = 0;
   int st = launch_pool_partials(X, xdtype, rows, tok_offsets, P, d, partial, &Q, s);
   if (st != PARSE_OK) return st;
-  hipLaunchKernelGGL(pool_finish, dim3((d + 1023) / 1024, P), dim3(256), 0, s, partial, Q, rows, d, tok_offsets, emb);
-  PARSE_LAUNCH_CHECK();
+  st = launch_pool_finish(partial, Q, rows, d, tok_offsets, P, emb, s);
+  if (st != PARSE_OK) return st;
   hipLaunchKernelGGL(rank_scores, dim3((G + RK_ROWS - 1) / RK_ROWS, (P + RK_PB - 1) / RK_PB), dim3(256), 0, s, Wr, emb, G,
                      d, P, scores);
   PARSE_LAUNCH_CHECK();

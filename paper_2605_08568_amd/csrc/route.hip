@@ -143,6 +143,9 @@ int launch_pool_partials(const void *X, int xdtype, int rows, const int32_t *tok
   return PARSE_OK;
 }
 
+int launch_pool_finish(const float *partial, int Q, int rows, int d, const int32_t *tok_offsets, int P, float *emb,
+                       hipStream_t s);   // with the rank-granular router
+
 }  // namespace parse
 
 using namespace parse;
@@ -155,6 +158,23 @@ size_t parse_route_workspace_bytes(int32_t rows, int32_t P, int32_t d) {
   const int q = pool_slices(rows, P, d, false) > pool_slices(rows, P, d, true) ? pool_slices(rows, P, d, false)
                                                                                   : pool_slices(rows, P, d, true);
   return round_up((size_t)P * q * d * sizeof(float), 256);
+}
+
+int parse_pool(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_offsets, int32_t P, int32_t d,
+               float *emb_out, void *workspace, size_t workspace_bytes, parse_stream stream) {
+  if (!X || !tok_offsets || !emb_out) return PARSE_EINVAL;
+  if (xdtype != PARSE_F32 && xdtype != PARSE_BF16) return PARSE_EINVAL;
+  if (rows <= 0 || P <= 0 || d <= 0) return PARSE_EINVAL;
+  if (d > 16384 || P > rows) return PARSE_ESHAPE;
+  if (d % 8 != 0) return PARSE_EALIGN;
+  if (!aligned16(X) || !aligned16(emb_out) || !aligned16(workspace)) return PARSE_EALIGN;
+  if (!workspace || workspace_bytes < parse_route_workspace_bytes(rows, P, d)) return PARSE_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  float *partial = reinterpret_cast<float *>(workspace);
+  int Q = 0;
+  const int st = launch_pool_partials(X, xdtype, rows, tok_offsets, P, d, partial, &Q, s);
+  if (st != PARSE_OK) return st;
+  return launch_pool_finish(partial, Q, rows, d, tok_offsets, P, emb_out, s);
 }
 
 int parse_route(const void *X, int32_t xdtype, int32_t rows, const int32_t *tok_offsets, int32_t P, int32_t d,

@@ -75,6 +75,16 @@ def test_route_rejects_bad_arguments():
     assert call(d=60) == -3 and call(X=ODD) == -3
     assert call(ws=None) == -5 and call(wsb=16) == -5
 
+    def pool(**kw):     # the embedding-only call: the same checks without the router's
+        a = dict(ok, emb=FAKE); a.update(kw)
+        return lib.parse_pool(a["X"], a["xdt"], a["rows"], a["off"], a["P"], a["d"], a["emb"], a["ws"], a["wsb"], None)
+
+    assert pool(X=None) == -1 and pool(off=None) == -1 and pool(emb=None) == -1
+    assert pool(xdt=7) == -1 and pool(rows=0) == -1 and pool(P=0) == -1
+    assert pool(P=9) == -2 and pool(d=16392, wsb=1 << 30) == -2
+    assert pool(d=60) == -3 and pool(X=ODD) == -3 and pool(emb=ODD) == -3
+    assert pool(ws=None) == -5 and pool(wsb=16) == -5
+
 
 def test_cache_create_rejects_bad_arguments():
     lib = pa.lib()

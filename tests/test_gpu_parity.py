@@ -55,6 +55,11 @@ def test_route_matches_oracle(dtype, lengths, d, G, k):
     assert np.array_equal(sub.cpu().numpy(), ref)
     assert np.allclose(emb.cpu().numpy(), E, rtol=1e-5, atol=1e-6)
     assert np.allclose(scores.cpu().numpy(), S, rtol=1e-4, atol=1e-5)
+    # the embedding-only call: same bits as the router call's embedding, output between guard bands
+    whole, mid = guarded_bytes(P * d * 4)
+    emb2 = pa.pool(upload_tokens(X, dtype), i32(off), emb_out=mid[:P * d * 4].view(torch.float32).view(P, d))
+    check_guards(whole, "pool")
+    assert torch.equal(emb2, emb) and bool(torch.all(mid[P * d * 4:] == 0xA5))
 
 
 def test_route_strided_output_and_determinism():
