@@ -347,6 +347,114 @@ __global__ __launch_bounds__(DR_THREADS) void decode_zr(DecArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// decode_zv: z for a handful of sequences (B <= 4), on the vector units.  With one to four sequences the 32-wide N side
+// of the matrix instruction is almost empty and, worse, a 32-rank block per workgroup leaves most compute units without
+// work (one sequence selects k groups: a 4096x4096 layer with 8 groups of 96 ranks has 24 blocks for 256 units).  Here a
+// workgroup owns EIGHT ranks of a block over the whole reduction range: in the operand order the 16-byte pieces of 8
+// consecutive ranks are 128 contiguous bytes, so a wavefront instruction reads 8 such lines (4 reduction steps x 2
+// halves), every line exactly once in the launch.  Lane (step s of 4, half q, rank j of 8) multiplies its 8 factor values
+// with the matching 8 values of each sequence's x row (all of x sits in LDS) and keeps one fp32 sum per sequence; the 8
+// lanes of a rank are added by a butterfly, the eight wavefronts through LDS in wavefront order.  No partial sums leave
+// the workgroup.  The result is masked, rounded and stored exactly like decode_zr's (one 16-byte piece per sequence).
+constexpr int DV_WAVES = 8, DV_THREADS = DV_WAVES * 64;
+constexpr int DV_JW = 8;                     // ranks per workgroup
+constexpr int DV_DEPTH = 24;                 // factor loads a lane has in flight: reductions of up to 12288 in one batch
+constexpr int DV_XBYTES = 96 * 1024;         // LDS for the x rows
+constexpr int DV_MAXB = 4;
+
+template <int NB>
+__global__ __launch_bounds__(DV_THREADS) void decode_zv(DecArgs a) {
+  int li = 0;
+#pragma unroll
+  for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].z_first) ? 1 : 0;
+  const DecLayer &ly = a.L[li];
+  const int bid = blockIdx.x - ly.z_first;
+  const int rb = bid / (32 / DV_JW), j0 = (bid % (32 / DV_JW)) * DV_JW;
+  const int n = a.n, B = a.B;
+  const uint32_t mask = (uint32_t)ly.plan[65 + (rb * 32) / ly.gs];
+  if (mask == 0u) return;                    // a block nobody selected is neither read nor written
+  __shared__ __attribute__((aligned(16))) char xs[DV_XBYTES];
+  __shared__ float red[DV_WAVES][NB][DV_JW];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int jl = lane & 7, q = (lane >> 3) & 1, ks = lane >> 4;
+  const int nkb = n / 16;
+  const int ninstr = (nkb + 3) / 4;                                  // wavefront instructions of the block, 4 steps each
+  const int nw = (ninstr - wave + DV_WAVES - 1) / DV_WAVES;          // ... of this wavefront: wave, wave + 4, ...
+  const char *vbase = (const char *)ly.Vt + (size_t)rb * nkb * 1024 + (q * 32 + j0 + jl) * 16;
+  u32x4 v[DV_DEPTH];
+  auto request = [&](int i0) {               // lanes past the last step re-read it (switched off when used)
+#pragma unroll
+    for (int u = 0; u < DV_DEPTH; ++u) {
+      if (i0 + u < nw) {                     // uniform
+        const int kb = min(((wave + (i0 + u) * DV_WAVES) << 2) + ks, nkb - 1);
+        v[u] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)kb * 1024);
+      }
+    }
+  };
+  request(0);
+  __builtin_amdgcn_sched_barrier(0);
+  // the x rows: B * n contiguous bf16, copied as they are; rows B .. NB-1 (never stored) are cleared
+  for (int i = threadIdx.x; i < NB * n / 8; i += DV_THREADS) {
+    u32x4 w = {0, 0, 0, 0};
+    if (i < B * n / 8) w = *reinterpret_cast<const u32x4 *>((const char *)a.x + (size_t)i * 16);
+    *reinterpret_cast<u32x4 *>(xs + (size_t)i * 16) = w;
+  }
+  __syncthreads();
+  float acc[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) acc[b] = 0.f;
+  for (int i0 = 0; i0 < nw; i0 += DV_DEPTH) {
+#pragma unroll
+    for (int u = 0; u < DV_DEPTH; ++u) {
+      if (i0 + u >= nw) break;               // uniform
+      const int kbr = ((wave + (i0 + u) * DV_WAVES) << 2) + ks;
+      const bool on = kbr < nkb;
+      const int kb = min(kbr, nkb - 1);
+      const u32x4 vv = v[u];
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const u32x4 xv = *reinterpret_cast<const u32x4 *>(xs + ((size_t)b * n + kb * 16 + q * 8) * 2);
+        float t = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          t += __uint_as_float(vv[e] << 16) * __uint_as_float(xv[e] << 16);
+          t += __uint_as_float(vv[e] & 0xFFFF0000u) * __uint_as_float(xv[e] & 0xFFFF0000u);
+        }
+        acc[b] += on ? t : 0.f;
+      }
+    }
+    if (i0 + DV_DEPTH < nw) request(i0 + DV_DEPTH);     // uniform
+  }
+  // the 8 lanes of a rank (4 steps x 2 halves), then the wavefronts
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    float t = acc[b];
+    t += __shfl_xor(t, 8, 64);
+    t += __shfl_xor(t, 16, 64);
+    t += __shfl_xor(t, 32, 64);
+    if (lane < DV_JW) red[wave][b][lane] = t;
+  }
+  __syncthreads();
+  if (threadIdx.x < 32) {                    // one 16-byte piece per sequence: its 8 ranks, zeros outside the group's mask
+    const int b = threadIdx.x;
+    u32x4 out = {0, 0, 0, 0};
+    if (b < B && b < NB && ((mask >> b) & 1u)) {
+      float s8[DV_JW];
+#pragma unroll
+      for (int e = 0; e < DV_JW; ++e) {
+        float t = red[0][min(b, NB - 1)][e];
+#pragma unroll
+        for (int w = 1; w < DV_WAVES; ++w) t += red[w][min(b, NB - 1)][e];
+        s8[e] = t;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) out[e] = cvt_pk_bf16(s8[2 * e], s8[2 * e + 1]);
+    }
+    *reinterpret_cast<u32x4 *>((char *)ly.zf + (size_t)(rb * 2 + (j0 >> 4)) * 1024 + (((j0 >> 3) & 1) * 32 + b) * 16) = out;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // decode_y: y.  grid = ceil(ncb / NC) workgroups per layer, each owns NC consecutive 32-column output blocks;
 // wavefront w owns an eighth of the used reduction blocks for all NC column blocks, so one z operand (cache-resident)
 // feeds NC products; the Ut operands of its first MAXK reduction blocks are requested at once (MAXK sized so that
@@ -567,9 +675,19 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
     d.y_first = yb; yb += (L->m / 32 + NC - 1) / NC;
   }
   const int nkb = a.n / 16;
-  const bool two = (nkb + KS - 1) / KS > DR_HALF_KB;     // the longest slice needs two stagings of x
-  if (two) hipLaunchKernelGGL(decode_zr<true>, dim3(zb), dim3(DR_THREADS), 0, s, a);
-  else hipLaunchKernelGGL(decode_zr<false>, dim3(zb), dim3(DR_THREADS), 0, s, a);
+  const int NB = B <= 1 ? 1 : (B <= 2 ? 2 : 4);
+  if (B <= DV_MAXB && (size_t)NB * a.n * 2 <= (size_t)DV_XBYTES) {
+    // a handful of sequences: eight ranks per workgroup on the vector units, no split of the reduction range
+    zb = 0;
+    for (int l = 0; l < n_layers; ++l) { a.L[l].z_first = zb; zb += (layers[l].R / 32) * (32 / DV_JW); }
+    if (NB == 1) hipLaunchKernelGGL(decode_zv<1>, dim3(zb), dim3(DV_THREADS), 0, s, a);
+    else if (NB == 2) hipLaunchKernelGGL(decode_zv<2>, dim3(zb), dim3(DV_THREADS), 0, s, a);
+    else hipLaunchKernelGGL(decode_zv<4>, dim3(zb), dim3(DV_THREADS), 0, s, a);
+  } else {
+    const bool two = (nkb + KS - 1) / KS > DR_HALF_KB;     // the longest slice needs two stagings of x
+    if (two) hipLaunchKernelGGL(decode_zr<true>, dim3(zb), dim3(DR_THREADS), 0, s, a);
+    else hipLaunchKernelGGL(decode_zr<false>, dim3(zb), dim3(DR_THREADS), 0, s, a);
+  }
   PARSE_LAUNCH_CHECK();
   if (NC == 1) hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   else if (NC == 2) hipLaunchKernelGGL(decode_y<2>, dim3(yb), dim3(DY_THREADS), 0, s, a);

@@ -614,6 +614,13 @@ def test_prefill_config1_full_size_sampled():
     (512, 32768, 96, 3, 2, 9, 3, 0),       # four column blocks per workgroup
     (2048, 2048, 2048, 64, 20, 32, 4, 0),  # the most groups a layer may have (64 of 32 ranks): quads span four groups
     (8192, 512, 256, 8, 3, 32, 4, 0),      # a long reduction over few rank blocks: 16 slices, two stagings of x each
+    (4096, 4096, 1536, 16, 8, 1, 1, 0),    # one sequence: eight ranks per workgroup on the vector units
+    (11008, 4096, 2048, 16, 8, 1, 1, 0),   # ... a reduction whose step count is no multiple of four (688 steps, 3 batches of loads)
+    (1040, 512, 256, 8, 3, 2, 2, 0),       # two sequences, 65 reduction steps (a ragged last instruction)
+    (2752, 1024, 640, 20, 10, 3, 2, 0),    # three sequences (computed as four)
+    (512, 256, 256, 8, 3, 4, 4, 0),        # four sequences, four patterns
+    (32, 64, 32, 1, 1, 1, 1, 0),           # a tiny layer: two reduction steps, one instruction, three idle wavefronts
+    (16384, 256, 64, 2, 1, 4, 2, 0),       # four sequences whose x rows do not fit the small-batch staging: the matrix path
 ])
 def test_decode_matches_oracle_and_prefill(n, m, R, G, k, B, npat, schedule):
     say(f"decode n={n} m={m} R={R} G={G} k={k} B={B} patterns={npat} schedule={schedule}")
@@ -687,7 +694,7 @@ def _decode_case(n, m, R, G, k, B, npat):
     x = si.make_tokens(rng, B, n, "bf16")
     U0, sg, V = oracle_factors(lay)
     # at the full workload shape the dense oracle is run on a sample of the sequences (one per pattern, two here)
-    rows = np.arange(B) if R <= 1024 else np.array([1, B - 2])
+    rows = np.arange(B) if (R <= 1024 or B <= 2) else np.array([1, B - 2])
     Yref = po.decode_step(U0, sg, V, lay.gs, si.bf16_bits_to_f32(x[rows]).astype(np.float64), pats[seq_pat[rows]])
     dl = pa.layer_to_mfma16(upload_layer(lay))
     xd = upload_tokens(x, "bf16")
@@ -816,6 +823,8 @@ def test_decode_unselected_groups_are_not_needed():
     ([(1536, 640, 20, 10), (1536, 640, 20, 10)], 1024, 32),                      # gate/up-like pair
     ([(512, 256, 8, 3), (256, 128, 4, 2), (768, 256, 8, 4)], 512, 7),           # Q/K/V-like, different m, R, G, k
     ([(11008, 2560, 20, 10), (11008, 2560, 20, 10)], 4096, 32),                  # the decode workload's gate + up
+    ([(4096, 1536, 16, 8), (4096, 1536, 16, 8), (4096, 1536, 16, 8)], 4096, 1),   # q/k/v of one sequence (small-batch kernel)
+    ([(1536, 640, 20, 10), (768, 256, 8, 4)], 1024, 3),                           # three sequences, two different layers
 ])
 def test_decode_multi_matches_oracle_and_single_calls(shapes, n, B):
     """Horizontal fusion (Sec. 4.4, Eq. 11-12): layers sharing x in one decode step = the separate steps."""
