@@ -18,9 +18,14 @@
 //              the second product.
 //   decode_y   NC (1..4) 32-column output blocks per workgroup; the eight wavefronts split the used reduction blocks,
 //              all Ut operands requested up front; LDS reduction in wavefront order.
+// A handful of sequences (B <= 4) take decode_zv / decode_yv instead: the same two products on the vector units with a
+// finer split of the work (eight ranks, sixteen or thirty-two columns per workgroup), because one to four sequences
+// leave the matrix instruction's 32-wide N side and most 32-rank workgroups idle.
 // Horizontal fusion (Sec. 4.4, Eq. 11-12): up to DEC_MAX_LAYERS layers that read the SAME x (Q/K/V, gate/up) go
 // through the same two launches together -- each launch's grid is the concatenation of the layers' task lists.
 // No floating-point atomics; the summation order is fixed: same inputs, same bits.
+#include <algorithm>
+
 #include "prefill_common.hpp"
 
 namespace parse {
@@ -359,7 +364,7 @@ __global__ __launch_bounds__(DR_THREADS) void decode_zr(DecArgs a) {
 constexpr int DV_WAVES = 8, DV_THREADS = DV_WAVES * 64;
 constexpr int DV_JW = 8;                     // ranks per workgroup
 constexpr int DV_DEPTH = 24;                 // factor loads a lane has in flight: reductions of up to 12288 in one batch
-constexpr int DV_XBYTES = 96 * 1024;         // LDS for the x rows
+constexpr int DV_XBYTES = 96 * 1024;         // most LDS the x rows may take
 constexpr int DV_MAXB = 4;
 
 template <int NB>
@@ -373,7 +378,7 @@ __global__ __launch_bounds__(DV_THREADS) void decode_zv(DecArgs a) {
   const int n = a.n, B = a.B;
   const uint32_t mask = (uint32_t)ly.plan[65 + (rb * 32) / ly.gs];
   if (mask == 0u) return;                    // a block nobody selected is neither read nor written
-  __shared__ __attribute__((aligned(16))) char xs[DV_XBYTES];
+  extern __shared__ __attribute__((aligned(16))) char xs[];      // NB * n bf16: several workgroups fit a compute unit
   __shared__ float red[DV_WAVES][NB][DV_JW];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int jl = lane & 7, q = (lane >> 3) & 1, ks = lane >> 4;
@@ -569,6 +574,123 @@ __global__ __launch_bounds__(DY_THREADS) void decode_y(DecArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// decode_yv: y for a handful of sequences (B <= 4), on the vector units -- the counterpart of decode_zv.  decode_y feeds
+// z to the matrix cores as a 32-sequence operand (1 KiB per reduction block whatever B is) that every workgroup re-reads;
+// here z is a few values per rank: a workgroup copies the B sequences' pieces of the used reduction blocks into LDS once
+// (16 bytes per block half and sequence) and then streams nothing but Ut.  Workgroup = 8 * CG consecutive output columns
+// of one layer (CG = 2 or 4 groups of 8 columns: 128-byte lines of the operand order, each read once in the launch);
+// wavefront w owns column group w % CG and every (8 / CG)-th instruction of the used reduction blocks, 4 blocks per
+// instruction: lane (block s of 4, half q, column j of 8) multiplies its 8 Ut values with the 8 matching z values of
+// each sequence.  The 8 lanes of a column are added by a butterfly, the wavefronts of a column group through LDS in
+// wavefront order; one 16-byte store per sequence and column group.
+constexpr int DYV_WAVES = 8, DYV_THREADS = DYV_WAVES * 64;
+constexpr int DYV_DEPTH = 16;                // Ut loads a lane has in flight
+constexpr int DYV_ZBYTES = 96 * 1024;        // most LDS the z pieces may take
+
+template <int NB, int CG>
+__global__ __launch_bounds__(DYV_THREADS) void decode_yv(DecArgs a) {
+  constexpr int PARTS = DYV_WAVES / CG;      // wavefronts that share a column group
+  int li = 0;
+#pragma unroll
+  for (int i = 1; i < DEC_MAX_LAYERS; ++i) li += (i < a.n_layers && (int)blockIdx.x >= a.L[i].y_first) ? 1 : 0;
+  const DecLayer &ly = a.L[li];
+  const int32_t *__restrict__ plan = ly.plan;
+  const int B = a.B, m = ly.m, G = ly.G, gs = ly.gs;
+  const int bid = blockIdx.x - ly.y_first;
+  extern __shared__ __attribute__((aligned(16))) char zs[];          // [used reduction block][half][NB] pieces of 16 bytes
+  __shared__ int32_t kb_list[DY_MAXKB];
+  __shared__ int32_t used[DEC_MAXG];
+  __shared__ float red[DYV_WAVES][NB][8];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int jl = lane & 7, q = (lane >> 3) & 1, ks = lane >> 4;
+  const int cg = wave % CG, part = wave / CG;
+  const int ncb = m / 32;
+  const int col0 = (bid * CG + cg) * 8;                              // first column of this wavefront's group
+  const int n_used_raw = plan[0];
+  if (threadIdx.x < DEC_MAXG) used[threadIdx.x] = plan[1 + threadIdx.x];
+  const int n_used = max(0, min(n_used_raw, G));
+  __syncthreads();
+  const int kpg = gs / 16;
+  const int total_kb = n_used * kpg;
+  for (int i = threadIdx.x; i < total_kb; i += DYV_THREADS) kb_list[i] = max(used[i / kpg], 0) * kpg + i % kpg;
+  __syncthreads();
+  // z pieces of the used blocks: piece (i, h, b) = ranks kb_list[i]*16 + 8h .. +7 of sequence b (zeros for b >= B)
+  for (int t = threadIdx.x; t < total_kb * 2 * NB; t += DYV_THREADS) {
+    const int b = t % NB, h = (t / NB) & 1, i = t / (2 * NB);
+    u32x4 w = {0, 0, 0, 0};
+    if (b < B) w = *reinterpret_cast<const u32x4 *>((const char *)ly.zf + (size_t)kb_list[i] * 1024 + (h * 32 + b) * 16);
+    *reinterpret_cast<u32x4 *>(zs + (size_t)t * 16) = w;
+  }
+  const int ninstr = (total_kb + 3) / 4;
+  const int nw = col0 < m ? (ninstr - part + PARTS - 1) / PARTS : 0;  // instructions of this wavefront: part, part + PARTS, ...
+  // column col0 + jl sits in column block c / 32 at place c % 32 of the operand
+  const int cc = min(col0, m - 8) + jl;
+  const char *ubase = (const char *)ly.Ut + (size_t)(cc >> 5) * 1024 + (q * 32 + (cc & 31)) * 16;
+  const size_t ustep = (size_t)ncb * 1024;
+  u32x4 v[DYV_DEPTH];
+  auto request = [&](int i0) {               // lanes past the last block re-read it (switched off when used)
+#pragma unroll
+    for (int u = 0; u < DYV_DEPTH; ++u) {
+      if (i0 + u < nw) {                     // uniform
+        const int i = min(((part + (i0 + u) * PARTS) << 2) + ks, total_kb - 1);
+        v[u] = *reinterpret_cast<const u32x4 *>(ubase + (size_t)kb_list[i] * ustep);
+      }
+    }
+  };
+  request(0);
+  __syncthreads();                           // the z pieces are in LDS
+  float acc[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) acc[b] = 0.f;
+  for (int i0 = 0; i0 < nw; i0 += DYV_DEPTH) {
+#pragma unroll
+    for (int u = 0; u < DYV_DEPTH; ++u) {
+      if (i0 + u >= nw) break;               // uniform
+      const int ir = ((part + (i0 + u) * PARTS) << 2) + ks;
+      const bool on = ir < total_kb;
+      const int i = min(ir, total_kb - 1);
+      const u32x4 uv = v[u];
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const u32x4 zv = *reinterpret_cast<const u32x4 *>(zs + (size_t)((i * 2 + q) * NB + b) * 16);
+        float t = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          t += __uint_as_float(uv[e] << 16) * __uint_as_float(zv[e] << 16);
+          t += __uint_as_float(uv[e] & 0xFFFF0000u) * __uint_as_float(zv[e] & 0xFFFF0000u);
+        }
+        acc[b] += on ? t : 0.f;
+      }
+    }
+    if (i0 + DYV_DEPTH < nw) request(i0 + DYV_DEPTH);   // uniform
+  }
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    float t = acc[b];
+    t += __shfl_xor(t, 8, 64);
+    t += __shfl_xor(t, 16, 64);
+    t += __shfl_xor(t, 32, 64);
+    if (lane < 8) red[wave][b][lane] = t;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < CG * NB) {          // thread (column group, sequence): 8 columns = one 16-byte store
+    const int g2 = threadIdx.x / NB, b = threadIdx.x % NB;
+    const int c = (bid * CG + g2) * 8;
+    if (b < B && c < m) {
+      u32x4 out;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int pt = 0; pt < PARTS; ++pt) { s0 += red[pt * CG + g2][b][2 * e]; s1 += red[pt * CG + g2][b][2 * e + 1]; }
+        out[e] = pack_bf16x2(s0, s1);
+      }
+      *reinterpret_cast<u32x4 *>(ly.y + (size_t)b * m + c) = out;
+    }
+  }
+}
+
 // workspace of one layer: z in operand order (R/16 operands of 1 KiB), then the partial sums of decode_zr
 static size_t dec_zf_bytes(const parse_layer *L) { return round_up((size_t)(L->R / 16) * 1024, 256); }
 // decode_zr takes reductions of up to DR_MAX_KS slices of 8 * DR_MAXK steps (n <= 65536) and layers of up to DEC_TICKETS
@@ -680,16 +802,44 @@ int forward_decode_planned_bf16(const parse_layer *layers, int n_layers, const u
     // a handful of sequences: eight ranks per workgroup on the vector units, no split of the reduction range
     zb = 0;
     for (int l = 0; l < n_layers; ++l) { a.L[l].z_first = zb; zb += (layers[l].R / 32) * (32 / DV_JW); }
-    if (NB == 1) hipLaunchKernelGGL(decode_zv<1>, dim3(zb), dim3(DV_THREADS), 0, s, a);
-    else if (NB == 2) hipLaunchKernelGGL(decode_zv<2>, dim3(zb), dim3(DV_THREADS), 0, s, a);
-    else hipLaunchKernelGGL(decode_zv<4>, dim3(zb), dim3(DV_THREADS), 0, s, a);
+    const size_t lds = (size_t)NB * a.n * 2;
+    if (NB == 1) {
+      PARSE_ALLOW_LDS(decode_zv<1>, lds);
+      hipLaunchKernelGGL(decode_zv<1>, dim3(zb), dim3(DV_THREADS), lds, s, a);
+    } else if (NB == 2) {
+      PARSE_ALLOW_LDS(decode_zv<2>, lds);
+      hipLaunchKernelGGL(decode_zv<2>, dim3(zb), dim3(DV_THREADS), lds, s, a);
+    } else {
+      PARSE_ALLOW_LDS(decode_zv<4>, lds);
+      hipLaunchKernelGGL(decode_zv<4>, dim3(zb), dim3(DV_THREADS), lds, s, a);
+    }
   } else {
     const bool two = (nkb + KS - 1) / KS > DR_HALF_KB;     // the longest slice needs two stagings of x
     if (two) hipLaunchKernelGGL(decode_zr<true>, dim3(zb), dim3(DR_THREADS), 0, s, a);
     else hipLaunchKernelGGL(decode_zr<false>, dim3(zb), dim3(DR_THREADS), 0, s, a);
   }
   PARSE_LAUNCH_CHECK();
-  if (NC == 1) hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
+  size_t max_kb = 0;
+  for (int l = 0; l < n_layers; ++l) max_kb = std::max(max_kb, (size_t)layers[l].R / 16);
+  const size_t zs_bytes = max_kb * 2 * NB * 16;            // z pieces of every reduction block a layer has
+  if (B <= DV_MAXB && zs_bytes <= (size_t)DYV_ZBYTES) {
+    // a handful of sequences: z as a few values per rank in LDS, the launch streams only Ut.  16 columns per workgroup
+    // unless that makes more than about four workgroups per compute unit
+    int cols = 0;
+    for (int l = 0; l < n_layers; ++l) cols += layers[l].m;
+    const int CG = cols / 16 > 4 * n_cu ? 4 : 2;
+    yb = 0;
+    for (int l = 0; l < n_layers; ++l) { a.L[l].y_first = yb; yb += (layers[l].m + 8 * CG - 1) / (8 * CG); }
+#define PARSE_YV(NB_, CG_)                                                                     \
+  do {                                                                                         \
+    PARSE_ALLOW_LDS((decode_yv<NB_, CG_>), zs_bytes);                                          \
+    hipLaunchKernelGGL((decode_yv<NB_, CG_>), dim3(yb), dim3(DYV_THREADS), zs_bytes, s, a);    \
+  } while (0)
+    if (NB == 1) { if (CG == 2) PARSE_YV(1, 2); else PARSE_YV(1, 4); }
+    else if (NB == 2) { if (CG == 2) PARSE_YV(2, 2); else PARSE_YV(2, 4); }
+    else { if (CG == 2) PARSE_YV(4, 2); else PARSE_YV(4, 4); }
+#undef PARSE_YV
+  } else if (NC == 1) hipLaunchKernelGGL(decode_y<1>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   else if (NC == 2) hipLaunchKernelGGL(decode_y<2>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   else if (NC == 3) hipLaunchKernelGGL(decode_y<3>, dim3(yb), dim3(DY_THREADS), 0, s, a);
   else hipLaunchKernelGGL(decode_y<4>, dim3(yb), dim3(DY_THREADS), 0, s, a);
