@@ -267,7 +267,9 @@ size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *layer, int
  *                of that panel's sequences selected it.  Per panel: streams every group that some sequence selected exactly
  *                once from the layer's own store (layer->Vt / layer->Ut, not the packed copies) and applies
  *                it to the sequences whose pattern holds it (Sec. 4.3, rank reuse: pattern_id is fixed
- *                at prefill).  Bandwidth-bound.
+ *                at prefill).  Bandwidth-bound.  A panel of one to four sequences is computed on the vector
+ *                units with a finer split of the work (same rounding points: z and y to bf16, fp32 sums); a
+ *                sequence's result may therefore differ in rounding between a small and a large panel.
  * workspace: device, >= parse_lowrank_workspace_bytes(mode, layer, rows, k, P, n_patterns) bytes (optional for
  *            bf16 prefill). */
 int parse_lowrank_forward(int32_t mode, const parse_layer *layer, const parse_patterns *patterns,
