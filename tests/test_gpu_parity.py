@@ -744,6 +744,44 @@ def test_decode_more_than_32_sequences_in_panels():
                 assert_close(yn[b:b + 1], Yo[b:b + 1], TOL_BF16, f"layer {li} sequence {b}")
 
 
+def test_decode_of_a_few_sequences_masks_and_panels():
+    """The small-batch kernels (one to four sequences): sequences with DIFFERENT patterns share a group's stream and are
+    masked per sequence; an invalid pattern id gives a zero row; the planned step equals the ordinary one bit for bit and
+    stays inside its buffers; and a batch of 33 ends in a panel of one sequence, which takes the same kernels."""
+    say("decode of 2-4 sequences with different patterns, an invalid id, and a 33-sequence batch (last panel of one)")
+    n, m, R, G, k, npat = 1024, 640, 512, 16, 5, 6
+    lay = si.make_layer(np.random.default_rng(641), n, m, R, G, "bf16")
+    rng = np.random.default_rng(642)
+    sub = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(npat)]).astype(np.int32)
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    pt = pa.Patterns(k, npat, subsets=i32(sub))
+    U0, sg, V = oracle_factors(lay)
+    for B, seq_pat in ((2, [3, 0]), (3, [5, 99, 1]), (4, [2, 2, 4, -1]), (33, list(rng.integers(0, npat, size=33)))):
+        seq_pat = np.array(seq_pat, np.int32)
+        x = si.make_tokens(rng, B, n, "bf16")
+        xd, pid = upload_tokens(x, "bf16"), i32(seq_pat)
+        y = forward_guarded(pa.PARSE_DECODE, dl, pt, xd, None, pid)
+        torch.cuda.synchronize()
+        yn = y.float().cpu().numpy().astype(np.float64)
+        ok = np.flatnonzero((seq_pat >= 0) & (seq_pat < npat))
+        Yo = po.decode_step(U0, sg, V, lay.gs, si.bf16_bits_to_f32(x[ok]).astype(np.float64), sub[seq_pat[ok]])
+        for i, b in enumerate(ok):
+            assert_close(yn[b:b + 1], Yo[i:i + 1], TOL_BF16, f"B={B} sequence {b}")
+        for b in np.setdiff1d(np.arange(B), ok):
+            assert np.all(yn[b] == 0), "a sequence with an invalid pattern id must get zeros"
+        if B <= 32:
+            plan = pa.decode_plan([dl], [pt], pid)
+            nbytes = B * m * 2
+            whole, mid = guarded_bytes(nbytes)
+            wsb = pa.lowrank_decode_planned_workspace_bytes([dl])
+            wwhole, wmid = guarded_bytes(wsb)
+            yv = mid[:nbytes].view(torch.bfloat16).view(B, m)
+            pa.lowrank_decode_planned([dl], xd, plan, [yv], wmid[:wsb])
+            check_guards(whole, "planned small-batch decode: Y"); check_guards(wwhole, "planned small-batch decode: workspace")
+            assert bool(torch.all(mid[nbytes:] == 0xA5))
+            assert torch.equal(yv.view(torch.int16), y.view(torch.int16))
+
+
 def test_decode_with_a_shared_head_streams_it_once():
     """Shared experts (Sec. 4.4): every pattern starts with the same two groups.  Decode reads the layer's own store by
     group id, so the shared groups are simply groups that every sequence selected: streamed once, applied to all."""
