@@ -782,6 +782,95 @@ def test_decode_of_a_few_sequences_masks_and_panels():
             assert torch.equal(yv.view(torch.int16), y.view(torch.int16))
 
 
+def test_steps_replayed_from_a_graph_equal_the_eager_steps():
+    """Every call of the path only enqueues kernels, so whole steps can be recorded into a HIP graph.  Three graphs -- a
+    decode step with a split reduction (arrival counters drawn and reset inside every replay), a decode step of four
+    sequences whose kernels need more than 64 KiB of LDS (the limit is raised inside the capture), and two consecutive
+    prefill steps over the pattern cache (its probe alternates between two device counters) -- are each replayed
+    three times with eager work of the same kind in between; every replay must reproduce the eager result bit for bit."""
+    say("graph capture: decode (split reduction), small-batch decode (88 KiB LDS), two prefill steps with the cache")
+    rng = np.random.default_rng(651)
+    side = torch.cuda.Stream()
+
+    def capture(fn):
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):           # warm-up outside the capture, as torch asks
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g
+
+    # --- decode: n = 8192 over few rank blocks -> 16 slices with tickets; then 4 sequences at n = 11008
+    for (n, m, R, G, k, B, npat) in ((8192, 512, 256, 8, 3, 32, 4), (11008, 512, 256, 8, 3, 4, 2)):
+        lay = si.make_layer(np.random.default_rng(652), n, m, R, G, "bf16", fast=True)
+        sub = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in range(npat)]).astype(np.int32)
+        dl = pa.layer_to_mfma16(upload_layer(lay))
+        pt = pa.Patterns(k, npat, subsets=i32(sub))
+        pid = i32((np.arange(B) % npat).astype(np.int32))
+        xs = [upload_tokens(si.make_tokens(rng, B, n, "bf16"), "bf16") for _ in range(2)]
+        x = xs[0].clone()
+        y = torch.empty((B, m), dtype=torch.bfloat16, device=DEV)
+        ws = torch.empty(pa.lowrank_decode_planned_workspace_bytes([dl]), dtype=torch.uint8, device=DEV)
+        plan = pa.decode_plan([dl], [pt], pid)
+        g = capture(lambda: pa.lowrank_decode_planned([dl], x, plan, [y], ws))
+        for rep in range(3):
+            x.copy_(xs[rep % 2])
+            pa.lowrank_decode_planned([dl], x, plan, [y], ws)          # eager
+            torch.cuda.synchronize()
+            ref = y.clone(); y.zero_()
+            g.replay(); torch.cuda.synchronize()
+            assert torch.equal(y.view(torch.int16), ref.view(torch.int16)), f"decode n={n} B={B}: replay {rep} differs"
+
+    # --- prefill: pool -> probe (route on miss) -> buckets + plan -> aggregation of new entries -> planned product
+    n, m, R, G, k, P, n_slots = 512, 384, 256, 8, 3, 6, 16         # room for the patterns of both token sets
+    lay = si.small_layer(653, n, m, R, G, "bf16")
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    lengths = [70, 300, 5, 129, 64, 256]
+    off = si.offsets_from_lengths(lengths); rows = int(off[-1])
+    offd = i32(off)
+    Wr = torch.from_numpy(si.make_router(rng, 1, G, n)).to(DEV)
+    Xs = [upload_tokens(si.make_tokens(rng, rows, n, "bf16"), "bf16") for _ in range(2)]
+    X = Xs[0].clone()
+    cache = pa.Cache(n_slots, n, 1, k, P)
+    emb = torch.empty((P, n), dtype=torch.float32, device=DEV)
+    ws_pool = torch.empty(max(pa.route_workspace_bytes(rows, P, n), 256), dtype=torch.uint8, device=DEV)
+    entry = torch.empty(P, dtype=torch.int32, device=DEV); hit = torch.empty(P, dtype=torch.uint8, device=DEV)
+    sim = torch.empty(P, dtype=torch.float32, device=DEV); sub = torch.empty((P, 1, k), dtype=torch.int32, device=DEV)
+    bout = (torch.empty(P, dtype=torch.int32, device=DEV), torch.empty(P, dtype=torch.int32, device=DEV),
+            torch.empty(P + 1, dtype=torch.int32, device=DEV), torch.empty(1, dtype=torch.int32, device=DEV),
+            torch.empty(P, dtype=torch.int32, device=DEV))
+    Vs = torch.zeros((n_slots, k * lay.gs, n), dtype=torch.bfloat16, device=DEV)
+    Us = torch.zeros((n_slots, k * lay.gs, m), dtype=torch.bfloat16, device=DEV)
+    pt = pa.Patterns(k, n_slots, Vs, Us)
+    plan = torch.empty(pa.prefill_plan_bytes(rows, P, n_slots), dtype=torch.uint8, device=DEV)
+    Y = torch.empty((rows, m), dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(max(pa.lowrank_prefill_planned_workspace_bytes(dl, rows, P, k, n_slots), 256), dtype=torch.uint8, device=DEV)
+
+    def step():
+        pa.pool(X, offd, emb, ws_pool)
+        cache.lookup_or_route(emb, 0.9, Wr, entry, hit, sim, sub)
+        pa.bucket_and_plan(sub, k, k, offd, entry, rows, n_slots, bout, plan)
+        pa.pack_new_entries(dl, sub, k, k, entry, hit, Vs, Us)
+        pa.lowrank_prefill_planned(dl, pt, X, offd, entry, plan, Y, ws)
+
+    for _ in range(4):                                 # an even number of probes; the host-side bound of the entry count
+        step()                                         # has reached the capacity, so the recorded probe covers every entry
+    torch.cuda.synchronize()
+    g = capture(lambda: (step(), step()))
+    for rep in range(3):
+        X.copy_(Xs[rep % 2])
+        step(); step(); torch.cuda.synchronize()
+        ref, eref, href = Y.clone(), entry.clone(), hit.clone()
+        Y.zero_(); entry.fill_(-5)
+        g.replay(); torch.cuda.synchronize()
+        assert torch.equal(Y.view(torch.int16), ref.view(torch.int16)) and torch.equal(entry, eref) and torch.equal(hit, href), \
+            f"prefill: replay {rep} differs"
+    cache.close()
+
+
 def test_decode_with_a_shared_head_streams_it_once():
     """Shared experts (Sec. 4.4): every pattern starts with the same two groups.  Decode reads the layer's own store by
     group id, so the shared groups are simply groups that every sequence selected: streamed once, applied to all."""
