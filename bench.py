@@ -148,23 +148,25 @@ def bench_prefill(args, torch, pa, si):
     per = {nm: sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)) / args.steps * 1e3
            for i, nm in enumerate(names)}                                  # microseconds
     hits = int(hit.sum().item())
-    # The same steps replayed from a HIP graph of two consecutive steps (every launch of both steps is a kernel node;
-    # the library records no memset).  Two steps per graph, because the cache probe alternates between two device
-    # counters from call to call; the probe grid is sized for the cache's capacity once the host-side bound has
+    # The same steps replayed from a HIP graph of consecutive steps (every launch of every step is a kernel node;
+    # the library records no memset).  An even number of steps per graph (ten, or two when K is no multiple of ten),
+    # because the cache probe alternates between two device counters from call to call; the probe grid is sized for the cache's capacity once the host-side bound has
     # reached it (it has, after the warm-up), so the recorded launches stay valid whatever the cache holds.
-    # The eager loop above gives the per-row breakdown; K steps are timed again here as K/2 replays.
+    # The eager loop above gives the per-row breakdown; K steps are timed again here as K/10 (K/2) replays.
     # (One linear chain of kernel nodes: putting bucket / pack / plan on parallel branches was measured slower, 148 us
     # per step against 127 -- dependencies across queues cost more than the three small kernels they would overlap.)
     graph = None
     if not args.no_prefill_graph and args.steps >= 2:
         Y_ref, entry_ref, hit_ref = Y.clone(), entry.clone(), hit.clone()
+        spg = 10 if args.steps % 10 == 0 else 2      # an even number of steps per graph (the two counters)
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            step(); step()
+            for _ in range(spg):
+                step()
         for _ in range(2):
             g.replay()
         torch.cuda.synchronize()
-        reps = args.steps // 2
+        reps = args.steps // spg
         tg0 = time.perf_counter()
         for _ in range(reps):
             g.replay()
@@ -172,7 +174,7 @@ def bench_prefill(args, torch, pa, si):
         tg1 = time.perf_counter()
         same = bool(torch.equal(Y.view(torch.int16), Y_ref.view(torch.int16)) and torch.equal(entry, entry_ref)
                     and torch.equal(hit, hit_ref))
-        graph = {"ms_per_step": (tg1 - tg0) / (2 * reps) * 1e3, "steps": 2 * reps, "steps_per_graph": 2,
+        graph = {"ms_per_step": (tg1 - tg0) / (spg * reps) * 1e3, "steps": spg * reps, "steps_per_graph": spg,
                  "matches_eager_bitwise": same}
     sched_us, rank_us, pipelined = {}, None, None
     if not args.no_extras:
@@ -825,7 +827,8 @@ def main():
                                f"{lay.gs}, top-{w.k}, {w.P} prompts x {args.tokens} tokens, one routed subset per prompt",
                    "step": "pool, cache probe (route-on-miss), buckets + plan (one launch), pack of new cache entries, forward; "
                            "warm cache in the timed steps, cold_step_ms = the same step with an empty cache",
-                   "launch_mode": pre["launch_mode"] + (": the K timed steps are K/2 replays of a HIP graph of two "
+                   "launch_mode": pre["launch_mode"] + (f": the K timed steps are replays of a HIP graph of "
+                                                        f"{(pre['graph_replay'] or {}).get('steps_per_graph', 2)} "
                                                         "consecutive steps, checked bitwise against the eager steps; "
                                                         "rows_us and roofline come from the eager steps"
                                                         if pre["launch_mode"] == "graph" else "")},
