@@ -361,18 +361,22 @@ int forward_prefill_planned_multi_bf16(const PfArgs *p, int n_layers, const int3
   // chip enough workgroups, 128 x 128 tiles otherwise (config 1's first product: 64 large tiles or 256 small ones)
   const bool big1 = tiles256 * ct1 >= 192;
   const bool big2 = tiles256 * ct2 >= 192;
-  // a first product that does not even fill the chip with 128 x 128 tiles (one long prompt through a narrow selection:
+  // a product that does not even fill the chip with 128 x 128 tiles (one long prompt through a narrow selection:
   // 2048 tokens x 1024 ranks are 128 tiles for 256 compute units) takes 64-token tiles: more bytes per flop for a unit,
   // but twice the units at work
   long long t128 = 0;
   for (int l = 0; l < n_layers; ++l) t128 += (long long)((p[0].rows + 127) / 128) * ((p[l].rS + 127) / 128);
   const bool small1 = !big1 && t128 <= 192;
+  long long u128 = 0;                          // the same for the second product
+  for (int l = 0; l < n_layers; ++l) u128 += (long long)((p[0].rows + 127) / 128) * ((p[l].m + 127) / 128);
+  const bool small2 = !big2 && u128 <= 192;
   int st;
   if (big1) st = launch_gemm_lds<256, 256, 2, 2, 32, 4, 0, 1, 0>(g1, per_pattern, s);
   else if (small1) st = launch_gemm_lds<64, 128, 2, 2, 64, 4, 0, 1, 0>(g1, per_pattern, s);
   else st = launch_gemm_lds<128, 128, 2, 2, 64, 4, 0, 1, 0>(g1, per_pattern, s);
   if (st != PARSE_OK) return st;
   if (big2) return launch_gemm_lds<256, 256, 2, 4, 32, 4, 1, 0, 1>(g2, per_pattern, s);
+  if (small2) return launch_gemm_lds<64, 128, 2, 2, 32, 4, 1, 0, 1>(g2, per_pattern, s);
   return launch_gemm_lds<128, 128, 2, 2, 32, 4, 1, 0, 1>(g2, per_pattern, s);
 }
 
