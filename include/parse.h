@@ -308,7 +308,10 @@ int parse_bucket_and_plan(const int32_t *subset, int32_t P, int32_t k, int32_t s
  * have been built from the same tok_offsets, pattern_id, rows, P and patterns->n_patterns (the two arrays are checked
  * for presence only: everything the kernels need from them is in the plan).
  *   workspace  device, >= parse_lowrank_prefill_planned_workspace_bytes(layer, rows, P, k, n_patterns): the
- *              intermediate of the padded virtual rows, in operand order. */
+ *              intermediate of the padded virtual rows, in operand order; for batches of at most 1024 token rows
+ *              (n >= 1024) also the fp32 partial sums of the first product, whose reduction over n is then cut in
+ *              2..8 slices (one more small launch adds them in slice order; the count depends on rows and n only,
+ *              so fused and single-layer calls agree bit for bit). */
 size_t parse_lowrank_prefill_planned_workspace_bytes(const parse_layer *layer, int32_t rows, int32_t P, int32_t k,
                                                      int32_t n_patterns);
 int parse_lowrank_prefill_planned(const parse_layer *layer, const parse_patterns *patterns, const void *X,

@@ -15,7 +15,8 @@ int prefill_plan_capacity(int rows, int P, int n_patterns);
 bool prefill_plan_supported(int P, int n_patterns);
 int build_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, int P, int rows, int n_patterns,
                        int32_t *plan, hipStream_t s);
-size_t prefill_planned_z_bytes(int cap_tiles, int rS);
+size_t prefill_planned_z_bytes(int cap_tiles, int rS, int ks);
+int prefill_planned_split(int rows, int n);
 bool prefill_planned_supported(int n, int m, int rS);
 int forward_prefill_planned_multi_bf16(const PfArgs *p, int n_layers, const int32_t *plan, int cap, uint16_t *const *Z,
                                        int avg_prompt_rows, hipStream_t s);
@@ -43,7 +44,8 @@ extern "C" {
 // workspace of the planned schedule inside parse_lowrank_forward: the intermediate, then the plan
 static size_t planned_total_bytes(const parse_layer *L, int rows, int P, int k, int n_patterns) {
   const int rS = k * (L->R / L->G);
-  return prefill_planned_z_bytes(prefill_plan_capacity(rows, P, n_patterns), rS) + prefill_plan_bytes(rows, P, n_patterns);
+  return prefill_planned_z_bytes(prefill_plan_capacity(rows, P, n_patterns), rS, prefill_planned_split(rows, L->n)) +
+         prefill_plan_bytes(rows, P, n_patterns);
 }
 
 size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *L, int32_t rows, int32_t k, int32_t P,
@@ -64,7 +66,8 @@ size_t parse_lowrank_workspace_bytes(int32_t mode, const parse_layer *L, int32_t
 size_t parse_lowrank_prefill_planned_workspace_bytes(const parse_layer *L, int32_t rows, int32_t P, int32_t k,
                                                      int32_t n_patterns) {
   if (!L || rows <= 0 || k <= 0 || P <= 0 || n_patterns <= 0 || L->G <= 0 || L->R <= 0) return 0;
-  return prefill_planned_z_bytes(prefill_plan_capacity(rows, P, n_patterns), k * (L->R / L->G));
+  const int rS = k * (L->R / L->G);
+  return prefill_planned_z_bytes(prefill_plan_capacity(rows, P, n_patterns), rS, prefill_planned_split(rows, L->n));
 }
 
 int parse_lowrank_prefill_planned(const parse_layer *L, const parse_patterns *pt, const void *X, int32_t rows,
@@ -86,7 +89,8 @@ int parse_lowrank_prefill_planned(const parse_layer *L, const parse_patterns *pt
       !prefill_planned_supported(L->n, L->m, rS)) return PARSE_ESHAPE;
   if (!aligned16(X) || !aligned16(Y) || !aligned16(plan) || !aligned16(pt->Vt_S) || !aligned16(pt->Ut_S)) return PARSE_EALIGN;
   const int cap = prefill_plan_capacity(rows, P, pt->n_patterns);
-  if (!workspace || workspace_bytes < prefill_planned_z_bytes(cap, rS)) return PARSE_EWORKSPACE;
+  if (!workspace || workspace_bytes < prefill_planned_z_bytes(cap, rS, prefill_planned_split(rows, L->n)))
+    return PARSE_EWORKSPACE;
   if (!aligned16(workspace)) return PARSE_EALIGN;
   PfArgs a{(const uint16_t *)X, (const uint16_t *)pt->Vt_S, (const uint16_t *)pt->Ut_S, (uint16_t *)Y, tok_offsets, pattern_id,
            pt->n_patterns, rows, L->n, L->m, rS, P};
@@ -268,7 +272,8 @@ static bool multi_planned_shapes(const parse_layer *layers, const parse_patterns
 static size_t multi_planned_bytes(const parse_layer *layers, const parse_patterns *patterns, int n_layers, int rows, int P) {
   const int cap = prefill_plan_capacity(rows, P, patterns[0].n_patterns);
   size_t total = prefill_plan_bytes(rows, P, patterns[0].n_patterns);
-  for (int l = 0; l < n_layers; ++l) total += prefill_planned_z_bytes(cap, patterns[l].k * (layers[l].R / layers[l].G));
+  const int ks = prefill_planned_split(rows, layers[0].n);
+  for (int l = 0; l < n_layers; ++l) total += prefill_planned_z_bytes(cap, patterns[l].k * (layers[l].R / layers[l].G), ks);
   return total;
 }
 
@@ -336,9 +341,10 @@ int parse_lowrank_prefill_multi(const parse_layer *layers, const parse_patterns 
     // planned: every layer's padded intermediate, then the plan; one plan launch, then two launches for all layers
     const int cap = prefill_plan_capacity(rows, P, patterns[0].n_patterns);
     uint16_t *Z[4];
+    const int ks = prefill_planned_split(rows, args[0].n);
     for (int l = 0; l < n_layers; ++l) {
       Z[l] = reinterpret_cast<uint16_t *>(ws);
-      ws += prefill_planned_z_bytes(cap, args[l].rS);
+      ws += prefill_planned_z_bytes(cap, args[l].rS, ks);
     }
     int32_t *plan = reinterpret_cast<int32_t *>(ws);
     int st = build_prefill_plan(tok_offsets, pattern_id, P, rows, patterns[0].n_patterns, plan, s);

@@ -361,7 +361,8 @@ int prefill_plan_capacity(int rows, int P, int n_patterns);
 bool prefill_plan_supported(int P, int n_patterns);
 int build_prefill_plan(const int32_t *tok_offsets, const int32_t *pattern_id, int P, int rows, int n_patterns,
                        int32_t *plan, hipStream_t s);
-size_t prefill_planned_z_bytes(int cap_tiles, int rS);
+size_t prefill_planned_z_bytes(int cap_tiles, int rS, int ks);
+int prefill_planned_split(int rows, int n);
 bool prefill_planned_supported(int n, int m, int rS);
 int forward_prefill_planned_bf16(const PfArgs &p, const int32_t *plan, int cap, uint16_t *Z, int avg_prompt_rows,
                                  hipStream_t s);
@@ -383,7 +384,7 @@ int forward_prefill_bf16(const parse_layer *L, const parse_patterns *pt, const u
   const bool planned_shapes = a.sh_ranks % 32 == 0 && prefill_plan_supported(P, pt->n_patterns) &&
                               prefill_planned_supported(L->n, L->m, rS);
   const int cap = planned_shapes ? prefill_plan_capacity(rows, P, pt->n_patterns) : 0;
-  const size_t zb = planned_shapes ? prefill_planned_z_bytes(cap, rS) : 0;
+  const size_t zb = planned_shapes ? prefill_planned_z_bytes(cap, rS, prefill_planned_split(rows, L->n)) : 0;
   const bool can_plan = planned_shapes && workspace != nullptr &&
                         workspace_bytes >= zb + prefill_plan_bytes(rows, P, pt->n_patterns);
   if (schedule == PARSE_SCHED_PLANNED && !can_plan) return planned_shapes ? PARSE_EWORKSPACE : PARSE_ESHAPE;

@@ -19,6 +19,8 @@
 // token in each of four 8-row bands; one 32-lane swap pairs the bands up to 8 consecutive columns = 16 bytes, which is
 // one piece of a Z operand (launch 1: stored linearly, 1 KiB per instruction) or a 16-byte store into the token's
 // row of Y (launch 2).
+#include <algorithm>
+
 #include "prefill_common.hpp"
 
 namespace parse {
@@ -47,6 +49,7 @@ struct LgLayer {
   const uint16_t *Tk;      // TROW 1: row-major [rows][K] (X);  TROW 0: Z in operand order [(virtual rows)/32][K/16][1 KiB]
   const uint16_t *F;       // factor operands of all patterns
   uint16_t *O;             // OROW 0: Z (operand order);  OROW 1: Y row-major [rows][M]
+  float *Pz;               // SPLIT: fp32 partial sums of Z, [slice][token block][reduction block][64 lanes][8]
   size_t pattern_stride;   // elements of F per pattern
   int K, M;                // reduction length, factor rows (= output columns)
   // shared head (Sec. 4.4: shared experts at the head of memory, stored once): the first sh_blocks 32-rank blocks of
@@ -63,14 +66,19 @@ struct LgArgs {
   const int32_t *plan;     // header | tile patterns | row map (plan.hip)
   int cap;                 // plan capacity in 256-row tiles (fixes where the row map starts)
   int ntn, gm, ngroups;    // column tiles (all layers), token tiles per locality group, groups
+  int ks;                  // SPLIT: slices of the reduction range, one workgroup each
 };
 
 // FORD: factor order, 0 = right factor (operand (rb, kb) at rb*(K/16)+kb), 1 = left factor (operand (kb, cb) at kb*(M/32)+cb).
 // TROW: token operand 1 = row-major rows looked up through the plan's row map (X, or a row-major intermediate),
 //       0 = operand order over the plan's virtual rows.   OROW: output 1 = row-major through the row map, 0 = operand order.
 // First product: <FORD 0, TROW 1, OROW 0>; second product: <FORD 1, TROW 0, OROW 1>.
-template <int BM, int BN, int WM, int WN, int BK, int STAGES, int FORD, int TROW, int OROW>
+// SPLIT (first product only): the reduction range is cut in a.ks slices, one workgroup each; a workgroup stores its fp32
+// sums as slice s of the partial sums and z_combine adds the slices (in slice order) and rounds -- for launches whose
+// tiles alone would leave most compute units idle (one short prompt).
+template <int BM, int BN, int WM, int WN, int BK, int STAGES, int FORD, int TROW, int OROW, int SPLIT = 0>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
+  static_assert(!SPLIT || (FORD == 0 && OROW == 0), "only the first product is split");
   constexpr int NW = WM * WN;
   constexpr int KK = BK / 16;                 // matrix-instruction steps per staged slice
   constexpr int TB = BM / WM / 32, FB = BN / WN / 32;
@@ -92,8 +100,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
   const int per = a.gm * a.ntn;
   const int vrows = a.plan[1];
   const int n_real = ((vrows + BM - 1) / BM + a.gm - 1) / a.gm * per;
-  if ((int)blockIdx.x >= n_real) return;
-  const int tile = xcd_tile(blockIdx.x, n_real);
+  const int ks = SPLIT ? a.ks : 1;
+  const int bid = SPLIT ? (int)blockIdx.x / ks : (int)blockIdx.x, sl = SPLIT ? (int)blockIdx.x % ks : 0;
+  if (bid >= n_real) return;
+  const int tile = xcd_tile(bid, n_real);
   const int g = tile / per, r = tile % per;
   const int tm = g * a.gm + r % a.gm;
   int tn = r / a.gm;                           // column tile over all layers of the launch
@@ -103,7 +113,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
   const LgLayer &ly = a.L[li];
   tn -= ly.tn_first;
   const int K = ly.K, M = ly.M;
-  const int nk = K / BK;
+  const int kt0 = SPLIT ? (int)(((long long)(K / BK) * sl) / ks) : 0;           // first slice of BK of this workgroup
+  const int nk = (SPLIT ? (int)(((long long)(K / BK) * (sl + 1)) / ks) : K / BK) - kt0;
   if (tm * BM >= vrows) return;                // the last locality group may be partial
   const int32_t *tile_pat = a.plan + 16;
   const int32_t *rowmap = a.plan + 16 + (a.cap + 15) / 16 * 16;
@@ -168,6 +179,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
     tdst[i] = F_BYTES + ins * 1024;
   }
   const size_t tstep = TROW == 0 ? (size_t)KK * 1024 : (size_t)BK * 2;
+  if (SPLIT) {
+#pragma unroll
+    for (int i = 0; i < LF; ++i) { fsrc[i] += (size_t)kt0 * fstep; fsrc_own[i] = fsrc[i]; }
+#pragma unroll
+    for (int i = 0; i < LT; ++i) tsrc[i] += (size_t)kt0 * tstep;
+  }
 
   auto issue = [&](int stage_buf) {
     char *base = smem + stage_buf * STAGE_BYTES;
@@ -283,6 +300,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
       const int gb = tn * (BN / 32) + wn * FB + i;     // 32-row factor block of the whole matrix
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
+        if (SPLIT) {   // the same exchange on the fp32 sums: lane (j, q) ends up with the 8 consecutive factor rows of its token
+          float w8[8];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[t][i][(2 * h) * 4 + e]),
+                                                             __float_as_uint(acc[t][i][(2 * h + 1) * 4 + e]), false, false);
+            w8[e] = __uint_as_float(sw[0]); w8[4 + e] = __uint_as_float(sw[1]);
+          }
+          if (gb < M / 32) {
+            const int tbg = tm * (BM / 32) + wm * TB + t;
+            float *dst = ly.Pz + (((size_t)sl * (a.cap * 8) + tbg) * (M / 16) + gb * 2 + h) * 512 + lane * 8;
+            *reinterpret_cast<float4 *>(dst) = float4{w8[0], w8[1], w8[2], w8[3]};
+            *reinterpret_cast<float4 *>(dst + 4) = float4{w8[4], w8[5], w8[6], w8[7]};
+          }
+          continue;
+        }
         const uint32_t p0x = cvt_pk_bf16(acc[t][i][(2 * h) * 4 + 0], acc[t][i][(2 * h) * 4 + 1]);
         const uint32_t p0y = cvt_pk_bf16(acc[t][i][(2 * h) * 4 + 2], acc[t][i][(2 * h) * 4 + 3]);
         const uint32_t p1x = cvt_pk_bf16(acc[t][i][(2 * h + 1) * 4 + 0], acc[t][i][(2 * h + 1) * 4 + 1]);
@@ -305,10 +338,41 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds(LgArgs a) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int STAGES, int FORD, int TROW, int OROW>
+// Adds the ks partial sums of every 16-byte piece of Z (8 consecutive ranks of a token) in slice order and rounds to
+// bf16.  One thread per piece, over the plan's virtual rows (pieces of tiles without a pattern hold nothing and are not
+// read by the second product either).
+__global__ __launch_bounds__(256) void z_combine(const float *__restrict__ Pz, int ks, int cap, int M, const int32_t *__restrict__ plan,
+                                                 uint16_t *__restrict__ Z) {
+  const size_t pieces = (size_t)(plan[1] / 32) * (M / 16) * 64;      // virtual rows / 32 token blocks x reduction blocks x lanes
+  const size_t slice = (size_t)cap * 8 * (M / 16) * 512;             // floats per slice
+  for (size_t o = (size_t)blockIdx.x * 256 + threadIdx.x; o < pieces; o += (size_t)gridDim.x * 256) {
+    const float *src = Pz + o * 8;
+    float4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < ks; s0 += 4) {      // four slices requested at a time (slices past the last re-read it)
+      float4 l4[4], h4[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float *ps = src + (size_t)min(s0 + u, ks - 1) * slice;
+        l4[u] = *reinterpret_cast<const float4 *>(ps);
+        h4[u] = *reinterpret_cast<const float4 *>(ps + 4);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (s0 + u < ks) {
+          lo.x += l4[u].x; lo.y += l4[u].y; lo.z += l4[u].z; lo.w += l4[u].w;
+          hi.x += h4[u].x; hi.y += h4[u].y; hi.z += h4[u].z; hi.w += h4[u].w;
+        }
+      }
+    }
+    *reinterpret_cast<u32x4 *>(Z + o * 8) =
+        u32x4{cvt_pk_bf16(lo.x, lo.y), cvt_pk_bf16(lo.z, lo.w), cvt_pk_bf16(hi.x, hi.y), cvt_pk_bf16(hi.z, hi.w)};
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int STAGES, int FORD, int TROW, int OROW, int SPLIT = 0>
 static int launch_gemm_lds(LgArgs a, int avg_tiles_per_pattern, hipStream_t s) {
   constexpr int smem = STAGES * (BM + BN) * BK * 2;
-  auto kern = gemm_lds<BM, BN, WM, WN, BK, STAGES, FORD, TROW, OROW>;
+  auto kern = gemm_lds<BM, BN, WM, WN, BK, STAGES, FORD, TROW, OROW, SPLIT>;
   static bool attr_done[64] = {false};
   int dev = 0;
   PARSE_HIP_TRY(hipGetDevice(&dev));
@@ -326,13 +390,31 @@ static int launch_gemm_lds(LgArgs a, int avg_tiles_per_pattern, hipStream_t s) {
   int gm = avg_tiles_per_pattern * (256 / BM);
   a.gm = gm < 1 ? 1 : (gm > 8 ? 8 : gm);
   a.ngroups = (ntm + a.gm - 1) / a.gm;
-  hipLaunchKernelGGL(kern, dim3(a.ngroups * a.gm * a.ntn), dim3(WM * WN * 64), smem, s, a);
+  hipLaunchKernelGGL(kern, dim3(a.ngroups * a.gm * a.ntn * (SPLIT ? a.ks : 1)), dim3(WM * WN * 64), smem, s, a);
   PARSE_LAUNCH_CHECK();
   return PARSE_OK;
 }
 
 // Z workspace of the planned form: the plan's capacity in virtual rows x rS bf16 (operand order)
-size_t prefill_planned_z_bytes(int cap_tiles, int rS) { return round_up((size_t)cap_tiles * 256 * rS * sizeof(uint16_t), 256); }
+// Slices of the first product's reduction range (1 = no split): only for batches of at most 1024 token rows (16 tiles
+// of 64 tokens: with the eight or so 128-rank tiles of a selection they leave half of the compute units without a
+// workgroup), as many as bring the token tiles x slices to 32, at most 8, at least 8 staged slices of 64 per workgroup.
+// A function of (rows, n) alone, so that a call over several layers splits exactly like its single-layer calls and
+// gives the same bits.
+int prefill_planned_split(int rows, int n) {
+  const int tiles = (rows + 63) / 64;
+  if (tiles <= 0 || tiles > 16) return 1;
+  int ks = 32 / tiles;
+  if (ks > 8) ks = 8;
+  if (ks > n / 64 / 8) ks = n / 64 / 8;
+  return ks < 2 ? 1 : ks;
+}
+// Z of one layer (bf16, operand order over the plan's capacity), then -- when the first product is split -- the fp32
+// partial sums of its ks slices
+static size_t planned_z_only_bytes(int cap_tiles, int rS) { return round_up((size_t)cap_tiles * 256 * rS * sizeof(uint16_t), 256); }
+size_t prefill_planned_z_bytes(int cap_tiles, int rS, int ks) {
+  return planned_z_only_bytes(cap_tiles, rS) + (ks > 1 ? round_up((size_t)ks * cap_tiles * 256 * rS * sizeof(float), 256) : 0);
+}
 
 bool prefill_planned_supported(int n, int m, int rS) { return n % 64 == 0 && rS % 32 == 0 && m % 32 == 0 && n >= 64 && rS >= 32; }
 
@@ -350,8 +432,8 @@ int forward_prefill_planned_multi_bf16(const PfArgs *p, int n_layers, const int3
   for (int l = 0; l < n_layers; ++l) {
     if (p[l].sh_ranks % 32 != 0 || p[l].sh_ranks >= p[l].rS) return PARSE_ESHAPE;
     const int own = p[l].rS - p[l].sh_ranks;   // ranks in a pattern's own block
-    g1.L[l] = LgLayer{p[l].X, p[l].Vt_S, Z[l], (size_t)own * p[l].n, p[l].n, p[l].rS, p[l].Vt_sh, p[l].sh_ranks / 32, 0};
-    g2.L[l] = LgLayer{Z[l], p[l].Ut_S, p[l].Y, (size_t)own * p[l].m, p[l].rS, p[l].m, p[l].Ut_sh, p[l].sh_ranks / 32, 0};
+    g1.L[l] = LgLayer{p[l].X, p[l].Vt_S, Z[l], nullptr, (size_t)own * p[l].n, p[l].n, p[l].rS, p[l].Vt_sh, p[l].sh_ranks / 32, 0};
+    g2.L[l] = LgLayer{Z[l], p[l].Ut_S, p[l].Y, nullptr, (size_t)own * p[l].m, p[l].rS, p[l].m, p[l].Ut_sh, p[l].sh_ranks / 32, 0};
     ct1 += (p[l].rS + 255) / 256;
     ct2 += (p[l].m + 255) / 256;
   }
@@ -367,11 +449,25 @@ int forward_prefill_planned_multi_bf16(const PfArgs *p, int n_layers, const int3
   long long t128 = 0;
   for (int l = 0; l < n_layers; ++l) t128 += (long long)((p[0].rows + 127) / 128) * ((p[l].rS + 127) / 128);
   const bool small1 = !big1 && t128 <= 192;
+  const int ks = small1 ? prefill_planned_split(p[0].rows, p[0].n) : 1;
+  if (ks > 1) {      // the partial sums follow each layer's Z in the workspace
+    g1.ks = ks;
+    for (int l = 0; l < n_layers; ++l)
+      g1.L[l].Pz = reinterpret_cast<float *>(reinterpret_cast<char *>(Z[l]) + planned_z_only_bytes(cap, p[l].rS));
+  }
   long long u128 = 0;                          // the same for the second product
   for (int l = 0; l < n_layers; ++l) u128 += (long long)((p[0].rows + 127) / 128) * ((p[l].m + 127) / 128);
   const bool small2 = !big2 && u128 <= 192;
   int st;
-  if (big1) st = launch_gemm_lds<256, 256, 2, 2, 32, 4, 0, 1, 0>(g1, per_pattern, s);
+  if (ks > 1) {
+    st = launch_gemm_lds<64, 128, 2, 2, 64, 4, 0, 1, 0, 1>(g1, per_pattern, s);
+    for (int l = 0; l < n_layers && st == PARSE_OK; ++l) {
+      const size_t pieces = (size_t)cap * 8 * (p[l].rS / 16) * 64;
+      hipLaunchKernelGGL(z_combine, dim3((unsigned)std::min<size_t>((pieces + 255) / 256, 2048)), dim3(256), 0, s, g1.L[l].Pz, ks, cap,
+                         p[l].rS, plan, Z[l]);
+      PARSE_LAUNCH_CHECK();
+    }
+  } else if (big1) st = launch_gemm_lds<256, 256, 2, 2, 32, 4, 0, 1, 0>(g1, per_pattern, s);
   else if (small1) st = launch_gemm_lds<64, 128, 2, 2, 64, 4, 0, 1, 0>(g1, per_pattern, s);
   else st = launch_gemm_lds<128, 128, 2, 2, 64, 4, 0, 1, 0>(g1, per_pattern, s);
   if (st != PARSE_OK) return st;

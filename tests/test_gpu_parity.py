@@ -506,6 +506,43 @@ def test_prefill_bf16_small(n, m, R, G, k, lengths, schedule):
         assert_close(Yg[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"prompt {p}")
 
 
+@pytest.mark.parametrize("n,m,R,G,k,lengths", [
+    (2048, 512, 256, 8, 3, [200]),              # one short prompt: 4 token tiles x 1 rank tile -> 4 slices of the reduction
+    (4096, 512, 512, 8, 4, [70, 1, 130]),       # three short prompts with different subsets, 8 slices (ragged last tile)
+    (1024, 256, 128, 4, 2, [33, 500]),          # 2 slices of 8 staged steps each
+])
+def test_prefill_of_short_prompts_splits_the_first_reduction(n, m, R, G, k, lengths):
+    """A batch too short to fill the chip with tiles of the first product: its reduction range is cut in slices whose fp32
+    partial sums a second small launch adds and rounds.  Planned schedule through parse_lowrank_forward (guards around Y
+    and the workspace of exactly the queried size), over a ready plan, and two layers in one call -- every prompt against
+    the oracle, and the three entry points bit-identical."""
+    say(f"prefill of short prompts (split first product) n={n} m={m} R={R} G={G} k={k} lengths={lengths}")
+    lay = si.make_layer(np.random.default_rng(661), n, m, R, G, "bf16", fast=True)
+    rng = np.random.default_rng(662)
+    subs = np.stack([np.sort(rng.choice(G, size=k, replace=False)) for _ in lengths]).astype(np.int32)
+    Yg, Yref, off = _run_prefill(lay, lengths, subs, 663, "bf16", 3)
+    for p in range(len(lengths)):
+        assert_close(Yg[off[p]:off[p + 1]], Yref[off[p]:off[p + 1]], TOL_BF16, f"prompt {p}")
+    # the same call over a ready plan, and as a two-layer call (the second layer is the same factors)
+    X = si.make_tokens(np.random.default_rng(663), int(off[-1]), n, "bf16")
+    dl = pa.layer_to_mfma16(upload_layer(lay))
+    sd = i32(subs)
+    pid, perm, boff, npat, rep = pa.bucket_patterns(sd, k)
+    Vs, Us = pa.pack_patterns(dl, sd, k, k, rep, npat, len(lengths))
+    pt = pa.Patterns(k, len(lengths), Vs, Us, schedule=3)
+    Xd, offd = upload_tokens(X, "bf16"), i32(off)
+    rows = int(off[-1])
+    plan = pa.prefill_plan(offd, pid, rows, len(lengths))
+    need = pa.lowrank_prefill_planned_workspace_bytes(dl, rows, len(lengths), k, len(lengths))
+    whole, mid = guarded_bytes(need)
+    Y1 = pa.lowrank_prefill_planned(dl, pt, Xd, offd, pid, plan, workspace=mid[:need])
+    check_guards(whole, "planned prefill over a ready plan: workspace")
+    assert np.array_equal(Y1.float().cpu().numpy().astype(np.float64), Yg)
+    Ys = prefill_multi_guarded([dl, dl], [pt, pt], Xd, offd, pid)
+    torch.cuda.synchronize()
+    assert torch.equal(Ys[0].view(torch.int16), Y1.view(torch.int16)) and torch.equal(Ys[1].view(torch.int16), Y1.view(torch.int16))
+
+
 def test_prefill_plan_matches_the_row_grouping_and_serves_shared_patterns():
     """The prefill plan against the oracle's row grouping (bit-exact), then the planned product with prompts that share
     patterns in interleaved arrival order, one prompt with an invalid pattern id (zero rows), and guard rows around Y."""
